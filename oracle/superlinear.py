@@ -1,0 +1,192 @@
+"""CPU fp64 oracle for the N=2 Superlinear attention hot path (span-search + span-attention).
+
+TEST INFRASTRUCTURE ONLY.  Nothing in the product path may import this module: it is called
+by the tests, by the smoke check and by the benchmark's cpu-baseline leg.  It shares no code
+with the HIP kernels and never reads their output.
+
+What it computes is the *definition* of the result, written out per query row in float64:
+
+* span-search  -- Section 3.2, eq. (2) (score = <Q_s(i), K_a(t)>) and eq. (3) (TopK over the
+  candidate anchors), with the candidate set of Algorithm 1 (anchors minus the local window).
+* span-attention -- Section 3.3, eq. (4): standard scaled dot-product attention over the keys
+  of the selected spans, merged (de-duplicated) with the local window as in Algorithm 1
+  (the DedupConcat step).  The empty-selection branch of Algorithm 1 (attend the window only)
+  falls out of the same code.
+
+Geometry (fixed span grid).  The span grid specialises the paper's span construction
+(Section 3.3, Algorithm 1: S_t = [t - b*l, t + f*l]) to f = 0 and b*l = S for every query:
+span j is the token range [j*S, (j+1)*S - 1] and its anchor is its last token
+t_j = (j+1)*S - 1.  The query at absolute position i lies in span c = i // S; its local
+window W is [c*S, i]; its candidate anchors are the spans j < c (window indices are excluded
+from the candidates, Algorithm 1).  K_a = K (Section 3.5 / 4.2), so the default search key of
+span j is K[t_j].
+
+Readings of points the paper leaves open (all listed in the design notes of the repository):
+ties in TopK go to the lower span index; selected spans are reported in ascending index order
+and padded with -1; selection is per query head; the search score is the raw dot product (no
+scale); attention uses one joint softmax over the union of the selected spans and the local
+window, scale 1/sqrt(D) unless given; LSE is the natural-log sum of exp(logit) over that set.
+
+Every function is pinned by tests that do not call it back: brute-force dense causal
+attention, brute-force argsort, closed forms, a library softmax with an explicit mask, and
+hand-derived values stored under tests/golden/.
+"""
+from __future__ import annotations
+
+import math
+
+import numpy as np
+
+F64 = np.float64
+
+
+def _f64(a):
+    """Widen anything array-like (numpy, or an object exposing .numpy()) to float64."""
+    return np.asarray(a, dtype=F64)
+
+
+def n_spans(L: int, S: int) -> int:
+    """Number of grid spans touching [0, L): ceil(L / S)."""
+    return -(-int(L) // int(S))
+
+
+def anchor_of_span(j: int, S: int) -> int:
+    """Anchor token of span j: its last token (Algorithm 1's span with f = 0 ends at the anchor)."""
+    return (int(j) + 1) * int(S) - 1
+
+
+def span_keys(K, S: int):
+    """Search keys K_a(t_j) = K[t_j] for every *complete* span j (Section 3.5: K_a = K).
+
+    K: [Hkv, L, D].  Returns [Hkv, L // S, D] float64.
+    """
+    K = np.asarray(K)
+    L = K.shape[1]
+    nfull = L // S
+    anchors = [anchor_of_span(j, S) for j in range(nfull)]
+    return _f64(K[:, anchors, :])
+
+
+def search_scores_row(qs, Ks_kv, c: int):
+    """Eq. (2): s_j = sum_d Qs[d] * Ks[j, d] for the candidate spans j = 0 .. c-1 (no scale)."""
+    if c <= 0:
+        return np.zeros((0,), dtype=F64)
+    return _f64(Ks_kv[:c]) @ _f64(qs)
+
+
+def select_topk(scores, k: int):
+    """Eq. (3) with the tie rule: the min(k, len) largest scores, ties to the lower index.
+
+    Returns the selected indices in ascending index order (a python list of ints).
+    """
+    scores = _f64(scores)
+    order = sorted(range(scores.shape[0]), key=lambda j: (-scores[j], j))
+    return sorted(order[: max(0, int(k))])
+
+
+def span_search(Qs, Ks, S: int, topk: int, q_pos0: int = 0, return_scores: bool = False):
+    """Span-search for every (head, query row).
+
+    Qs: [Hq, Lq, D] search queries; Ks: [Hkv, n, D] span search keys (n >= number of complete
+    spans below the last query); query row r sits at absolute position q_pos0 + r.
+    Returns idx [Hq, Lq, topk] int32 (ascending span indices, -1 padding) and, if asked, the
+    fp64 scores of the selected spans in the same slots (-inf in padded slots).
+    """
+    Qs = np.asarray(Qs)
+    Ks = np.asarray(Ks)
+    Hq, Lq, _ = Qs.shape
+    Hkv = Ks.shape[0]
+    G = Hq // Hkv
+    idx = np.full((Hq, Lq, topk), -1, dtype=np.int32)
+    sc = np.full((Hq, Lq, topk), -np.inf, dtype=F64)
+    for h in range(Hq):
+        kv = h // G
+        for r in range(Lq):
+            i = q_pos0 + r
+            c = i // S
+            s = search_scores_row(Qs[h, r], Ks[kv], c)
+            sel = select_topk(s, topk)
+            for slot, j in enumerate(sel):
+                idx[h, r, slot] = j
+                sc[h, r, slot] = s[j]
+    if return_scores:
+        return idx, sc
+    return idx
+
+
+def selection_margin(scores, k: int) -> float:
+    """Gap between the k-th and (k+1)-th largest candidate score (inf if fewer than k+1)."""
+    s = np.sort(_f64(scores))[::-1]
+    if s.shape[0] <= k or k <= 0:
+        return math.inf
+    return float(s[k - 1] - s[k])
+
+
+def attended_ranges(i: int, S: int, sel):
+    """Token ranges [t0, t1) attended by the query at position i: the selected spans (entries
+    < 0 or >= c are empty slots) followed by the local window [c*S, i]."""
+    c = i // S
+    out = []
+    for j in sel:
+        j = int(j)
+        if 0 <= j < c:
+            out.append((j * S, (j + 1) * S))
+    out.append((c * S, i + 1))
+    return out
+
+
+def attention_row(q, K, V, kv: int, i: int, S: int, sel, scale: float, return_weights=False):
+    """Eq. (4) over J = union of selected spans and the local window, one joint softmax.
+
+    K, V: anything indexable as X[kv, t0:t1] -> [t1-t0, D].  Returns (o [D], lse), fp64.
+    """
+    q = _f64(q)
+    ks, vs = [], []
+    for (t0, t1) in attended_ranges(i, S, sel):
+        ks.append(_f64(K[kv, t0:t1]))
+        vs.append(_f64(V[kv, t0:t1]))
+    Kj = np.concatenate(ks, axis=0)
+    Vj = np.concatenate(vs, axis=0)
+    z = scale * (Kj @ q)
+    m = np.max(z)
+    e = np.exp(z - m)
+    l = np.sum(e)
+    o = (e @ Vj) / l
+    lse = m + math.log(l)
+    if return_weights:
+        return o, lse, e / l
+    return o, lse
+
+
+def span_attention(Q, K, V, idx, S: int, scale: float | None = None, q_pos0: int = 0):
+    """Span-attention for every (head, query row): O [Hq, Lq, D] and LSE [Hq, Lq], fp64.
+
+    Q: [Hq, Lq, D]; K, V: [Hkv, L, D]; idx: [Hq, Lq, k] from span_search.
+    """
+    Q = np.asarray(Q)
+    Hq, Lq, D = Q.shape
+    Hkv = K.shape[0]
+    G = Hq // Hkv
+    if scale is None:
+        scale = 1.0 / math.sqrt(D)
+    O = np.zeros((Hq, Lq, D), dtype=F64)
+    LSE = np.zeros((Hq, Lq), dtype=F64)
+    for h in range(Hq):
+        kv = h // G
+        for r in range(Lq):
+            o, lse = attention_row(Q[h, r], K, V, kv, q_pos0 + r, S, idx[h, r], scale)
+            O[h, r] = o
+            LSE[h, r] = lse
+    return O, LSE
+
+
+def merge_partials(os_, lses):
+    """Log-sum-exp merge of attention partials over disjoint key sets: given each part's
+    normalised output o_p and its lse_p, the joint result is sum_p w_p o_p with
+    w_p = exp(lse_p - LSE), LSE = log sum_p exp(lse_p)."""
+    os_ = _f64(os_)
+    lses = _f64(lses)
+    M = np.max(lses)
+    w = np.exp(lses - M)
+    tot = np.sum(w)
+    return (w[:, None] * os_).sum(axis=0) / tot, M + math.log(tot)

@@ -1,0 +1,269 @@
+"""Pins for the CPU oracle: every check compares oracle/ against something that is not oracle/
+(brute force over the full L x L problem, library routines, closed forms, hand-derived values
+under tests/golden/).  No GPU needed."""
+import math
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import superlinear as orc
+from tests import brute
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _rand(seed, Hq, Hkv, L, D, Lq=None):
+    rng = np.random.default_rng(seed)
+    Lq = L if Lq is None else Lq
+    return (rng.standard_normal((Hq, Lq, D)), rng.standard_normal((Hkv, L, D)),
+            rng.standard_normal((Hkv, L, D)))
+
+
+def _rows(path):
+    with open(path) as f:
+        for line in f:
+            line = line.strip()
+            if line and not line.startswith("#"):
+                yield [c.strip() for c in line.split(";")]
+
+
+# ---------------------------------------------------------------- golden, hand-derived values
+
+def test_golden_attention_closed_form():
+    L, S = 6, 2
+    K = np.log(np.arange(1, L + 1, dtype=np.float64)).reshape(1, L, 1)
+    V = np.arange(L, dtype=np.float64).reshape(1, L, 1)
+    n = 0
+    for i, sel, num, den, elsE in _rows(os.path.join(GOLD, "attention_closed_form.txt")):
+        i = int(i)
+        sel = [] if sel == "-" else [int(x) for x in sel.split(",")]
+        o, lse = orc.attention_row(np.array([1.0]), K, V, 0, i, S, sel, 1.0)
+        assert o[0] == pytest.approx(int(num) / int(den), rel=1e-13, abs=1e-13)
+        assert lse == pytest.approx(math.log(int(elsE)), rel=1e-13, abs=1e-13)
+        n += 1
+    assert n == 11
+
+
+def test_golden_search_ties():
+    S = 2
+    Ks = np.array([[[3, 9], [5, 9], [5, -2], [1, 0], [4, 4], [5, 1]]], dtype=np.float64)
+    n = 0
+    for c, k, exp in _rows(os.path.join(GOLD, "search_ties.txt")):
+        c, k = int(c), int(k)
+        exp = [int(x) for x in exp.split(",")]
+        # one query at position c*S (first token of span c): candidates are spans 0..c-1
+        Qs = np.array([[[1.0, 0.0]]])
+        idx = orc.span_search(Qs, Ks, S, k, q_pos0=c * S)
+        assert idx.dtype == np.int32 and idx.shape == (1, 1, k)
+        assert idx[0, 0].tolist() == exp
+        n += 1
+    assert n == 10
+
+
+# ---------------------------------------------------------------- span-search pins
+
+@pytest.mark.parametrize("seed,Hq,Hkv,L,D,S,k", [
+    (0, 2, 1, 48, 8, 4, 3), (1, 4, 2, 60, 16, 5, 4), (2, 3, 3, 33, 4, 3, 12), (3, 4, 1, 64, 8, 8, 1)])
+def test_search_equals_bruteforce_argsort(seed, Hq, Hkv, L, D, S, k):
+    Qs, K, _ = _rand(seed, Hq, Hkv, L, D)
+    Ks = orc.span_keys(K, S)
+    # independent expression of the span keys: strided slice of K at the last token of each span
+    assert np.array_equal(Ks, K[:, S - 1::S, :][:, :L // S])
+    idx, sc = orc.span_search(Qs, Ks, S, k, return_scores=True)
+    G = Hq // Hkv
+    allscores = np.einsum("hqd,hjd->hqj", Qs, np.repeat(Ks, G, axis=0))   # full score matrix
+    for h in range(Hq):
+        for i in range(L):
+            c = i // S                                   # closed form: floor(i / S) candidates
+            want = brute.argsort_topk(allscores[h, i, :c], k)
+            got = idx[h, i]
+            assert np.array_equal(got[:len(want)], want)
+            assert np.all(got[len(want):] == -1)
+            assert len(want) == min(k, c)
+            # every selected anchor is causal and lies below the query's own span
+            assert all((j + 1) * S - 1 < c * S <= i for j in want)
+            assert np.allclose(sc[h, i, :len(want)], allscores[h, i, want], rtol=1e-13)
+            assert np.all(np.isneginf(sc[h, i, len(want):]))
+
+
+def test_search_duplicate_keys_lower_index_wins():
+    rng = np.random.default_rng(7)
+    D, S, n = 8, 4, 10
+    base = rng.standard_normal((3, D))
+    # spans 0..9 carry one of three distinct keys -> many exact ties
+    pattern = [0, 1, 0, 2, 1, 0, 2, 2, 1, 0]
+    Ks = base[pattern][None]
+    q = rng.standard_normal((1, 1, D))
+    s = base @ q[0, 0]
+    best = int(np.argmax(s))
+    members = [j for j, p in enumerate(pattern) if p == best]
+    for k in range(1, len(members) + 1):
+        idx = orc.span_search(q, Ks, S, k, q_pos0=n * S)
+        assert idx[0, 0].tolist() == members[:k]
+
+
+def test_search_chunked_equals_whole():
+    Qs, K, _ = _rand(11, 2, 1, 40, 8)
+    Ks = orc.span_keys(K, 4)
+    whole = orc.span_search(Qs, Ks, 4, 3)
+    part = orc.span_search(Qs[:, 17:29], Ks, 4, 3, q_pos0=17)
+    assert np.array_equal(whole[:, 17:29], part)
+
+
+def test_selection_margin():
+    assert orc.selection_margin([5.0, 1.0, 4.0, 3.5], 2) == pytest.approx(0.5)
+    assert orc.selection_margin([5.0, 1.0], 2) == math.inf
+
+
+# ---------------------------------------------------------------- span-attention pins
+
+@pytest.mark.parametrize("seed,Hq,Hkv,L,D,S", [(0, 2, 1, 24, 8, 4), (1, 4, 2, 30, 16, 5), (2, 2, 2, 17, 4, 3)])
+def test_all_spans_selected_equals_dense_causal(seed, Hq, Hkv, L, D, S):
+    Q, K, V = _rand(seed, Hq, Hkv, L, D)
+    n = orc.n_spans(L, S)
+    idx = orc.span_search(Q, orc.span_keys(K, S), S, n)          # top-k covers every span
+    scale = 0.37
+    O, LSE = orc.span_attention(Q, K, V, idx, S, scale=scale)
+    Od, LSEd, _ = brute.dense_masked_attention(Q, K, V, brute.causal_mask(Hq, L, L), scale)
+    assert np.allclose(O, Od, rtol=1e-12, atol=1e-13)
+    assert np.allclose(LSE, LSEd, rtol=1e-12, atol=1e-13)
+
+
+def test_single_span_is_dense_causal_and_default_scale():
+    Q, K, V = _rand(5, 2, 1, 16, 8)
+    idx = np.full((2, 16, 2), -1, dtype=np.int32)
+    O, LSE = orc.span_attention(Q, K, V, idx, 16)                 # S = L: one span, window = prefix
+    Od, LSEd, _ = brute.dense_masked_attention(Q, K, V, brute.causal_mask(2, 16, 16), 1 / math.sqrt(8))
+    assert np.allclose(O, Od, rtol=1e-12) and np.allclose(LSE, LSEd, rtol=1e-12)
+
+
+def test_topk_zero_is_block_diagonal_causal_vs_torch_sdpa():
+    # textbook special case reproduced by a library routine with an explicit mask
+    Hq, Hkv, L, D, S = 4, 2, 24, 8, 6
+    Q, K, V = _rand(9, Hq, Hkv, L, D)
+    idx = np.full((Hq, L, 1), -1, dtype=np.int32)
+    O, _ = orc.span_attention(Q, K, V, idx, S)
+    i = torch.arange(L)[:, None]
+    t = torch.arange(L)[None, :]
+    mask = (t <= i) & (t // S == i // S)
+    Kt = torch.from_numpy(K).repeat_interleave(Hq // Hkv, dim=0)
+    Vt = torch.from_numpy(V).repeat_interleave(Hq // Hkv, dim=0)
+    ref = torch.nn.functional.scaled_dot_product_attention(
+        torch.from_numpy(Q)[None], Kt[None], Vt[None], attn_mask=mask)[0].numpy()
+    assert np.allclose(O, ref, rtol=1e-11, atol=1e-12)
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_arbitrary_selection_equals_masked_dense(seed):
+    # random (not searched) span sets, incl. empty slots and out-of-range entries that must be ignored
+    Hq, Hkv, L, D, S, k = 4, 2, 40, 8, 5, 3
+    Q, K, V = _rand(20 + seed, Hq, Hkv, L, D)
+    rng = np.random.default_rng(seed)
+    idx = np.full((Hq, L, k), -1, dtype=np.int32)
+    for h in range(Hq):
+        for i in range(L):
+            c = i // S
+            pool = list(rng.permutation(c))[:k]
+            row = sorted(pool) + [-1] * (k - len(pool))
+            if rng.random() < 0.3 and c < L // S:
+                row[-1] = c if row[-1] == -1 else row[-1]       # own span or beyond: ignored
+            idx[h, i] = row
+    O, LSE = orc.span_attention(Q, K, V, idx, S, scale=0.5)
+    Od, LSEd, _ = brute.dense_masked_attention(Q, K, V, brute.span_mask(idx, S, L), 0.5)
+    assert np.allclose(O, Od, rtol=1e-12, atol=1e-13)
+    assert np.allclose(LSE, LSEd, rtol=1e-12, atol=1e-13)
+
+
+def test_weights_sum_to_one_and_key_count_closed_form():
+    Hq, Hkv, L, D, S, k = 2, 1, 50, 8, 5, 3
+    Q, K, V = _rand(3, Hq, Hkv, L, D)
+    idx = orc.span_search(Q, orc.span_keys(K, S), S, k)
+    for h in range(Hq):
+        for i in range(L):
+            o, lse, w = orc.attention_row(Q[h, i], K, V, 0, i, S, idx[h, i], 0.3, return_weights=True)
+            assert w.sum() == pytest.approx(1.0, abs=1e-14)
+            assert np.all(w > 0)
+            # attended keys = min(k, c) * S + (i mod S) + 1
+            assert w.shape[0] == min(k, i // S) * S + (i % S) + 1
+
+
+def test_slot_permutation_invariance():
+    Hq, Hkv, L, D, S, k = 2, 2, 48, 8, 4, 4
+    Q, K, V = _rand(4, Hq, Hkv, L, D)
+    idx = orc.span_search(Q, orc.span_keys(K, S), S, k)
+    O, LSE = orc.span_attention(Q, K, V, idx, S)
+    rng = np.random.default_rng(0)
+    perm = idx.copy()
+    for h in range(Hq):
+        for i in range(L):
+            perm[h, i] = idx[h, i][rng.permutation(k)]
+    O2, LSE2 = orc.span_attention(Q, K, V, perm, S)
+    assert np.allclose(O, O2, rtol=1e-13, atol=1e-14) and np.allclose(LSE, LSE2, rtol=1e-13)
+
+
+def test_identical_keys_give_mean_of_values():
+    # closed form: if every key is the same vector the weights are uniform over J
+    Hq, Hkv, L, D, S, k = 1, 1, 32, 4, 4, 2
+    rng = np.random.default_rng(1)
+    kvec = rng.standard_normal(D)
+    K = np.broadcast_to(kvec, (1, L, D)).copy()
+    V = rng.standard_normal((1, L, D))
+    Q = rng.standard_normal((1, L, D))
+    idx = orc.span_search(Q, orc.span_keys(K, S), S, k)      # all ties -> lowest spans
+    O, LSE = orc.span_attention(Q, K, V, idx, S, scale=1.0)
+    for i in range(L):
+        c = i // S
+        sel = list(range(min(k, c)))
+        assert idx[0, i, :len(sel)].tolist() == sel
+        toks = [t for j in sel for t in range(j * S, (j + 1) * S)] + list(range(c * S, i + 1))
+        assert np.allclose(O[0, i], V[0, toks].mean(axis=0), rtol=1e-12)
+        assert LSE[0, i] == pytest.approx(float(Q[0, i] @ kvec) + math.log(len(toks)), rel=1e-12)
+
+
+def test_gqa_head_mapping():
+    # head h must read kv head h // G (not h % Hkv): make kv heads wildly different
+    Hq, Hkv, L, D, S = 4, 2, 12, 4, 4
+    Q, K, V = _rand(8, Hq, Hkv, L, D)
+    V[1] += 100.0
+    idx = np.full((Hq, L, 1), -1, dtype=np.int32)
+    O, _ = orc.span_attention(Q, K, V, idx, S)
+    assert np.all(np.abs(O[0:2]) < 50) and np.all(O[2:4] > 50)
+
+
+def test_attention_chunked_equals_whole():
+    Hq, Hkv, L, D, S, k = 2, 1, 36, 8, 4, 2
+    Q, K, V = _rand(12, Hq, Hkv, L, D)
+    idx = orc.span_search(Q, orc.span_keys(K, S), S, k)
+    O, LSE = orc.span_attention(Q, K, V, idx, S)
+    O2, LSE2 = orc.span_attention(Q[:, 13:30], K, V, idx[:, 13:30], S, q_pos0=13)
+    assert np.array_equal(O[:, 13:30], O2) and np.array_equal(LSE[:, 13:30], LSE2)
+
+
+def test_merge_partials_identity():
+    # merging per-span partials equals the one-shot softmax over the union (textbook identity)
+    Hq, Hkv, L, D, S = 1, 1, 40, 8, 8
+    Q, K, V = _rand(13, Hq, Hkv, L, D)
+    i, sel, scale = 37, [0, 2, 3], 0.4
+    o_all, lse_all = orc.attention_row(Q[0, i], K, V, 0, i, S, sel, scale)
+    parts_o, parts_l = [], []
+    for (t0, t1) in orc.attended_ranges(i, S, sel):
+        Od, Ld, _ = brute.dense_masked_attention(
+            Q[:, i:i + 1], K[:, t0:t1], V[:, t0:t1], np.ones((1, 1, t1 - t0), bool), scale)
+        parts_o.append(Od[0, 0])
+        parts_l.append(Ld[0, 0])
+    o, lse = orc.merge_partials(np.stack(parts_o), np.array(parts_l))
+    assert np.allclose(o, o_all, rtol=1e-12) and lse == pytest.approx(lse_all, rel=1e-13)
+
+
+def test_random_context_access_cover():
+    # structural non-exclusion (Section 2.3) on the grid: candidate spans plus the local window
+    # cover every key position j <= i
+    for S in (1, 3, 8):
+        for i in range(0, 70):
+            c = i // S
+            cover = set()
+            for (t0, t1) in orc.attended_ranges(i, S, list(range(c))):
+                cover |= set(range(t0, t1))
+            assert cover == set(range(i + 1))
