@@ -1,0 +1,154 @@
+/* sl.h -- C ABI of the Superlinear attention (N = 2) span-search / span-attention library
+ * for AMD MI355X (gfx950).
+ *
+ * The library implements the two data-parallel steps of the baseline N = 2 instantiation of
+ * Superlinear multi-step attention on a fixed span grid:
+ *
+ *   span-search    (paper Section 3.2, eq. (2) and (3); Algorithm 1, the scoring loop and TopK):
+ *                  score every candidate span of a causal query by the raw dot product of the
+ *                  search query with the span's search key, keep the top-k spans.
+ *   span-attention (paper Section 3.3, eq. (4); Algorithm 1, the DedupConcat + Attention steps
+ *                  and the empty-selection branch): exact softmax attention of the query over
+ *                  the union of the selected spans and its local window; returns the output
+ *                  and the log-sum-exp of the logits.
+ *
+ * Geometry.  Tokens 0 .. L-1; span j is the token range [j*S, min((j+1)*S, L) - 1]; its anchor
+ * (search position) is its last token (j+1)*S - 1 (Algorithm 1's span [t - b*l, t + f*l] with
+ * f = 0, b*l = S).  Query row r has absolute position i = q_pos0 + r and lies in span
+ * c = i / S.  Its candidates are the complete spans j < c (Algorithm 1 removes the window's
+ * indices from the anchor candidates); its local window is [c*S, i].
+ *
+ * Conventions shared by every entry point
+ *   - All tensor pointers are DEVICE pointers owned by the caller; the library never allocates,
+ *     frees or synchronises.  Work is enqueued on `hip_stream` (a hipStream_t, NULL = the
+ *     default stream) and completes asynchronously.
+ *   - Layouts (element strides, innermost dimension D contiguous):
+ *       Q, Qs, O : [Hq ][Lq][D]  strides (q_stride_h, q_stride_t, 1);  O is always packed [Hq][Lq][D]
+ *       K, V     : [Hkv][L ][D]  strides (kv_stride_h, kv_stride_t, 1)
+ *       Ks       : [Hkv][n ][D]  packed, n = ceil(L / S); row j = search key of span j
+ *       idx      : [Hq ][Lq][topk] int32, packed
+ *       scores   : [Hq ][Lq][topk] float, packed
+ *       LSE      : [Hq ][Lq] float, packed
+ *     A stride given as 0 means "packed".  Query head h reads KV head h / (Hq / Hkv).
+ *   - dtype selects the element type of Q, Qs, K, V, Ks and O (fp32, or bf16 with fp32
+ *     accumulation); scores, LSE and all softmax statistics are fp32.
+ *   - Base pointers must be 16-byte aligned and strides multiples of 16 bytes.
+ *   - Errors: every argument is validated on the host before anything is enqueued; on error
+ *     nothing has been launched and a status other than SL_OK is returned (no exceptions, no
+ *     abort).  A failed kernel launch returns SL_ERR_LAUNCH.
+ *   - Scratch memory comes from the caller through (ws, ws_bytes); ask sl_workspace_bytes for
+ *     the size.  ws must be 256-byte aligned.  Calls that share a workspace must be ordered on
+ *     one stream.
+ */
+#ifndef SL_H_
+#define SL_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  SL_OK = 0,
+  SL_ERR_INVALID_ARG = 1, /* null pointer, non-positive size, bad stride or alignment, ...     */
+  SL_ERR_UNSUPPORTED = 2, /* valid request outside the compiled envelope (D, topk, dtype)      */
+  SL_ERR_WORKSPACE = 3,   /* workspace missing, misaligned or smaller than sl_workspace_bytes  */
+  SL_ERR_LAUNCH = 4       /* HIP reported an error when enqueueing                             */
+} sl_status;
+
+typedef enum { SL_F32 = 0, SL_BF16 = 1 } sl_dtype;
+
+typedef enum {
+  SL_OP_SEARCH_PREFILL = 0,
+  SL_OP_SEARCH_DECODE = 1,
+  SL_OP_ATTENTION_PREFILL = 2,
+  SL_OP_ATTENTION_DECODE = 3
+} sl_op;
+
+/* Largest supported top-k (routed spans per query and head; the local window is extra). */
+#define SL_MAX_TOPK 32
+
+typedef struct sl_params {
+  int64_t L;       /* keys visible: sequence length (prefill) or cache length incl. the current token (decode) */
+  int64_t Lq;      /* query rows per head; decode entry points require Lq == 1                    */
+  int64_t q_pos0;  /* absolute position of query row 0 (prefill: 0, or chunk start; decode: L-1)   */
+  int32_t Hq;      /* query heads                                                                  */
+  int32_t Hkv;     /* key/value heads, Hq % Hkv == 0                                               */
+  int32_t D;       /* head dimension: 64 or 128                                                    */
+  int32_t S;       /* span length in tokens, >= 1                                                  */
+  int32_t topk;    /* routed spans per (head, query): 1..SL_MAX_TOPK for search, 0..SL_MAX_TOPK for attention */
+  int32_t dtype;   /* sl_dtype                                                                     */
+  float scale;     /* softmax scale of span-attention; 0 means 1/sqrt(D). Search scores are unscaled (eq. (2)) */
+  int32_t reserved0;
+  int64_t q_stride_h, q_stride_t;   /* element strides of Q / Qs; 0 = packed                       */
+  int64_t kv_stride_h, kv_stride_t; /* element strides of K and V; 0 = packed                      */
+  /* Optional profiling hooks: two caller-owned hipEvent_t handles.  When both are non-NULL the
+   * call records prof_start immediately before, and prof_stop immediately after, its dominant
+   * kernel (the K/V-streaming kernel of span-attention, the scoring kernel of span-search). */
+  void* prof_start;
+  void* prof_stop;
+} sl_params;
+
+/* Bytes of scratch the given operation needs for these parameters (0 if none, or if the
+ * parameters are invalid -- the entry point itself reports why). Host-only, no HIP call. */
+size_t sl_workspace_bytes(const sl_params* p, int op /* sl_op */);
+
+/* Span-key formation.  Section 3.5 / 4.2: the representative stream reuses the key tensor,
+ * K_a = K, so the search key of span j is K at the span's anchor.  Gathers
+ * Ks[kv][j][:] = K[kv][(j+1)*S - 1][:] for every complete span j < L / S into the packed
+ * tensor Ks [Hkv][ceil(L/S)][D] (device memory, caller-owned; the row of a trailing partial
+ * span is left untouched).  Uses L, Hkv, D, S, dtype and the kv strides of p. */
+sl_status sl_span_keys(const sl_params* p, const void* K, void* Ks, void* hip_stream);
+
+/* Span-search, prefill form (Section 3.2, eq. (2)-(3); Algorithm 1 scoring loop + TopK) for
+ * Lq query rows per head at positions q_pos0 .. q_pos0 + Lq - 1.
+ *   Qs     search queries Q_s, layout of Q.
+ *   K      key tensor; only read when Ks == NULL (then span j's key is K[kv][(j+1)*S-1]).
+ *   Ks     packed span search keys, or NULL.
+ *   idx    out: for each (h, r) the min(topk, c) best candidate spans in ASCENDING span index,
+ *          remaining slots -1.  Ties in score go to the lower span index.
+ *   scores out, optional (NULL to skip): fp32 score of the span in the same slot, -inf in
+ *          empty slots.
+ * Scores are accumulated in fp32 from exact products of the inputs. */
+sl_status sl_span_search_prefill(const sl_params* p, const void* Qs, const void* K, const void* Ks,
+                                 int32_t* idx, float* scores, void* ws, size_t ws_bytes,
+                                 void* hip_stream);
+
+/* Span-search, decode form: the same operation for one query row per head (Lq must be 1) at
+ * position q_pos0 against an L-token cache (Section 4.3, decoding path: routing scores over
+ * the anchor set of the current position).  Same arguments and outputs as the prefill form. */
+sl_status sl_span_search_decode(const sl_params* p, const void* Qs, const void* K, const void* Ks,
+                                int32_t* idx, float* scores, void* ws, size_t ws_bytes,
+                                void* hip_stream);
+
+/* Span-attention, prefill form (Section 3.3, eq. (4); Algorithm 1 DedupConcat + Attention, and
+ * the window-only branch when nothing is selected).  For each (h, r): one softmax over
+ * J = union of spans idx[h][r][*] and the local window [c*S, i], logits scale * <Q, K_t>.
+ *   idx    in: span indices as produced by span-search.  Entries < 0 or >= c are empty slots
+ *          (so arbitrary garbage cannot cause an out-of-range read); a span listed twice in a
+ *          row is counted twice (caller error).
+ *   O      out: [Hq][Lq][D] in the input dtype.
+ *   LSE    out: natural-log sum over J of exp(logit), fp32. */
+sl_status sl_span_attention_prefill(const sl_params* p, const void* Q, const void* K, const void* V,
+                                    const int32_t* idx, void* O, float* LSE, void* ws,
+                                    size_t ws_bytes, void* hip_stream);
+
+/* Span-attention, decode form: one query row per head (Lq must be 1) against an L-token KV
+ * cache; split over the selected spans and merged by log-sum-exp (Section 4.3, decoding path:
+ * attention over the routed spans, O(L^{1/2}) keys per step).  Same arguments as the prefill form. */
+sl_status sl_span_attention_decode(const sl_params* p, const void* Q, const void* K, const void* V,
+                                   const int32_t* idx, void* O, float* LSE, void* ws,
+                                   size_t ws_bytes, void* hip_stream);
+
+/* Static, human-readable name of a status code. */
+const char* sl_status_string(int status);
+
+/* Library version as major * 10000 + minor * 100 + patch. */
+int sl_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SL_H_ */

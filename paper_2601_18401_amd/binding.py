@@ -1,0 +1,216 @@
+"""Thin ctypes binding over the C-ABI library libsl.so (argument marshalling only).
+
+Every step of the hot path runs in the library's HIP kernels; PyTorch is used for device
+memory and the current stream.  Importing this module needs only the built library; calling an
+operation needs a GPU.  There is no CPU fallback: a missing library raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import math
+import os
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libsl.so")
+
+SL_OK = 0
+SL_F32, SL_BF16 = 0, 1
+OP_SEARCH_PREFILL, OP_SEARCH_DECODE, OP_ATTENTION_PREFILL, OP_ATTENTION_DECODE = 0, 1, 2, 3
+SL_MAX_TOPK = 32
+
+EXPORTS = ("sl_workspace_bytes", "sl_span_keys", "sl_span_search_prefill", "sl_span_search_decode",
+           "sl_span_attention_prefill", "sl_span_attention_decode", "sl_status_string", "sl_version")
+
+
+class SlParams(ctypes.Structure):
+    _fields_ = [
+        ("L", ctypes.c_int64), ("Lq", ctypes.c_int64), ("q_pos0", ctypes.c_int64),
+        ("Hq", ctypes.c_int32), ("Hkv", ctypes.c_int32), ("D", ctypes.c_int32),
+        ("S", ctypes.c_int32), ("topk", ctypes.c_int32), ("dtype", ctypes.c_int32),
+        ("scale", ctypes.c_float), ("reserved0", ctypes.c_int32),
+        ("q_stride_h", ctypes.c_int64), ("q_stride_t", ctypes.c_int64),
+        ("kv_stride_h", ctypes.c_int64), ("kv_stride_t", ctypes.c_int64),
+        ("prof_start", ctypes.c_void_p), ("prof_stop", ctypes.c_void_p),
+    ]
+
+
+class SlError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)}")
+
+
+_lib = None
+
+
+def load():
+    """Load libsl.so (built in-tree by paper_2601_18401_amd.build). Raises if it is missing."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(
+            f"{LIB_PATH} not found: build it first (python -m paper_2601_18401_amd.build, or "
+            "__graft_entry__.build()). There is no fallback path.")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i32p, f32p = ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p
+    pp = ctypes.POINTER(SlParams)
+    lib.sl_workspace_bytes.restype = ctypes.c_size_t
+    lib.sl_workspace_bytes.argtypes = [pp, ctypes.c_int]
+    lib.sl_span_keys.restype = ctypes.c_int
+    lib.sl_span_keys.argtypes = [pp, vp, vp, vp]
+    for name in ("sl_span_search_prefill", "sl_span_search_decode"):
+        fn = getattr(lib, name)
+        fn.restype = ctypes.c_int
+        fn.argtypes = [pp, vp, vp, vp, i32p, f32p, vp, ctypes.c_size_t, vp]
+    for name in ("sl_span_attention_prefill", "sl_span_attention_decode"):
+        fn = getattr(lib, name)
+        fn.restype = ctypes.c_int
+        fn.argtypes = [pp, vp, vp, vp, i32p, vp, f32p, vp, ctypes.c_size_t, vp]
+    lib.sl_status_string.restype = ctypes.c_char_p
+    lib.sl_status_string.argtypes = [ctypes.c_int]
+    lib.sl_version.restype = ctypes.c_int
+    lib.sl_version.argtypes = []
+    _lib = lib
+    return lib
+
+
+def status_string(status: int) -> str:
+    return load().sl_status_string(int(status)).decode()
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return SL_F32
+    if t.dtype == torch.bfloat16:
+        return SL_BF16
+    raise TypeError(f"unsupported dtype {t.dtype}: fp32 or bf16 only")
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def make_params(Q, K, S, topk, q_pos0=0, scale=0.0, prof=None) -> SlParams:
+    """Q: [Hq, Lq, D] (innermost contiguous), K: [Hkv, L, D]."""
+    if Q.dim() != 3 or K.dim() != 3 or Q.stride(2) != 1 or K.stride(2) != 1:
+        raise ValueError("expect Q [Hq, Lq, D] and K [Hkv, L, D] with contiguous innermost dimension")
+    p = SlParams()
+    p.L, p.Lq, p.q_pos0 = K.shape[1], Q.shape[1], int(q_pos0)
+    p.Hq, p.Hkv, p.D = Q.shape[0], K.shape[0], Q.shape[2]
+    p.S, p.topk, p.dtype = int(S), int(topk), _dtype_code(Q)
+    p.scale = float(scale)
+    p.q_stride_h, p.q_stride_t = Q.stride(0), Q.stride(1)
+    p.kv_stride_h, p.kv_stride_t = K.stride(0), K.stride(1)
+    if prof is not None:
+        p.prof_start, p.prof_stop = prof
+    return p
+
+
+def workspace_bytes(p: SlParams, op: int) -> int:
+    return int(load().sl_workspace_bytes(ctypes.byref(p), op))
+
+
+class Workspace:
+    """Caller-owned scratch: one growing uint8 device tensor per instance."""
+
+    def __init__(self, device="cuda"):
+        self.device = device
+        self.buf = None
+
+    def get(self, nbytes: int):
+        if nbytes == 0:
+            return None, 0
+        if self.buf is None or self.buf.numel() < nbytes:
+            self.buf = torch.empty(int(nbytes) + 256, dtype=torch.uint8, device=self.device)
+        off = (-self.buf.data_ptr()) % 256
+        return ctypes.c_void_p(self.buf.data_ptr() + off), self.buf.numel() - off
+
+
+_default_ws = None
+
+
+def _ws(ws):
+    global _default_ws
+    if ws is not None:
+        return ws
+    if _default_ws is None:
+        _default_ws = Workspace()
+    return _default_ws
+
+
+def _check(status, where):
+    if status != SL_OK:
+        raise SlError(status, where)
+
+
+def sl_span_keys(K, S, out=None):
+    """Ks[kv, j] = K[kv, (j+1)S - 1] for every complete span j; returns Ks [Hkv, ceil(L/S), D]."""
+    Hkv, L, D = K.shape
+    n = -(-L // S)
+    if out is None:
+        out = torch.zeros((Hkv, n, D), dtype=K.dtype, device=K.device)
+    p = make_params(K[:, :1], K, S, 0)
+    p.Hq = Hkv
+    _check(load().sl_span_keys(ctypes.byref(p), _ptr(K), _ptr(out), _stream()), "sl_span_keys")
+    return out
+
+
+def _search(fn_name, op, Qs, K, Ks, S, topk, q_pos0, want_scores, ws, prof):
+    lib = load()
+    p = make_params(Qs, K, S, topk, q_pos0, prof=prof)
+    Hq, Lq, _ = Qs.shape
+    idx = torch.empty((Hq, Lq, topk), dtype=torch.int32, device=Qs.device)
+    scores = torch.empty((Hq, Lq, topk), dtype=torch.float32, device=Qs.device) if want_scores else None
+    wptr, wbytes = _ws(ws).get(workspace_bytes(p, op))
+    st = getattr(lib, fn_name)(ctypes.byref(p), _ptr(Qs), _ptr(K), _ptr(Ks), _ptr(idx), _ptr(scores),
+                               wptr, wbytes, _stream())
+    _check(st, fn_name)
+    return (idx, scores) if want_scores else idx
+
+
+def sl_span_search_prefill(Qs, K, Ks, S, topk, q_pos0=0, want_scores=False, ws=None, prof=None):
+    return _search("sl_span_search_prefill", OP_SEARCH_PREFILL, Qs, K, Ks, S, topk, q_pos0,
+                   want_scores, ws, prof)
+
+
+def sl_span_search_decode(Qs, K, Ks, S, topk, q_pos0=None, want_scores=False, ws=None, prof=None):
+    q_pos0 = K.shape[1] - 1 if q_pos0 is None else q_pos0
+    return _search("sl_span_search_decode", OP_SEARCH_DECODE, Qs, K, Ks, S, topk, q_pos0,
+                   want_scores, ws, prof)
+
+
+def _attention(fn_name, op, Q, K, V, idx, S, q_pos0, scale, ws, prof, out):
+    lib = load()
+    topk = 0 if idx is None else idx.shape[2]
+    p = make_params(Q, K, S, topk, q_pos0, scale, prof=prof)
+    if V.shape != K.shape or V.stride() != K.stride():
+        raise ValueError("V must have the shape and strides of K")
+    Hq, Lq, D = Q.shape
+    if out is None:
+        O = torch.empty((Hq, Lq, D), dtype=Q.dtype, device=Q.device)
+        LSE = torch.empty((Hq, Lq), dtype=torch.float32, device=Q.device)
+    else:
+        O, LSE = out
+    wptr, wbytes = _ws(ws).get(workspace_bytes(p, op))
+    st = getattr(lib, fn_name)(ctypes.byref(p), _ptr(Q), _ptr(K), _ptr(V), _ptr(idx), _ptr(O), _ptr(LSE),
+                               wptr, wbytes, _stream())
+    _check(st, fn_name)
+    return O, LSE
+
+
+def sl_span_attention_prefill(Q, K, V, idx, S, q_pos0=0, scale=0.0, ws=None, prof=None, out=None):
+    return _attention("sl_span_attention_prefill", OP_ATTENTION_PREFILL, Q, K, V, idx, S, q_pos0,
+                      scale, ws, prof, out)
+
+
+def sl_span_attention_decode(Q, K, V, idx, S, q_pos0=None, scale=0.0, ws=None, prof=None, out=None):
+    q_pos0 = K.shape[1] - 1 if q_pos0 is None else q_pos0
+    return _attention("sl_span_attention_decode", OP_ATTENTION_DECODE, Q, K, V, idx, S, q_pos0,
+                      scale, ws, prof, out)

@@ -1,0 +1,182 @@
+// C-ABI layer: argument validation on the host, then dispatch to the kernel launchers.
+// Nothing is enqueued before every check has passed.
+#include <cmath>
+#include <cstring>
+
+#include "kernels.h"
+
+namespace sl {
+
+namespace {
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// Validates p for the given operation and fills pb.  Pure host code (no HIP call), so every
+// error path can be exercised without a GPU.
+sl_status make_problem(const sl_params* p, int op, Problem* pb) {
+  if (!p) return SL_ERR_INVALID_ARG;
+  if (p->L < 1 || p->Lq < 1 || p->q_pos0 < 0) return SL_ERR_INVALID_ARG;
+  if (p->q_pos0 > p->L - p->Lq) return SL_ERR_INVALID_ARG;  // last query must be a visible key
+  if (p->Hq < 1 || p->Hkv < 1 || p->Hq % p->Hkv != 0) return SL_ERR_INVALID_ARG;
+  if (p->S < 1 || p->topk < 0) return SL_ERR_INVALID_ARG;
+  if (p->dtype != SL_F32 && p->dtype != SL_BF16) return SL_ERR_INVALID_ARG;
+  if (!(p->scale >= 0.f) || std::isinf(p->scale)) return SL_ERR_INVALID_ARG;
+  const bool is_search = (op == SL_OP_SEARCH_PREFILL || op == SL_OP_SEARCH_DECODE);
+  const bool is_decode = (op == SL_OP_SEARCH_DECODE || op == SL_OP_ATTENTION_DECODE);
+  if (op < SL_OP_SEARCH_PREFILL || op > SL_OP_ATTENTION_DECODE) return SL_ERR_INVALID_ARG;
+  if (is_search && p->topk < 1) return SL_ERR_INVALID_ARG;
+  if (is_decode && p->Lq != 1) return SL_ERR_INVALID_ARG;
+  if (p->D != 64 && p->D != 128) return SL_ERR_UNSUPPORTED;
+  if (p->topk > SL_MAX_TOPK) return SL_ERR_UNSUPPORTED;
+  if (p->Hq / p->Hkv > 64) return SL_ERR_UNSUPPORTED;
+  if ((int64_t)p->Hq * p->Lq > ((int64_t)1 << 31) - 1) return SL_ERR_UNSUPPORTED;
+
+  const int64_t epl = p->dtype == SL_BF16 ? 8 : 4;  // elements per 16 bytes
+  const int64_t qst = p->q_stride_t ? p->q_stride_t : p->D;
+  const int64_t qsh = p->q_stride_h ? p->q_stride_h : p->Lq * qst;
+  const int64_t kvst = p->kv_stride_t ? p->kv_stride_t : p->D;
+  const int64_t kvsh = p->kv_stride_h ? p->kv_stride_h : p->L * kvst;
+  if (qst < p->D || kvst < p->D || qsh < 0 || kvsh < 0) return SL_ERR_INVALID_ARG;
+  if (qst % epl || qsh % epl || kvst % epl || kvsh % epl) return SL_ERR_INVALID_ARG;
+
+  pb->L = p->L;
+  pb->Lq = p->Lq;
+  pb->q_pos0 = p->q_pos0;
+  pb->Hq = p->Hq;
+  pb->Hkv = p->Hkv;
+  pb->G = p->Hq / p->Hkv;
+  pb->D = p->D;
+  pb->S = p->S;
+  pb->topk = p->topk;
+  pb->dtype = p->dtype;
+  pb->scale = p->scale > 0.f ? p->scale : 1.0f / std::sqrt((float)p->D);
+  pb->qsh = qsh;
+  pb->qst = qst;
+  pb->kvsh = kvsh;
+  pb->kvst = kvst;
+  pb->n = (p->L + p->S - 1) / p->S;
+  const bool prof = p->prof_start && p->prof_stop;
+  pb->prof_start = prof ? static_cast<hipEvent_t>(p->prof_start) : nullptr;
+  pb->prof_stop = prof ? static_cast<hipEvent_t>(p->prof_stop) : nullptr;
+  return SL_OK;
+}
+
+size_t ws_bytes_for(const Problem& pb, int op) {
+  switch (op) {
+    case SL_OP_SEARCH_PREFILL: return prefill_search_ws_bytes(pb);
+    case SL_OP_SEARCH_DECODE: return decode_search_ws_bytes(pb);
+    case SL_OP_ATTENTION_PREFILL: return prefill_attention_ws_bytes(pb);
+    case SL_OP_ATTENTION_DECODE: return decode_attention_ws_bytes(pb);
+  }
+  return 0;
+}
+
+sl_status check_ws(const Problem& pb, int op, const void* ws, size_t ws_bytes) {
+  const size_t need = ws_bytes_for(pb, op);
+  if (need == 0) return SL_OK;
+  if (!ws || ws_bytes < need) return SL_ERR_WORKSPACE;
+  if (reinterpret_cast<uintptr_t>(ws) & 255u) return SL_ERR_WORKSPACE;
+  return SL_OK;
+}
+
+sl_status search_entry(const sl_params* p, int op, const void* Qs, const void* K, const void* Ks,
+                       int32_t* idx, float* scores, void* ws, size_t ws_bytes, void* stream) {
+  Problem pb;
+  sl_status s = make_problem(p, op, &pb);
+  if (s != SL_OK) return s;
+  if (!Qs || !idx || (!K && !Ks)) return SL_ERR_INVALID_ARG;
+  if (!aligned16(Qs) || !aligned16(K) || !aligned16(Ks) || !aligned16(idx) || !aligned16(scores))
+    return SL_ERR_INVALID_ARG;
+  s = check_ws(pb, op, ws, ws_bytes);
+  if (s != SL_OK) return s;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (op == SL_OP_SEARCH_DECODE) return decode_search(pb, Qs, K, Ks, idx, scores, ws, st);
+  return prefill_search(pb, Qs, K, Ks, idx, scores, ws, st);
+}
+
+sl_status attention_entry(const sl_params* p, int op, const void* Q, const void* K, const void* V,
+                          const int32_t* idx, void* O, float* LSE, void* ws, size_t ws_bytes,
+                          void* stream) {
+  Problem pb;
+  sl_status s = make_problem(p, op, &pb);
+  if (s != SL_OK) return s;
+  if (!Q || !K || !V || !O || !LSE) return SL_ERR_INVALID_ARG;
+  if (pb.topk > 0 && !idx) return SL_ERR_INVALID_ARG;
+  if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O) || !aligned16(idx) ||
+      !aligned16(LSE))
+    return SL_ERR_INVALID_ARG;
+  s = check_ws(pb, op, ws, ws_bytes);
+  if (s != SL_OK) return s;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (op == SL_OP_ATTENTION_DECODE) return decode_attention(pb, Q, K, V, idx, O, LSE, ws, st);
+  return prefill_attention(pb, Q, K, V, idx, O, LSE, ws, st);
+}
+
+}  // namespace
+
+}  // namespace sl
+
+extern "C" {
+
+size_t sl_workspace_bytes(const sl_params* p, int op) {
+  sl::Problem pb;
+  if (sl::make_problem(p, op, &pb) != SL_OK) return 0;
+  return sl::ws_bytes_for(pb, op);
+}
+
+sl_status sl_span_keys(const sl_params* p, const void* K, void* Ks, void* hip_stream) {
+  if (!p) return SL_ERR_INVALID_ARG;
+  sl_params q = *p;  // only L, Hkv, D, S, dtype and the kv strides matter here
+  q.Lq = 1;
+  q.q_pos0 = 0;
+  q.Hq = q.Hkv;
+  q.topk = 0;
+  q.scale = 0.f;
+  q.q_stride_h = q.q_stride_t = 0;
+  sl::Problem pb;
+  sl_status s = sl::make_problem(&q, SL_OP_ATTENTION_PREFILL, &pb);
+  if (s != SL_OK) return s;
+  if (!K || !Ks || !sl::aligned16(K) || !sl::aligned16(Ks)) return SL_ERR_INVALID_ARG;
+  return sl::span_keys(pb, K, Ks, static_cast<hipStream_t>(hip_stream));
+}
+
+sl_status sl_span_search_prefill(const sl_params* p, const void* Qs, const void* K, const void* Ks,
+                                 int32_t* idx, float* scores, void* ws, size_t ws_bytes,
+                                 void* hip_stream) {
+  return sl::search_entry(p, SL_OP_SEARCH_PREFILL, Qs, K, Ks, idx, scores, ws, ws_bytes, hip_stream);
+}
+
+sl_status sl_span_search_decode(const sl_params* p, const void* Qs, const void* K, const void* Ks,
+                                int32_t* idx, float* scores, void* ws, size_t ws_bytes,
+                                void* hip_stream) {
+  return sl::search_entry(p, SL_OP_SEARCH_DECODE, Qs, K, Ks, idx, scores, ws, ws_bytes, hip_stream);
+}
+
+sl_status sl_span_attention_prefill(const sl_params* p, const void* Q, const void* K, const void* V,
+                                    const int32_t* idx, void* O, float* LSE, void* ws,
+                                    size_t ws_bytes, void* hip_stream) {
+  return sl::attention_entry(p, SL_OP_ATTENTION_PREFILL, Q, K, V, idx, O, LSE, ws, ws_bytes,
+                             hip_stream);
+}
+
+sl_status sl_span_attention_decode(const sl_params* p, const void* Q, const void* K, const void* V,
+                                   const int32_t* idx, void* O, float* LSE, void* ws,
+                                   size_t ws_bytes, void* hip_stream) {
+  return sl::attention_entry(p, SL_OP_ATTENTION_DECODE, Q, K, V, idx, O, LSE, ws, ws_bytes,
+                             hip_stream);
+}
+
+const char* sl_status_string(int status) {
+  switch (status) {
+    case SL_OK: return "SL_OK";
+    case SL_ERR_INVALID_ARG: return "SL_ERR_INVALID_ARG: bad pointer, size, stride or alignment";
+    case SL_ERR_UNSUPPORTED: return "SL_ERR_UNSUPPORTED: outside the compiled envelope (D, topk, dtype, span count)";
+    case SL_ERR_WORKSPACE: return "SL_ERR_WORKSPACE: workspace missing, misaligned or too small";
+    case SL_ERR_LAUNCH: return "SL_ERR_LAUNCH: HIP failed to enqueue a kernel";
+  }
+  return "unknown sl_status";
+}
+
+int sl_version(void) { return 100; }
+
+}  // extern "C"

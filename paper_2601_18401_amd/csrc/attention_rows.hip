@@ -1,0 +1,96 @@
+// Row-stationary prefill span-attention: one wavefront per (head, query row) streams the rows
+// of the selected spans and of the local window (eq. (4) over the de-duplicated union,
+// Algorithm 1) with an online softmax.  Exact and simple; used for fp32 and for shapes the
+// matrix-core path does not cover.
+#include "kernels.h"
+#include "stream_attend.h"
+
+namespace sl {
+
+namespace {
+
+template <typename T, int D>
+__global__ __launch_bounds__(256) void prefill_attention_rows_kernel(
+    const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
+    const int32_t* __restrict__ idx, T* __restrict__ O, float* __restrict__ LSE, int64_t Lq,
+    int64_t q_pos0, int Hq, int G, int S, int topk, float scale_log2e, int64_t qsh, int64_t qst,
+    int64_t kvsh, int64_t kvst) {
+  using RL = RowLayout<T, D>;
+  constexpr int EPL = RL::EPL, LPR = RL::LPR;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int64_t row = (int64_t)blockIdx.x * 4 + wave;
+  if (row >= (int64_t)Hq * Lq) return;
+  const int h = (int)(row / Lq);
+  const int64_t r = row % Lq, i = q_pos0 + r;
+  const int kv = h / G;
+  const int64_t c = i / S;
+  const int lr = lane % LPR;
+  float q2[EPL];
+  {
+    float qf[EPL];
+    Elem<T>::unpack(load16(Q + h * qsh + r * qst + lr * EPL), qf);
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) q2[e] = qf[e] * scale_log2e;
+  }
+  const T* Kb = K + kv * kvsh;
+  const T* Vb = V + kv * kvsh;
+  AttendState<T, D> st;
+  st.init();
+  for (int slot = 0; slot < topk; ++slot) {
+    const int64_t j = idx[row * topk + slot];
+    if (j >= 0 && j < c) attend_range<T, D, 4>(q2, Kb, Vb, kvst, j * S, (j + 1) * S, lane, st);
+  }
+  attend_range<T, D, 4>(q2, Kb, Vb, kvst, c * S, i + 1, lane, st);
+
+  // merge the row groups of the wavefront (lanes with equal lane % LPR hold the same d-slice)
+#pragma unroll
+  for (int off = LPR; off < 64; off <<= 1) {
+    const float mo = __shfl_xor(st.m, off, 64);
+    const float lo = __shfl_xor(st.l, off, 64);
+    const float M = fmaxf(st.m, mo);
+    const float wa = st.m > -INFINITY ? fast_exp2(st.m - M) : 0.f;
+    const float wb = mo > -INFINITY ? fast_exp2(mo - M) : 0.f;
+    st.l = st.l * wa + lo * wb;
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) {
+      const float oo = __shfl_xor(st.o[e], off, 64);
+      st.o[e] = st.o[e] * wa + oo * wb;
+    }
+    st.m = M;
+  }
+  if (lane < LPR) {
+    const float inv = 1.f / st.l;  // the local window always holds the query's own token: l > 0
+    T* op = O + row * D + lr * EPL;
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) Elem<T>::store1(op + e, st.o[e] * inv);
+    if (lane == 0) LSE[row] = (st.m + __log2f(st.l)) * kLn2;
+  }
+}
+
+template <typename T, int D>
+sl_status launch_rows(const Problem& pb, const void* Q, const void* K, const void* V,
+                      const int32_t* idx, void* O, float* LSE, hipStream_t st) {
+  const int64_t rows = (int64_t)pb.Hq * pb.Lq;
+  if (pb.prof_start) (void)hipEventRecord(pb.prof_start, st);
+  hipLaunchKernelGGL((prefill_attention_rows_kernel<T, D>), dim3((unsigned)((rows + 3) / 4)),
+                     dim3(256), 0, st, static_cast<const T*>(Q), static_cast<const T*>(K),
+                     static_cast<const T*>(V), idx, static_cast<T*>(O), LSE, pb.Lq, pb.q_pos0,
+                     pb.Hq, pb.G, pb.S, pb.topk, pb.scale * kLog2e, pb.qsh, pb.qst, pb.kvsh,
+                     pb.kvst);
+  if (pb.prof_stop) (void)hipEventRecord(pb.prof_stop, st);
+  return hipGetLastError() == hipSuccess ? SL_OK : SL_ERR_LAUNCH;
+}
+
+}  // namespace
+
+sl_status prefill_attention_rows(const Problem& pb, const void* Q, const void* K, const void* V,
+                                 const int32_t* idx, void* O, float* LSE, hipStream_t st) {
+  if (pb.dtype == SL_BF16) {
+    if (pb.D == 128) return launch_rows<bf16_t, 128>(pb, Q, K, V, idx, O, LSE, st);
+    return launch_rows<bf16_t, 64>(pb, Q, K, V, idx, O, LSE, st);
+  }
+  if (pb.D == 128) return launch_rows<float, 128>(pb, Q, K, V, idx, O, LSE, st);
+  return launch_rows<float, 64>(pb, Q, K, V, idx, O, LSE, st);
+}
+
+}  // namespace sl

@@ -1,0 +1,226 @@
+// Decode span-attention: split-KV streaming kernel + log-sum-exp reduction.
+//
+// One query row per head against an L-token cache (Section 4.3, decoding path).  The attended
+// set of a head is its <= topk routed spans plus the local window, each a contiguous run of
+// K/V rows, so the step is a pure HBM stream: 2 flops per element read.  Work is cut into
+// (head, slot, chunk) items of CT tokens so that thousands of workgroups are in flight.
+#include "kernels.h"
+#include "stream_attend.h"
+
+namespace sl {
+
+namespace {
+
+constexpr int kDecodeThreads = 256;
+
+// Partial record of one (head, slot, chunk): o[D] (unnormalised, relative to m), m (log2 units), l.
+template <typename T, int D>
+__global__ __launch_bounds__(kDecodeThreads) void decode_split_kernel(
+    const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
+    const int32_t* __restrict__ idx, float* __restrict__ part, int64_t q_pos, int Hq, int Hkv,
+    int S, int topk, int nchunks, int CT, float scale_log2e, int64_t qsh, int64_t kvsh,
+    int64_t kvst, int n_routed_blocks, int local_stride) {
+  using RL = RowLayout<T, D>;
+  constexpr int EPL = RL::EPL, LPR = RL::LPR, RPW = RL::RPW;
+  constexpr int NG = (kDecodeThreads / 64) * RPW;  // row groups per workgroup
+  __shared__ float s_m[NG], s_l[NG];
+  __shared__ float s_o[NG][D];
+
+  const int G = Hq / Hkv;
+  const int64_t c = q_pos / S;
+  int h, slot, ck;
+  int bid = blockIdx.x;
+  if (bid < n_routed_blocks) {
+    ck = bid % nchunks;
+    const int u = bid / nchunks;
+    h = u / topk;
+    slot = u % topk;
+  } else {
+    // Local-window items: the G heads of one kv head read the same rows; their block ids differ
+    // by a multiple of 8 so that they run on the same XCD and share its L2.
+    const int lid = bid - n_routed_blocks;
+    const int hl = lid / local_stride, r = lid % local_stride;
+    if (r >= Hkv * nchunks) return;
+    const int kv = r / nchunks;
+    ck = r % nchunks;
+    h = kv * G + hl;
+    slot = topk;
+  }
+  const int kv = h / G;
+
+  int64_t t0, t1;
+  if (slot < topk) {
+    const int64_t j = idx[(int64_t)h * topk + slot];
+    if (j >= 0 && j < c) {
+      t0 = j * S + (int64_t)ck * CT;
+      t1 = t0 + CT < (j + 1) * S ? t0 + CT : (j + 1) * S;
+    } else {
+      t0 = t1 = 0;
+    }
+  } else {
+    t0 = c * S + (int64_t)ck * CT;
+    t1 = t0 + CT < q_pos + 1 ? t0 + CT : q_pos + 1;
+  }
+
+  float* prec = part + (((int64_t)h * (topk + 1) + slot) * nchunks + ck) * (D + 2);
+  const int tid = threadIdx.x;
+  if (t0 >= t1) {  // empty slot or chunk past the end of the range (uniform over the workgroup)
+    if (tid < D) prec[tid] = 0.f;
+    if (tid == 0) {
+      prec[D] = -INFINITY;
+      prec[D + 1] = 0.f;
+    }
+    return;
+  }
+
+  const int lane = tid & 63, wave = tid >> 6;
+  const int g = lane / LPR, lr = lane % LPR;
+  float q2[EPL];
+  {
+    float qf[EPL];
+    Elem<T>::unpack(load16(Q + (int64_t)h * qsh + lr * EPL), qf);
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) q2[e] = qf[e] * scale_log2e;
+  }
+  const T* Kb = K + (int64_t)kv * kvsh;
+  const T* Vb = V + (int64_t)kv * kvsh;
+
+  // each wave takes a contiguous quarter of the chunk
+  const int per_wave = CT / (kDecodeThreads / 64);
+  int64_t w0 = t0 + (int64_t)wave * per_wave;
+  int64_t w1 = w0 + per_wave < t1 ? w0 + per_wave : t1;
+  AttendState<T, D> st;
+  st.init();
+  attend_range<T, D, 8>(q2, Kb, Vb, kvst, w0, w1, lane, st);
+
+  const int gi = wave * RPW + g;
+#pragma unroll
+  for (int e = 0; e < EPL; ++e) s_o[gi][lr * EPL + e] = st.o[e];
+  if (lr == 0) {
+    s_m[gi] = st.m;
+    s_l[gi] = st.l;
+  }
+  __syncthreads();
+  if (tid < D) {
+    float M = -INFINITY;
+#pragma unroll
+    for (int i = 0; i < NG; ++i) M = fmaxf(M, s_m[i]);
+    float acc = 0.f, lt = 0.f;
+#pragma unroll
+    for (int i = 0; i < NG; ++i) {
+      const float mi = s_m[i];
+      if (mi > -INFINITY) {
+        const float w = fast_exp2(mi - M);
+        acc = fmaf(w, s_o[i][tid], acc);
+        lt = fmaf(w, s_l[i], lt);
+      }
+    }
+    prec[tid] = acc;
+    if (tid == 0) {
+      prec[D] = M;
+      prec[D + 1] = lt;
+    }
+  }
+}
+
+// One workgroup per head merges its (topk + 1) * nchunks partial records.
+template <typename T, int D>
+__global__ __launch_bounds__(256) void decode_reduce_kernel(const float* __restrict__ part,
+                                                            T* __restrict__ O,
+                                                            float* __restrict__ LSE, int nrec) {
+  __shared__ float s_red[4];
+  __shared__ float s_acc[256];
+  const int h = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const float* base = part + (int64_t)h * nrec * (D + 2);
+
+  float M = -INFINITY;
+  for (int p = tid; p < nrec; p += 256) M = fmaxf(M, base[(int64_t)p * (D + 2) + D]);
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) M = fmaxf(M, __shfl_xor(M, off, 64));
+  if (lane == 0) s_red[wave] = M;
+  __syncthreads();
+  M = fmaxf(fmaxf(s_red[0], s_red[1]), fmaxf(s_red[2], s_red[3]));
+  __syncthreads();
+
+  float lt = 0.f;
+  for (int p = tid; p < nrec; p += 256) {
+    const float mp = base[(int64_t)p * (D + 2) + D];
+    if (mp > -INFINITY) lt = fmaf(fast_exp2(mp - M), base[(int64_t)p * (D + 2) + D + 1], lt);
+  }
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) lt += __shfl_xor(lt, off, 64);
+  if (lane == 0) s_red[wave] = lt;
+  __syncthreads();
+  lt = (s_red[0] + s_red[1]) + (s_red[2] + s_red[3]);
+
+  constexpr int SUB = 256 / D;  // record subsets accumulated in parallel
+  const int d = tid % D, sub = tid / D;
+  float acc = 0.f;
+#pragma unroll 4
+  for (int p = sub; p < nrec; p += SUB) {
+    const float mp = base[(int64_t)p * (D + 2) + D];
+    const float w = mp > -INFINITY ? fast_exp2(mp - M) : 0.f;
+    const float ov = base[(int64_t)p * (D + 2) + d];
+    acc = w > 0.f ? fmaf(w, ov, acc) : acc;
+  }
+  s_acc[tid] = acc;
+  __syncthreads();
+  if (tid < D) {
+    float tot = 0.f;
+#pragma unroll
+    for (int s2 = 0; s2 < SUB; ++s2) tot += s_acc[s2 * D + tid];
+    Elem<T>::store1(O + (int64_t)h * D + tid, tot / lt);
+    if (tid == 0) LSE[h] = (M + __log2f(lt)) * kLn2;
+  }
+}
+
+int pick_chunk_tokens(const Problem& pb) {
+  // Aim for a few thousand workgroups so the 256 CUs keep enough loads in flight, without
+  // going below 64 tokens per item.
+  const int64_t units = (int64_t)pb.Hq * (pb.topk + 1);
+  int ct = 512;
+  while (ct > 64 && units * ((pb.S + ct - 1) / ct) < 4096) ct >>= 1;
+  return ct;
+}
+
+template <typename T, int D>
+sl_status launch_decode(const Problem& pb, const void* Q, const void* K, const void* V,
+                        const int32_t* idx, void* O, float* LSE, void* ws, hipStream_t st) {
+  const int CT = pick_chunk_tokens(pb);
+  const int nchunks = (pb.S + CT - 1) / CT;
+  const int n_routed = pb.Hq * pb.topk * nchunks;
+  const int local_stride = (int)align_up((size_t)pb.Hkv * nchunks, 8);
+  const int grid = n_routed + pb.G * local_stride;
+  float* part = static_cast<float*>(ws);
+  if (pb.prof_start) (void)hipEventRecord(pb.prof_start, st);
+  hipLaunchKernelGGL((decode_split_kernel<T, D>), dim3(grid), dim3(kDecodeThreads), 0, st,
+                     static_cast<const T*>(Q), static_cast<const T*>(K), static_cast<const T*>(V),
+                     idx, part, pb.q_pos0, pb.Hq, pb.Hkv, pb.S, pb.topk, nchunks, CT,
+                     pb.scale * kLog2e, pb.qsh, pb.kvsh, pb.kvst, n_routed, local_stride);
+  if (pb.prof_stop) (void)hipEventRecord(pb.prof_stop, st);
+  if (hipGetLastError() != hipSuccess) return SL_ERR_LAUNCH;
+  hipLaunchKernelGGL((decode_reduce_kernel<T, D>), dim3(pb.Hq), dim3(256), 0, st, part,
+                     static_cast<T*>(O), LSE, (pb.topk + 1) * nchunks);
+  if (hipGetLastError() != hipSuccess) return SL_ERR_LAUNCH;
+  return SL_OK;
+}
+
+}  // namespace
+
+size_t decode_attention_ws_bytes(const Problem& pb) {
+  const int CT = pick_chunk_tokens(pb);
+  const int nchunks = (pb.S + CT - 1) / CT;
+  return (size_t)pb.Hq * (pb.topk + 1) * nchunks * (pb.D + 2) * sizeof(float);
+}
+
+sl_status decode_attention(const Problem& pb, const void* Q, const void* K, const void* V,
+                           const int32_t* idx, void* O, float* LSE, void* ws, hipStream_t st) {
+  if (pb.dtype == SL_BF16) {
+    if (pb.D == 128) return launch_decode<bf16_t, 128>(pb, Q, K, V, idx, O, LSE, ws, st);
+    return launch_decode<bf16_t, 64>(pb, Q, K, V, idx, O, LSE, ws, st);
+  }
+  if (pb.D == 128) return launch_decode<float, 128>(pb, Q, K, V, idx, O, LSE, ws, st);
+  return launch_decode<float, 64>(pb, Q, K, V, idx, O, LSE, ws, st);
+}
+
+}  // namespace sl

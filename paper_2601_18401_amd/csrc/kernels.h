@@ -1,0 +1,39 @@
+// Internal launch interface between the C-ABI layer (api.hip) and the kernel translation units.
+#pragma once
+
+#include "sl_common.h"
+
+namespace sl {
+
+// a0: span-key gather
+sl_status span_keys(const Problem& pb, const void* K, void* Ks, hipStream_t st);
+
+// a7: decode span-search (score kernel + select kernel)
+size_t decode_search_ws_bytes(const Problem& pb);
+sl_status decode_search(const Problem& pb, const void* Qs, const void* K, const void* Ks,
+                        int32_t* idx, float* scores, void* ws, hipStream_t st);
+
+// a8 + a9: decode span-attention (split-KV + reduce)
+size_t decode_attention_ws_bytes(const Problem& pb);
+sl_status decode_attention(const Problem& pb, const void* Q, const void* K, const void* V,
+                           const int32_t* idx, void* O, float* LSE, void* ws, hipStream_t st);
+
+// a1 + a2: prefill span-search
+size_t prefill_search_ws_bytes(const Problem& pb);
+sl_status prefill_search(const Problem& pb, const void* Qs, const void* K, const void* Ks,
+                         int32_t* idx, float* scores, void* ws, hipStream_t st);
+
+// a1 + a2, row-stationary form (fp32 and shapes outside the matrix-core path)
+sl_status prefill_search_rows(const Problem& pb, const void* Qs, const void* K, const void* Ks,
+                              int32_t* idx, float* scores, hipStream_t st);
+
+// a4 .. a6, row-stationary form
+sl_status prefill_attention_rows(const Problem& pb, const void* Q, const void* K, const void* V,
+                                 const int32_t* idx, void* O, float* LSE, hipStream_t st);
+
+// a3 .. a6: prefill span-attention
+size_t prefill_attention_ws_bytes(const Problem& pb);
+sl_status prefill_attention(const Problem& pb, const void* Q, const void* K, const void* V,
+                            const int32_t* idx, void* O, float* LSE, void* ws, hipStream_t st);
+
+}  // namespace sl

@@ -1,0 +1,107 @@
+// Shared host/device helpers for the gfx950 kernels of the span-search / span-attention library.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "sl.h"
+
+namespace sl {
+
+// Host-side, validated view of sl_params with defaults resolved.
+struct Problem {
+  int64_t L, Lq, q_pos0;
+  int Hq, Hkv, G, D, S, topk;
+  int dtype;
+  float scale;  // resolved softmax scale
+  int64_t qsh, qst, kvsh, kvst;
+  int64_t n;  // ceil(L / S)
+  hipEvent_t prof_start, prof_stop;
+};
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// ---------------------------------------------------------------- device helpers
+#if defined(__HIPCC__)
+
+typedef uint16_t bf16_t;  // raw bfloat16 storage
+
+__device__ __forceinline__ float bf16_to_f32(bf16_t x) { return __uint_as_float(((uint32_t)x) << 16); }
+
+// round-to-nearest-even fp32 -> bf16 (NaN stays NaN)
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40u);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (bf16_t)(u >> 16);
+}
+
+template <typename T>
+struct Elem;
+template <>
+struct Elem<float> {
+  static constexpr int EPL = 4;  // elements per 16-byte lane load
+  __device__ static __forceinline__ void unpack(const uint4& r, float* f) {
+    f[0] = __uint_as_float(r.x);
+    f[1] = __uint_as_float(r.y);
+    f[2] = __uint_as_float(r.z);
+    f[3] = __uint_as_float(r.w);
+  }
+  __device__ static __forceinline__ float load1(const float* p) { return *p; }
+  __device__ static __forceinline__ void store1(float* p, float v) { *p = v; }
+};
+template <>
+struct Elem<bf16_t> {
+  static constexpr int EPL = 8;
+  __device__ static __forceinline__ void unpack(const uint4& r, float* f) {
+    f[0] = __uint_as_float(r.x << 16);
+    f[1] = __uint_as_float(r.x & 0xffff0000u);
+    f[2] = __uint_as_float(r.y << 16);
+    f[3] = __uint_as_float(r.y & 0xffff0000u);
+    f[4] = __uint_as_float(r.z << 16);
+    f[5] = __uint_as_float(r.z & 0xffff0000u);
+    f[6] = __uint_as_float(r.w << 16);
+    f[7] = __uint_as_float(r.w & 0xffff0000u);
+  }
+  __device__ static __forceinline__ float load1(const bf16_t* p) { return bf16_to_f32(*p); }
+  __device__ static __forceinline__ void store1(bf16_t* p, float v) { *p = f32_to_bf16(v); }
+};
+
+// One row of D elements is covered by LPR lanes, each holding 16 bytes; a wavefront of 64
+// lanes covers RPW rows per load instruction.
+template <typename T, int D>
+struct RowLayout {
+  static constexpr int EPL = Elem<T>::EPL;
+  static constexpr int LPR = D / EPL;
+  static constexpr int RPW = 64 / LPR;
+  static_assert(LPR >= 8 && LPR <= 32, "unsupported row width");
+};
+
+__device__ __forceinline__ uint4 load16(const void* p) { return *reinterpret_cast<const uint4*>(p); }
+
+// DPP lane exchange (no LDS traffic). ctrl: quad_perm 0x00-0xFF, row_mirror 0x140,
+// row_half_mirror 0x141.
+template <int CTRL>
+__device__ __forceinline__ float dpp_f32(float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, true));
+}
+
+// Sum over the LPR consecutive lanes of a row group; every lane of the group gets the total.
+template <int LPR>
+__device__ __forceinline__ float group_sum(float v) {
+  v += dpp_f32<0xB1>(v);   // lane ^ 1
+  v += dpp_f32<0x4E>(v);   // lane ^ 2
+  v += dpp_f32<0x141>(v);  // mirror within 8 lanes: adds the other quad
+  if (LPR >= 16) v += dpp_f32<0x140>(v);  // mirror within 16 lanes: adds the other half-row
+  if (LPR >= 32) v += __shfl_xor(v, 16, 64);
+  return v;
+}
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+#endif  // __HIPCC__
+
+}  // namespace sl

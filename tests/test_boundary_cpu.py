@@ -1,0 +1,126 @@
+"""Host-side checks of the C-ABI boundary that need no GPU: the library loads, exports every
+symbol the header declares, and rejects bad arguments before touching the device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2601_18401_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = ctypes.c_void_p(0x1000)       # non-null, 16-byte aligned, never dereferenced on these paths
+FAKE_WS = ctypes.c_void_p(0x10000)
+
+
+def good(**kw):
+    p = B.SlParams()
+    p.L, p.Lq, p.q_pos0 = 4096, 4096, 0
+    p.Hq, p.Hkv, p.D, p.S, p.topk, p.dtype = 8, 2, 128, 64, 4, B.SL_BF16
+    p.scale = 0.0
+    for k, v in kw.items():
+        setattr(p, k, v)
+    return p
+
+
+def test_library_exports_every_declared_symbol():
+    lib = B.load()
+    header = open(os.path.join(ROOT, "include", "sl.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(sl_[a-z_]+)\s*\(", header))
+    assert declared == set(B.EXPORTS)
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert lib.sl_version() >= 100
+    assert B.status_string(0) == "SL_OK"
+    for s in range(1, 5):
+        assert B.status_string(s).startswith("SL_ERR_")
+
+
+def test_params_struct_matches_header_size():
+    # 3 x int64, 6 x int32, float, int32, 4 x int64, 2 pointers
+    assert ctypes.sizeof(B.SlParams) == 24 + 24 + 8 + 32 + 16
+
+
+BAD = [
+    (dict(L=0), 1), (dict(Lq=0), 1), (dict(q_pos0=-1), 1), (dict(q_pos0=1), 1),
+    (dict(Hq=0), 1), (dict(Hkv=3), 1), (dict(S=0), 1), (dict(topk=-1), 1), (dict(dtype=7), 1),
+    (dict(scale=-1.0), 1), (dict(scale=float("inf")), 1), (dict(scale=float("nan")), 1),
+    (dict(D=96), 2), (dict(topk=B.SL_MAX_TOPK + 1), 2), (dict(Hq=130, Hkv=2), 2),
+    (dict(q_stride_t=64), 1), (dict(kv_stride_t=129), 1), (dict(q_stride_h=4), 1),
+]
+
+
+@pytest.mark.parametrize("kw,status", BAD)
+def test_invalid_params_rejected_before_launch(kw, status):
+    lib = B.load()
+    p = good(**kw)
+    for fn in (lib.sl_span_search_prefill, ):
+        assert fn(ctypes.byref(p), FAKE, FAKE, FAKE, FAKE, None, FAKE_WS, 1 << 40, None) == status
+    assert lib.sl_span_attention_prefill(ctypes.byref(p), FAKE, FAKE, FAKE, FAKE, FAKE, FAKE,
+                                         FAKE_WS, 1 << 40, None) == status
+    assert lib.sl_workspace_bytes(ctypes.byref(p), B.OP_ATTENTION_DECODE) == 0
+
+
+def test_null_and_misaligned_pointers():
+    lib = B.load()
+    p = good()
+    odd = ctypes.c_void_p(0x1004)
+    assert lib.sl_span_search_prefill(None, FAKE, FAKE, FAKE, FAKE, None, FAKE_WS, 1 << 40, None) == 1
+    assert lib.sl_span_search_prefill(ctypes.byref(p), None, FAKE, FAKE, FAKE, None, FAKE_WS, 1 << 40, None) == 1
+    assert lib.sl_span_search_prefill(ctypes.byref(p), FAKE, None, None, FAKE, None, FAKE_WS, 1 << 40, None) == 1
+    assert lib.sl_span_search_prefill(ctypes.byref(p), FAKE, FAKE, FAKE, None, None, FAKE_WS, 1 << 40, None) == 1
+    assert lib.sl_span_search_prefill(ctypes.byref(p), odd, FAKE, FAKE, FAKE, None, FAKE_WS, 1 << 40, None) == 1
+    for pos in range(6):
+        args = [FAKE] * 6
+        args[pos] = None
+        assert lib.sl_span_attention_prefill(ctypes.byref(p), *args, FAKE_WS, 1 << 40, None) == 1
+        args[pos] = odd
+        assert lib.sl_span_attention_prefill(ctypes.byref(p), *args, FAKE_WS, 1 << 40, None) == 1
+    assert lib.sl_span_keys(None, FAKE, FAKE, None) == 1
+    assert lib.sl_span_keys(ctypes.byref(p), None, FAKE, None) == 1
+
+
+def test_decode_requires_single_query_row_and_search_needs_topk():
+    lib = B.load()
+    p = good()
+    assert lib.sl_span_search_decode(ctypes.byref(p), FAKE, FAKE, FAKE, FAKE, None, FAKE_WS, 1 << 40, None) == 1
+    assert lib.sl_span_attention_decode(ctypes.byref(p), FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE_WS, 1 << 40, None) == 1
+    p = good(topk=0)
+    assert lib.sl_span_search_prefill(ctypes.byref(p), FAKE, FAKE, FAKE, FAKE, None, FAKE_WS, 1 << 40, None) == 1
+
+
+def test_workspace_checks():
+    lib = B.load()
+    p = good(Lq=1, q_pos0=4095)
+    need = lib.sl_workspace_bytes(ctypes.byref(p), B.OP_ATTENTION_DECODE)
+    assert need > 0
+    args = [FAKE] * 6
+    assert lib.sl_span_attention_decode(ctypes.byref(p), *args, None, 0, None) == 3
+    assert lib.sl_span_attention_decode(ctypes.byref(p), *args, FAKE_WS, need - 1, None) == 3
+    assert lib.sl_span_attention_decode(ctypes.byref(p), *args, ctypes.c_void_p(0x10010), need, None) == 3
+    need_s = lib.sl_workspace_bytes(ctypes.byref(p), B.OP_SEARCH_DECODE)
+    assert need_s >= p.Hq * (p.L // p.S) * 4
+    assert lib.sl_span_search_decode(ctypes.byref(p), FAKE, FAKE, FAKE, FAKE, None, FAKE_WS, need_s - 1, None) == 3
+
+
+def test_binding_fails_loudly_without_library(monkeypatch, tmp_path):
+    monkeypatch.setattr(B, "_lib", None)
+    monkeypatch.setattr(B, "LIB_PATH", str(tmp_path / "missing.so"))
+    with pytest.raises(RuntimeError, match="no fallback"):
+        B.load()
+
+
+def test_workloads_are_seeded_and_shaped():
+    import torch
+    from paper_2601_18401_amd import workloads as W
+    cfg = W.CONFIGS["C4"].scaled(L=4096, S=64)
+    a = W.generate(cfg)
+    b = W.generate(cfg)
+    assert torch.equal(a["K"], b["K"]) and torch.equal(a["Q"], b["Q"])
+    assert a["Q"].shape == (32, 4096, 128) and a["K"].shape == (4, 4096, 128)
+    assert a["K"].dtype == torch.bfloat16
+    assert len(set(a["needle_spans"].tolist())) == 16
+    d = W.generate(W.CONFIGS["C3"].scaled(L=8192, S=128), n_queries=3)
+    assert d["Q"].shape == (3, 32, 1, 128)
+    assert [W.CONFIGS[c].n_spans for c in ("C1", "C2", "C3", "C4", "C5")] == [64, 256, 1024, 512, 2560]

@@ -1,0 +1,96 @@
+"""GPU parity at the benchmark configurations' full sizes, in the launch configuration the
+benchmark times.  Prefill outputs are compared with the oracle on a seeded sample of rows
+(first rows, span boundaries, last row, rows after planted needles); decode steps are compared
+on every head.  The needle configuration is additionally checked on ALL rows through a
+property that needs no oracle (selected spans must be needles when enough are eligible)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import superlinear as orc
+from paper_2601_18401_amd import binding as B
+from paper_2601_18401_amd import workloads as W
+from tests.test_parity_gpu import DEV, check_attention, check_idx, f64
+
+pytestmark = pytest.mark.gpu
+
+
+def sample_rows(cfg, data, n_random=24, seed=0):
+    rng = np.random.default_rng(seed)
+    S, L = cfg.S, cfg.L
+    pos = {0, 1, S - 1, S, S + 1, 2 * S - 1, 2 * S, L - 1, L - S, L - S - 1, (cfg.topk + 1) * S, cfg.topk * S - 1}
+    pos |= {int(x) for x in rng.integers(0, L, n_random)}
+    if "needle_spans" in data:
+        for j in data["needle_spans"].tolist()[:6]:
+            pos |= {min(L - 1, (j + 1) * S), min(L - 1, (j + 1) * S + 17)}
+    pos = sorted(p for p in pos if 0 <= p < L)
+    heads = sorted({0, cfg.Hq - 1, int(rng.integers(0, cfg.Hq)), int(rng.integers(0, cfg.Hq))})
+    return [(h, r) for h in heads for r in pos]
+
+
+def run_prefill_config(name):
+    cfg = W.CONFIGS[name]
+    data = W.generate(cfg, device=DEV)
+    Q, K, V = data["Q"], data["K"], data["V"]
+    Ks = B.sl_span_keys(K, cfg.S)
+    idx = B.sl_span_search_prefill(data["Qs"], K, Ks, cfg.S, cfg.topk)
+    torch.cuda.synchronize()
+    rows = sample_rows(cfg, data)
+    amb = check_idx(idx, data["Qs"], Ks, cfg.S, cfg.topk, 0, rows)
+    assert amb <= len(rows) // 2
+    # attention on the oracle's indices for the sampled rows (other rows keep the GPU indices)
+    Qn, Kn = f64(data["Qs"][:, [r for _, r in rows]]), f64(Ks)
+    idx_o = idx.clone()
+    G = cfg.Hq // cfg.Hkv
+    for (h, r) in rows:
+        s = orc.search_scores_row(f64(data["Qs"][h, r]), Kn[h // G], r // cfg.S)
+        sel = orc.select_topk(s, cfg.topk)
+        idx_o[h, r] = torch.tensor(sel + [-1] * (cfg.topk - len(sel)), dtype=torch.int32)
+    O, LSE = B.sl_span_attention_prefill(Q, K, V, idx_o, cfg.S)
+    torch.cuda.synchronize()
+    assert torch.isfinite(O.float()).all() and torch.isfinite(LSE).all()
+    check_attention(O, LSE, Q, K, V, idx_o, cfg.S, 0, 0.0, rows)
+    return cfg, data, idx
+
+
+def test_config2_prefill_65k():
+    run_prefill_config("C2")
+
+
+def test_config4_prefill_262k_needles():
+    cfg, data, idx = run_prefill_config("C4")
+    # Property on all 8.39 M rows: with E(i) = number of needle spans below the query's span,
+    # E >= k  ->  every selected span is a needle;  E < k -> all E needles are selected.
+    needles = data["needle_spans"].to(DEV)
+    is_needle = torch.zeros(cfg.n_spans + 1, dtype=torch.bool, device=DEV)
+    is_needle[needles] = True
+    c = (torch.arange(cfg.L, device=DEV) // cfg.S)                      # [L]
+    E = (needles[None, :] < c[:, None]).sum(dim=1)                      # [L]
+    for h in range(cfg.Hq):
+        sel = idx[h].long()                                             # [L, k]
+        valid = sel >= 0
+        hit = is_needle[sel.clamp(min=0)] & valid
+        nh = hit.sum(dim=1)
+        assert torch.equal(nh, torch.minimum(E, torch.tensor(cfg.topk, device=DEV)))
+        assert torch.equal(valid.sum(dim=1), torch.minimum(c, torch.tensor(cfg.topk, device=DEV)))
+
+
+@pytest.mark.parametrize("name", ["C3", "C5"])
+def test_decode_configs_full_cache(name):
+    cfg = W.CONFIGS[name]
+    data = W.generate(cfg, device=DEV, n_queries=2)
+    K, V = data["K"], data["V"]
+    Ks = B.sl_span_keys(K, cfg.S)
+    for qi in range(2):
+        Q = data["Q"][qi]
+        idx = B.sl_span_search_decode(Q, K, Ks, cfg.S, cfg.topk)
+        idx_k = B.sl_span_search_decode(Q, K, None, cfg.S, cfg.topk)
+        torch.cuda.synchronize()
+        assert torch.equal(idx, idx_k)
+        check_idx(idx, Q, Ks, cfg.S, cfg.topk, cfg.L - 1)
+        idx_o = torch.from_numpy(orc.span_search(f64(Q), f64(Ks), cfg.S, cfg.topk, q_pos0=cfg.L - 1)).to(DEV)
+        O, LSE = B.sl_span_attention_decode(Q, K, V, idx_o, cfg.S)
+        torch.cuda.synchronize()
+        check_attention(O, LSE, Q, K, V, idx_o, cfg.S, cfg.L - 1, 0.0)
+    del data, K, V
+    torch.cuda.empty_cache()
