@@ -1,0 +1,292 @@
+#!/usr/bin/env python3
+"""Benchmark of the span-search + span-attention hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--configs C3,C5,...] [--no-cpu-baseline]
+
+A step is one pass of the whole hot path over one batch of synthetic input already resident
+in HBM: prefill = span keys + span-search + span-attention over all L queries; decode = span-search
++ span-attention for one new token against the L-token cache (span keys are cache state).
+The primary workload (the JSON line's `value`) is the 1M-token decode configuration; the other
+four configurations are reported under `all_configs` in the same line.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_HBM = 8.0e12           # B/s, MI355X HBM3E
+PEAK_BF16 = 2.5e15          # flop/s, dense bf16 MFMA
+PEAK_FP32_VALU = 157.3e12   # flop/s, fp32 vector
+N_DECODE_QUERIES = 8        # decode steps rotate over this many independent queries (different span sets)
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+class ProfEvents:
+    """Two HIP events the library records around its dominant kernel (caller-owned)."""
+
+    def __init__(self, torch):
+        self.a = torch.cuda.Event(enable_timing=True)
+        self.b = torch.cuda.Event(enable_timing=True)
+        self.a.record()
+        self.b.record()          # creates the underlying hipEvent_t handles
+        torch.cuda.synchronize()
+
+    def handles(self):
+        return (self.a.cuda_event, self.b.cuda_event)
+
+    def ms(self):
+        self.b.synchronize()
+        return self.a.elapsed_time(self.b)
+
+
+def prefill_flops(cfg):
+    """Algorithmic flops of one prefill step: causal search + attention over selected keys."""
+    L, S, k, D, Hq = cfg.L, cfg.S, cfg.topk, cfg.D, cfg.Hq
+    search = 0
+    attn = 0
+    for c in range(cfg.n_spans):
+        rows = min(S, L - c * S)
+        search += rows * c * 2 * D
+        # keys per row: min(k, c) * S + (i mod S) + 1
+        attn += (rows * min(k, c) * S + rows * (rows + 1) // 2) * 4 * D
+    return Hq * search, Hq * attn
+
+
+def decode_bytes(cfg, idx, q_pos):
+    """Algorithmic HBM bytes of one decode span-attention: distinct (kv head, span) pairs x K and V rows."""
+    G = cfg.Hq // cfg.Hkv
+    c = q_pos // cfg.S
+    esz = 2 if cfg.dtype == "bf16" else 4
+    pairs = set()
+    for h, row in enumerate(idx.reshape(cfg.Hq, -1).tolist()):
+        for j in row:
+            if 0 <= j < c:
+                pairs.add((h // G, j))
+    tokens = len(pairs) * cfg.S + cfg.Hkv * (q_pos - c * cfg.S + 1)
+    return tokens * cfg.D * esz * 2
+
+
+def bench_decode(cfg, steps, warmup, torch, B, W):
+    dev = "cuda"
+    data = W.generate(cfg, device=dev, n_queries=N_DECODE_QUERIES)
+    K, V = data["K"], data["V"]
+    Ks = B.sl_span_keys(K, cfg.S)
+    Qs = [data["Q"][i] for i in range(N_DECODE_QUERIES)]
+    q_pos = cfg.L - 1
+    ws = B.Workspace()
+    outs = [(torch.empty((cfg.Hq, 1, cfg.D), dtype=K.dtype, device=dev),
+             torch.empty((cfg.Hq, 1), dtype=torch.float32, device=dev)) for _ in range(N_DECODE_QUERIES)]
+
+    def step(i, prof=None):
+        q = Qs[i % N_DECODE_QUERIES]
+        idx = B.sl_span_search_decode(q, K, Ks, cfg.S, cfg.topk, ws=ws)
+        B.sl_span_attention_decode(q, K, V, idx, cfg.S, ws=ws, prof=prof, out=outs[i % N_DECODE_QUERIES])
+        return idx
+
+    idxs = [step(i).cpu().numpy() for i in range(N_DECODE_QUERIES)]
+    abytes = [decode_bytes(cfg, ix, q_pos) for ix in idxs]
+    for i in range(warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        step(i)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    # dominant kernel (K/V streaming) timed with HIP events recorded by the library on the same stream
+    ev = ProfEvents(torch)
+    kms, kbytes = [], []
+    nprof = max(16, min(steps, 64))
+    for i in range(nprof):
+        step(i, prof=ev.handles())
+        kms.append(ev.ms())
+        kbytes.append(abytes[i % N_DECODE_QUERIES])
+    kms_avg = sum(kms) / len(kms)
+    achieved = (sum(kbytes) / len(kbytes)) / (kms_avg * 1e-3)
+    res = {
+        "workload": f"{cfg.name} decode L={cfg.L} Hq={cfg.Hq} Hkv={cfg.Hkv} D={cfg.D} S={cfg.S} topk={cfg.topk}+local",
+        "metric": "decode steps/s (span-search + span-attention)", "value": steps / dt, "unit": "steps/s",
+        "ms_per_step": dt / steps * 1e3, "steps": steps, "dtype": cfg.dtype,
+        "roofline": {"bound": "hbm", "kernel": "decode_split_kernel", "achieved": achieved / 1e9, "peak": PEAK_HBM / 1e9,
+                     "unit": "GB/s", "frac": achieved / PEAK_HBM, "traffic": None,
+                     "kernel_ms": kms_avg, "kernel_ms_min": min(kms), "algorithmic_bytes": sum(kbytes) / len(kbytes)},
+    }
+    return res, dict(data=data, Ks=Ks, idx0=idxs[0])
+
+
+def bench_prefill(cfg, steps, warmup, torch, B, W):
+    dev = "cuda"
+    data = W.generate(cfg, device=dev)
+    Q, K, V, Qs = data["Q"], data["K"], data["V"], data["Qs"]
+    ws = B.Workspace()
+    out = (torch.empty((cfg.Hq, cfg.L, cfg.D), dtype=Q.dtype, device=dev),
+           torch.empty((cfg.Hq, cfg.L), dtype=torch.float32, device=dev))
+    Ks = torch.zeros((cfg.Hkv, cfg.n_spans, cfg.D), dtype=K.dtype, device=dev)
+
+    def step(prof_s=None, prof_a=None):
+        B.sl_span_keys(K, cfg.S, out=Ks)
+        idx = B.sl_span_search_prefill(Qs, K, Ks, cfg.S, cfg.topk, ws=ws, prof=prof_s)
+        B.sl_span_attention_prefill(Q, K, V, idx, cfg.S, ws=ws, prof=prof_a, out=out)
+        return idx
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ev_s, ev_a = ProfEvents(torch), ProfEvents(torch)
+    ms_s, ms_a = [], []
+    for _ in range(max(2, min(steps, 10))):
+        step(ev_s.handles(), ev_a.handles())
+        ms_s.append(ev_s.ms())
+        ms_a.append(ev_a.ms())
+    f_search, f_attn = prefill_flops(cfg)
+    ka = sum(ms_a) / len(ms_a)
+    ks = sum(ms_s) / len(ms_s)
+    peak, bound = (PEAK_BF16, "mfma") if cfg.dtype == "bf16" else (PEAK_FP32_VALU, "alu")
+    tflops_attn = f_attn / (ka * 1e-3)
+    res = {
+        "workload": f"{cfg.name} prefill L={cfg.L} Hq={cfg.Hq} Hkv={cfg.Hkv} D={cfg.D} S={cfg.S} topk={cfg.topk}+local",
+        "metric": "prefill tokens/s (span-search + span-attention)", "value": cfg.L * steps / dt, "unit": "tokens/s",
+        "ms_per_step": dt / steps * 1e3, "steps": steps, "dtype": cfg.dtype,
+        "step_frac_of_peak": (f_search + f_attn) / (dt / steps) / peak,
+        "roofline": {"bound": bound, "kernel": "span-attention dominant kernel", "achieved": tflops_attn / 1e12,
+                     "peak": peak / 1e12, "unit": "TFLOP/s", "frac": tflops_attn / peak, "traffic": None,
+                     "kernel_ms": ka, "algorithmic_flops": f_attn,
+                     "search_kernel_ms": ks, "search_algorithmic_flops": f_search},
+    }
+    return res, dict(data=data)
+
+
+def cpu_baseline_decode(cfg, ctx, torch, budget_s=12.0):
+    """The fp64 oracle, as it stands, on whole decode steps (all heads) of the same workload."""
+    import numpy as np
+    from threadpoolctl import threadpool_limits
+    from oracle import superlinear as orc
+
+    class HostKV:
+        def __init__(self, t):
+            self.t = t
+            self.shape = t.shape
+
+        def __getitem__(self, key):
+            kv, sl = key
+            return self.t[kv, sl].float().numpy()
+
+    data, Ks = ctx["data"], ctx["Ks"]
+    Kh, Vh = HostKV(data["K"].cpu()), HostKV(data["V"].cpu())
+    Ksn = Ks.float().cpu().numpy().astype(np.float64)
+    q_pos = cfg.L - 1
+    done, t0 = 0, time.perf_counter()
+    with threadpool_limits(limits=1):
+        while done < N_DECODE_QUERIES and (time.perf_counter() - t0) < budget_s:
+            Qn = data["Q"][done].float().cpu().numpy().astype(np.float64)
+            idx = orc.span_search(Qn, Ksn, cfg.S, cfg.topk, q_pos0=q_pos)
+            orc.span_attention(Qn, Kh, Vh, idx, cfg.S, q_pos0=q_pos)
+            done += 1
+    dt = time.perf_counter() - t0
+    return {"value": done / dt, "unit": "steps/s", "cores": 1, "kind": "oracle",
+            "sample": f"{done} whole decode steps (all {cfg.Hq} heads, search + attention) of {cfg.name}; "
+                      "numpy fp64, BLAS limited to 1 thread, K/V resident in host RAM as bf16"}
+
+
+def cpu_baseline_prefill(cfg, ctx, torch, budget_s=12.0):
+    import numpy as np
+    from threadpoolctl import threadpool_limits
+    from oracle import superlinear as orc
+    data = ctx["data"]
+    Qn = data["Q"].float().cpu().numpy()
+    Kn = data["K"].float().cpu().numpy()
+    Vn = data["V"].float().cpu().numpy()
+    Ksn = orc.span_keys(Kn, cfg.S)
+    G = cfg.Hq // cfg.Hkv
+    rng = np.random.default_rng(0)
+    rows, t0 = 0, time.perf_counter()
+    sc = 1.0 / math.sqrt(cfg.D)
+    with threadpool_limits(limits=1):
+        while (time.perf_counter() - t0) < budget_s:
+            r = int(rng.integers(0, cfg.L))
+            for h in range(cfg.Hq):
+                s = orc.search_scores_row(Qn[h, r], Ksn[h // G], r // cfg.S)
+                sel = orc.select_topk(s, cfg.topk)
+                orc.attention_row(Qn[h, r], Kn, Vn, h // G, r, cfg.S, sel, sc)
+            rows += 1
+    dt = time.perf_counter() - t0
+    return {"value": rows / dt, "unit": "tokens/s", "cores": 1, "kind": "oracle",
+            "sample": f"{rows} seeded random query positions x all {cfg.Hq} heads of {cfg.name} "
+                      "(search + attention per row); numpy fp64, 1 BLAS thread; tokens/s extrapolates rows/s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--configs", default="C3,C5,C4,C2,C1")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2601_18401_amd import binding as B
+    from paper_2601_18401_amd import workloads as W
+    B.load()    # raises if the HIP library is missing: there is no fallback
+    torch.cuda.set_device(0)
+
+    names = [c.strip() for c in args.configs.split(",") if c.strip()]
+    results, primary, cpu = {}, None, None
+    for name in names:
+        cfg = W.CONFIGS[name]
+        t_cfg = time.perf_counter()
+        if cfg.kind == "decode":
+            steps = args.steps
+            res, ctx = bench_decode(cfg, steps, args.warmup, torch, B, W)
+        else:
+            # prefill steps are long: a few of them are enough for a stable mean
+            steps = max(2, min(args.steps, 10 if name != "C1" else 50))
+            res, ctx = bench_prefill(cfg, steps, min(args.warmup, 2), torch, B, W)
+        results[name] = res
+        log(f"[bench] {name}: {res['value']:.4g} {res['unit']}, {res['ms_per_step']:.4f} ms/step, "
+            f"roofline {res['roofline']['frac'] * 100:.1f}% of {res['roofline']['bound']} "
+            f"(kernel {res['roofline']['kernel_ms']:.4f} ms) [{time.perf_counter() - t_cfg:.1f}s]")
+        if name == names[0]:
+            primary = (cfg, res)
+            if not args.no_cpu_baseline:
+                cpu = (cpu_baseline_decode if cfg.kind == "decode" else cpu_baseline_prefill)(cfg, ctx, torch)
+                log(f"[bench] cpu oracle baseline: {cpu['value']:.4g} {cpu['unit']} ({cpu['sample']})")
+        del ctx
+        torch.cuda.empty_cache()
+
+    cfg, res = primary
+    line = {
+        "metric": "span-attn decode steps/s at L=1M" if cfg.name == "C3" else res["metric"],
+        "value": res["value"], "unit": res["unit"], "n_gpus": 1, "steps": res["steps"], "warmup": args.warmup,
+        "ms_per_step": res["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": res["dtype"], "data": "synthetic",
+        "config": {"workload": res["workload"], "decode_queries_rotated": N_DECODE_QUERIES},
+        "roofline": res["roofline"], "cpu_baseline": cpu,
+        "all_configs": results,
+        "context_only": {"paper_whole_model_decode_tokens_per_s_B200": {"1M": 109, "10M": 76}},
+    }
+    print(json.dumps(line), flush=True)
+
+
+if __name__ == "__main__":
+    main()
