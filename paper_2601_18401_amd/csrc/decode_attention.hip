@@ -123,18 +123,40 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_split_kernel(
   }
 }
 
-// One workgroup per head merges its (topk + 1) * nchunks partial records.
+// Merges the (topk + 1) * nchunks partial records of a head.  grid (Hq, D / 32): each workgroup
+// produces 32 output dims; its 256 threads are 8 record subsets x 32 dims.  All record loads of a
+// thread are issued before the first dependent use, so the kernel costs about two memory round
+// trips (statistics, then the partial outputs) instead of one per record.
+constexpr int kReduceDims = 32;
+constexpr int kReduceSub = 256 / kReduceDims;
+constexpr int kReduceBatch = 16;  // records per thread held in registers at a time
+
 template <typename T, int D>
 __global__ __launch_bounds__(256) void decode_reduce_kernel(const float* __restrict__ part,
                                                             T* __restrict__ O,
                                                             float* __restrict__ LSE, int nrec) {
+  extern __shared__ float s_w[];  // nrec weights
   __shared__ float s_red[4];
   __shared__ float s_acc[256];
-  const int h = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int h = blockIdx.x, d0 = blockIdx.y * kReduceDims;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const float* base = part + (int64_t)h * nrec * (D + 2);
+  const int d = tid % kReduceDims, sub = tid / kReduceDims;
+
+  // first batch of partial outputs: independent of the statistics, issued first
+  float ov[kReduceBatch];
+#pragma unroll
+  for (int i = 0; i < kReduceBatch; ++i) {
+    const int p = sub + i * kReduceSub;
+    ov[i] = p < nrec ? base[(int64_t)p * (D + 2) + d0 + d] : 0.f;
+  }
 
   float M = -INFINITY;
-  for (int p = tid; p < nrec; p += 256) M = fmaxf(M, base[(int64_t)p * (D + 2) + D]);
+  for (int p = tid; p < nrec; p += 256) {
+    const float mp = base[(int64_t)p * (D + 2) + D];
+    s_w[p] = mp;
+    M = fmaxf(M, mp);
+  }
 #pragma unroll
   for (int off = 32; off >= 1; off >>= 1) M = fmaxf(M, __shfl_xor(M, off, 64));
   if (lane == 0) s_red[wave] = M;
@@ -144,8 +166,10 @@ __global__ __launch_bounds__(256) void decode_reduce_kernel(const float* __restr
 
   float lt = 0.f;
   for (int p = tid; p < nrec; p += 256) {
-    const float mp = base[(int64_t)p * (D + 2) + D];
-    if (mp > -INFINITY) lt = fmaf(fast_exp2(mp - M), base[(int64_t)p * (D + 2) + D + 1], lt);
+    const float mp = s_w[p];
+    const float w = mp > -INFINITY ? fast_exp2(mp - M) : 0.f;
+    s_w[p] = w;
+    if (w > 0.f) lt = fmaf(w, base[(int64_t)p * (D + 2) + D + 1], lt);
   }
 #pragma unroll
   for (int off = 32; off >= 1; off >>= 1) lt += __shfl_xor(lt, off, 64);
@@ -153,24 +177,38 @@ __global__ __launch_bounds__(256) void decode_reduce_kernel(const float* __restr
   __syncthreads();
   lt = (s_red[0] + s_red[1]) + (s_red[2] + s_red[3]);
 
-  constexpr int SUB = 256 / D;  // record subsets accumulated in parallel
-  const int d = tid % D, sub = tid / D;
   float acc = 0.f;
-#pragma unroll 4
-  for (int p = sub; p < nrec; p += SUB) {
-    const float mp = base[(int64_t)p * (D + 2) + D];
-    const float w = mp > -INFINITY ? fast_exp2(mp - M) : 0.f;
-    const float ov = base[(int64_t)p * (D + 2) + d];
-    acc = w > 0.f ? fmaf(w, ov, acc) : acc;
+#pragma unroll
+  for (int i = 0; i < kReduceBatch; ++i) {
+    const int p = sub + i * kReduceSub;
+    if (p < nrec) {
+      const float w = s_w[p];
+      acc = w > 0.f ? fmaf(w, ov[i], acc) : acc;
+    }
+  }
+  for (int p0 = kReduceBatch * kReduceSub; p0 < nrec; p0 += kReduceBatch * kReduceSub) {
+#pragma unroll
+    for (int i = 0; i < kReduceBatch; ++i) {
+      const int p = p0 + sub + i * kReduceSub;
+      ov[i] = p < nrec ? base[(int64_t)p * (D + 2) + d0 + d] : 0.f;
+    }
+#pragma unroll
+    for (int i = 0; i < kReduceBatch; ++i) {
+      const int p = p0 + sub + i * kReduceSub;
+      if (p < nrec) {
+        const float w = s_w[p];
+        acc = w > 0.f ? fmaf(w, ov[i], acc) : acc;
+      }
+    }
   }
   s_acc[tid] = acc;
   __syncthreads();
-  if (tid < D) {
+  if (tid < kReduceDims) {
     float tot = 0.f;
 #pragma unroll
-    for (int s2 = 0; s2 < SUB; ++s2) tot += s_acc[s2 * D + tid];
-    Elem<T>::store1(O + (int64_t)h * D + tid, tot / lt);
-    if (tid == 0) LSE[h] = (M + __log2f(lt)) * kLn2;
+    for (int s2 = 0; s2 < kReduceSub; ++s2) tot += s_acc[s2 * kReduceDims + tid];
+    Elem<T>::store1(O + (int64_t)h * D + d0 + tid, tot / lt);
+    if (tid == 0 && blockIdx.y == 0) LSE[h] = (M + __log2f(lt)) * kLn2;
   }
 }
 
@@ -199,8 +237,9 @@ sl_status launch_decode(const Problem& pb, const void* Q, const void* K, const v
                      pb.scale * kLog2e, pb.qsh, pb.kvsh, pb.kvst, n_routed, local_stride);
   if (pb.prof_stop) (void)hipEventRecord(pb.prof_stop, st);
   if (hipGetLastError() != hipSuccess) return SL_ERR_LAUNCH;
-  hipLaunchKernelGGL((decode_reduce_kernel<T, D>), dim3(pb.Hq), dim3(256), 0, st, part,
-                     static_cast<T*>(O), LSE, (pb.topk + 1) * nchunks);
+  const int nrec = (pb.topk + 1) * nchunks;
+  hipLaunchKernelGGL((decode_reduce_kernel<T, D>), dim3(pb.Hq, D / kReduceDims), dim3(256),
+                     (size_t)nrec * sizeof(float), st, part, static_cast<T*>(O), LSE, nrec);
   if (hipGetLastError() != hipSuccess) return SL_ERR_LAUNCH;
   return SL_OK;
 }

@@ -1,5 +1,5 @@
 // Span-search kernels that need no matrix cores: the span-key gather, the decode form
-// (score kernel spread over many workgroups + one selecting wavefront per head) and the
+// (one workgroup per head scores its candidates into LDS and selects) and the
 // row-stationary prefill form (one wavefront per query row) used for fp32 and for shapes the
 // MFMA path does not cover.
 //
@@ -32,72 +32,80 @@ __device__ __forceinline__ const T* span_key_ptr(const T* K, const T* Ks, int kv
   return Ks ? Ks + ((int64_t)kv * n + j) * D : K + kv * kvsh + ((j + 1) * S - 1) * kvst;
 }
 
-// ------------------------------------------------------------------ a7: decode scores
-// grid (ceil(c / ROWS), Hkv); each wavefront scores RPW span keys per load for all G heads of
-// the kv head.  The query slices live in LDS as fp32.
+// ------------------------------------------------------------------ a7: decode search
+// One workgroup of 16 wavefronts per query head: the wavefronts score the head's c candidate
+// span keys into LDS (RPW keys per load instruction, 16-byte lanes), then wavefront 0 selects.
+// Heads of one kv group re-read the same keys; they are a few hundred KB and L2-resident.
+constexpr int kDecodeSearchThreads = 1024;
+
 template <typename T, int D>
-__global__ __launch_bounds__(256) void decode_score_kernel(const T* __restrict__ Qs,
-                                                           const T* __restrict__ K,
-                                                           const T* __restrict__ Ks,
-                                                           float* __restrict__ sc_out, int64_t c,
-                                                           int64_t n, int G, int S, int64_t qsh,
-                                                           int64_t kvsh, int64_t kvst) {
+__global__ __launch_bounds__(kDecodeSearchThreads) void decode_search_kernel(
+    const T* __restrict__ Qs, const T* __restrict__ K, const T* __restrict__ Ks,
+    int32_t* __restrict__ idx, float* __restrict__ scores, int64_t c, int64_t n, int G, int S,
+    int topk, int64_t qsh, int64_t kvsh, int64_t kvst) {
   using RL = RowLayout<T, D>;
   constexpr int EPL = RL::EPL, LPR = RL::LPR, RPW = RL::RPW;
-  constexpr int ROWS = 4 * RPW;  // span keys per workgroup
-  extern __shared__ float s_q[];  // [G][D]
-  const int kv = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  for (int e = tid; e < G * D; e += 256)
-    s_q[e] = Elem<T>::load1(Qs + (int64_t)(kv * G + e / D) * qsh + e % D);
-  __syncthreads();
+  // 16 independent 16-byte loads per lane are in flight before the first use: a head's whole
+  // candidate set is covered in one to three memory round trips
+  constexpr int U = 16, NW = kDecodeSearchThreads / 64;
+  extern __shared__ float s_sc[];  // lane-major score array of the selecting wavefront
+  const int h = blockIdx.x, kv = h / G;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int g = lane / LPR, lr = lane % LPR;
-  const int64_t j = (int64_t)blockIdx.x * ROWS + wave * RPW + g;
-  const int64_t jc = j < c ? j : c - 1;
-  float kf[EPL];
-  Elem<T>::unpack(load16(span_key_ptr<T, D>(K, Ks, kv, jc, n, S, kvsh, kvst) + lr * EPL), kf);
-  for (int hl = 0; hl < G; ++hl) {
-    const float* q = s_q + hl * D + lr * EPL;
-    float acc = 0.f;
+  const LaneMajor lm = LaneMajor::make(c);
+  if (wave == 0) select_clear(s_sc, lm, lane);
+  float qf[EPL];
+  Elem<T>::unpack(load16(Qs + (int64_t)h * qsh + lr * EPL), qf);
+  __syncthreads();
+  for (int64_t jb = (int64_t)wave * RPW * U; jb < c; jb += NW * RPW * U) {
+    uint4 kr[U];
 #pragma unroll
-    for (int e = 0; e < EPL; ++e) acc = fmaf(q[e], kf[e], acc);
-    acc = group_sum<LPR>(acc);
-    if (lr == 0 && j < c) sc_out[(int64_t)(kv * G + hl) * n + j] = acc;
+    for (int u = 0; u < U; ++u) {
+      int64_t j = jb + u * RPW + g;
+      j = j < c ? j : c - 1;
+      kr[u] = load16(span_key_ptr<T, D>(K, Ks, kv, j, n, S, kvsh, kvst) + lr * EPL);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      float kf[EPL];
+      Elem<T>::unpack(kr[u], kf);
+      float acc = 0.f;
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) acc = fmaf(qf[e], kf[e], acc);
+      acc = group_sum<LPR>(acc);
+      const int64_t j = jb + u * RPW + g;
+      if (lr == 0 && j < c) s_sc[lm.slot((int)j)] = acc;
+    }
   }
-}
-
-// One wavefront per head: stage the c scores in LDS and select.
-__global__ __launch_bounds__(64) void decode_select_kernel(const float* __restrict__ sc_in,
-                                                           int32_t* __restrict__ idx,
-                                                           float* __restrict__ scores, int64_t c,
-                                                           int64_t n, int topk) {
-  extern __shared__ float s_sc[];
-  const int h = blockIdx.x, lane = threadIdx.x;
-  for (int j = lane; j < c; j += 64) s_sc[j] = sc_in[(int64_t)h * n + j];
-  __builtin_amdgcn_wave_barrier();
-  wave_select_topk(s_sc, (int)c, topk, lane, idx + (int64_t)h * topk,
-                   scores ? scores + (int64_t)h * topk : nullptr);
+  __syncthreads();
+  if (wave == 0)
+    wave_select_topk(s_sc, lm, (int)c, topk, lane, idx + (int64_t)h * topk,
+                     scores ? scores + (int64_t)h * topk : nullptr);
 }
 
 // ------------------------------------------------------------------ a1 + a2: prefill, row-stationary
-// One wavefront per (head, query row); W rows per workgroup; dynamic LDS = W * n floats.
+// One wavefront per (head, query row); W rows per workgroup; dynamic LDS = W lane-major score arrays.
 template <typename T, int D>
 __global__ __launch_bounds__(256) void prefill_search_rows_kernel(
     const T* __restrict__ Qs, const T* __restrict__ K, const T* __restrict__ Ks,
     int32_t* __restrict__ idx, float* __restrict__ scores, int64_t Lq, int64_t q_pos0, int Hq,
-    int G, int S, int topk, int64_t n, int W, int64_t qsh, int64_t qst, int64_t kvsh,
-    int64_t kvst) {
+    int G, int S, int topk, int64_t n, int W, int lds_per_wave, int64_t qsh, int64_t qst,
+    int64_t kvsh, int64_t kvst) {
   using RL = RowLayout<T, D>;
   constexpr int EPL = RL::EPL, LPR = RL::LPR, RPW = RL::RPW;
   extern __shared__ float s_all[];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int64_t row = (int64_t)blockIdx.x * W + wave;
   if (wave >= W || row >= (int64_t)Hq * Lq) return;
-  float* sc = s_all + (int64_t)wave * n;
+  float* sc = s_all + (int64_t)wave * lds_per_wave;
   const int h = (int)(row / Lq);
   const int64_t r = row % Lq, i = q_pos0 + r;
   const int kv = h / G;
   const int64_t c = i / S;
   const int g = lane / LPR, lr = lane % LPR;
+  const LaneMajor lm = LaneMajor::make(c);
+  select_clear(sc, lm, lane);
+  __builtin_amdgcn_wave_barrier();
   float qf[EPL];
   Elem<T>::unpack(load16(Qs + h * qsh + r * qst + lr * EPL), qf);
   constexpr int U = 4;
@@ -118,11 +126,12 @@ __global__ __launch_bounds__(256) void prefill_search_rows_kernel(
       for (int e = 0; e < EPL; ++e) acc = fmaf(qf[e], kf[e], acc);
       acc = group_sum<LPR>(acc);
       const int64_t j = jb + u * RPW + g;
-      if (lr == 0 && j < c) sc[j] = acc;
+      if (lr == 0 && j < c) sc[lm.slot((int)j)] = acc;
     }
   }
   __builtin_amdgcn_wave_barrier();
-  wave_select_topk(sc, (int)c, topk, lane, idx + row * topk, scores ? scores + row * topk : nullptr);
+  wave_select_topk(sc, lm, (int)c, topk, lane, idx + row * topk,
+                   scores ? scores + row * topk : nullptr);
 }
 
 template <typename T, int D>
@@ -139,23 +148,15 @@ sl_status launch_span_keys(const Problem& pb, const void* K, void* Ks, hipStream
 
 template <typename T, int D>
 sl_status launch_decode_search(const Problem& pb, const void* Qs, const void* K, const void* Ks,
-                               int32_t* idx, float* scores, void* ws, hipStream_t st) {
-  using RL = RowLayout<T, D>;
+                               int32_t* idx, float* scores, hipStream_t st) {
   const int64_t c = pb.q_pos0 / pb.S;
-  float* sc = static_cast<float*>(ws);
-  if (c > 0) {
-    constexpr int ROWS = 4 * RL::RPW;
-    dim3 grid((unsigned)((c + ROWS - 1) / ROWS), pb.Hkv);
-    if (pb.prof_start) (void)hipEventRecord(pb.prof_start, st);
-    hipLaunchKernelGGL((decode_score_kernel<T, D>), grid, dim3(256), pb.G * D * sizeof(float), st,
-                       static_cast<const T*>(Qs), static_cast<const T*>(K),
-                       static_cast<const T*>(Ks), sc, c, pb.n, pb.G, pb.S, pb.qsh, pb.kvsh,
-                       pb.kvst);
-    if (pb.prof_stop) (void)hipEventRecord(pb.prof_stop, st);
-    if (hipGetLastError() != hipSuccess) return SL_ERR_LAUNCH;
-  }
-  hipLaunchKernelGGL(decode_select_kernel, dim3(pb.Hq), dim3(64), (size_t)c * sizeof(float), st,
-                     sc, idx, scores, c, pb.n, pb.topk);
+  if (pb.prof_start) (void)hipEventRecord(pb.prof_start, st);
+  hipLaunchKernelGGL((decode_search_kernel<T, D>), dim3(pb.Hq), dim3(kDecodeSearchThreads),
+                     (size_t)LaneMajor::make(c).lds_floats() * sizeof(float), st,
+                     static_cast<const T*>(Qs),
+                     static_cast<const T*>(K), static_cast<const T*>(Ks), idx, scores, c, pb.n,
+                     pb.G, pb.S, pb.topk, pb.qsh, pb.kvsh, pb.kvst);
+  if (pb.prof_stop) (void)hipEventRecord(pb.prof_stop, st);
   return hipGetLastError() == hipSuccess ? SL_OK : SL_ERR_LAUNCH;
 }
 
@@ -163,16 +164,18 @@ template <typename T, int D>
 sl_status launch_prefill_search_rows(const Problem& pb, const void* Qs, const void* K,
                                      const void* Ks, int32_t* idx, float* scores,
                                      hipStream_t st) {
+  // the widest row (last query) sizes the per-wavefront score array
+  const int lds_per_wave = LaneMajor::make((pb.q_pos0 + pb.Lq - 1) / pb.S).lds_floats();
   int W = 4;
-  while (W > 1 && (size_t)W * pb.n * sizeof(float) > 64 * 1024) W >>= 1;
+  while (W > 1 && (size_t)W * lds_per_wave * sizeof(float) > 64 * 1024) W >>= 1;
   const int64_t rows = (int64_t)pb.Hq * pb.Lq;
   const int64_t grid = (rows + W - 1) / W;
   if (pb.prof_start) (void)hipEventRecord(pb.prof_start, st);
   hipLaunchKernelGGL((prefill_search_rows_kernel<T, D>), dim3((unsigned)grid), dim3(256),
-                     (size_t)W * pb.n * sizeof(float), st, static_cast<const T*>(Qs),
+                     (size_t)W * lds_per_wave * sizeof(float), st, static_cast<const T*>(Qs),
                      static_cast<const T*>(K), static_cast<const T*>(Ks), idx, scores, pb.Lq,
-                     pb.q_pos0, pb.Hq, pb.G, pb.S, pb.topk, pb.n, W, pb.qsh, pb.qst, pb.kvsh,
-                     pb.kvst);
+                     pb.q_pos0, pb.Hq, pb.G, pb.S, pb.topk, pb.n, W, lds_per_wave, pb.qsh, pb.qst,
+                     pb.kvsh, pb.kvst);
   if (pb.prof_stop) (void)hipEventRecord(pb.prof_stop, st);
   return hipGetLastError() == hipSuccess ? SL_OK : SL_ERR_LAUNCH;
 }
@@ -190,18 +193,18 @@ sl_status launch_prefill_search_rows(const Problem& pb, const void* Qs, const vo
 }  // namespace
 
 // The selecting wavefront keeps one head's (decode) or one row's (prefill) scores in LDS.
-constexpr int64_t kMaxSpansLds = 16384;
+constexpr int64_t kMaxSpansLds = 12288;
 
 sl_status span_keys(const Problem& pb, const void* K, void* Ks, hipStream_t st) {
   SL_DISPATCH(launch_span_keys, pb, K, Ks, st);
 }
 
-size_t decode_search_ws_bytes(const Problem& pb) { return (size_t)pb.Hq * pb.n * sizeof(float); }
+size_t decode_search_ws_bytes(const Problem&) { return 0; }
 
 sl_status decode_search(const Problem& pb, const void* Qs, const void* K, const void* Ks,
-                        int32_t* idx, float* scores, void* ws, hipStream_t st) {
+                        int32_t* idx, float* scores, void* /*ws*/, hipStream_t st) {
   if (pb.n > kMaxSpansLds) return SL_ERR_UNSUPPORTED;
-  SL_DISPATCH(launch_decode_search, pb, Qs, K, Ks, idx, scores, ws, st);
+  SL_DISPATCH(launch_decode_search, pb, Qs, K, Ks, idx, scores, st);
 }
 
 sl_status prefill_search_rows(const Problem& pb, const void* Qs, const void* K, const void* Ks,
