@@ -127,8 +127,8 @@ sl_status sl_span_search_decode(const sl_params* p, const void* Qs, const void* 
  * the window-only branch when nothing is selected).  For each (h, r): one softmax over
  * J = union of spans idx[h][r][*] and the local window [c*S, i], logits scale * <Q, K_t>.
  *   idx    in: span indices as produced by span-search.  Entries < 0 or >= c are empty slots
- *          (so arbitrary garbage cannot cause an out-of-range read); a span listed twice in a
- *          row is counted twice (caller error).
+ *          (so arbitrary garbage cannot cause an out-of-range read).  A row must not list a
+ *          span twice: the result for such a row is unspecified (still memory-safe).
  *   O      out: [Hq][Lq][D] in the input dtype.
  *   LSE    out: natural-log sum over J of exp(logit), fp32. */
 sl_status sl_span_attention_prefill(const sl_params* p, const void* Q, const void* K, const void* V,

@@ -31,6 +31,12 @@ sl_status prefill_search_rows(const Problem& pb, const void* Qs, const void* K, 
 sl_status prefill_attention_rows(const Problem& pb, const void* Q, const void* K, const void* V,
                                  const int32_t* idx, void* O, float* LSE, hipStream_t st);
 
+// a3 .. a6 on the matrix cores (bf16, D = 128, S % 64 == 0)
+bool prefill_attention_mfma_supported(const Problem& pb);
+size_t prefill_attention_mfma_ws_bytes(const Problem& pb);
+sl_status prefill_attention_mfma(const Problem& pb, const void* Q, const void* K, const void* V,
+                                 const int32_t* idx, void* O, float* LSE, void* ws, hipStream_t st);
+
 // a3 .. a6: prefill span-attention
 size_t prefill_attention_ws_bytes(const Problem& pb);
 sl_status prefill_attention(const Problem& pb, const void* Q, const void* K, const void* V,
