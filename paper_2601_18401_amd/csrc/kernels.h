@@ -31,6 +31,11 @@ sl_status prefill_search_rows(const Problem& pb, const void* Qs, const void* K, 
 sl_status prefill_attention_rows(const Problem& pb, const void* Q, const void* K, const void* V,
                                  const int32_t* idx, void* O, float* LSE, hipStream_t st);
 
+// a1 + a2 on the matrix cores (bf16, D = 128)
+bool prefill_search_mfma_supported(const Problem& pb);
+sl_status prefill_search_mfma(const Problem& pb, const void* Qs, const void* K, const void* Ks,
+                              int32_t* idx, float* scores, hipStream_t st);
+
 // a3 .. a6 on the matrix cores (bf16, D = 128, S % 64 == 0)
 bool prefill_attention_mfma_supported(const Problem& pb);
 size_t prefill_attention_mfma_ws_bytes(const Problem& pb);

@@ -8,6 +8,7 @@ size_t prefill_search_ws_bytes(const Problem&) { return 0; }
 
 sl_status prefill_search(const Problem& pb, const void* Qs, const void* K, const void* Ks,
                          int32_t* idx, float* scores, void* /*ws*/, hipStream_t st) {
+  if (prefill_search_mfma_supported(pb)) return prefill_search_mfma(pb, Qs, K, Ks, idx, scores, st);
   return prefill_search_rows(pb, Qs, K, Ks, idx, scores, st);
 }
 

@@ -12,8 +12,9 @@
 //                                   softmax, MFMA QK^T and PV; writes a normalised partial
 //                                   (o, lse) per (row, slot)
 //   span_flash<true>                the local window [c*S, i]: regular 128-row tiles of one
-//                                   head with the causal mask, then the log-sum-exp merge with
-//                                   the row's routed partials; writes O and LSE
+//                                   head with the causal mask; writes the row's last partial
+//   merge_partials                  streaming log-sum-exp merge of the <= topk + 1 partials of
+//                                   every row; writes O and LSE
 //
 // MFMA formulation.  Both products are computed transposed so that a lane owns a query column:
 //   S^T[kv][q] = K[kv][:] . Q[q][:]      A = K tile (LDS), B = Q rows (registers)
@@ -266,7 +267,7 @@ __global__ __launch_bounds__(kFlashThreads, 2) void span_flash_kernel(const Flas
       if (it < i1) {
         const int32_t* row = a.idx + ((int64_t)h * a.Lq + r) * a.topk;
         for (int s = a.topk - 1; s >= 0; --s)  // first slot that lists the span
-          if (row[s] == j) out = ((int64_t)h * a.Lq + r) * a.topk + s;
+          if (row[s] == j) out = ((int64_t)h * a.Lq + r) * (a.topk + 1) + s;
       }
       sm.row_q[tid] = qoff;
       sm.row_out[tid] = out;
@@ -283,7 +284,7 @@ __global__ __launch_bounds__(kFlashThreads, 2) void span_flash_kernel(const Flas
       const int64_t r = r0 + tid;
       const int64_t rc = r < a.Lq ? r : a.Lq - 1;
       sm.row_q[tid] = (int)(h * a.qsh + rc * a.qst);
-      sm.row_out[tid] = r < a.Lq ? (int64_t)h * a.Lq + r : -1;
+      sm.row_out[tid] = r < a.Lq ? ((int64_t)h * a.Lq + r) * (a.topk + 1) + a.topk : -1;
     }
     const int64_t i_first = a.q_pos0 + r0;
     const int64_t i_last = min(a.q_pos0 + r0 + TM - 1, a.q_pos0 + a.Lq - 1);
@@ -420,52 +421,71 @@ __global__ __launch_bounds__(kFlashThreads, 2) void span_flash_kernel(const Flas
     const int64_t out = sm.row_out[row];
     if (out < 0) continue;
     const uint4 mine = *reinterpret_cast<const uint4*>(&sm.o[row * OSTR + piece * 8]);
-    if (!LOCAL) {
-      *reinterpret_cast<uint4*>(a.part_o + out * HD + piece * 8) = mine;
-      if (piece == 0) a.part_lse[out] = sm.row_lse[row];
-    } else {
-      // merge the local window with the row's routed partials (log-sum-exp weights)
-      const int64_t r = out - (int64_t)h_local * a.Lq;
-      const int64_t c = (a.q_pos0 + r) / a.S;
-      const float lse_loc = sm.row_lse[row];
-      // a slot takes part if its span is a candidate and no earlier slot lists the same span
-      // (only the first listing of a span has a partial)
-      const int32_t* irow = a.idx + out * a.topk;
-      unsigned live = 0;
-      float M = lse_loc;
-      for (int s2 = 0; s2 < a.topk; ++s2) {
-        const int j = irow[s2];
-        bool ok = j >= 0 && j < c;
-        for (int s3 = 0; s3 < s2; ++s3) ok = ok && irow[s3] != j;
-        if (ok) {
-          live |= 1u << s2;
-          M = fmaxf(M, a.part_lse[out * a.topk + s2]);
-        }
-      }
-      float acc[8], f[8];
-      float wsum = __expf(lse_loc - M);
-      Elem<bf16_t>::unpack(mine, f);
-#pragma unroll
-      for (int e = 0; e < 8; ++e) acc[e] = wsum * f[e];
-      for (int s2 = 0; s2 < a.topk; ++s2) {
-        if (live & (1u << s2)) {
-          const float w = __expf(a.part_lse[out * a.topk + s2] - M);
-          wsum += w;
-          Elem<bf16_t>::unpack(load16(a.part_o + (out * a.topk + s2) * HD + piece * 8), f);
-#pragma unroll
-          for (int e = 0; e < 8; ++e) acc[e] = fmaf(w, f[e], acc[e]);
-        }
-      }
-      const float winv = 1.f / wsum;
-      uint4 res;
-      res.x = (uint32_t)f32_to_bf16(acc[0] * winv) | ((uint32_t)f32_to_bf16(acc[1] * winv) << 16);
-      res.y = (uint32_t)f32_to_bf16(acc[2] * winv) | ((uint32_t)f32_to_bf16(acc[3] * winv) << 16);
-      res.z = (uint32_t)f32_to_bf16(acc[4] * winv) | ((uint32_t)f32_to_bf16(acc[5] * winv) << 16);
-      res.w = (uint32_t)f32_to_bf16(acc[6] * winv) | ((uint32_t)f32_to_bf16(acc[7] * winv) << 16);
-      *reinterpret_cast<uint4*>(a.O + out * HD + piece * 8) = res;
-      if (piece == 0) a.LSE[out] = M + __logf(wsum);
-    }
+    *reinterpret_cast<uint4*>(a.part_o + out * HD + piece * 8) = mine;
+    if (piece == 0) a.part_lse[out] = sm.row_lse[row];
   }
+}
+
+// ------------------------------------------------------------------ merge
+// Log-sum-exp merge of a row's partials: up to topk routed slots plus the local window (slot
+// topk).  16 lanes per row, 16 bytes per lane; every load of a lane is issued before the first
+// dependent use, so the kernel streams at HBM rate.
+template <int KMAX>
+__global__ __launch_bounds__(256) void merge_partials_kernel(
+    const int32_t* __restrict__ idx, const bf16_t* __restrict__ part_o,
+    const float* __restrict__ part_lse, bf16_t* __restrict__ O, float* __restrict__ LSE,
+    int64_t rows, int64_t Lq, int64_t q_pos0, int S, int topk) {
+  const int64_t row = (int64_t)blockIdx.x * 16 + (threadIdx.x >> 4);
+  const int piece = threadIdx.x & 15;
+  if (row >= rows) return;
+  const int64_t r = row % Lq;
+  const int c = (int)((q_pos0 + r) / S);
+  const int nslot = topk + 1;
+  const int32_t* irow = idx + row * topk;
+  const float* lrow = part_lse + row * nslot;
+  const bf16_t* orow = part_o + row * nslot * HD + piece * 8;
+
+  int js[KMAX];
+  float ls[KMAX + 1];
+  uint4 ov[KMAX + 1];
+#pragma unroll
+  for (int s = 0; s < KMAX; ++s) js[s] = s < topk ? irow[s] : -1;
+#pragma unroll
+  for (int s = 0; s < KMAX; ++s) {
+    // a slot takes part if its span is a candidate and no earlier slot lists the same span
+    bool ok = js[s] >= 0 && js[s] < c;
+#pragma unroll
+    for (int u = 0; u < s; ++u) ok = ok && js[u] != js[s];
+    ls[s] = ok ? lrow[s] : -INFINITY;
+    ov[s] = ok ? load16(orow + (int64_t)s * HD) : make_uint4(0, 0, 0, 0);
+  }
+  ls[KMAX] = lrow[topk];
+  ov[KMAX] = load16(orow + (int64_t)topk * HD);
+
+  float M = ls[KMAX];
+#pragma unroll
+  for (int s = 0; s < KMAX; ++s) M = fmaxf(M, ls[s]);
+  float acc[8], f[8];
+  float wsum = __expf(ls[KMAX] - M);
+  Elem<bf16_t>::unpack(ov[KMAX], f);
+#pragma unroll
+  for (int e = 0; e < 8; ++e) acc[e] = wsum * f[e];
+#pragma unroll
+  for (int s = 0; s < KMAX; ++s) {
+    const float w = ls[s] > -INFINITY ? __expf(ls[s] - M) : 0.f;
+    wsum += w;
+    Elem<bf16_t>::unpack(ov[s], f);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[e] = fmaf(w, f[e], acc[e]);
+  }
+  const float winv = 1.f / wsum;
+  uint4 res;
+  res.x = (uint32_t)f32_to_bf16(acc[0] * winv) | ((uint32_t)f32_to_bf16(acc[1] * winv) << 16);
+  res.y = (uint32_t)f32_to_bf16(acc[2] * winv) | ((uint32_t)f32_to_bf16(acc[3] * winv) << 16);
+  res.z = (uint32_t)f32_to_bf16(acc[4] * winv) | ((uint32_t)f32_to_bf16(acc[5] * winv) << 16);
+  res.w = (uint32_t)f32_to_bf16(acc[6] * winv) | ((uint32_t)f32_to_bf16(acc[7] * winv) << 16);
+  *reinterpret_cast<uint4*>(O + row * HD + piece * 8) = res;
+  if (piece == 0) LSE[row] = M + __logf(wsum);
 }
 
 // ------------------------------------------------------------------ workspace carving
@@ -495,8 +515,9 @@ MfmaWs carve(const Problem& pb) {
   w.cursor = take((size_t)w.B * sizeof(int));
   w.tile_bucket = take((size_t)w.max_tiles * sizeof(int));
   w.items = take((size_t)w.max_items * sizeof(int));
-  w.part_lse = take((size_t)w.max_items * sizeof(float));
-  w.part_o = take((size_t)w.max_items * HD * sizeof(bf16_t));
+  const size_t nparts = (size_t)pb.Hq * pb.Lq * (pb.topk + 1);  // routed slots + the local window
+  w.part_lse = take(nparts * sizeof(float));
+  w.part_o = take(nparts * HD * sizeof(bf16_t));
   w.total = off;
   return w;
 }
@@ -506,7 +527,7 @@ MfmaWs carve(const Problem& pb) {
 bool prefill_attention_mfma_supported(const Problem& pb) {
   return pb.dtype == SL_BF16 && pb.D == HD && pb.S % TN == 0 && pb.n <= 4096 &&
          (int64_t)pb.G * pb.Lq < ((int64_t)1 << 31) &&
-         (int64_t)pb.Hq * pb.Lq * pb.topk < ((int64_t)1 << 31) &&
+         (int64_t)pb.Hq * pb.Lq * (pb.topk + 1) < ((int64_t)1 << 31) &&
          // row_q holds 32-bit element offsets into Q
          (int64_t)pb.Hq * pb.qsh + pb.Lq * pb.qst < ((int64_t)1 << 31);
 }
@@ -579,6 +600,16 @@ sl_status prefill_attention_mfma(const Problem& pb, const void* Q, const void* K
   const int tiles_per_head = (int)((pb.Lq + TM - 1) / TM);
   hipLaunchKernelGGL(span_flash_kernel<true>, dim3(pb.Hq * tiles_per_head), dim3(kFlashThreads), 0,
                      st, a);
+  const int64_t rows = (int64_t)pb.Hq * pb.Lq;
+  const dim3 mgrid((unsigned)((rows + 15) / 16));
+#define SL_MERGE(KM)                                                                             \
+  hipLaunchKernelGGL(merge_partials_kernel<KM>, mgrid, dim3(256), 0, st, idx, part_o, part_lse,  \
+                     a.O, LSE, rows, pb.Lq, pb.q_pos0, pb.S, pb.topk)
+  if (pb.topk == 0) SL_MERGE(1);
+  else if (pb.topk <= 8) SL_MERGE(8);
+  else if (pb.topk <= 16) SL_MERGE(16);
+  else SL_MERGE(32);
+#undef SL_MERGE
   return hipGetLastError() == hipSuccess ? SL_OK : SL_ERR_LAUNCH;
 }
 
