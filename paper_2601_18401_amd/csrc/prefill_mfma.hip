@@ -7,11 +7,11 @@
 //
 //   bucket_count / bucket_scan / bucket_tiles / bucket_fill   invert idx into per-(kv, span)
 //                                   lists of query rows (integer work, LDS histograms)
-//   span_flash<false>               one workgroup per (bucket, 128-row tile): gathered Q rows
-//                                   against the span's K/V tiles staged through LDS, flash
-//                                   softmax, MFMA QK^T and PV; writes a normalised partial
-//                                   (o, lse) per (row, slot)
-//   span_flash<true>                the local window [c*S, i]: regular 128-row tiles of one
+//   span_flash_routed               persistent workgroups walk the (bucket, 128-row tile) list:
+//                                   gathered Q rows against the span's K/V tiles staged through
+//                                   LDS, flash softmax, MFMA QK^T and PV; writes a normalised
+//                                   partial (o, lse) per (row, slot)
+//   span_flash_local                the local window [c*S, i]: regular 128-row tiles of one
 //                                   head with the causal mask; writes the row's last partial
 //   merge_partials                  streaming log-sum-exp merge of the <= topk + 1 partials of
 //                                   every row; writes O and LSE
@@ -37,24 +37,31 @@ typedef float f32x8 __attribute__((ext_vector_type(8)));
 constexpr int TM = 128;            // query rows per workgroup: 4 wavefronts x 32 columns
 constexpr int TN = 64;             // kv positions per staged tile
 constexpr int HD = 128;            // head dimension of this path
-constexpr int KSTR = HD + 8;       // LDS row stride of the K tile, bf16 elements (272 B: conflict-free b128 reads)
-constexpr int VSTR = TN + 8;       // LDS row stride of the V^T tile (144 B)
 constexpr int OSTR = HD + 8;       // LDS row stride of the output staging tile
 constexpr int kFlashThreads = 256;
 constexpr int kBucketRows = 1024;  // query rows of one head per bucketing workgroup
 
+// LDS of the flash kernel.  Main loop: two stages of (K tile, V^T tile), filled by direct
+// global->LDS loads (16 bytes per lane, a wavefront instruction fills 1 KB contiguously), rows
+// unpadded with an XOR swizzle of the 16-byte pieces so that the MFMA operand reads of 16
+// consecutive lanes hit 16 distinct bank groups.  Epilogue: the same memory holds the output
+// tile [row][d] and the per-row output indices.
 struct __align__(16) FlashSmem {
   union {
     struct {
-      bf16_t k[TN * KSTR];   // 17408 B
-      bf16_t vt[HD * VSTR];  // 18432 B
+      bf16_t k[2][TN * HD];   // 2 x 16 KB, row = 16 pieces of 16 B, piece p of row r at p ^ (r & 15)
+      bf16_t vt[2][HD * TN];  // 2 x 16 KB, row = 8 pieces, piece p of row d at p ^ ((d >> 1) & 7)
     } kv;
-    bf16_t o[TM * OSTR];     // 34816 B, epilogue only
+    struct {
+      bf16_t o[TM * OSTR];    // 34816 B
+      int64_t row_out[TM];
+      float row_lse[TM];
+    } ep;
   };
-  int row_q[TM];             // element offset of the row's Q vector
-  int64_t row_out[TM];       // partial index (routed) or output row index (local); -1 = no row
-  float row_lse[TM];
 };
+
+#define SL_LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
+#define SL_GLOBAL_PTR(p) ((const __attribute__((address_space(1))) void*)(p))
 
 __device__ __forceinline__ float pair_max(float x) {
   // lanes l and l^32 hold the two halves of a query column
@@ -147,7 +154,8 @@ __global__ __launch_bounds__(256) void bucket_kernel(const int32_t* __restrict__
       const int32_t* row = idx + ((int64_t)h * Lq + r) * topk;
       for (int s = 0; s < topk; ++s) {
         const int j = row[s];
-        if (j >= 0 && j < c) items[s_base[j] + atomicAdd(&s_hist[j], 1)] = (int)(hl * Lq + r);
+        if (j >= 0 && j < c)
+          items[s_base[j] + atomicAdd(&s_hist[j], 1)] = (int)(((hl * Lq + r) << 5) | s);
       }
     }
   }
@@ -195,12 +203,18 @@ __global__ __launch_bounds__(1024) void bucket_scan_kernel(const int* __restrict
   }
 }
 
-// One workgroup per bucket writes the bucket id of each of its tiles.
+// One workgroup per bucket writes the record of each of its tiles:
+// {bucket, first item, number of items (1..TM), unused}.
 __global__ __launch_bounds__(256) void bucket_tiles_kernel(const int* __restrict__ tile_off,
-                                                           int* __restrict__ tile_bucket) {
+                                                           const int* __restrict__ item_off,
+                                                           int4* __restrict__ tile_info) {
   const int b = blockIdx.x;
   const int t0 = tile_off[b], t1 = tile_off[b + 1];
-  for (int t = t0 + threadIdx.x; t < t1; t += 256) tile_bucket[t] = b;
+  const int i0 = item_off[b], i1 = item_off[b + 1];
+  for (int t = t0 + threadIdx.x; t < t1; t += 256) {
+    const int first = i0 + (t - t0) * TM;
+    tile_info[t] = make_int4(b, first, min(TM, i1 - first), 0);
+  }
 }
 
 // ------------------------------------------------------------------ flash tile
@@ -212,7 +226,7 @@ struct FlashArgs {
   // routed
   const int* item_off;
   const int* tile_off;
-  const int* tile_bucket;
+  const int4* tile_info;
   const int* items;
   bf16_t* part_o;
   float* part_lse;
@@ -230,80 +244,66 @@ __device__ __forceinline__ int perm_row(int rho) {
   return (rho & 0x13) | ((rho & 4) << 1) | ((rho & 8) >> 1);
 }
 
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+// What one lane knows about its query column in the current tile.
+struct ColInfo {
+  int64_t q_off;    // element offset of the Q vector
+  int64_t row_out;  // partial record index, -1 = no row
+  int64_t i_q, lo_q;  // LOCAL: query position and start of its window
+};
+
+// One 128-row tile against the kv range [kv_begin, kv_end) (a multiple of TN long) of kv head
+// `kv`.  All 256 threads call; LDS is free on entry and free again on return.
 template <bool LOCAL>
-__global__ __launch_bounds__(kFlashThreads, 2) void span_flash_kernel(const FlashArgs a) {
-  __shared__ FlashSmem sm;
+__device__ __forceinline__ void flash_tile(const FlashArgs& a, FlashSmem& sm, int kv,
+                                           int64_t kv_begin, int64_t kv_end, const ColInfo& ci) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int qc = lane & 31, hf = lane >> 5;
   const int qrow = wave * 32 + qc;
+  const bf16_t* Kb = a.K + (int64_t)kv * a.kvsh;
+  const bf16_t* Vtb = a.Vt + (int64_t)kv * HD * a.Lp;
 
-  int kv;
-  int64_t kv_begin, kv_end;  // staged kv range [kv_begin, kv_end), multiple of TN long
-  int h_local = 0;
-  int64_t r0 = 0;
-  if (!LOCAL) {
-    // XCD-aware block -> tile map: blocks b, b+8, b+16, ... run on one XCD and take consecutive
-    // tiles, so the tiles of a bucket share that XCD's L2 copy of the span.
-    const int T = a.tile_off[a.Hq / a.G * a.n];
-    const int per = (T + 7) / 8;
-    const int bx = blockIdx.x;
-    if (bx / 8 >= per) return;
-    const int t = (bx % 8) * per + bx / 8;
-    if (t >= T) return;
-    const int b = a.tile_bucket[t];
-    kv = b / a.n;
-    const int j = b % a.n;
-    const int i0 = a.item_off[b] + (t - a.tile_off[b]) * TM;
-    const int i1 = a.item_off[b + 1];
-    if (tid < TM) {
-      const int it = i0 + tid;
-      int64_t out = -1;
-      int qoff = 0;
-      const int id = a.items[it < i1 ? it : i1 - 1];
-      const int hl = id / (int)a.Lq;
-      const int64_t r = id - (int64_t)hl * a.Lq;
-      const int h = kv * a.G + hl;
-      qoff = (int)(h * a.qsh + r * a.qst);
-      if (it < i1) {
-        const int32_t* row = a.idx + ((int64_t)h * a.Lq + r) * a.topk;
-        for (int s = a.topk - 1; s >= 0; --s)  // first slot that lists the span
-          if (row[s] == j) out = ((int64_t)h * a.Lq + r) * (a.topk + 1) + s;
-      }
-      sm.row_q[tid] = qoff;
-      sm.row_out[tid] = out;
-    }
-    kv_begin = (int64_t)j * a.S;
-    kv_end = kv_begin + a.S;
-  } else {
-    const int tiles_per_head = (int)((a.Lq + TM - 1) / TM);
-    const int h = blockIdx.x / tiles_per_head;
-    r0 = (int64_t)(blockIdx.x % tiles_per_head) * TM;
-    kv = h / a.G;
-    h_local = h;
-    if (tid < TM) {
-      const int64_t r = r0 + tid;
-      const int64_t rc = r < a.Lq ? r : a.Lq - 1;
-      sm.row_q[tid] = (int)(h * a.qsh + rc * a.qst);
-      sm.row_out[tid] = r < a.Lq ? ((int64_t)h * a.Lq + r) * (a.topk + 1) + a.topk : -1;
-    }
-    const int64_t i_first = a.q_pos0 + r0;
-    const int64_t i_last = min(a.q_pos0 + r0 + TM - 1, a.q_pos0 + a.Lq - 1);
-    kv_begin = (i_first / a.S) * a.S;
-    kv_end = kv_begin + ((i_last - kv_begin) / TN + 1) * TN;
+  // Direct global -> LDS staging of one (K, V^T) tile pair: wavefront w fills K blocks 4w..4w+3
+  // (4 rows each) and V^T blocks 4w..4w+3 (8 rows each); lane L of a block lands at byte 16*L.
+  // Per-lane byte offsets are loop-invariant 32-bit values; the tile position goes into the
+  // wave-uniform base pointer.
+  uint32_t koff[4], voff[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int blk = wave * 4 + i;
+    const int row = blk * 4 + (lane >> 4), pc = lane & 15, gp = pc ^ (row & 15);
+    koff[i] = (uint32_t)((row * a.kvst + gp * 8) * sizeof(bf16_t));
+    const int d = blk * 8 + (lane >> 3), pv = lane & 7, gv = pv ^ ((d >> 1) & 7);
+    voff[i] = (uint32_t)((d * a.Lp + gv * 8) * sizeof(bf16_t));
   }
-  __syncthreads();
+  auto stage = [&](int64_t t0, int buf) {
+    const char* kbase = reinterpret_cast<const char*>(Kb + t0 * a.kvst);
+    const char* vbase = reinterpret_cast<const char*>(Vtb + t0);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      uint32_t off = koff[i];
+      if (LOCAL) {  // rows past the end of the sequence re-read the last row (masked later)
+        const int row = (wave * 4 + i) * 4 + (lane >> 4);
+        if (t0 + row >= a.L) off -= (uint32_t)((t0 + row - (a.L - 1)) * a.kvst * sizeof(bf16_t));
+      }
+      __builtin_amdgcn_global_load_lds(SL_GLOBAL_PTR(kbase + off),
+                                       SL_LDS_PTR(&sm.kv.k[buf][(wave * 4 + i) * 512]), 16, 0, 0);
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      __builtin_amdgcn_global_load_lds(SL_GLOBAL_PTR(vbase + voff[i]),
+                                       SL_LDS_PTR(&sm.kv.vt[buf][(wave * 4 + i) * 512]), 16, 0, 0);
+  };
+  stage(kv_begin, 0);
 
   // Q rows of this lane's column, as the B operand of S^T = K Q^T
   bf16x8 qf[8];
   {
-    const bf16_t* qp = a.Q + sm.row_q[qrow];
+    const bf16_t* qp = a.Q + ci.q_off;
 #pragma unroll
     for (int kk = 0; kk < 8; ++kk) qf[kk] = *reinterpret_cast<const bf16x8*>(qp + kk * 16 + hf * 8);
-  }
-  int64_t i_q = 0, lo_q = 0;
-  if (LOCAL) {
-    i_q = a.q_pos0 + min(r0 + qrow, a.Lq - 1);
-    lo_q = (i_q / a.S) * a.S;
   }
 
   f32x16 o[4];
@@ -311,68 +311,81 @@ __global__ __launch_bounds__(kFlashThreads, 2) void span_flash_kernel(const Flas
   for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
     for (int r = 0; r < 16; ++r) o[dt][r] = 0.f;
-  float m = -INFINITY, l = 0.f;
+  float m = -INFINITY, l = 0.f;  // m in log2 units of the scaled logit
 
-  const bf16_t* Kb = a.K + (int64_t)kv * a.kvsh;
-  const bf16_t* Vtb = a.Vt + (int64_t)kv * HD * a.Lp;
   const int krow = perm_row(qc);
+  const int kswz = krow & 15;      // swizzle key of this lane's K rows (32*sub does not change it)
+  const int vswz = (qc >> 1) & 7;  // swizzle key of this lane's V^T rows (32*dt does not change it)
+  const float sc = a.scale_log2e;
 
-  for (int64_t t0 = kv_begin; t0 < kv_end; t0 += TN) {
-    // stage K [TN][HD] and V^T [HD][TN]
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int id = tid + kFlashThreads * i, row = id >> 4, piece = id & 15;
-      int64_t tok = t0 + row;
-      if (LOCAL) tok = tok < a.L ? tok : a.L - 1;
-      const uint4 v = load16(Kb + tok * a.kvst + piece * 8);
-      *reinterpret_cast<uint4*>(&sm.kv.k[row * KSTR + piece * 8]) = v;
-    }
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int id = tid + kFlashThreads * i, d = id >> 3, piece = id & 7;
-      const uint4 v = load16(Vtb + (int64_t)d * a.Lp + t0 + piece * 8);
-      *reinterpret_cast<uint4*>(&sm.kv.vt[d * VSTR + piece * 8]) = v;
-    }
+  int buf = 0;
+  for (int64_t t0 = kv_begin; t0 < kv_end; t0 += TN, buf ^= 1) {
+    // the tile for this iteration has landed for every wavefront, and every wavefront is done
+    // with the other stage, which is refilled while this one is consumed
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
     __syncthreads();
+    if (t0 + TN < kv_end) stage(t0 + TN, buf ^ 1);
 
-    // S^T = K Q^T for the two 32-row halves of the tile
+    // S^T = K Q^T for the two 32-row halves of the tile.  The K fragments are fetched from LDS in
+    // batches of 8 ahead of the MFMAs that use them, and the two accumulator chains alternate,
+    // so an MFMA neither waits for its own LDS read nor for the MFMA issued just before it.
     f32x16 s[2];
 #pragma unroll
-    for (int sub = 0; sub < 2; ++sub) {
+    for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
       for (int r = 0; r < 16; ++r) s[sub][r] = 0.f;
 #pragma unroll
-      for (int kk = 0; kk < 8; ++kk) {
-        const bf16x8 ka =
-            *reinterpret_cast<const bf16x8*>(&sm.kv.k[(32 * sub + krow) * KSTR + kk * 16 + hf * 8]);
-        s[sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qf[kk], s[sub], 0, 0, 0);
-      }
+    for (int half = 0; half < 2; ++half) {
+      bf16x8 ka[8];
+#pragma unroll
+      for (int k4 = 0; k4 < 4; ++k4)
+#pragma unroll
+        for (int sub = 0; sub < 2; ++sub)
+          ka[2 * k4 + sub] = *reinterpret_cast<const bf16x8*>(
+              &sm.kv.k[buf][(32 * sub + krow) * HD + (((2 * (4 * half + k4) + hf) ^ kswz) << 3)]);
+#pragma unroll
+      for (int k4 = 0; k4 < 4; ++k4)
+#pragma unroll
+        for (int sub = 0; sub < 2; ++sub)
+          s[sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[2 * k4 + sub], qf[4 * half + k4], s[sub], 0, 0, 0);
     }
+    // scheduling pattern for the block above: 4 LDS reads up front, then MFMA / LDS read pairs,
+    // then the last 4 MFMAs (0x100 = LDS read, 0x008 = MFMA)
+    __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+#pragma unroll
+    for (int i = 0; i < 12; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+    }
+    __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
 
-    // logits in log2 units, mask (local window only), running max
+    // mask (local window only) and column maximum of the raw scores
     float mx = -INFINITY;
 #pragma unroll
     for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        float x = s[sub][r] * a.scale_log2e;
         if (LOCAL) {
           const int64_t t = t0 + 32 * sub + 16 * (r >> 3) + 8 * hf + (r & 7);
-          x = (t <= i_q && t >= lo_q) ? x : -INFINITY;
+          s[sub][r] = (t <= ci.i_q && t >= ci.lo_q) ? s[sub][r] : -INFINITY;
         }
-        s[sub][r] = x;
-        mx = fmaxf(mx, x);
+        mx = fmaxf(mx, s[sub][r]);
       }
-    mx = pair_max(mx);
-    const float m_new = fmaxf(m, mx);
-    const float m_use = m_new > -INFINITY ? m_new : 0.f;  // whole column masked so far
-    const float alpha = fast_exp2(m - m_use);
-    m = m_new;
-    l *= alpha;
+    mx = pair_max(mx) * sc;
+    // Lazy rescale: the running maximum only moves when some column of the wavefront grew by
+    // more than 2^8; until then exponentials are taken against the old maximum (p <= 256).
+    const bool grow = mx > m + 8.f || (m == -INFINITY && mx > -INFINITY);
+    if (__builtin_amdgcn_ballot_w64(grow) != 0ull) {
+      const float m_new = fmaxf(m, mx);
+      const float alpha = m_new > -INFINITY ? fast_exp2(m - m_new) : 1.f;
+      m = m_new;
+      l *= alpha;
 #pragma unroll
-    for (int dt = 0; dt < 4; ++dt)
+      for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) o[dt][r] *= alpha;
+        for (int r = 0; r < 16; ++r) o[dt][r] *= alpha;
+    }
+    const float nm = m > -INFINITY ? -m : 0.f;  // whole column masked so far: exponentials are 0 anyway
 
     bf16x8 pb[4];
 #pragma unroll
@@ -380,50 +393,133 @@ __global__ __launch_bounds__(kFlashThreads, 2) void span_flash_kernel(const Flas
       f32x8 p;
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
-        p[e] = fast_exp2(s[ks >> 1][8 * (ks & 1) + e] - m_use);
+        p[e] = fast_exp2(fmaf(s[ks >> 1][8 * (ks & 1) + e], sc, nm));
         l += p[e];
       }
       pb[ks] = __builtin_convertvector(p, bf16x8);
     }
 
-    // O^T += V^T P^T
+    // O^T += V^T P^T: the four V^T fragments of a k-step are fetched together, one step ahead
+    bf16x8 va[2][4];
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks)
+    for (int dt = 0; dt < 4; ++dt)
+      va[0][dt] = *reinterpret_cast<const bf16x8*>(
+          &sm.kv.vt[buf][(32 * dt + qc) * TN + (((0 + hf) ^ vswz) << 3)]);
 #pragma unroll
-      for (int dt = 0; dt < 4; ++dt) {
-        const bf16x8 va =
-            *reinterpret_cast<const bf16x8*>(&sm.kv.vt[(32 * dt + qc) * VSTR + ks * 16 + hf * 8]);
-        o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb[ks], o[dt], 0, 0, 0);
+    for (int ks = 0; ks < 4; ++ks) {
+      if (ks + 1 < 4) {
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt)
+          va[(ks + 1) & 1][dt] = *reinterpret_cast<const bf16x8*>(
+              &sm.kv.vt[buf][(32 * dt + qc) * TN + (((2 * (ks + 1) + hf) ^ vswz) << 3)]);
       }
-    __syncthreads();
+#pragma unroll
+      for (int dt = 0; dt < 4; ++dt)
+        o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[ks & 1][dt], pb[ks], o[dt], 0, 0, 0);
+    }
+    // 4 LDS reads up front, then MFMA / LDS read pairs, then the last 4 MFMAs
+    __builtin_amdgcn_sched_group_barrier(0x100, 4, 1);
+#pragma unroll
+    for (int i = 0; i < 12; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 1);
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 1);
+    }
+    __builtin_amdgcn_sched_group_barrier(0x008, 4, 1);
   }
 
-  // epilogue: normalise, stage the tile as [row][d] bf16 in LDS
+  // epilogue: normalise, stage the tile as [row][d] bf16 in LDS (the K/V stages are dead)
   const float lt = pair_sum(l);
   const float inv = 1.f / lt;
-  if (hf == 0) sm.row_lse[qrow] = (m + __log2f(lt)) * kLn2;
+  __syncthreads();
+  if (hf == 0) {
+    sm.ep.row_lse[qrow] = (m + __log2f(lt)) * kLn2;
+    sm.ep.row_out[qrow] = ci.row_out;
+  }
 #pragma unroll
   for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
     for (int g4 = 0; g4 < 4; ++g4) {
       const int d = 32 * dt + 8 * g4 + 4 * hf;
-      uint32_t w0 = (uint32_t)f32_to_bf16(o[dt][4 * g4 + 0] * inv) |
-                    ((uint32_t)f32_to_bf16(o[dt][4 * g4 + 1] * inv) << 16);
-      uint32_t w1 = (uint32_t)f32_to_bf16(o[dt][4 * g4 + 2] * inv) |
-                    ((uint32_t)f32_to_bf16(o[dt][4 * g4 + 3] * inv) << 16);
-      *reinterpret_cast<uint2*>(&sm.o[qrow * OSTR + d]) = make_uint2(w0, w1);
+      f32x4 v;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) v[e] = o[dt][4 * g4 + e] * inv;
+      const bf16x4 w = __builtin_convertvector(v, bf16x4);
+      *reinterpret_cast<bf16x4*>(&sm.ep.o[qrow * OSTR + d]) = w;
     }
   __syncthreads();
 
   // 16 lanes per row, 16 bytes per lane
+#pragma unroll
   for (int pass = 0; pass < TM / 16; ++pass) {
     const int row = pass * 16 + (tid >> 4), piece = tid & 15;
-    const int64_t out = sm.row_out[row];
-    if (out < 0) continue;
-    const uint4 mine = *reinterpret_cast<const uint4*>(&sm.o[row * OSTR + piece * 8]);
-    *reinterpret_cast<uint4*>(a.part_o + out * HD + piece * 8) = mine;
-    if (piece == 0) a.part_lse[out] = sm.row_lse[row];
+    const int64_t out = sm.ep.row_out[row];
+    if (out >= 0) {
+      const uint4 mine = *reinterpret_cast<const uint4*>(&sm.ep.o[row * OSTR + piece * 8]);
+      *reinterpret_cast<uint4*>(a.part_o + out * HD + piece * 8) = mine;
+      if (piece == 0) a.part_lse[out] = sm.ep.row_lse[row];
+    }
   }
+  __syncthreads();  // LDS is free again
+}
+
+// Routed spans: persistent workgroups, each owning a contiguous range of the tile list.
+// Workgroups w, w+8, w+16, ... run on one XCD and own adjacent ranges, so the tiles of a bucket
+// are consumed by one XCD and share its L2 copy of the span.  The record and the item of the
+// next tile are fetched while the current tile is computed.
+__global__ __launch_bounds__(kFlashThreads, 2) void span_flash_routed_kernel(const FlashArgs a) {
+  __shared__ FlashSmem sm;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int qrow = wave * 32 + (lane & 31);
+  const int64_t T = a.tile_off[a.Hq / a.G * a.n];
+  const int NW = gridDim.x;  // a multiple of 8
+  const int range = (blockIdx.x % 8) * (NW / 8) + blockIdx.x / 8;
+  const int64_t t_begin = T * range / NW, t_end = T * (range + 1) / NW;
+  if (t_begin >= t_end) return;
+
+  int4 info = a.tile_info[t_begin];
+  int item = a.items[info.y + min(qrow, info.z - 1)];
+  for (int64_t t = t_begin; t < t_end; ++t) {
+    int4 next_info = info;
+    int next_item = item;
+    if (t + 1 < t_end) {
+      next_info = a.tile_info[t + 1];
+      next_item = a.items[next_info.y + min(qrow, next_info.z - 1)];
+    }
+    const int kv = info.x / a.n, j = info.x % a.n;
+    const int rowid = item >> 5, slot = item & 31;
+    const int hl = rowid / (int)a.Lq;
+    const int64_t r = rowid - (int64_t)hl * a.Lq;
+    const int h = kv * a.G + hl;
+    ColInfo ci;
+    ci.q_off = h * a.qsh + r * a.qst;
+    ci.row_out = qrow < info.z ? ((int64_t)h * a.Lq + r) * (a.topk + 1) + slot : -1;
+    ci.i_q = ci.lo_q = 0;
+    flash_tile<false>(a, sm, kv, (int64_t)j * a.S, (int64_t)(j + 1) * a.S, ci);
+    info = next_info;
+    item = next_item;
+  }
+}
+
+// Local window [c*S, i]: regular 128-row tiles of one head with the causal / window mask.
+__global__ __launch_bounds__(kFlashThreads, 2) void span_flash_local_kernel(const FlashArgs a) {
+  __shared__ FlashSmem sm;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int qrow = wave * 32 + (lane & 31);
+  const int tiles_per_head = (int)((a.Lq + TM - 1) / TM);
+  const int h = blockIdx.x / tiles_per_head;
+  const int64_t r0 = (int64_t)(blockIdx.x % tiles_per_head) * TM;
+  const int64_t r = r0 + qrow;
+  const int64_t rc = r < a.Lq ? r : a.Lq - 1;
+  ColInfo ci;
+  ci.q_off = h * a.qsh + rc * a.qst;
+  ci.row_out = r < a.Lq ? ((int64_t)h * a.Lq + r) * (a.topk + 1) + a.topk : -1;
+  ci.i_q = a.q_pos0 + rc;
+  ci.lo_q = (ci.i_q / a.S) * a.S;
+  const int64_t i_first = a.q_pos0 + r0;
+  const int64_t i_last = min(a.q_pos0 + r0 + TM - 1, a.q_pos0 + a.Lq - 1);
+  const int64_t kv_begin = (i_first / a.S) * a.S;
+  const int64_t kv_end = kv_begin + ((i_last - kv_begin) / TN + 1) * TN;
+  flash_tile<true>(a, sm, h / a.G, kv_begin, kv_end, ci);
 }
 
 // ------------------------------------------------------------------ merge
@@ -490,11 +586,24 @@ __global__ __launch_bounds__(256) void merge_partials_kernel(
 
 // ------------------------------------------------------------------ workspace carving
 struct MfmaWs {
-  size_t vt, counts, item_off, tile_off, cursor, tile_bucket, items, part_lse, part_o, total;
+  size_t vt, counts, item_off, tile_off, cursor, tile_info, items, part_lse, part_o, total;
   int64_t Lp;
   int B, max_tiles;
   int64_t max_items;
 };
+
+// Two resident workgroups per compute unit (LDS and registers allow exactly two).
+int persistent_grid() {
+  static int grid = 0;
+  if (grid == 0) {
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+      cus = 256;
+    grid = (2 * cus + 7) / 8 * 8;
+  }
+  return grid;
+}
 
 MfmaWs carve(const Problem& pb) {
   MfmaWs w;
@@ -513,7 +622,7 @@ MfmaWs carve(const Problem& pb) {
   w.item_off = take((size_t)(w.B + 1) * sizeof(int));
   w.tile_off = take((size_t)(w.B + 1) * sizeof(int));
   w.cursor = take((size_t)w.B * sizeof(int));
-  w.tile_bucket = take((size_t)w.max_tiles * sizeof(int));
+  w.tile_info = take((size_t)w.max_tiles * sizeof(int4));
   w.items = take((size_t)w.max_items * sizeof(int));
   const size_t nparts = (size_t)pb.Hq * pb.Lq * (pb.topk + 1);  // routed slots + the local window
   w.part_lse = take(nparts * sizeof(float));
@@ -526,7 +635,10 @@ MfmaWs carve(const Problem& pb) {
 
 bool prefill_attention_mfma_supported(const Problem& pb) {
   return pb.dtype == SL_BF16 && pb.D == HD && pb.S % TN == 0 && pb.n <= 4096 &&
-         (int64_t)pb.G * pb.Lq < ((int64_t)1 << 31) &&
+         (int64_t)pb.G * pb.Lq < ((int64_t)1 << 26) &&  // item = (row id << 5) | slot
+         // staging uses 32-bit byte offsets inside one kv head's V^T and inside a 64-row K tile
+         (int64_t)HD * (int64_t)align_up((size_t)pb.L, 64) * 2 < ((int64_t)1 << 32) &&
+         64 * pb.kvst * 2 < ((int64_t)1 << 31) &&
          (int64_t)pb.Hq * pb.Lq * (pb.topk + 1) < ((int64_t)1 << 31) &&
          // row_q holds 32-bit element offsets into Q
          (int64_t)pb.Hq * pb.qsh + pb.Lq * pb.qst < ((int64_t)1 << 31);
@@ -544,7 +656,7 @@ sl_status prefill_attention_mfma(const Problem& pb, const void* Q, const void* K
   int* item_off = reinterpret_cast<int*>(base + w.item_off);
   int* tile_off = reinterpret_cast<int*>(base + w.tile_off);
   int* cursor = reinterpret_cast<int*>(base + w.cursor);
-  int* tile_bucket = reinterpret_cast<int*>(base + w.tile_bucket);
+  int4* tile_info = reinterpret_cast<int4*>(base + w.tile_info);
   int* items = reinterpret_cast<int*>(base + w.items);
   float* part_lse = reinterpret_cast<float*>(base + w.part_lse);
   bf16_t* part_o = reinterpret_cast<bf16_t*>(base + w.part_o);
@@ -560,7 +672,7 @@ sl_status prefill_attention_mfma(const Problem& pb, const void* Q, const void* K
   a.idx = idx;
   a.item_off = item_off;
   a.tile_off = tile_off;
-  a.tile_bucket = tile_bucket;
+  a.tile_info = tile_info;
   a.items = items;
   a.part_o = part_o;
   a.part_lse = part_lse;
@@ -588,17 +700,16 @@ sl_status prefill_attention_mfma(const Problem& pb, const void* Q, const void* K
                        counts, cursor, items, pb.Lq, pb.q_pos0, pb.G, pb.S, pb.topk, n);
     hipLaunchKernelGGL(bucket_scan_kernel, dim3(1), dim3(1024), 0, st, counts, item_off, tile_off,
                        cursor, w.B);
-    hipLaunchKernelGGL(bucket_tiles_kernel, dim3(w.B), dim3(256), 0, st, tile_off, tile_bucket);
+    hipLaunchKernelGGL(bucket_tiles_kernel, dim3(w.B), dim3(256), 0, st, tile_off, item_off, tile_info);
     hipLaunchKernelGGL(bucket_kernel<true>, bgrid, dim3(256), (size_t)2 * n * sizeof(int), st, idx,
                        counts, cursor, items, pb.Lq, pb.q_pos0, pb.G, pb.S, pb.topk, n);
     if (hipGetLastError() != hipSuccess) return SL_ERR_LAUNCH;
-    const int grid = (int)align_up((size_t)w.max_tiles, 8);
     if (pb.prof_start) (void)hipEventRecord(pb.prof_start, st);
-    hipLaunchKernelGGL(span_flash_kernel<false>, dim3(grid), dim3(kFlashThreads), 0, st, a);
+    hipLaunchKernelGGL(span_flash_routed_kernel, dim3(persistent_grid()), dim3(kFlashThreads), 0, st, a);
     if (pb.prof_stop) (void)hipEventRecord(pb.prof_stop, st);
   }
   const int tiles_per_head = (int)((pb.Lq + TM - 1) / TM);
-  hipLaunchKernelGGL(span_flash_kernel<true>, dim3(pb.Hq * tiles_per_head), dim3(kFlashThreads), 0,
+  hipLaunchKernelGGL(span_flash_local_kernel, dim3(pb.Hq * tiles_per_head), dim3(kFlashThreads), 0,
                      st, a);
   const int64_t rows = (int64_t)pb.Hq * pb.Lq;
   const dim3 mgrid((unsigned)((rows + 15) / 16));
