@@ -83,6 +83,150 @@ __global__ __launch_bounds__(kDecodeSearchThreads) void decode_search_kernel(
                      scores ? scores + (int64_t)h * topk : nullptr);
 }
 
+// ------------------------------------------------------------------ a7: decode search, block-parallel select
+// Same scoring as above, but the selection uses all 16 wavefronts and has no k-long chain of
+// dependent rounds:
+//   1. every thread owns up to RMAX consecutive candidates (registers);
+//   2. the k-th largest value T is found by a most-significant-digit-first radix select on
+//      order-preserving 32-bit keys: four passes of an 8-bit LDS histogram over the candidates
+//      that still match the digits fixed so far; wavefront 0 picks the digit in which the k-th
+//      largest key lies from a suffix sum over the 256 bins;
+//   3. every candidate > T is selected, plus the lowest-index candidates == T that are needed to
+//      reach k (ties to the lower index); the output slot of a selected candidate is the number
+//      of selected candidates below it, from one block-wide prefix sum of (count > T, count == T).
+template <typename T, int D, int RMAX>
+__global__ __launch_bounds__(kDecodeSearchThreads) void decode_search_block_kernel(
+    const T* __restrict__ Qs, const T* __restrict__ K, const T* __restrict__ Ks,
+    int32_t* __restrict__ idx, float* __restrict__ scores, int64_t c, int64_t n, int G, int S,
+    int topk, int64_t qsh, int64_t kvsh, int64_t kvst) {
+  using RL = RowLayout<T, D>;
+  constexpr int EPL = RL::EPL, LPR = RL::LPR, RPW = RL::RPW;
+  constexpr int U = 16, NW = kDecodeSearchThreads / 64;
+  __shared__ float s_sc[kDecodeSearchThreads * RMAX];
+  __shared__ __align__(16) unsigned s_hist[256];
+  __shared__ int s_wave_tot[NW];
+  __shared__ int s_digit, s_krem;
+  const int h = blockIdx.x, kv = h / G;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int g = lane / LPR, lr = lane % LPR;
+  const int kk = topk < c ? topk : (int)c;
+
+  float qf[EPL];
+  Elem<T>::unpack(load16(Qs + (int64_t)h * qsh + lr * EPL), qf);
+  for (int64_t jb = (int64_t)wave * RPW * U; jb < c; jb += NW * RPW * U) {
+    uint4 kr[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      int64_t j = jb + u * RPW + g;
+      j = j < c ? j : c - 1;
+      kr[u] = load16(span_key_ptr<T, D>(K, Ks, kv, j, n, S, kvsh, kvst) + lr * EPL);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      float kf[EPL];
+      Elem<T>::unpack(kr[u], kf);
+      float acc = 0.f;
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) acc = fmaf(qf[e], kf[e], acc);
+      acc = group_sum<LPR>(acc);
+      const int64_t j = jb + u * RPW + g;
+      if (lr == 0 && j < c) s_sc[j] = acc;
+    }
+  }
+  __syncthreads();
+
+  // 1. thread t owns candidates t*R .. t*R + R-1 (index order = thread order)
+  const int R = (int)((c + kDecodeSearchThreads - 1) / kDecodeSearchThreads);
+  float v[RMAX];
+  unsigned key[RMAX];
+#pragma unroll
+  for (int r = 0; r < RMAX; ++r) {
+    const int j = tid * R + r;
+    v[r] = (r < R && j < c) ? s_sc[j] : -INFINITY;
+    const unsigned u = __float_as_uint(v[r]);
+    key[r] = (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+    if (!(v[r] > -INFINITY)) key[r] = 0u;  // empty slots (and non-finite input) never match
+  }
+
+  // 2. radix select of the kk-th largest key
+  float Tval = INFINITY;  // kk == 0: nothing is selected
+  if (kk > 0) {
+    unsigned prefix = 0u, mask = 0u;
+    int krem = kk;
+    for (int pass = 0; pass < 4; ++pass) {
+      const int shift = 24 - 8 * pass;
+      if (tid < 256) s_hist[tid] = 0u;
+      __syncthreads();
+#pragma unroll
+      for (int r = 0; r < RMAX; ++r)
+        if (key[r] != 0u && (key[r] & mask) == prefix) atomicAdd(&s_hist[(key[r] >> shift) & 255u], 1u);
+      __syncthreads();
+      if (wave == 0) {
+        const uint4 c4 = *reinterpret_cast<const uint4*>(&s_hist[4 * lane]);
+        const int lane_sum = (int)(c4.x + c4.y + c4.z + c4.w);
+        const int incl = wave_inclusive_scan(lane_sum);
+        const int total = __builtin_amdgcn_readlane(incl, 63);
+        int above = total - incl;  // candidates in bins above this lane's four
+        const unsigned cnt[4] = {c4.x, c4.y, c4.z, c4.w};
+#pragma unroll
+        for (int b4 = 3; b4 >= 0; --b4) {
+          if (above < krem && krem <= above + (int)cnt[b4]) {
+            s_digit = 4 * lane + b4;
+            s_krem = krem - above;
+          }
+          above += (int)cnt[b4];
+        }
+      }
+      __syncthreads();
+      prefix |= (unsigned)s_digit << shift;
+      mask |= 255u << shift;
+      krem = s_krem;
+    }
+    const unsigned tu = (prefix & 0x80000000u) ? (prefix & 0x7fffffffu) : ~prefix;
+    Tval = __uint_as_float(tu);
+  }
+
+  // 3. select and place
+  int gt = 0, eq = 0;
+#pragma unroll
+  for (int r = 0; r < RMAX; ++r) {
+    gt += v[r] > Tval ? 1 : 0;
+    eq += (v[r] == Tval && v[r] > -INFINITY) ? 1 : 0;
+  }
+  const int packed = gt | (eq << 16);
+  const int incl = wave_inclusive_scan(packed);
+  if (lane == 63) s_wave_tot[wave] = incl;
+  __syncthreads();
+  int before = incl - packed, total = 0;
+#pragma unroll
+  for (int w = 0; w < NW; ++w) {
+    const int t = s_wave_tot[w];
+    before += w < wave ? t : 0;
+    total += t;
+  }
+  const int gt_total = total & 0xffff;
+  const int need_eq = kk - gt_total;  // ties accepted, lowest index first
+  int gt_before = before & 0xffff, eq_before = before >> 16;
+  int32_t* oi = idx + (int64_t)h * topk;
+  float* os = scores ? scores + (int64_t)h * topk : nullptr;
+#pragma unroll
+  for (int r = 0; r < RMAX; ++r) {
+    const bool is_gt = v[r] > Tval;
+    const bool is_eq = v[r] == Tval && v[r] > -INFINITY;
+    if (is_gt || (is_eq && eq_before < need_eq)) {
+      const int pos = gt_before + (eq_before < need_eq ? eq_before : need_eq);
+      oi[pos] = tid * R + r;
+      if (os) os[pos] = v[r];
+    }
+    gt_before += is_gt ? 1 : 0;
+    eq_before += is_eq ? 1 : 0;
+  }
+  if (tid >= kk && tid < topk) {
+    oi[tid] = -1;
+    if (os) os[tid] = -INFINITY;
+  }
+}
+
 // ------------------------------------------------------------------ a1 + a2: prefill, row-stationary
 // One wavefront per (head, query row); W rows per workgroup; dynamic LDS = W lane-major score arrays.
 template <typename T, int D>
@@ -151,6 +295,21 @@ sl_status launch_decode_search(const Problem& pb, const void* Qs, const void* K,
                                int32_t* idx, float* scores, hipStream_t st) {
   const int64_t c = pb.q_pos0 / pb.S;
   if (pb.prof_start) (void)hipEventRecord(pb.prof_start, st);
+  if (c <= (int64_t)kDecodeSearchThreads * 4) {
+    // block-parallel selection: candidates fit 4 registers per thread
+    if (c <= kDecodeSearchThreads)
+      hipLaunchKernelGGL((decode_search_block_kernel<T, D, 1>), dim3(pb.Hq),
+                         dim3(kDecodeSearchThreads), 0, st, static_cast<const T*>(Qs),
+                         static_cast<const T*>(K), static_cast<const T*>(Ks), idx, scores, c, pb.n,
+                         pb.G, pb.S, pb.topk, pb.qsh, pb.kvsh, pb.kvst);
+    else
+      hipLaunchKernelGGL((decode_search_block_kernel<T, D, 4>), dim3(pb.Hq),
+                         dim3(kDecodeSearchThreads), 0, st, static_cast<const T*>(Qs),
+                         static_cast<const T*>(K), static_cast<const T*>(Ks), idx, scores, c, pb.n,
+                         pb.G, pb.S, pb.topk, pb.qsh, pb.kvsh, pb.kvst);
+    if (pb.prof_stop) (void)hipEventRecord(pb.prof_stop, st);
+    return hipGetLastError() == hipSuccess ? SL_OK : SL_ERR_LAUNCH;
+  }
   hipLaunchKernelGGL((decode_search_kernel<T, D>), dim3(pb.Hq), dim3(kDecodeSearchThreads),
                      (size_t)LaneMajor::make(c).lds_floats() * sizeof(float), st,
                      static_cast<const T*>(Qs),

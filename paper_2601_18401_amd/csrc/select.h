@@ -111,4 +111,21 @@ __device__ __forceinline__ void wave_select_topk(float* sc, const LaneMajor& lm,
   }
 }
 
+
+// Inclusive prefix sum over the 64 lanes (DPP only): Hillis-Steele inside each row of 16 lanes
+// (row_shr 1, 2, 4, 8 with zero fill), then the row totals ripple up through row broadcasts.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ int scan_dpp_step(int v) {
+  return v + __builtin_amdgcn_update_dpp(0, v, CTRL, ROW_MASK, 0xF, true);
+}
+__device__ __forceinline__ int wave_inclusive_scan(int v) {
+  v = scan_dpp_step<0x111, 0xF>(v);
+  v = scan_dpp_step<0x112, 0xF>(v);
+  v = scan_dpp_step<0x114, 0xF>(v);
+  v = scan_dpp_step<0x118, 0xF>(v);
+  v = scan_dpp_step<0x142, 0xA>(v);  // rows 1, 3 += total of rows 0, 2
+  v = scan_dpp_step<0x143, 0xC>(v);  // rows 2, 3 += total of rows 0..1
+  return v;
+}
+
 }  // namespace sl

@@ -294,3 +294,23 @@ def test_invalid_arguments_raise_on_gpu_too():
     assert e.value.status == 2
     with pytest.raises(B.SlError):
         B.sl_span_attention_decode(Q, K, V, None, 64)      # Lq != 1
+
+
+@pytest.mark.parametrize("L,S,k", [(64 * 300, 64, 16), (128 * 2000, 128, 8), (64 * 40, 64, 32)])
+def test_decode_search_ties_lower_index_wins(L, S, k):
+    # many spans share one of a few distinct keys -> exact fp32 score ties across the whole cache
+    Hq, Hkv, D = 8, 2, 128
+    Q, K, V = make(13, Hq, Hkv, L, D, torch.bfloat16, Lq=1)
+    n = L // S
+    g = torch.Generator().manual_seed(3)
+    base = torch.randn((Hkv, 5, D), generator=g).to(torch.bfloat16).to(DEV)
+    which = torch.randint(0, 5, (n,), generator=g)
+    for j in range(n):
+        K[:, (j + 1) * S - 1] = base[:, which[j]]
+    Ks = B.sl_span_keys(K, S)
+    idx, sc = B.sl_span_search_decode(Q, K, Ks, S, k, want_scores=True)
+    torch.cuda.synchronize()
+    want, wsc = orc.span_search(f64(Q), f64(Ks), S, k, q_pos0=L - 1, return_scores=True)
+    # identical keys give bit-identical fp32 scores, so the tie rule decides: must match exactly
+    assert np.array_equal(idx.cpu().numpy(), want)
+    assert np.allclose(sc.cpu().numpy(), wsc, atol=1e-3)
