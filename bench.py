@@ -266,6 +266,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--configs", default="C3,C5,C4,C2,C1")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="first run a plain elementwise copy of known size (reads 1 GiB, writes 1 GiB) three "
+                         "times, so that rocprofv3 FETCH_SIZE / WRITE_SIZE readings can be scaled")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1",
@@ -278,6 +281,14 @@ def main():
     B.load()    # raises if the HIP library is missing: there is no fallback
     torch.cuda.set_device(0)
 
+    if args.calibrate_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")    # 1 GiB
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.add(src, 0.0, out=dst)       # one kernel: reads 2^30 bytes, writes 2^30 bytes
+        torch.cuda.synchronize()
+        del src, dst
+        torch.cuda.empty_cache()
     names = [c.strip() for c in args.configs.split(",") if c.strip()]
     results, primary, cpu = {}, None, None
     for name in names:
