@@ -7,11 +7,11 @@
 //
 //   bucket_count / bucket_scan / bucket_tiles / bucket_fill   invert idx into per-(kv, span)
 //                                   lists of query rows (integer work, LDS histograms)
-//   span_flash_routed               persistent workgroups walk the (bucket, 128-row tile) list:
+//   span_flash_routed               persistent workgroups walk the (bucket, 256-row tile) list:
 //                                   gathered Q rows against the span's K/V tiles staged through
 //                                   LDS, flash softmax, MFMA QK^T and PV; writes a normalised
 //                                   partial (o, lse) per (row, slot)
-//   span_flash_local                the local window [c*S, i]: regular 128-row tiles of one
+//   span_flash_local                the local window [c*S, i]: regular 256-row tiles of one
 //                                   head with the causal mask; writes the row's last partial
 //   merge_partials                  streaming log-sum-exp merge of the <= topk + 1 partials of
 //                                   every row; writes O and LSE
@@ -34,31 +34,31 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x8 __attribute__((ext_vector_type(8)));
 
-constexpr int TM = 128;            // query rows per workgroup: 4 wavefronts x 32 columns
+constexpr int TM = 256;            // query rows per workgroup: two groups of 4 wavefronts x 32 columns
+constexpr int TG = 128;            // rows of one wavefront group
 constexpr int TN = 64;             // kv positions per staged tile
 constexpr int HD = 128;            // head dimension of this path
-constexpr int OSTR = HD + 8;       // LDS row stride of the output staging tile
-constexpr int kFlashThreads = 256;
+constexpr int kFlashThreads = 512;
 constexpr int kBucketRows = 1024;  // query rows of one head per bucketing workgroup
 
-// LDS of the flash kernel.  Main loop: two stages of (K tile, V^T tile), filled by direct
-// global->LDS loads (16 bytes per lane, a wavefront instruction fills 1 KB contiguously), rows
-// unpadded with an XOR swizzle of the 16-byte pieces so that the MFMA operand reads of 16
-// consecutive lanes hit 16 distinct bank groups.  Epilogue: the same memory holds the output
-// tile [row][d] and the per-row output indices.
-struct __align__(16) FlashSmem {
-  union {
-    struct {
-      bf16_t k[2][TN * HD];   // 2 x 16 KB, row = 16 pieces of 16 B, piece p of row r at p ^ (r & 15)
-      bf16_t vt[2][HD * TN];  // 2 x 16 KB, row = 8 pieces, piece p of row d at p ^ ((d >> 1) & 7)
-    } kv;
-    struct {
-      bf16_t o[TM * OSTR];    // 34816 B
-      int64_t row_out[TM];
-      float row_lse[TM];
-    } ep;
-  };
-};
+// LDS of the flash kernel (dynamic, 150528 bytes, one workgroup per compute unit).
+// Main loop: three stages of the V^T tile and two of the K tile, filled by direct global->LDS
+// loads (16 bytes per lane, a wavefront instruction fills 1 KB contiguously); rows are unpadded
+// and their 16-byte pieces XOR-swizzled so that the MFMA operand reads of 16 consecutive lanes
+// hit 16 distinct bank groups:
+//   K tile  [64][128]: piece p of row r at position p ^ (r & 15)
+//   V^T tile [128][64]: piece p of row d at position p ^ ((d >> 1) & 7)
+// Epilogue: each wavefront group stages its output tile [128][128] bf16 in a region of its own
+// (piece p of row r at p ^ (r & 15)), so the first K/V tile of the next 256-row tile can be
+// fetched while the current one is written out.
+constexpr int kStageElems = TN * HD;                        // 8192 bf16 = 16 KB
+constexpr int kStagesK = 2, kStagesV = 3;
+constexpr int kLdsV = 0;
+constexpr int kLdsK = kStagesV * kStageElems * 2;           // byte offset 49152
+constexpr int kLdsOut = (kStagesV + kStagesK) * kStageElems * 2;  // bf16[2][TG][HD], byte offset 81920
+constexpr int kLdsRowOut = kLdsOut + 2 * TG * HD * 2;       // int64[2][TG], byte offset 147456
+constexpr int kLdsRowLse = kLdsRowOut + 2 * TG * 8;         // float[2][TG]
+constexpr int kFlashLdsBytes = kLdsRowLse + 2 * TG * 4;     // 150528
 
 #define SL_LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
 #define SL_GLOBAL_PTR(p) ((const __attribute__((address_space(1))) void*)(p))
@@ -247,63 +247,88 @@ __device__ __forceinline__ int perm_row(int rho) {
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-// What one lane knows about its query column in the current tile.
-struct ColInfo {
-  int64_t q_off;    // element offset of the Q vector
-  int64_t row_out;  // partial record index, -1 = no row
+// One 256-row tile as seen by a lane: the kv head and kv range [kv_begin, kv_end) (a multiple of
+// TN long) shared by the workgroup, and the lane's own query column.
+struct TileDesc {
+  int kv;
+  int64_t kv_begin, kv_end;
+  int64_t q_off;      // element offset of the lane's Q vector
+  int64_t row_out;    // partial record index of the lane's column, -1 = no row
   int64_t i_q, lo_q;  // LOCAL: query position and start of its window
 };
 
-// One 128-row tile against the kv range [kv_begin, kv_end) (a multiple of TN long) of kv head
-// `kv`.  All 256 threads call; LDS is free on entry and free again on return.
-template <bool LOCAL>
-__device__ __forceinline__ void flash_tile(const FlashArgs& a, FlashSmem& sm, int kv,
-                                           int64_t kv_begin, int64_t kv_end, const ColInfo& ci) {
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int qc = lane & 31, hf = lane >> 5;
-  const int qrow = wave * 32 + qc;
-  const bf16_t* Kb = a.K + (int64_t)kv * a.kvsh;
-  const bf16_t* Vtb = a.Vt + (int64_t)kv * HD * a.Lp;
+// State a workgroup carries from one tile to the next: the rotating stage indices, whether the
+// tile's first K/V stage and Q fragments were already fetched by the previous tile's tail, and
+// the Q fragments themselves.
+struct FlashCarry {
+  int kb, vb;
+  bool primed;
+  bf16x8 qf[8];
+};
 
-  // Direct global -> LDS staging of one (K, V^T) tile pair: wavefront w fills K blocks 4w..4w+3
-  // (4 rows each) and V^T blocks 4w..4w+3 (8 rows each); lane L of a block lands at byte 16*L.
-  // Per-lane byte offsets are loop-invariant 32-bit values; the tile position goes into the
-  // wave-uniform base pointer.
-  uint32_t koff[4], voff[4];
+// One 256-row tile.  All 512 threads call.  `next` (if has_next) is the tile this workgroup
+// processes afterwards.
+//
+// The eight wavefronts form two groups of four (each group owns 128 rows, a wavefront 32
+// columns); SIMD s hosts wavefront s of both groups.  Both groups consume the same staged K/V
+// tiles, but the late group runs its PV product one kv tile behind:
+//     early, per kv tile i:   QK(i)    softmax(i)  PV(i)
+//     late,  per kv tile i:   PV(i-1)  QK(i)       softmax(i)          (+ PV(last) after the loop)
+// so that between two barriers the softmax arithmetic of one group runs in the shadow of the
+// other group's MFMAs instead of both groups asking for the matrix pipe at the same time.
+// When the kv loop is over, the first K/V stage and the Q fragments of the next tile are
+// requested before the output tile is normalised and written.
+template <bool LOCAL>
+__device__ __forceinline__ void flash_tile(const FlashArgs& a, char* lds, const TileDesc& cur,
+                                           const TileDesc& next, bool has_next, FlashCarry& c) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int grp = wave >> 2, w4 = wave & 3;  // grp 0 = early, 1 = late
+  const int qc = lane & 31, hf = lane >> 5;
+  const int srow = w4 * 32 + qc;             // row inside the group's 128-row half tile
+  bf16_t* const ldsV = reinterpret_cast<bf16_t*>(lds + kLdsV);
+  bf16_t* const ldsK = reinterpret_cast<bf16_t*>(lds + kLdsK);
+
+  // Direct global -> LDS staging of one (K, V^T) tile pair in 1 KB blocks (4 K rows or 8 V^T rows
+  // each); lane L of a block lands at byte 16*L.
+  // Per-lane byte offsets are loop-invariant 32-bit values; the kv head and the tile position
+  // go into the wave-uniform base pointer.
+  uint32_t koff[2], voff[2];
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int blk = wave * 4 + i;
+  for (int i = 0; i < 2; ++i) {
+    const int blk = wave * 2 + i;
     const int row = blk * 4 + (lane >> 4), pc = lane & 15, gp = pc ^ (row & 15);
     koff[i] = (uint32_t)((row * a.kvst + gp * 8) * sizeof(bf16_t));
     const int d = blk * 8 + (lane >> 3), pv = lane & 7, gv = pv ^ ((d >> 1) & 7);
     voff[i] = (uint32_t)((d * a.Lp + gv * 8) * sizeof(bf16_t));
   }
-  auto stage = [&](int64_t t0, int buf) {
-    const char* kbase = reinterpret_cast<const char*>(Kb + t0 * a.kvst);
-    const char* vbase = reinterpret_cast<const char*>(Vtb + t0);
+  // wavefront w fills blocks 2w, 2w+1 of both tiles
+  auto stage = [&](int kvh, int64_t t0, int kb, int vb) {
+    const char* kbase = reinterpret_cast<const char*>(a.K + (int64_t)kvh * a.kvsh + t0 * a.kvst);
+    const char* vbase = reinterpret_cast<const char*>(a.Vt + (int64_t)kvh * HD * a.Lp + t0);
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < 2; ++i) {
       uint32_t off = koff[i];
       if (LOCAL) {  // rows past the end of the sequence re-read the last row (masked later)
-        const int row = (wave * 4 + i) * 4 + (lane >> 4);
+        const int row = (wave * 2 + i) * 4 + (lane >> 4);
         if (t0 + row >= a.L) off -= (uint32_t)((t0 + row - (a.L - 1)) * a.kvst * sizeof(bf16_t));
       }
       __builtin_amdgcn_global_load_lds(SL_GLOBAL_PTR(kbase + off),
-                                       SL_LDS_PTR(&sm.kv.k[buf][(wave * 4 + i) * 512]), 16, 0, 0);
+                                       SL_LDS_PTR(ldsK + kb * kStageElems + (wave * 2 + i) * 512), 16, 0, 0);
     }
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < 2; ++i)
       __builtin_amdgcn_global_load_lds(SL_GLOBAL_PTR(vbase + voff[i]),
-                                       SL_LDS_PTR(&sm.kv.vt[buf][(wave * 4 + i) * 512]), 16, 0, 0);
+                                       SL_LDS_PTR(ldsV + vb * kStageElems + (wave * 2 + i) * 512), 16, 0, 0);
   };
-  stage(kv_begin, 0);
-
-  // Q rows of this lane's column, as the B operand of S^T = K Q^T
-  bf16x8 qf[8];
-  {
-    const bf16_t* qp = a.Q + ci.q_off;
+  // Q row of a lane's column, as the B operand of S^T = K Q^T
+  auto load_q = [&](int64_t q_off) {
+    const bf16_t* qp = a.Q + q_off;
 #pragma unroll
-    for (int kk = 0; kk < 8; ++kk) qf[kk] = *reinterpret_cast<const bf16x8*>(qp + kk * 16 + hf * 8);
+    for (int kk = 0; kk < 8; ++kk) c.qf[kk] = *reinterpret_cast<const bf16x8*>(qp + kk * 16 + hf * 8);
+  };
+  if (!c.primed) {
+    stage(cur.kv, cur.kv_begin, c.kb, c.vb);
+    load_q(cur.q_off);
   }
 
   f32x16 o[4];
@@ -312,45 +337,33 @@ __device__ __forceinline__ void flash_tile(const FlashArgs& a, FlashSmem& sm, in
 #pragma unroll
     for (int r = 0; r < 16; ++r) o[dt][r] = 0.f;
   float m = -INFINITY, l = 0.f;  // m in log2 units of the scaled logit
+  bf16x8 pb[4];                  // P^T fragments; the late group carries them to the next kv tile
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) pb[ks][e] = (__bf16)0.f;
 
   const int krow = perm_row(qc);
   const int kswz = krow & 15;      // swizzle key of this lane's K rows (32*sub does not change it)
   const int vswz = (qc >> 1) & 7;  // swizzle key of this lane's V^T rows (32*dt does not change it)
   const float sc = a.scale_log2e;
 
-  int buf = 0;
-  for (int64_t t0 = kv_begin; t0 < kv_end; t0 += TN, buf ^= 1) {
-    // the tile for this iteration has landed for every wavefront, and every wavefront is done
-    // with the other stage, which is refilled while this one is consumed
-    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
-    __syncthreads();
-    if (t0 + TN < kv_end) stage(t0 + TN, buf ^ 1);
-
-    // S^T = K Q^T for the two 32-row halves of the tile.  The K fragments are fetched from LDS in
-    // batches of 8 ahead of the MFMAs that use them, and the two accumulator chains alternate,
-    // so an MFMA neither waits for its own LDS read nor for the MFMA issued just before it.
+  // S^T = K Q^T (two 32-row halves of the tile), mask, running maximum, exponentials -> pb.
+  // LDS fragment reads run four MFMAs ahead (0x100 = LDS read, 0x008 = MFMA).
+  auto qk_softmax = [&](const bf16_t* kt, int64_t t0) {
     f32x16 s[2];
 #pragma unroll
     for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
       for (int r = 0; r < 16; ++r) s[sub][r] = 0.f;
 #pragma unroll
-    for (int half = 0; half < 2; ++half) {
-      bf16x8 ka[8];
+    for (int kk = 0; kk < 8; ++kk)
 #pragma unroll
-      for (int k4 = 0; k4 < 4; ++k4)
-#pragma unroll
-        for (int sub = 0; sub < 2; ++sub)
-          ka[2 * k4 + sub] = *reinterpret_cast<const bf16x8*>(
-              &sm.kv.k[buf][(32 * sub + krow) * HD + (((2 * (4 * half + k4) + hf) ^ kswz) << 3)]);
-#pragma unroll
-      for (int k4 = 0; k4 < 4; ++k4)
-#pragma unroll
-        for (int sub = 0; sub < 2; ++sub)
-          s[sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[2 * k4 + sub], qf[4 * half + k4], s[sub], 0, 0, 0);
-    }
-    // scheduling pattern for the block above: 4 LDS reads up front, then MFMA / LDS read pairs,
-    // then the last 4 MFMAs (0x100 = LDS read, 0x008 = MFMA)
+      for (int sub = 0; sub < 2; ++sub) {
+        const bf16x8 ka = *reinterpret_cast<const bf16x8*>(
+            &kt[(32 * sub + krow) * HD + (((2 * kk + hf) ^ kswz) << 3)]);
+        s[sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, c.qf[kk], s[sub], 0, 0, 0);
+      }
     __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
 #pragma unroll
     for (int i = 0; i < 12; ++i) {
@@ -359,7 +372,6 @@ __device__ __forceinline__ void flash_tile(const FlashArgs& a, FlashSmem& sm, in
     }
     __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
 
-    // mask (local window only) and column maximum of the raw scores
     float mx = -INFINITY;
 #pragma unroll
     for (int sub = 0; sub < 2; ++sub)
@@ -367,7 +379,7 @@ __device__ __forceinline__ void flash_tile(const FlashArgs& a, FlashSmem& sm, in
       for (int r = 0; r < 16; ++r) {
         if (LOCAL) {
           const int64_t t = t0 + 32 * sub + 16 * (r >> 3) + 8 * hf + (r & 7);
-          s[sub][r] = (t <= ci.i_q && t >= ci.lo_q) ? s[sub][r] : -INFINITY;
+          s[sub][r] = (t <= cur.i_q && t >= cur.lo_q) ? s[sub][r] : -INFINITY;
         }
         mx = fmaxf(mx, s[sub][r]);
       }
@@ -386,8 +398,6 @@ __device__ __forceinline__ void flash_tile(const FlashArgs& a, FlashSmem& sm, in
         for (int r = 0; r < 16; ++r) o[dt][r] *= alpha;
     }
     const float nm = m > -INFINITY ? -m : 0.f;  // whole column masked so far: exponentials are 0 anyway
-
-    bf16x8 pb[4];
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) {
       f32x8 p;
@@ -398,26 +408,17 @@ __device__ __forceinline__ void flash_tile(const FlashArgs& a, FlashSmem& sm, in
       }
       pb[ks] = __builtin_convertvector(p, bf16x8);
     }
-
-    // O^T += V^T P^T: the four V^T fragments of a k-step are fetched together, one step ahead
-    bf16x8 va[2][4];
+  };
+  // O^T += V^T P^T with the P^T fragments in pb
+  auto pv = [&](const bf16_t* vt) {
 #pragma unroll
-    for (int dt = 0; dt < 4; ++dt)
-      va[0][dt] = *reinterpret_cast<const bf16x8*>(
-          &sm.kv.vt[buf][(32 * dt + qc) * TN + (((0 + hf) ^ vswz) << 3)]);
+    for (int ks = 0; ks < 4; ++ks)
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-      if (ks + 1 < 4) {
-#pragma unroll
-        for (int dt = 0; dt < 4; ++dt)
-          va[(ks + 1) & 1][dt] = *reinterpret_cast<const bf16x8*>(
-              &sm.kv.vt[buf][(32 * dt + qc) * TN + (((2 * (ks + 1) + hf) ^ vswz) << 3)]);
+      for (int dt = 0; dt < 4; ++dt) {
+        const bf16x8 va = *reinterpret_cast<const bf16x8*>(
+            &vt[(32 * dt + qc) * TN + (((2 * ks + hf) ^ vswz) << 3)]);
+        o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb[ks], o[dt], 0, 0, 0);
       }
-#pragma unroll
-      for (int dt = 0; dt < 4; ++dt)
-        o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[ks & 1][dt], pb[ks], o[dt], 0, 0, 0);
-    }
-    // 4 LDS reads up front, then MFMA / LDS read pairs, then the last 4 MFMAs
     __builtin_amdgcn_sched_group_barrier(0x100, 4, 1);
 #pragma unroll
     for (int i = 0; i < 12; ++i) {
@@ -425,101 +426,162 @@ __device__ __forceinline__ void flash_tile(const FlashArgs& a, FlashSmem& sm, in
       __builtin_amdgcn_sched_group_barrier(0x100, 1, 1);
     }
     __builtin_amdgcn_sched_group_barrier(0x008, 4, 1);
-  }
+  };
 
-  // epilogue: normalise, stage the tile as [row][d] bf16 in LDS (the K/V stages are dead)
+  int kb = c.kb, vb = c.vb, vb_prev = c.vb;
+  for (int64_t t0 = cur.kv_begin; t0 < cur.kv_end; t0 += TN) {
+    // After the barrier the tile of this iteration is visible to every wavefront, every wavefront
+    // is done with the K stage of the previous tile and the late group with the V^T stage before
+    // that: exactly the stages that the next tile goes into.
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
+    __syncthreads();
+    const int kb1 = kb == kStagesK - 1 ? 0 : kb + 1, vb1 = vb == kStagesV - 1 ? 0 : vb + 1;
+    if (t0 + TN < cur.kv_end) stage(cur.kv, t0 + TN, kb1, vb1);
+    if (grp == 0) {
+      qk_softmax(ldsK + kb * kStageElems, t0);
+      pv(ldsV + vb * kStageElems);
+    } else {
+      if (t0 > cur.kv_begin) pv(ldsV + vb_prev * kStageElems);
+      qk_softmax(ldsK + kb * kStageElems, t0);
+    }
+    vb_prev = vb;
+    kb = kb1;
+    vb = vb1;
+  }
+  // Every wavefront is past its last QK: all K stages and the Q fragments are dead, and so is
+  // every V^T stage except the last tile's (the late group still owes its PV).  Request the next
+  // tile's first stage and Q fragments now; they land while this tile is written out.
+  __syncthreads();
+  c.kb = kb;
+  c.vb = vb;
+  c.primed = has_next;
+  if (has_next) {
+    stage(next.kv, next.kv_begin, kb, vb);
+    load_q(next.q_off);
+  }
+  if (grp == 1) pv(ldsV + vb_prev * kStageElems);  // the late group's last PV
+
+  // epilogue, wavefront-local (no workgroup barrier): normalise, stage the wavefront's 32 rows as
+  // [row][d] bf16 in its own slice of the group's LDS region (swizzled 16-byte pieces), then
+  // write 16 lanes per row, 16 bytes per lane.  LDS operations of one wavefront complete in
+  // issue order, so the reads below see the writes of the other lanes.
   const float lt = pair_sum(l);
   const float inv = 1.f / lt;
-  __syncthreads();
+  bf16_t* const ost = reinterpret_cast<bf16_t*>(lds + kLdsOut) + grp * TG * HD;
+  int64_t* const row_out = reinterpret_cast<int64_t*>(lds + kLdsRowOut) + grp * TG;
+  float* const row_lse = reinterpret_cast<float*>(lds + kLdsRowLse) + grp * TG;
   if (hf == 0) {
-    sm.ep.row_lse[qrow] = (m + __log2f(lt)) * kLn2;
-    sm.ep.row_out[qrow] = ci.row_out;
+    row_lse[srow] = (m + __log2f(lt)) * kLn2;
+    row_out[srow] = cur.row_out;
   }
 #pragma unroll
   for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
     for (int g4 = 0; g4 < 4; ++g4) {
-      const int d = 32 * dt + 8 * g4 + 4 * hf;
+      const int unit = (4 * dt + g4) ^ (srow & 15);
       f32x4 v;
 #pragma unroll
       for (int e = 0; e < 4; ++e) v[e] = o[dt][4 * g4 + e] * inv;
       const bf16x4 w = __builtin_convertvector(v, bf16x4);
-      *reinterpret_cast<bf16x4*>(&sm.ep.o[qrow * OSTR + d]) = w;
+      *reinterpret_cast<bf16x4*>(&ost[srow * HD + unit * 8 + 4 * hf]) = w;
     }
-  __syncthreads();
-
-  // 16 lanes per row, 16 bytes per lane
+  __builtin_amdgcn_wave_barrier();
 #pragma unroll
-  for (int pass = 0; pass < TM / 16; ++pass) {
-    const int row = pass * 16 + (tid >> 4), piece = tid & 15;
-    const int64_t out = sm.ep.row_out[row];
-    if (out >= 0) {
-      const uint4 mine = *reinterpret_cast<const uint4*>(&sm.ep.o[row * OSTR + piece * 8]);
-      *reinterpret_cast<uint4*>(a.part_o + out * HD + piece * 8) = mine;
-      if (piece == 0) a.part_lse[out] = sm.ep.row_lse[row];
+  for (int half = 0; half < 2; ++half) {
+    int64_t outs[4];
+    uint4 vals[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int row = w4 * 32 + (half * 4 + u) * 4 + (lane >> 4), piece = lane & 15;
+      outs[u] = row_out[row];
+      vals[u] = *reinterpret_cast<const uint4*>(&ost[row * HD + ((piece ^ (row & 15)) << 3)]);
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int row = w4 * 32 + (half * 4 + u) * 4 + (lane >> 4), piece = lane & 15;
+      if (outs[u] >= 0) {
+        *reinterpret_cast<uint4*>(a.part_o + outs[u] * HD + piece * 8) = vals[u];
+        if (piece == 0) a.part_lse[outs[u]] = row_lse[row];
+      }
     }
   }
-  __syncthreads();  // LDS is free again
+  __builtin_amdgcn_wave_barrier();
+  // No trailing barrier: a wavefront's output slice is private to it, and the K/V stages are
+  // handed over through c.kb / c.vb.
 }
 
-// Routed spans: persistent workgroups, each owning a contiguous range of the tile list.
-// Workgroups w, w+8, w+16, ... run on one XCD and own adjacent ranges, so the tiles of a bucket
-// are consumed by one XCD and share its L2 copy of the span.  The record and the item of the
-// next tile are fetched while the current tile is computed.
-__global__ __launch_bounds__(kFlashThreads, 2) void span_flash_routed_kernel(const FlashArgs a) {
-  __shared__ FlashSmem sm;
+// Routed spans: persistent workgroups walk the tile list.  XCD x (workgroups with
+// blockIdx % 8 == x) owns the contiguous chunk [x*T/8, (x+1)*T/8) of the tile list; its
+// workgroups walk the chunk interleaved, so at any moment they sit on neighbouring tiles -- the
+// same one or two buckets -- and share the span through that XCD's L2.  The record and the item
+// of a workgroup's next tile are fetched while its current tile is computed.
+__global__ __launch_bounds__(kFlashThreads, 1) void span_flash_routed_kernel(const FlashArgs a) {
+  extern __shared__ __align__(16) char lds[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int qrow = wave * 32 + (lane & 31);
+  const int qrow = (wave >> 2) * TG + (wave & 3) * 32 + (lane & 31);
   const int64_t T = a.tile_off[a.Hq / a.G * a.n];
-  const int NW = gridDim.x;  // a multiple of 8
-  const int range = (blockIdx.x % 8) * (NW / 8) + blockIdx.x / 8;
-  const int64_t t_begin = T * range / NW, t_end = T * (range + 1) / NW;
+  const int NWL = gridDim.x / 8;  // workgroups per XCD (the grid is a multiple of 8)
+  const int xcd = blockIdx.x % 8, wl = blockIdx.x / 8;
+  const int64_t c_begin = T * xcd / 8, c_end = T * (xcd + 1) / 8;
+  const int64_t t_begin = c_begin + wl, t_end = c_end;
   if (t_begin >= t_end) return;
 
-  int4 info = a.tile_info[t_begin];
-  int item = a.items[info.y + min(qrow, info.z - 1)];
-  for (int64_t t = t_begin; t < t_end; ++t) {
-    int4 next_info = info;
-    int next_item = item;
-    if (t + 1 < t_end) {
-      next_info = a.tile_info[t + 1];
-      next_item = a.items[next_info.y + min(qrow, next_info.z - 1)];
-    }
-    const int kv = info.x / a.n, j = info.x % a.n;
+  auto describe = [&](const int4& info, int item) {
+    TileDesc d;
+    d.kv = info.x / a.n;
+    const int j = info.x % a.n;
+    d.kv_begin = (int64_t)j * a.S;
+    d.kv_end = d.kv_begin + a.S;
     const int rowid = item >> 5, slot = item & 31;
     const int hl = rowid / (int)a.Lq;
     const int64_t r = rowid - (int64_t)hl * a.Lq;
-    const int h = kv * a.G + hl;
-    ColInfo ci;
-    ci.q_off = h * a.qsh + r * a.qst;
-    ci.row_out = qrow < info.z ? ((int64_t)h * a.Lq + r) * (a.topk + 1) + slot : -1;
-    ci.i_q = ci.lo_q = 0;
-    flash_tile<false>(a, sm, kv, (int64_t)j * a.S, (int64_t)(j + 1) * a.S, ci);
-    info = next_info;
-    item = next_item;
+    const int h = d.kv * a.G + hl;
+    d.q_off = h * a.qsh + r * a.qst;
+    d.row_out = qrow < info.z ? ((int64_t)h * a.Lq + r) * (a.topk + 1) + slot : -1;
+    d.i_q = d.lo_q = 0;
+    return d;
+  };
+  FlashCarry carry;
+  carry.kb = carry.vb = 0;
+  carry.primed = false;
+  int4 info = a.tile_info[t_begin];
+  TileDesc cur = describe(info, a.items[info.y + min(qrow, info.z - 1)]);
+  for (int64_t t = t_begin; t < t_end; t += NWL) {
+    const bool has_next = t + NWL < t_end;
+    TileDesc nxt = cur;
+    if (has_next) {
+      const int4 ninfo = a.tile_info[t + NWL];
+      nxt = describe(ninfo, a.items[ninfo.y + min(qrow, ninfo.z - 1)]);
+    }
+    flash_tile<false>(a, lds, cur, nxt, has_next, carry);
+    cur = nxt;
   }
 }
 
-// Local window [c*S, i]: regular 128-row tiles of one head with the causal / window mask.
-__global__ __launch_bounds__(kFlashThreads, 2) void span_flash_local_kernel(const FlashArgs a) {
-  __shared__ FlashSmem sm;
+// Local window [c*S, i]: regular 256-row tiles of one head with the causal / window mask.
+__global__ __launch_bounds__(kFlashThreads, 1) void span_flash_local_kernel(const FlashArgs a) {
+  extern __shared__ __align__(16) char lds[];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int qrow = wave * 32 + (lane & 31);
+  const int qrow = (wave >> 2) * TG + (wave & 3) * 32 + (lane & 31);
   const int tiles_per_head = (int)((a.Lq + TM - 1) / TM);
   const int h = blockIdx.x / tiles_per_head;
   const int64_t r0 = (int64_t)(blockIdx.x % tiles_per_head) * TM;
   const int64_t r = r0 + qrow;
   const int64_t rc = r < a.Lq ? r : a.Lq - 1;
-  ColInfo ci;
-  ci.q_off = h * a.qsh + rc * a.qst;
-  ci.row_out = r < a.Lq ? ((int64_t)h * a.Lq + r) * (a.topk + 1) + a.topk : -1;
-  ci.i_q = a.q_pos0 + rc;
-  ci.lo_q = (ci.i_q / a.S) * a.S;
+  TileDesc d;
+  d.kv = h / a.G;
+  d.q_off = h * a.qsh + rc * a.qst;
+  d.row_out = r < a.Lq ? ((int64_t)h * a.Lq + r) * (a.topk + 1) + a.topk : -1;
+  d.i_q = a.q_pos0 + rc;
+  d.lo_q = (d.i_q / a.S) * a.S;
   const int64_t i_first = a.q_pos0 + r0;
   const int64_t i_last = min(a.q_pos0 + r0 + TM - 1, a.q_pos0 + a.Lq - 1);
-  const int64_t kv_begin = (i_first / a.S) * a.S;
-  const int64_t kv_end = kv_begin + ((i_last - kv_begin) / TN + 1) * TN;
-  flash_tile<true>(a, sm, h / a.G, kv_begin, kv_end, ci);
+  d.kv_begin = (i_first / a.S) * a.S;
+  d.kv_end = d.kv_begin + ((i_last - d.kv_begin) / TN + 1) * TN;
+  FlashCarry carry;
+  carry.kb = carry.vb = 0;
+  carry.primed = false;
+  flash_tile<true>(a, lds, d, d, false, carry);
 }
 
 // ------------------------------------------------------------------ merge
@@ -592,7 +654,7 @@ struct MfmaWs {
   int64_t max_items;
 };
 
-// Two resident workgroups per compute unit (LDS and registers allow exactly two).
+// One resident workgroup of eight wavefronts per compute unit.
 int persistent_grid() {
   static int grid = 0;
   if (grid == 0) {
@@ -600,9 +662,23 @@ int persistent_grid() {
     if (hipGetDevice(&dev) != hipSuccess ||
         hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
       cus = 256;
-    grid = (2 * cus + 7) / 8 * 8;
+    grid = (cus + 7) / 8 * 8;
   }
   return grid;
+}
+
+// The flash kernels use more dynamic LDS than the 64 KB a kernel gets by default.
+bool allow_large_lds() {
+  static int done = 0;  // 0 = not yet, 1 = ok, -1 = failed
+  if (done == 0) {
+    const bool ok =
+        hipFuncSetAttribute(reinterpret_cast<const void*>(span_flash_routed_kernel),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, kFlashLdsBytes) == hipSuccess &&
+        hipFuncSetAttribute(reinterpret_cast<const void*>(span_flash_local_kernel),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, kFlashLdsBytes) == hipSuccess;
+    done = ok ? 1 : -1;
+  }
+  return done == 1;
 }
 
 MfmaWs carve(const Problem& pb) {
@@ -650,6 +726,7 @@ sl_status prefill_attention_mfma(const Problem& pb, const void* Q, const void* K
                                  const int32_t* idx, void* O, float* LSE, void* ws,
                                  hipStream_t st) {
   const MfmaWs w = carve(pb);
+  if (!allow_large_lds()) return SL_ERR_LAUNCH;
   char* base = static_cast<char*>(ws);
   bf16_t* Vt = reinterpret_cast<bf16_t*>(base + w.vt);
   int* counts = reinterpret_cast<int*>(base + w.counts);
@@ -705,12 +782,13 @@ sl_status prefill_attention_mfma(const Problem& pb, const void* Q, const void* K
                        counts, cursor, items, pb.Lq, pb.q_pos0, pb.G, pb.S, pb.topk, n);
     if (hipGetLastError() != hipSuccess) return SL_ERR_LAUNCH;
     if (pb.prof_start) (void)hipEventRecord(pb.prof_start, st);
-    hipLaunchKernelGGL(span_flash_routed_kernel, dim3(persistent_grid()), dim3(kFlashThreads), 0, st, a);
+    hipLaunchKernelGGL(span_flash_routed_kernel, dim3(persistent_grid()), dim3(kFlashThreads),
+                       kFlashLdsBytes, st, a);
     if (pb.prof_stop) (void)hipEventRecord(pb.prof_stop, st);
   }
   const int tiles_per_head = (int)((pb.Lq + TM - 1) / TM);
-  hipLaunchKernelGGL(span_flash_local_kernel, dim3(pb.Hq * tiles_per_head), dim3(kFlashThreads), 0,
-                     st, a);
+  hipLaunchKernelGGL(span_flash_local_kernel, dim3(pb.Hq * tiles_per_head), dim3(kFlashThreads),
+                     kFlashLdsBytes, st, a);
   const int64_t rows = (int64_t)pb.Hq * pb.Lq;
   const dim3 mgrid((unsigned)((rows + 15) / 16));
 #define SL_MERGE(KM)                                                                             \
