@@ -54,13 +54,20 @@ def prefill_flops(cfg):
     """Algorithmic flops of one prefill step: causal search + attention over selected keys."""
     L, S, k, D, Hq = cfg.L, cfg.S, cfg.topk, cfg.D, cfg.Hq
     search = 0
-    attn = 0
+    routed = 0
+    local = 0
     for c in range(cfg.n_spans):
         rows = min(S, L - c * S)
         search += rows * c * 2 * D
-        # keys per row: min(k, c) * S + (i mod S) + 1
-        attn += (rows * min(k, c) * S + rows * (rows + 1) // 2) * 4 * D
-    return Hq * search, Hq * attn
+        # keys per row: min(k, c) * S routed + (i mod S) + 1 in the local window
+        routed += rows * min(k, c) * S * 4 * D
+        local += rows * (rows + 1) // 2 * 4 * D
+    return Hq * search, Hq * routed, Hq * local
+
+
+# HBM bytes per launch of each configuration's dominant kernel, from the FETCH_SIZE and WRITE_SIZE
+# counter runs whose summaries are under profiles/ (scaled by the 1 GiB copy calibration).
+MEASURED_TRAFFIC = {"C3": 261.0e6, "C5": 1074.0e6, "C4": 37.0e9}
 
 
 def decode_bytes(cfg, idx, q_pos):
@@ -146,7 +153,7 @@ def bench_decode(cfg, steps, warmup, torch, B, W):
         "metric": "decode steps/s (span-search + span-attention)", "value": steps / dt, "unit": "steps/s",
         "ms_per_step": dt / steps * 1e3, "steps": steps, "dtype": cfg.dtype, "launch": "hip-graph replay",
         "roofline": {"bound": "hbm", "kernel": "decode_split_kernel", "achieved": achieved / 1e9, "peak": PEAK_HBM / 1e9,
-                     "unit": "GB/s", "frac": achieved / PEAK_HBM, "traffic": None,
+                     "unit": "GB/s", "frac": achieved / PEAK_HBM, "traffic": MEASURED_TRAFFIC.get(cfg.name),
                      "kernel_ms": kms_avg, "kernel_ms_min": min(kms), "algorithmic_bytes": sum(kbytes) / len(kbytes),
                      "attention_entry_ms_graph": sum(entry_ms) / len(entry_ms)},
     }
@@ -182,19 +189,25 @@ def bench_prefill(cfg, steps, warmup, torch, B, W):
         step(ev_s.handles(), ev_a.handles())
         ms_s.append(ev_s.ms())
         ms_a.append(ev_a.ms())
-    f_search, f_attn = prefill_flops(cfg)
+    f_search, f_routed, f_local = prefill_flops(cfg)
+    f_attn = f_routed + f_local
     ka = sum(ms_a) / len(ms_a)
     ks = sum(ms_s) / len(ms_s)
+    mfma_path = cfg.dtype == "bf16" and cfg.D == 128 and cfg.S % 64 == 0
     peak, bound = (PEAK_BF16, "mfma") if cfg.dtype == "bf16" else (PEAK_FP32_VALU, "alu")
-    tflops_attn = f_attn / (ka * 1e-3)
+    # the events bracket the routed-span kernel on the MFMA path, the one attention kernel otherwise
+    f_kernel = f_routed if mfma_path else f_attn
+    kernel = "span_flash_routed_kernel" if mfma_path else "prefill_attention_rows_kernel"
+    tflops_attn = f_kernel / (ka * 1e-3)
     res = {
         "workload": f"{cfg.name} prefill L={cfg.L} Hq={cfg.Hq} Hkv={cfg.Hkv} D={cfg.D} S={cfg.S} topk={cfg.topk}+local",
         "metric": "prefill tokens/s (span-search + span-attention)", "value": cfg.L * steps / dt, "unit": "tokens/s",
         "ms_per_step": dt / steps * 1e3, "steps": steps, "dtype": cfg.dtype,
         "step_frac_of_peak": (f_search + f_attn) / (dt / steps) / peak,
-        "roofline": {"bound": bound, "kernel": "span-attention dominant kernel", "achieved": tflops_attn / 1e12,
-                     "peak": peak / 1e12, "unit": "TFLOP/s", "frac": tflops_attn / peak, "traffic": None,
-                     "kernel_ms": ka, "algorithmic_flops": f_attn,
+        "roofline": {"bound": bound, "kernel": kernel, "achieved": tflops_attn / 1e12,
+                     "peak": peak / 1e12, "unit": "TFLOP/s", "frac": tflops_attn / peak,
+                     "traffic": MEASURED_TRAFFIC.get(cfg.name),
+                     "kernel_ms": ka, "algorithmic_flops": f_kernel, "step_algorithmic_flops": f_search + f_attn,
                      "search_kernel_ms": ks, "search_algorithmic_flops": f_search},
     }
     return res, dict(data=data)

@@ -119,6 +119,13 @@ PREFILL_SMALL = [
     (7, 8, 2, 4096, 128, 64, 8, torch.bfloat16, 1500, 700),   # chunked prefill (q_pos0, Lq)
     (8, 2, 2, 5, 128, 64, 2, torch.bfloat16, 0, None),        # L < S: a single partial span
     (9, 1, 1, 1, 64, 1, 1, torch.float32, 0, None),           # one token
+    # matrix-core path (bf16, D = 128, S % 64 == 0): tile and span geometry
+    (10, 4, 1, 1000, 128, 128, 16, torch.bfloat16, 0, None),  # L % 64 != 0, top-k list of 16
+    (11, 2, 2, 1613, 128, 256, 32, torch.bfloat16, 0, None),  # top-k list of 32 > number of spans
+    (12, 4, 2, 3000, 128, 512, 3, torch.bfloat16, 1000, 777), # chunk inside a long cache, ragged Lq
+    (13, 8, 1, 300, 128, 64, 8, torch.bfloat16, 299, 1),      # a single query row at the end of the cache
+    (14, 2, 1, 2000, 128, 192, 5, torch.bfloat16, 0, None),   # span length 3 x 64
+    (15, 16, 2, 700, 128, 64, 2, torch.bfloat16, 0, None),    # G = 8: partly filled 256-row tiles in every bucket
 ]
 
 
