@@ -86,7 +86,9 @@ typedef struct sl_params {
   int64_t kv_stride_h, kv_stride_t; /* element strides of K and V; 0 = packed                      */
   /* Optional profiling hooks: two caller-owned hipEvent_t handles.  When both are non-NULL the
    * call records prof_start immediately before, and prof_stop immediately after, its dominant
-   * kernel (the K/V-streaming kernel of span-attention, the scoring kernel of span-search). */
+   * kernel (the K/V-streaming kernel of span-attention, the scoring kernel of span-search); the
+   * decode span-attention entry point attaches them to that kernel's dispatch, so that they hold
+   * the kernel's own begin and end timestamps.  Do not pass them while the stream is capturing. */
   void* prof_start;
   void* prof_stop;
 } sl_params;

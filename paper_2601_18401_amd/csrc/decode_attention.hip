@@ -4,6 +4,8 @@
 // set of a head is its <= topk routed spans plus the local window, each a contiguous run of
 // K/V rows, so the step is a pure HBM stream: 2 flops per element read.  Work is cut into
 // (head, slot, chunk) items of CT tokens so that thousands of workgroups are in flight.
+#include <hip/hip_ext.h>
+
 #include "kernels.h"
 #include "stream_attend.h"
 
@@ -230,12 +232,22 @@ sl_status launch_decode(const Problem& pb, const void* Q, const void* K, const v
   const int local_stride = (int)align_up((size_t)pb.Hkv * nchunks, 8);
   const int grid = n_routed + pb.G * local_stride;
   float* part = static_cast<float*>(ws);
-  if (pb.prof_start) (void)hipEventRecord(pb.prof_start, st);
-  hipLaunchKernelGGL((decode_split_kernel<T, D>), dim3(grid), dim3(kDecodeThreads), 0, st,
-                     static_cast<const T*>(Q), static_cast<const T*>(K), static_cast<const T*>(V),
-                     idx, part, pb.q_pos0, pb.Hq, pb.Hkv, pb.S, pb.topk, nchunks, CT,
-                     pb.scale * kLog2e, pb.qsh, pb.kvsh, pb.kvst, n_routed, local_stride);
-  if (pb.prof_stop) (void)hipEventRecord(pb.prof_stop, st);
+  const float scale_log2e = pb.scale * kLog2e;
+  if (pb.prof_start) {
+    // With profiling events the launch itself carries them: they then hold the kernel's own
+    // begin and end timestamps (events recorded on the stream before / after a 45 us kernel would
+    // add the dispatch gaps, several microseconds).
+    hipExtLaunchKernelGGL((decode_split_kernel<T, D>), dim3(grid), dim3(kDecodeThreads), 0, st,
+                          pb.prof_start, pb.prof_stop, 0, static_cast<const T*>(Q),
+                          static_cast<const T*>(K), static_cast<const T*>(V), idx, part, pb.q_pos0,
+                          pb.Hq, pb.Hkv, pb.S, pb.topk, nchunks, CT, scale_log2e, pb.qsh, pb.kvsh,
+                          pb.kvst, n_routed, local_stride);
+  } else {
+    hipLaunchKernelGGL((decode_split_kernel<T, D>), dim3(grid), dim3(kDecodeThreads), 0, st,
+                       static_cast<const T*>(Q), static_cast<const T*>(K), static_cast<const T*>(V),
+                       idx, part, pb.q_pos0, pb.Hq, pb.Hkv, pb.S, pb.topk, nchunks, CT,
+                       scale_log2e, pb.qsh, pb.kvsh, pb.kvst, n_routed, local_stride);
+  }
   if (hipGetLastError() != hipSuccess) return SL_ERR_LAUNCH;
   const int nrec = (pb.topk + 1) * nchunks;
   hipLaunchKernelGGL((decode_reduce_kernel<T, D>), dim3(pb.Hq, D / kReduceDims), dim3(256),
