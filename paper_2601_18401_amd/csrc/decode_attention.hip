@@ -31,16 +31,19 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_split_kernel(
   const int G = Hq / Hkv;
   const int64_t c = q_pos / S;
   int h, slot, ck;
-  int bid = blockIdx.x;
-  if (bid < n_routed_blocks) {
+  // The local-window items come first in the grid: they are served by the L2 after their first
+  // reader, and at the end of the grid they would leave the HBM idle while the last of them run.
+  const int n_local_blocks = (int)gridDim.x - n_routed_blocks;
+  int bid = (int)blockIdx.x - n_local_blocks;
+  if (bid >= 0) {
     ck = bid % nchunks;
     const int u = bid / nchunks;
     h = u / topk;
     slot = u % topk;
   } else {
-    // Local-window items: the G heads of one kv head read the same rows; their block ids differ
-    // by a multiple of 8 so that they run on the same XCD and share its L2.
-    const int lid = bid - n_routed_blocks;
+    // The G heads of one kv head read the same rows; their block ids differ by a multiple of 8
+    // so that they run on the same XCD and share its L2.
+    const int lid = (int)blockIdx.x;
     const int hl = lid / local_stride, r = lid % local_stride;
     if (r >= Hkv * nchunks) return;
     const int kv = r / nchunks;
