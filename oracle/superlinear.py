@@ -27,6 +27,12 @@ and padded with -1; selection is per query head; the search score is the raw dot
 scale); attention uses one joint softmax over the union of the selected spans and the local
 window, scale 1/sqrt(D) unless given; LSE is the natural-log sum of exp(logit) over that set.
 
+* combination -- Section 3.4, eq. (5)-(6), and Algorithm 1's last steps: per selected span t the
+  attention A_t over J_t = DedupConcat(S_t, W) with its own softmax, then
+  O = sum_t alpha_t A_t with alpha = softmax of the search scores of the selected spans; with
+  nothing selected, attention over the window alone.  (The joint softmax above is what the
+  task statement fixes for span-attention; the gate is the paper's own output rule.)
+
 Every function is pinned by tests that do not call it back: brute-force dense causal
 attention, brute-force argsort, closed forms, a library softmax with an explicit mask, and
 hand-derived values stored under tests/golden/.
@@ -190,3 +196,60 @@ def merge_partials(os_, lses):
     w = np.exp(lses - M)
     tot = np.sum(w)
     return (w[:, None] * os_).sum(axis=0) / tot, M + math.log(tot)
+
+
+def gate_weights(scores_sel):
+    """Eq. (6): alpha = softmax over the search scores of the selected spans (fp64)."""
+    s = _f64(scores_sel)
+    e = np.exp(s - np.max(s))
+    return e / np.sum(e)
+
+
+def combined_row(q, K, V, kv: int, i: int, S: int, sel, sel_scores, scale: float, return_parts=False):
+    """Algorithm 1, the per-span attention and the gate, for one query row.
+
+    sel: selected span indices (entries < 0 or >= c are empty slots); sel_scores: the search
+    score of the span in the same slot.  For every valid slot t: J_t = span t followed by the
+    local window [c*S, i] (disjoint on the grid, so DedupConcat is a concatenation) and
+    A_t = softmax-attention of q over J_t (eq. (4)).  O = sum_t alpha_t A_t (eq. (5)) with
+    alpha from eq. (6).  No valid slot: attention over the window only.  Returns o [D] (fp64);
+    with return_parts also (alpha, [A_t], valid slot numbers).
+    """
+    q = _f64(q)
+    c = i // S
+    Kw, Vw = _f64(K[kv, c * S:i + 1]), _f64(V[kv, c * S:i + 1])
+    slots = [n for n, j in enumerate(sel) if 0 <= int(j) < c]
+
+    def attend(Kj, Vj):
+        z = scale * (Kj @ q)
+        e = np.exp(z - np.max(z))
+        return (e @ Vj) / np.sum(e)
+
+    if not slots:
+        o = attend(Kw, Vw)
+        return (o, np.zeros(0), [], []) if return_parts else o
+    A = []
+    for n in slots:
+        j = int(sel[n])
+        Kj = np.concatenate([_f64(K[kv, j * S:(j + 1) * S]), Kw], axis=0)
+        Vj = np.concatenate([_f64(V[kv, j * S:(j + 1) * S]), Vw], axis=0)
+        A.append(attend(Kj, Vj))
+    alpha = gate_weights([sel_scores[n] for n in slots])
+    o = np.zeros_like(A[0])
+    for a, At in zip(alpha, A):
+        o = o + a * At
+    return (o, alpha, A, slots) if return_parts else o
+
+
+def span_attention_combined(Q, K, V, idx, scores, S: int, scale: float | None = None, q_pos0: int = 0):
+    """combined_row for every (head, query row): O [Hq, Lq, D], fp64.  idx, scores: [Hq, Lq, k]."""
+    Q = np.asarray(Q)
+    Hq, Lq, D = Q.shape
+    G = Hq // K.shape[0]
+    if scale is None:
+        scale = 1.0 / math.sqrt(D)
+    O = np.zeros((Hq, Lq, D), dtype=F64)
+    for h in range(Hq):
+        for r in range(Lq):
+            O[h, r] = combined_row(Q[h, r], K, V, h // G, q_pos0 + r, S, idx[h, r], scores[h, r], scale)
+    return O

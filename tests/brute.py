@@ -46,3 +46,32 @@ def argsort_topk(scores, k):
     scores = np.asarray(scores, dtype=np.float64)
     order = np.argsort(-scores, kind="stable")
     return np.sort(order[:k])
+
+
+def gated_combination(Q, K, V, idx, scores, S, scale, q_pos0=0):
+    """Algorithm 1's output rule by full masked matrices: one dense masked softmax per slot over
+    (span of the slot) | (local window), library softmax over the slot scores, weighted sum.
+    Rows without a valid slot get the window-only attention.  Q [Hq,Lq,D]; idx, scores [Hq,Lq,k]."""
+    Q = np.asarray(Q, dtype=np.float64)
+    Hq, Lq, _ = Q.shape
+    L = K.shape[1]
+    k = idx.shape[2]
+    pos = q_pos0 + np.arange(Lq)
+    c = pos // S
+    t = np.arange(L)[None, None, :]
+    window = (t >= (c * S)[None, :, None]) & (t <= pos[None, :, None])
+    window = np.broadcast_to(window, (Hq, Lq, L))
+    valid = (idx >= 0) & (idx < c[None, :, None])                       # [Hq,Lq,k]
+    gate_logits = np.where(valid, np.asarray(scores, dtype=np.float64), -np.inf)
+    any_valid = valid.any(axis=-1)
+    alpha = np.zeros((Hq, Lq, k))
+    alpha[any_valid] = softmax(gate_logits[any_valid], axis=-1)
+    O = np.zeros(Q.shape)
+    for n in range(k):
+        j = idx[:, :, n]
+        in_span = (t >= (j * S)[:, :, None]) & (t < ((j + 1) * S)[:, :, None]) & valid[:, :, n, None]
+        A, _, _ = dense_masked_attention(Q, K, V, in_span | window, scale)
+        O += alpha[:, :, n, None] * A
+    Aw, _, _ = dense_masked_attention(Q, K, V, window, scale)
+    O[~any_valid] = Aw[~any_valid]
+    return O, alpha

@@ -267,3 +267,86 @@ def test_random_context_access_cover():
             for (t0, t1) in orc.attended_ranges(i, S, list(range(c))):
                 cover |= set(range(t0, t1))
             assert cover == set(range(i + 1))
+
+
+# ---------------------------------------------------------------- combination (Section 3.4, eq. (5)-(6))
+
+def _searched(seed, Hq, Hkv, L, D, S, k):
+    Q, K, V = _rand(seed, Hq, Hkv, L, D)
+    idx, sc = orc.span_search(Q, orc.span_keys(K, S), S, k, return_scores=True)
+    return Q, K, V, idx, sc
+
+
+@pytest.mark.parametrize("seed,Hq,Hkv,L,D,S,k", [(0, 4, 2, 40, 8, 5, 3), (1, 2, 1, 33, 4, 4, 8), (2, 3, 3, 24, 8, 6, 1)])
+def test_combination_equals_dense_per_slot_bruteforce(seed, Hq, Hkv, L, D, S, k):
+    # one full masked softmax per slot + library softmax over the slot scores
+    Q, K, V, idx, sc = _searched(30 + seed, Hq, Hkv, L, D, S, k)
+    O = orc.span_attention_combined(Q, K, V, idx, sc, S, scale=0.4)
+    Ob, alpha = brute.gated_combination(Q, K, V, idx, sc, S, 0.4)
+    assert np.allclose(O, Ob, rtol=1e-12, atol=1e-13)
+    # gate weights of every row with a selection sum to one
+    has = (idx >= 0).any(axis=-1)
+    assert np.allclose(alpha.sum(-1)[has], 1.0, atol=1e-14)
+
+
+def test_combination_with_one_span_is_the_joint_softmax():
+    # k = 1: alpha = 1 and J_t = span | window is the whole attended set, so the gated output is
+    # eq. (4) over that set -- the same masked dense attention that pins attention_row
+    Hq, Hkv, L, D, S = 2, 1, 36, 8, 6
+    Q, K, V, idx, sc = _searched(40, Hq, Hkv, L, D, S, 1)
+    O = orc.span_attention_combined(Q, K, V, idx, sc, S, scale=0.7)
+    Od, _, _ = brute.dense_masked_attention(Q, K, V, brute.span_mask(idx, S, L), 0.7)
+    assert np.allclose(O, Od, rtol=1e-12, atol=1e-13)
+
+
+def test_combination_empty_selection_is_window_attention():
+    # rows of the first span have no candidate: Algorithm 1's window-only branch = block-diagonal causal
+    Hq, Hkv, L, D, S = 2, 2, 12, 4, 6
+    Q, K, V = _rand(41, Hq, Hkv, L, D)
+    idx = np.full((Hq, L, 2), -1, dtype=np.int32)
+    sc = np.full((Hq, L, 2), -np.inf)
+    O = orc.span_attention_combined(Q, K, V, idx, sc, S, scale=0.5)
+    Od, _, _ = brute.dense_masked_attention(Q, K, V, brute.span_mask(idx, S, L), 0.5)
+    assert np.allclose(O, Od, rtol=1e-12, atol=1e-13)
+
+
+def test_gate_weights_closed_forms():
+    # equal scores -> uniform; two scores -> logistic of their difference; shift invariance
+    assert np.allclose(orc.gate_weights([2.5, 2.5, 2.5, 2.5]), 0.25)
+    a = orc.gate_weights([1.0, 3.0])
+    assert a[1] == pytest.approx(1.0 / (1.0 + math.exp(-2.0)), abs=1e-15)
+    assert a.sum() == pytest.approx(1.0, abs=1e-15)
+    assert np.allclose(orc.gate_weights([1.0, 3.0, -2.0]), orc.gate_weights([101.0, 103.0, 98.0]), atol=1e-15)
+    # the scores are used as they are (no 1/sqrt(D), eq. (6)): a gap of 50 saturates the gate
+    assert orc.gate_weights([50.0, 0.0])[0] == pytest.approx(1.0, abs=1e-20)
+
+
+def test_combination_equal_scores_is_mean_of_span_outputs_and_slot_order_free():
+    Hq, Hkv, L, D, S, k = 1, 1, 40, 8, 5, 3
+    Q, K, V = _rand(42, Hq, Hkv, L, D)
+    i, sel = 37, [1, 4, 6]
+    o, alpha, A, slots = orc.combined_row(Q[0, i], K, V, 0, i, S, sel, [0.3, 0.3, 0.3], 0.5, return_parts=True)
+    assert np.allclose(alpha, 1 / 3) and slots == [0, 1, 2]
+    assert np.allclose(o, np.mean(A, axis=0), rtol=1e-13)
+    # each A_t is the one-span attention (masked dense over span | window)
+    for t, At in zip(sel, A):
+        ref, _, _ = brute.dense_masked_attention(Q[:, i:i + 1], K, V,
+                                                brute.span_mask(np.array([[[t]]]), S, L, q_pos0=i), 0.5)
+        assert np.allclose(At, ref[0, 0], rtol=1e-12, atol=1e-13)
+    # permuting the slots together with their scores changes nothing; empty slots are skipped
+    o1 = orc.combined_row(Q[0, i], K, V, 0, i, S, [6, -1, 1, 4], [0.9, 123.0, -0.2, 0.1], 0.5)
+    o2 = orc.combined_row(Q[0, i], K, V, 0, i, S, [1, 4, 6, 9], [-0.2, 0.1, 0.9, 55.0], 0.5)  # 9 >= c: empty
+    assert np.allclose(o1, o2, rtol=1e-13, atol=1e-14)
+
+
+def test_combination_identical_spans_collapse():
+    # if every selected span holds the same keys and values, all A_t coincide and O = A_t whatever the gate
+    Hq, Hkv, L, D, S = 1, 1, 30, 4, 5
+    Q, K, V = _rand(43, Hq, Hkv, L, D)
+    for j in (1, 2):
+        K[0, j * S:(j + 1) * S] = K[0, 0:S]
+        V[0, j * S:(j + 1) * S] = V[0, 0:S]
+    i = 28
+    o = orc.combined_row(Q[0, i], K, V, 0, i, S, [0, 1, 2], [5.0, -1.0, 0.2], 0.6)
+    one = orc.combined_row(Q[0, i], K, V, 0, i, S, [2], [0.0], 0.6)
+    assert np.allclose(o, one, rtol=1e-13, atol=1e-14)
