@@ -120,6 +120,29 @@ def bench_decode(cfg, steps, warmup, torch, B, W):
         graph.replay()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
+    # The combination form of the same steps (search with scores, gated reduction), same replay.
+    outs_c = [torch.empty((cfg.Hq, 1, cfg.D), dtype=K.dtype, device=dev) for _ in range(N_DECODE_QUERIES)]
+
+    def step_combined(i):
+        q = Qs[i % N_DECODE_QUERIES]
+        idx, sc = B.sl_span_search_decode(q, K, Ks, cfg.S, cfg.topk, want_scores=True, ws=ws)
+        B.sl_span_attention_combined_decode(q, K, V, idx, sc, cfg.S, ws=ws, out=outs_c[i % N_DECODE_QUERIES])
+
+    for i in range(N_DECODE_QUERIES):
+        step_combined(i)
+    torch.cuda.synchronize()
+    cgraph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(cgraph):
+        for i in range(N_DECODE_QUERIES):
+            step_combined(i)
+    cgraph.replay()
+    torch.cuda.synchronize()
+    tc = time.perf_counter()
+    nrep = max(1, steps // N_DECODE_QUERIES // 2)
+    for _ in range(nrep):
+        cgraph.replay()
+    torch.cuda.synchronize()
+    dt_combined = (time.perf_counter() - tc) / (nrep * N_DECODE_QUERIES)
     # Dominant kernel (K/V streaming + fused merge): a graph of N_DECODE_QUERIES back-to-back
     # span-attention launches, timed with HIP events on the launch stream.
     idx_dev = [torch.from_numpy(ix).to(dev) for ix in idxs]
@@ -157,6 +180,7 @@ def bench_decode(cfg, steps, warmup, torch, B, W):
         "workload": f"{cfg.name} decode L={cfg.L} Hq={cfg.Hq} Hkv={cfg.Hkv} D={cfg.D} S={cfg.S} topk={cfg.topk}+local",
         "metric": "decode steps/s (span-search + span-attention)", "value": steps / dt, "unit": "steps/s",
         "ms_per_step": dt / steps * 1e3, "steps": steps, "dtype": cfg.dtype, "launch": "hip-graph replay",
+        "combined_form": {"ms_per_step": dt_combined * 1e3, "value": 1.0 / dt_combined, "unit": "steps/s"},
         "roofline": {"bound": "hbm", "kernel": "decode_split_kernel", "achieved": achieved / 1e9, "peak": PEAK_HBM / 1e9,
                      "unit": "GB/s", "frac": achieved / PEAK_HBM, "traffic": MEASURED_TRAFFIC.get(cfg.name),
                      "kernel_ms": kms_avg, "kernel_ms_min": min(kms), "algorithmic_bytes": sum(kbytes) / len(kbytes),
@@ -194,6 +218,20 @@ def bench_prefill(cfg, steps, warmup, torch, B, W):
         step(ev_s.handles(), ev_a.handles())
         ms_s.append(ev_s.ms())
         ms_a.append(ev_a.ms())
+    # the combination form (per-span softmaxes gated by the search scores) of the same step
+    def step_combined():
+        B.sl_span_keys(K, cfg.S, out=Ks)
+        idx, sc = B.sl_span_search_prefill(Qs, K, Ks, cfg.S, cfg.topk, want_scores=True, ws=ws)
+        B.sl_span_attention_combined_prefill(Q, K, V, idx, sc, cfg.S, ws=ws, out=out[0])
+
+    step_combined()
+    torch.cuda.synchronize()
+    tc = time.perf_counter()
+    nc = max(1, min(steps, 3))
+    for _ in range(nc):
+        step_combined()
+    torch.cuda.synchronize()
+    dt_combined = (time.perf_counter() - tc) / nc
     f_search, f_routed, f_local = prefill_flops(cfg)
     f_attn = f_routed + f_local
     ka = sum(ms_a) / len(ms_a)
@@ -209,6 +247,7 @@ def bench_prefill(cfg, steps, warmup, torch, B, W):
         "metric": "prefill tokens/s (span-search + span-attention)", "value": cfg.L * steps / dt, "unit": "tokens/s",
         "ms_per_step": dt / steps * 1e3, "steps": steps, "dtype": cfg.dtype,
         "step_frac_of_peak": (f_search + f_attn) / (dt / steps) / peak,
+        "combined_form": {"ms_per_step": dt_combined * 1e3, "value": cfg.L / dt_combined, "unit": "tokens/s"},
         "roofline": {"bound": bound, "kernel": kernel, "achieved": tflops_attn / 1e12,
                      "peak": peak / 1e12, "unit": "TFLOP/s", "frac": tflops_attn / peak,
                      "traffic": MEASURED_TRAFFIC.get(cfg.name),

@@ -11,6 +11,9 @@
  *                  and the empty-selection branch): exact softmax attention of the query over
  *                  the union of the selected spans and its local window; returns the output
  *                  and the log-sum-exp of the logits.
+ *   combination    (paper Section 3.4, eq. (5) and (6); Algorithm 1's last two steps), as a
+ *                  second form of span-attention: one softmax per selected span (merged with
+ *                  the local window), gated by the softmax of the selected search scores.
  *
  * Geometry.  Tokens 0 .. L-1; span j is the token range [j*S, min((j+1)*S, L) - 1]; its anchor
  * (search position) is its last token (j+1)*S - 1 (Algorithm 1's span [t - b*l, t + f*l] with
@@ -143,6 +146,26 @@ sl_status sl_span_attention_prefill(const sl_params* p, const void* Q, const voi
 sl_status sl_span_attention_decode(const sl_params* p, const void* Q, const void* K, const void* V,
                                    const int32_t* idx, void* O, float* LSE, void* ws,
                                    size_t ws_bytes, void* hip_stream);
+
+/* Span-attention with the paper's combination step (Section 3.4, eq. (5) and (6); Algorithm 1:
+ * DedupConcat + Attention per selected span, Softmax over the selected scores, weighted sum).
+ * For each (h, r) and each non-empty slot t of idx: A_t = softmax attention of the query over
+ * span idx[h][r][t] followed by the local window [c*S, i] (its own softmax, logits
+ * scale * <Q, K_j>); O = sum_t alpha_t A_t with alpha = softmax over the non-empty slots of
+ * scores[h][r][t] (the raw search scores, as eq. (6) uses them).  A row without a non-empty slot
+ * gets the attention over its local window (Algorithm 1's empty-selection branch).
+ *   idx     in: as for sl_span_attention_* (entries < 0 or >= c are empty slots).
+ *   scores  in: [Hq][Lq][topk] float, the `scores` output of span-search for the same idx; only
+ *           the entries of non-empty slots are read and they must be finite.
+ *   O       out: [Hq][Lq][D] in the input dtype.  (No LSE: the output is a mixture of softmaxes.)
+ * Workspace: the same as the span-attention entry point of the same form
+ * (SL_OP_ATTENTION_PREFILL / SL_OP_ATTENTION_DECODE).  The decode form requires Lq == 1. */
+sl_status sl_span_attention_combined_prefill(const sl_params* p, const void* Q, const void* K,
+                                             const void* V, const int32_t* idx, const float* scores,
+                                             void* O, void* ws, size_t ws_bytes, void* hip_stream);
+sl_status sl_span_attention_combined_decode(const sl_params* p, const void* Q, const void* K,
+                                            const void* V, const int32_t* idx, const float* scores,
+                                            void* O, void* ws, size_t ws_bytes, void* hip_stream);
 
 /* Static, human-readable name of a status code. */
 const char* sl_status_string(int status);

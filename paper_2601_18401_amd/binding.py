@@ -21,7 +21,8 @@ OP_SEARCH_PREFILL, OP_SEARCH_DECODE, OP_ATTENTION_PREFILL, OP_ATTENTION_DECODE =
 SL_MAX_TOPK = 32
 
 EXPORTS = ("sl_workspace_bytes", "sl_span_keys", "sl_span_search_prefill", "sl_span_search_decode",
-           "sl_span_attention_prefill", "sl_span_attention_decode", "sl_status_string", "sl_version")
+           "sl_span_attention_prefill", "sl_span_attention_decode", "sl_span_attention_combined_prefill",
+           "sl_span_attention_combined_decode", "sl_status_string", "sl_version")
 
 
 class SlParams(ctypes.Structure):
@@ -69,6 +70,10 @@ def load():
         fn = getattr(lib, name)
         fn.restype = ctypes.c_int
         fn.argtypes = [pp, vp, vp, vp, i32p, vp, f32p, vp, ctypes.c_size_t, vp]
+    for name in ("sl_span_attention_combined_prefill", "sl_span_attention_combined_decode"):
+        fn = getattr(lib, name)
+        fn.restype = ctypes.c_int
+        fn.argtypes = [pp, vp, vp, vp, i32p, f32p, vp, vp, ctypes.c_size_t, vp]
     lib.sl_status_string.restype = ctypes.c_char_p
     lib.sl_status_string.argtypes = [ctypes.c_int]
     lib.sl_version.restype = ctypes.c_int
@@ -203,6 +208,35 @@ def _attention(fn_name, op, Q, K, V, idx, S, q_pos0, scale, ws, prof, out):
                                wptr, wbytes, _stream())
     _check(st, fn_name)
     return O, LSE
+
+
+def _combined(fn_name, op, Q, K, V, idx, scores, S, q_pos0, scale, ws, out):
+    lib = load()
+    topk = 0 if idx is None else idx.shape[2]
+    p = make_params(Q, K, S, topk, q_pos0, scale)
+    if V.shape != K.shape or V.stride() != K.stride():
+        raise ValueError("V must have the shape and strides of K")
+    if topk > 0 and (scores is None or scores.shape != idx.shape or scores.dtype != torch.float32
+                     or not scores.is_contiguous()):
+        raise ValueError("scores must be a contiguous float32 tensor of the shape of idx")
+    Hq, Lq, D = Q.shape
+    O = torch.empty((Hq, Lq, D), dtype=Q.dtype, device=Q.device) if out is None else out
+    wptr, wbytes = _ws(ws).get(workspace_bytes(p, op))
+    st = getattr(lib, fn_name)(ctypes.byref(p), _ptr(Q), _ptr(K), _ptr(V), _ptr(idx), _ptr(scores), _ptr(O),
+                               wptr, wbytes, _stream())
+    _check(st, fn_name)
+    return O
+
+
+def sl_span_attention_combined_prefill(Q, K, V, idx, scores, S, q_pos0=0, scale=0.0, ws=None, out=None):
+    return _combined("sl_span_attention_combined_prefill", OP_ATTENTION_PREFILL, Q, K, V, idx, scores, S,
+                     q_pos0, scale, ws, out)
+
+
+def sl_span_attention_combined_decode(Q, K, V, idx, scores, S, q_pos0=None, scale=0.0, ws=None, out=None):
+    q_pos0 = K.shape[1] - 1 if q_pos0 is None else q_pos0
+    return _combined("sl_span_attention_combined_decode", OP_ATTENTION_DECODE, Q, K, V, idx, scores, S,
+                     q_pos0, scale, ws, out)
 
 
 def sl_span_attention_prefill(Q, K, V, idx, S, q_pos0=0, scale=0.0, ws=None, prof=None, out=None):

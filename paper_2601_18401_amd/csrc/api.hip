@@ -58,6 +58,8 @@ sl_status make_problem(const sl_params* p, int op, Problem* pb) {
   const bool prof = p->prof_start && p->prof_stop;
   pb->prof_start = prof ? static_cast<hipEvent_t>(p->prof_start) : nullptr;
   pb->prof_stop = prof ? static_cast<hipEvent_t>(p->prof_stop) : nullptr;
+  pb->combined = false;
+  pb->gate = nullptr;
   return SL_OK;
 }
 
@@ -94,17 +96,20 @@ sl_status search_entry(const sl_params* p, int op, const void* Qs, const void* K
   return prefill_search(pb, Qs, K, Ks, idx, scores, ws, st);
 }
 
+// `combined`: the gated form (scores required when topk > 0, no LSE); otherwise LSE is required.
 sl_status attention_entry(const sl_params* p, int op, const void* Q, const void* K, const void* V,
-                          const int32_t* idx, void* O, float* LSE, void* ws, size_t ws_bytes,
-                          void* stream) {
+                          const int32_t* idx, const float* scores, bool combined, void* O,
+                          float* LSE, void* ws, size_t ws_bytes, void* stream) {
   Problem pb;
   sl_status s = make_problem(p, op, &pb);
   if (s != SL_OK) return s;
-  if (!Q || !K || !V || !O || !LSE) return SL_ERR_INVALID_ARG;
-  if (pb.topk > 0 && !idx) return SL_ERR_INVALID_ARG;
+  if (!Q || !K || !V || !O || (!combined && !LSE)) return SL_ERR_INVALID_ARG;
+  if (pb.topk > 0 && (!idx || (combined && !scores))) return SL_ERR_INVALID_ARG;
   if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O) || !aligned16(idx) ||
-      !aligned16(LSE))
+      !aligned16(LSE) || !aligned16(scores))
     return SL_ERR_INVALID_ARG;
+  pb.combined = combined;
+  pb.gate = scores;
   s = check_ws(pb, op, ws, ws_bytes);
   if (s != SL_OK) return s;
   hipStream_t st = static_cast<hipStream_t>(stream);
@@ -155,15 +160,29 @@ sl_status sl_span_search_decode(const sl_params* p, const void* Qs, const void* 
 sl_status sl_span_attention_prefill(const sl_params* p, const void* Q, const void* K, const void* V,
                                     const int32_t* idx, void* O, float* LSE, void* ws,
                                     size_t ws_bytes, void* hip_stream) {
-  return sl::attention_entry(p, SL_OP_ATTENTION_PREFILL, Q, K, V, idx, O, LSE, ws, ws_bytes,
-                             hip_stream);
+  return sl::attention_entry(p, SL_OP_ATTENTION_PREFILL, Q, K, V, idx, nullptr, false, O, LSE, ws,
+                             ws_bytes, hip_stream);
 }
 
 sl_status sl_span_attention_decode(const sl_params* p, const void* Q, const void* K, const void* V,
                                    const int32_t* idx, void* O, float* LSE, void* ws,
                                    size_t ws_bytes, void* hip_stream) {
-  return sl::attention_entry(p, SL_OP_ATTENTION_DECODE, Q, K, V, idx, O, LSE, ws, ws_bytes,
-                             hip_stream);
+  return sl::attention_entry(p, SL_OP_ATTENTION_DECODE, Q, K, V, idx, nullptr, false, O, LSE, ws,
+                             ws_bytes, hip_stream);
+}
+
+sl_status sl_span_attention_combined_prefill(const sl_params* p, const void* Q, const void* K,
+                                             const void* V, const int32_t* idx, const float* scores,
+                                             void* O, void* ws, size_t ws_bytes, void* hip_stream) {
+  return sl::attention_entry(p, SL_OP_ATTENTION_PREFILL, Q, K, V, idx, scores, true, O, nullptr, ws,
+                             ws_bytes, hip_stream);
+}
+
+sl_status sl_span_attention_combined_decode(const sl_params* p, const void* Q, const void* K,
+                                            const void* V, const int32_t* idx, const float* scores,
+                                            void* O, void* ws, size_t ws_bytes, void* hip_stream) {
+  return sl::attention_entry(p, SL_OP_ATTENTION_DECODE, Q, K, V, idx, scores, true, O, nullptr, ws,
+                             ws_bytes, hip_stream);
 }
 
 const char* sl_status_string(int status) {

@@ -9,6 +9,28 @@ namespace sl {
 
 namespace {
 
+// Merges the row groups of a wavefront (lanes with equal lane % LPR hold the same d-slice); on
+// return every lane holds the state of all rows the wavefront attended.
+template <typename T, int D>
+__device__ __forceinline__ void merge_row_groups(AttendState<T, D>& st) {
+  constexpr int EPL = RowLayout<T, D>::EPL, LPR = RowLayout<T, D>::LPR;
+#pragma unroll
+  for (int off = LPR; off < 64; off <<= 1) {
+    const float mo = __shfl_xor(st.m, off, 64);
+    const float lo = __shfl_xor(st.l, off, 64);
+    const float M = fmaxf(st.m, mo);
+    const float wa = st.m > -INFINITY ? fast_exp2(st.m - M) : 0.f;
+    const float wb = mo > -INFINITY ? fast_exp2(mo - M) : 0.f;
+    st.l = st.l * wa + lo * wb;
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) {
+      const float oo = __shfl_xor(st.o[e], off, 64);
+      st.o[e] = st.o[e] * wa + oo * wb;
+    }
+    st.m = M;
+  }
+}
+
 template <typename T, int D>
 __global__ __launch_bounds__(256) void prefill_attention_rows_kernel(
     const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
@@ -42,22 +64,7 @@ __global__ __launch_bounds__(256) void prefill_attention_rows_kernel(
   }
   attend_range<T, D, 4>(q2, Kb, Vb, kvst, c * S, i + 1, lane, st);
 
-  // merge the row groups of the wavefront (lanes with equal lane % LPR hold the same d-slice)
-#pragma unroll
-  for (int off = LPR; off < 64; off <<= 1) {
-    const float mo = __shfl_xor(st.m, off, 64);
-    const float lo = __shfl_xor(st.l, off, 64);
-    const float M = fmaxf(st.m, mo);
-    const float wa = st.m > -INFINITY ? fast_exp2(st.m - M) : 0.f;
-    const float wb = mo > -INFINITY ? fast_exp2(mo - M) : 0.f;
-    st.l = st.l * wa + lo * wb;
-#pragma unroll
-    for (int e = 0; e < EPL; ++e) {
-      const float oo = __shfl_xor(st.o[e], off, 64);
-      st.o[e] = st.o[e] * wa + oo * wb;
-    }
-    st.m = M;
-  }
+  merge_row_groups<T, D>(st);
   if (lane < LPR) {
     const float inv = 1.f / st.l;  // the local window always holds the query's own token: l > 0
     T* op = O + row * D + lr * EPL;
@@ -67,11 +74,89 @@ __global__ __launch_bounds__(256) void prefill_attention_rows_kernel(
   }
 }
 
+
+// Combination form (Section 3.4, eq. (5)-(6); Algorithm 1): per valid slot t the attention A_t
+// over span t and the local window with its own softmax, O = sum_t alpha_t A_t with
+// alpha = softmax of the slots' search scores; no valid slot: the window alone.  The window is
+// streamed once and its (m, l, o) state is merged into every span's state.
+template <typename T, int D>
+__global__ __launch_bounds__(256) void prefill_combined_rows_kernel(
+    const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
+    const int32_t* __restrict__ idx, const float* __restrict__ gate, T* __restrict__ O, int64_t Lq,
+    int64_t q_pos0, int Hq, int G, int S, int topk, float scale_log2e, int64_t qsh, int64_t qst,
+    int64_t kvsh, int64_t kvst) {
+  using RL = RowLayout<T, D>;
+  constexpr int EPL = RL::EPL, LPR = RL::LPR;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int64_t row = (int64_t)blockIdx.x * 4 + wave;
+  if (row >= (int64_t)Hq * Lq) return;
+  const int h = (int)(row / Lq);
+  const int64_t r = row % Lq, i = q_pos0 + r;
+  const int kv = h / G;
+  const int64_t c = i / S;
+  const int lr = lane % LPR;
+  float q2[EPL];
+  {
+    float qf[EPL];
+    Elem<T>::unpack(load16(Q + h * qsh + r * qst + lr * EPL), qf);
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) q2[e] = qf[e] * scale_log2e;
+  }
+  const T* Kb = K + kv * kvsh;
+  const T* Vb = V + kv * kvsh;
+  AttendState<T, D> win;
+  win.init();
+  attend_range<T, D, 4>(q2, Kb, Vb, kvst, c * S, i + 1, lane, win);
+  merge_row_groups<T, D>(win);  // the window always holds the query's own token: win.l > 0
+
+  // gate: softmax of the scores of the valid slots
+  float smax = -INFINITY;
+  for (int slot = 0; slot < topk; ++slot) {
+    const int64_t j = idx[row * topk + slot];
+    if (j >= 0 && j < c) smax = fmaxf(smax, gate[row * topk + slot]);
+  }
+  float acc[EPL];
+#pragma unroll
+  for (int e = 0; e < EPL; ++e) acc[e] = 0.f;
+  float asum = 0.f;
+  for (int slot = 0; slot < topk; ++slot) {
+    const int64_t j = idx[row * topk + slot];
+    if (!(j >= 0 && j < c)) continue;
+    AttendState<T, D> st;
+    st.init();
+    attend_range<T, D, 4>(q2, Kb, Vb, kvst, j * S, (j + 1) * S, lane, st);
+    merge_row_groups<T, D>(st);
+    const float M = fmaxf(st.m, win.m);
+    const float wa = fast_exp2(st.m - M), wb = fast_exp2(win.m - M);
+    const float a = __expf(gate[row * topk + slot] - smax);
+    const float f = a / (st.l * wa + win.l * wb);
+    asum += a;
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) acc[e] = fmaf(f, st.o[e] * wa + win.o[e] * wb, acc[e]);
+  }
+  if (lane < LPR) {
+    T* op = O + row * D + lr * EPL;
+    const bool any = asum > 0.f;
+    const float inv = any ? 1.f / asum : 1.f / win.l;
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) Elem<T>::store1(op + e, (any ? acc[e] : win.o[e]) * inv);
+  }
+}
+
 template <typename T, int D>
 sl_status launch_rows(const Problem& pb, const void* Q, const void* K, const void* V,
                       const int32_t* idx, void* O, float* LSE, hipStream_t st) {
   const int64_t rows = (int64_t)pb.Hq * pb.Lq;
   if (pb.prof_start) (void)hipEventRecord(pb.prof_start, st);
+  if (pb.combined) {
+    hipLaunchKernelGGL((prefill_combined_rows_kernel<T, D>), dim3((unsigned)((rows + 3) / 4)),
+                       dim3(256), 0, st, static_cast<const T*>(Q), static_cast<const T*>(K),
+                       static_cast<const T*>(V), idx, pb.gate, static_cast<T*>(O), pb.Lq, pb.q_pos0,
+                       pb.Hq, pb.G, pb.S, pb.topk, pb.scale * kLog2e, pb.qsh, pb.qst, pb.kvsh,
+                       pb.kvst);
+    if (pb.prof_stop) (void)hipEventRecord(pb.prof_stop, st);
+    return hipGetLastError() == hipSuccess ? SL_OK : SL_ERR_LAUNCH;
+  }
   hipLaunchKernelGGL((prefill_attention_rows_kernel<T, D>), dim3((unsigned)((rows + 3) / 4)),
                      dim3(256), 0, st, static_cast<const T*>(Q), static_cast<const T*>(K),
                      static_cast<const T*>(V), idx, static_cast<T*>(O), LSE, pb.Lq, pb.q_pos0,

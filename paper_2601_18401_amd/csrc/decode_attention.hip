@@ -217,6 +217,102 @@ __global__ __launch_bounds__(256) void decode_reduce_kernel(const float* __restr
   }
 }
 
+
+// Combination form of the reduction (Section 3.4, eq. (5)-(6); Algorithm 1) for one query: per
+// valid slot t, A_t = merge of the slot's chunk records with the window's chunk records (its own
+// softmax over span t and the window); O = sum_t alpha_t A_t, alpha = softmax of the slots' search
+// scores; no valid slot: the window alone.  Record p = slot * nchunks + chunk (slot topk = window)
+// holds (o[D] unnormalised, m, l), m in log2 units; a slot without a span has m = -inf in all
+// its records.  grid (Hq, D / 32) like decode_reduce_kernel: 256 threads = 8 chunk subsets x 32
+// dims; a thread's record loads are issued before the statistics they are weighted with arrive.
+constexpr int kMaxSlots = SL_MAX_TOPK + 1;
+
+template <typename T, int D>
+__global__ __launch_bounds__(256) void decode_reduce_combined_kernel(const float* __restrict__ part,
+                                                                    const float* __restrict__ gate,
+                                                                    T* __restrict__ O, int topk,
+                                                                    int nchunks) {
+  extern __shared__ float s_dyn[];  // [nrec] m, [nrec] l
+  __shared__ float s_ms[kMaxSlots], s_ls[kMaxSlots];           // per slot: max m, l relative to it
+  __shared__ float s_part[kMaxSlots][kReduceSub][kReduceDims];  // per slot and subset: o relative to it
+  const int h = blockIdx.x, d0 = blockIdx.y * kReduceDims;
+  const int tid = threadIdx.x;
+  const int d = tid % kReduceDims, sub = tid / kReduceDims;
+  const int nslot = topk + 1, nrec = nslot * nchunks;
+  float* s_m = s_dyn;
+  float* s_l = s_dyn + nrec;
+  const float* base = part + (int64_t)h * nrec * (D + 2);
+
+  // first chunk batch of every slot: independent of the statistics, issued first
+  float ov[kMaxSlots];
+#pragma unroll
+  for (int slot = 0; slot < kMaxSlots; ++slot)
+    ov[slot] = (slot < nslot && sub < nchunks)
+                   ? base[(int64_t)(slot * nchunks + sub) * (D + 2) + d0 + d]
+                   : 0.f;
+  for (int p = tid; p < nrec; p += 256) {
+    s_m[p] = base[(int64_t)p * (D + 2) + D];
+    s_l[p] = base[(int64_t)p * (D + 2) + D + 1];
+  }
+  __syncthreads();
+  if (tid < nslot) {
+    float m = -INFINITY;
+    for (int ck = 0; ck < nchunks; ++ck) m = fmaxf(m, s_m[tid * nchunks + ck]);
+    float l = 0.f;
+    for (int ck = 0; ck < nchunks; ++ck) {
+      const float mp = s_m[tid * nchunks + ck];
+      if (mp > -INFINITY) l = fmaf(fast_exp2(mp - m), s_l[tid * nchunks + ck], l);
+    }
+    s_ms[tid] = m;
+    s_ls[tid] = l;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int slot = 0; slot < kMaxSlots; ++slot) {
+    if (slot < nslot) {
+      const float ms = s_ms[slot];
+      float acc = 0.f;
+      if (ms > -INFINITY) {
+        if (sub < nchunks) {
+          const float mp = s_m[slot * nchunks + sub];
+          if (mp > -INFINITY) acc = fast_exp2(mp - ms) * ov[slot];
+        }
+        for (int ck = sub + kReduceSub; ck < nchunks; ck += kReduceSub) {  // more than 8 chunks
+          const float mp = s_m[slot * nchunks + ck];
+          if (mp > -INFINITY)
+            acc = fmaf(fast_exp2(mp - ms), base[(int64_t)(slot * nchunks + ck) * (D + 2) + d0 + d], acc);
+        }
+      }
+      s_part[slot][sub][d] = acc;
+    }
+  }
+  __syncthreads();
+  if (tid < kReduceDims) {
+    auto slot_o = [&](int slot) {
+      float o = 0.f;
+#pragma unroll
+      for (int s2 = 0; s2 < kReduceSub; ++s2) o += s_part[slot][s2][tid];
+      return o;
+    };
+    const float mw = s_ms[topk], lw = s_ls[topk];  // the window always holds the query's own token
+    const float ow = slot_o(topk);
+    float gmax = -INFINITY;
+    for (int slot = 0; slot < topk; ++slot)
+      if (s_ms[slot] > -INFINITY) gmax = fmaxf(gmax, gate[(int64_t)h * topk + slot]);
+    float acc = 0.f, asum = 0.f;
+    for (int slot = 0; slot < topk; ++slot) {
+      const float m = s_ms[slot];
+      if (m == -INFINITY) continue;
+      const float M = fmaxf(m, mw);
+      const float wa = fast_exp2(m - M), wb = fast_exp2(mw - M);
+      const float a = __expf(gate[(int64_t)h * topk + slot] - gmax);
+      asum += a;
+      acc = fmaf(a, (slot_o(slot) * wa + ow * wb) / (s_ls[slot] * wa + lw * wb), acc);
+    }
+    Elem<T>::store1(O + (int64_t)h * D + d0 + tid, asum > 0.f ? acc / asum : ow / lw);
+  }
+}
+
 int pick_chunk_tokens(const Problem& pb) {
   // Aim for a few thousand workgroups so the 256 CUs keep enough loads in flight, without
   // going below 64 tokens per item.
@@ -253,6 +349,12 @@ sl_status launch_decode(const Problem& pb, const void* Q, const void* K, const v
   }
   if (hipGetLastError() != hipSuccess) return SL_ERR_LAUNCH;
   const int nrec = (pb.topk + 1) * nchunks;
+  if (pb.combined) {
+    hipLaunchKernelGGL((decode_reduce_combined_kernel<T, D>), dim3(pb.Hq, D / kReduceDims), dim3(256),
+                       (size_t)2 * nrec * sizeof(float), st, part, pb.gate, static_cast<T*>(O),
+                       pb.topk, nchunks);
+    return hipGetLastError() == hipSuccess ? SL_OK : SL_ERR_LAUNCH;
+  }
   hipLaunchKernelGGL((decode_reduce_kernel<T, D>), dim3(pb.Hq, D / kReduceDims), dim3(256),
                      (size_t)nrec * sizeof(float), st, part, static_cast<T*>(O), LSE, nrec);
   if (hipGetLastError() != hipSuccess) return SL_ERR_LAUNCH;

@@ -646,6 +646,77 @@ __global__ __launch_bounds__(256) void merge_partials_kernel(
   if (piece == 0) LSE[row] = M + __logf(wsum);
 }
 
+
+// Combination form of the merge (Section 3.4, eq. (5)-(6); Algorithm 1): per valid slot t,
+// A_t = log-sum-exp merge of the slot's partial with the local window's partial (the attention
+// over span t and the window with its own softmax); O = sum_t alpha_t A_t with alpha = softmax of
+// the slots' search scores; no valid slot: the window's partial.
+template <int KMAX>
+__global__ __launch_bounds__(256) void merge_combined_kernel(
+    const int32_t* __restrict__ idx, const float* __restrict__ gate,
+    const bf16_t* __restrict__ part_o, const float* __restrict__ part_lse, bf16_t* __restrict__ O,
+    int64_t rows, int64_t Lq, int64_t q_pos0, int S, int topk) {
+  const int64_t row = (int64_t)blockIdx.x * 16 + (threadIdx.x >> 4);
+  const int piece = threadIdx.x & 15;
+  if (row >= rows) return;
+  const int64_t r = row % Lq;
+  const int c = (int)((q_pos0 + r) / S);
+  const int nslot = topk + 1;
+  const int32_t* irow = idx + row * topk;
+  const float* grow = gate + row * topk;
+  const float* lrow = part_lse + row * nslot;
+  const bf16_t* orow = part_o + row * nslot * HD + piece * 8;
+
+  int js[KMAX];
+  float ls[KMAX], gs[KMAX];
+  uint4 ov[KMAX + 1];
+#pragma unroll
+  for (int s = 0; s < KMAX; ++s) js[s] = s < topk ? irow[s] : -1;
+  float gmax = -INFINITY;
+#pragma unroll
+  for (int s = 0; s < KMAX; ++s) {
+    bool ok = js[s] >= 0 && js[s] < c;
+#pragma unroll
+    for (int u = 0; u < s; ++u) ok = ok && js[u] != js[s];
+    ls[s] = ok ? lrow[s] : -INFINITY;
+    gs[s] = ok ? grow[s] : -INFINITY;
+    ov[s] = ok ? load16(orow + (int64_t)s * HD) : make_uint4(0, 0, 0, 0);
+    gmax = fmaxf(gmax, gs[s]);
+  }
+  const float lw = lrow[topk];
+  ov[KMAX] = load16(orow + (int64_t)topk * HD);
+
+  float acc[8], fw[8], f[8];
+  Elem<bf16_t>::unpack(ov[KMAX], fw);
+#pragma unroll
+  for (int e = 0; e < 8; ++e) acc[e] = 0.f;
+  float asum = 0.f;
+#pragma unroll
+  for (int s = 0; s < KMAX; ++s) {
+    if (ls[s] > -INFINITY) {  // valid slot
+      const float M = fmaxf(ls[s], lw);
+      const float wa = __expf(ls[s] - M), wb = __expf(lw - M);
+      const float a = __expf(gs[s] - gmax);
+      const float fa = a * wa / (wa + wb), fb = a * wb / (wa + wb);
+      asum += a;
+      Elem<bf16_t>::unpack(ov[s], f);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc[e] = fmaf(fa, f[e], fmaf(fb, fw[e], acc[e]));
+    }
+  }
+  const bool any = asum > 0.f;
+  const float inv = any ? 1.f / asum : 1.f;
+  uint4 res;
+  float o8[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) o8[e] = (any ? acc[e] : fw[e]) * inv;
+  res.x = (uint32_t)f32_to_bf16(o8[0]) | ((uint32_t)f32_to_bf16(o8[1]) << 16);
+  res.y = (uint32_t)f32_to_bf16(o8[2]) | ((uint32_t)f32_to_bf16(o8[3]) << 16);
+  res.z = (uint32_t)f32_to_bf16(o8[4]) | ((uint32_t)f32_to_bf16(o8[5]) << 16);
+  res.w = (uint32_t)f32_to_bf16(o8[6]) | ((uint32_t)f32_to_bf16(o8[7]) << 16);
+  *reinterpret_cast<uint4*>(O + row * HD + piece * 8) = res;
+}
+
 // ------------------------------------------------------------------ workspace carving
 struct MfmaWs {
   size_t vt, counts, item_off, tile_off, cursor, tile_info, items, part_lse, part_o, total;
@@ -792,8 +863,14 @@ sl_status prefill_attention_mfma(const Problem& pb, const void* Q, const void* K
   const int64_t rows = (int64_t)pb.Hq * pb.Lq;
   const dim3 mgrid((unsigned)((rows + 15) / 16));
 #define SL_MERGE(KM)                                                                             \
-  hipLaunchKernelGGL(merge_partials_kernel<KM>, mgrid, dim3(256), 0, st, idx, part_o, part_lse,  \
-                     a.O, LSE, rows, pb.Lq, pb.q_pos0, pb.S, pb.topk)
+  do {                                                                                           \
+    if (pb.combined)                                                                                 \
+      hipLaunchKernelGGL(merge_combined_kernel<KM>, mgrid, dim3(256), 0, st, idx, pb.gate,       \
+                         part_o, part_lse, a.O, rows, pb.Lq, pb.q_pos0, pb.S, pb.topk);          \
+    else                                                                                         \
+      hipLaunchKernelGGL(merge_partials_kernel<KM>, mgrid, dim3(256), 0, st, idx, part_o,        \
+                         part_lse, a.O, LSE, rows, pb.Lq, pb.q_pos0, pb.S, pb.topk);             \
+  } while (0)
   if (pb.topk == 0) SL_MERGE(1);
   else if (pb.topk <= 8) SL_MERGE(8);
   else if (pb.topk <= 16) SL_MERGE(16);

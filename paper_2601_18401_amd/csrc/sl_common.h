@@ -17,6 +17,10 @@ struct Problem {
   int64_t qsh, qst, kvsh, kvst;
   int64_t n;  // ceil(L / S)
   hipEvent_t prof_start, prof_stop;
+  // Combination (Section 3.4) instead of one joint softmax over the selected spans and the
+  // window; gate = search scores [Hq][Lq][topk] of the slots of idx (unread when topk == 0).
+  bool combined;
+  const float* gate;
 };
 
 constexpr float kLog2e = 1.4426950408889634f;

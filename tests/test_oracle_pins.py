@@ -335,7 +335,9 @@ def test_combination_equal_scores_is_mean_of_span_outputs_and_slot_order_free():
         assert np.allclose(At, ref[0, 0], rtol=1e-12, atol=1e-13)
     # permuting the slots together with their scores changes nothing; empty slots are skipped
     o1 = orc.combined_row(Q[0, i], K, V, 0, i, S, [6, -1, 1, 4], [0.9, 123.0, -0.2, 0.1], 0.5)
-    o2 = orc.combined_row(Q[0, i], K, V, 0, i, S, [1, 4, 6, 9], [-0.2, 0.1, 0.9, 55.0], 0.5)  # 9 >= c: empty
+    o2 = orc.combined_row(Q[0, i], K, V, 0, i, S, [1, 4, 6, 7], [-0.2, 0.1, 0.9, 55.0], 0.5)  # 7 = c, the query's own span: empty
+    o3 = orc.combined_row(Q[0, i], K, V, 0, i, S, [9, 1, 4, 6], [7.0, -0.2, 0.1, 0.9], 0.5)   # beyond the cache: empty
+    assert np.allclose(o1, o3, rtol=1e-13, atol=1e-14)
     assert np.allclose(o1, o2, rtol=1e-13, atol=1e-14)
 
 

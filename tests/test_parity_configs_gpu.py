@@ -10,7 +10,7 @@ import torch
 from oracle import superlinear as orc
 from paper_2601_18401_amd import binding as B
 from paper_2601_18401_amd import workloads as W
-from tests.test_parity_gpu import DEV, check_attention, check_idx, f64
+from tests.test_parity_gpu import DEV, check_attention, check_combined, check_idx, f64
 
 pytestmark = pytest.mark.gpu
 
@@ -75,6 +75,20 @@ def test_config4_prefill_262k_needles():
         assert torch.equal(valid.sum(dim=1), torch.minimum(c, torch.tensor(cfg.topk, device=DEV)))
 
 
+def test_config2_prefill_combined_65k():
+    # the combination form (Section 3.4) at config 2's size, on the library's own indices and scores
+    cfg = W.CONFIGS["C2"]
+    data = W.generate(cfg, device=DEV)
+    Q, K, V = data["Q"], data["K"], data["V"]
+    Ks = B.sl_span_keys(K, cfg.S)
+    idx, sc = B.sl_span_search_prefill(data["Qs"], K, Ks, cfg.S, cfg.topk, want_scores=True)
+    sc = torch.where(torch.isfinite(sc), sc, torch.zeros_like(sc))
+    O = B.sl_span_attention_combined_prefill(Q, K, V, idx, sc, cfg.S)
+    torch.cuda.synchronize()
+    assert torch.isfinite(O.float()).all()
+    check_combined(O, Q, K, V, idx, sc, cfg.S, 0, 0.0, sample_rows(cfg, data))
+
+
 @pytest.mark.parametrize("name", ["C3", "C5"])
 def test_decode_configs_full_cache(name):
     cfg = W.CONFIGS[name]
@@ -92,5 +106,10 @@ def test_decode_configs_full_cache(name):
         O, LSE = B.sl_span_attention_decode(Q, K, V, idx_o, cfg.S)
         torch.cuda.synchronize()
         check_attention(O, LSE, Q, K, V, idx_o, cfg.S, cfg.L - 1, 0.0)
+        if qi == 0 and name == "C3":   # the combination form on the same step (a few heads: the oracle is slow)
+            idx_g, sc_g = B.sl_span_search_decode(Q, K, Ks, cfg.S, cfg.topk, want_scores=True)
+            Oc = B.sl_span_attention_combined_decode(Q, K, V, idx_g, sc_g, cfg.S)
+            torch.cuda.synchronize()
+            check_combined(Oc, Q, K, V, idx_g, sc_g, cfg.S, cfg.L - 1, 0.0, [(0, 0), (13, 0), (31, 0)])
     del data, K, V
     torch.cuda.empty_cache()

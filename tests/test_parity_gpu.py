@@ -321,3 +321,98 @@ def test_decode_search_ties_lower_index_wins(L, S, k):
     # identical keys give bit-identical fp32 scores, so the tie rule decides: must match exactly
     assert np.array_equal(idx.cpu().numpy(), want)
     assert np.allclose(sc.cpu().numpy(), wsc, atol=1e-3)
+
+
+# ------------------------------------------------------------------------------ combination (Section 3.4)
+
+def check_combined(O, Q, K, V, idx, scores, S, q_pos0, scale, rows=None):
+    tol = TOL[Q.dtype]
+    On, Qn = f64(O), f64(Q)
+    idxn, scn = idx.cpu().numpy(), scores.cpu().numpy().astype(np.float64)
+    Kd, Vd = DevKV(K), DevKV(V)
+    Hq, Lq, D = Qn.shape
+    G = Hq // K.shape[0]
+    sc = scale if scale else 1.0 / math.sqrt(D)
+    if rows is None:
+        rows = [(h, r) for h in range(Hq) for r in range(Lq)]
+    for (h, r) in rows:
+        o = orc.combined_row(Qn[h, r], Kd, Vd, h // G, q_pos0 + r, S, idxn[h, r], scn[h, r], sc)
+        err = float(np.max(np.abs(On[h, r] - o)))
+        assert err <= tol, (h, r, err)
+
+
+COMBINED_PREFILL = [
+    # seed Hq Hkv L     D    S    k  dtype           q_pos0 Lq
+    (21, 4, 4, 1024, 64, 64, 4, torch.float32, 0, None),       # row-stationary fp32 (config-1 shape, shorter)
+    (22, 4, 2, 777, 128, 48, 5, torch.bfloat16, 0, None),      # row-stationary bf16, ragged
+    (23, 8, 2, 2048, 128, 64, 8, torch.bfloat16, 0, None),     # matrix-core path, GQA 4:1
+    (24, 4, 1, 1613, 128, 256, 16, torch.bfloat16, 0, None),   # matrix-core path, list of 16, ragged L
+    (25, 4, 2, 3000, 128, 512, 3, torch.bfloat16, 1000, 500),  # matrix-core path, chunk inside a cache
+    (26, 2, 2, 40, 128, 64, 2, torch.bfloat16, 0, None),       # no candidate at all: window-only branch
+]
+
+
+@pytest.mark.parametrize("seed,Hq,Hkv,L,D,S,k,dtype,q_pos0,Lq", COMBINED_PREFILL)
+def test_combined_prefill(seed, Hq, Hkv, L, D, S, k, dtype, q_pos0, Lq):
+    # inputs scaled so that the raw search scores (the gate logits) spread over a few units
+    Q, K, V = make(seed, Hq, Hkv, L, D, dtype, Lq=Lq, scale=0.35)
+    Ks = B.sl_span_keys(K, S)
+    idx_o, sc_o = orc.span_search(f64(Q), f64(Ks), S, k, q_pos0=q_pos0, return_scores=True)
+    idx_t = torch.from_numpy(idx_o).to(DEV)
+    sc_t = torch.from_numpy(np.where(np.isfinite(sc_o), sc_o, 0.0).astype(np.float32)).to(DEV)
+    O = B.sl_span_attention_combined_prefill(Q, K, V, idx_t, sc_t, S, q_pos0=q_pos0)
+    torch.cuda.synchronize()
+    rows = None if Q.shape[0] * Q.shape[1] <= 6000 else \
+        [(h, r) for h in range(Hq) for r in range(0, Q.shape[1], 7)]
+    check_combined(O, Q, K, V, idx_t, sc_t, S, q_pos0, 0.0, rows)
+    # the library's own search output feeds the same entry point
+    idx_g, sc_g = B.sl_span_search_prefill(Q, K, Ks, S, k, q_pos0=q_pos0, want_scores=True)
+    O2 = B.sl_span_attention_combined_prefill(Q, K, V, idx_g, sc_g, S, q_pos0=q_pos0)
+    torch.cuda.synchronize()
+    same = (idx_g == idx_t).all(dim=-1)
+    assert torch.allclose(O2[same].float(), O[same].float(), atol=TOL[dtype], rtol=0)
+
+
+def test_combined_prefill_one_slot_equals_plain_attention():
+    # k = 1: the gate is 1 and span | window is the whole attended set
+    Hq, Hkv, L, D, S = 4, 2, 1536, 128, 128
+    Q, K, V = make(27, Hq, Hkv, L, D, torch.bfloat16)
+    Ks = B.sl_span_keys(K, S)
+    idx, sc = B.sl_span_search_prefill(Q, K, Ks, S, 1, want_scores=True)
+    O1, _ = B.sl_span_attention_prefill(Q, K, V, idx, S)
+    O2 = B.sl_span_attention_combined_prefill(Q, K, V, idx, sc, S)
+    torch.cuda.synchronize()
+    assert torch.allclose(O1.float(), O2.float(), atol=2e-2, rtol=0)
+
+
+@pytest.mark.parametrize("seed,Hq,Hkv,L,D,S,k,dtype", [
+    (31, 8, 2, 70000, 128, 256, 16, torch.bfloat16),
+    (32, 4, 4, 5000, 64, 64, 4, torch.float32),
+    (33, 4, 1, 30000, 128, 1000, 3, torch.bfloat16),   # S % 64 != 0, last chunk ragged
+    (34, 2, 2, 50, 128, 64, 4, torch.bfloat16),        # no candidate: window only
+])
+def test_combined_decode(seed, Hq, Hkv, L, D, S, k, dtype):
+    Q, K, V = make(seed, Hq, Hkv, L, D, dtype, Lq=1, scale=0.35)
+    Ks = B.sl_span_keys(K, S)
+    idx, sc = B.sl_span_search_decode(Q, K, Ks, S, k, want_scores=True)
+    torch.cuda.synchronize()
+    sc = torch.where(torch.isfinite(sc), sc, torch.zeros_like(sc))
+    O = B.sl_span_attention_combined_decode(Q, K, V, idx, sc, S)
+    torch.cuda.synchronize()
+    check_combined(O, Q, K, V, idx, sc, S, L - 1, 0.0)
+
+
+def test_combined_invalid_arguments():
+    Q, K, V = make(35, 2, 2, 256, 128, torch.bfloat16)
+    idx = torch.zeros((2, 256, 2), dtype=torch.int32, device=DEV)
+    with pytest.raises(ValueError):
+        B.sl_span_attention_combined_prefill(Q, K, V, idx, None, 64)
+    lib = B.load()
+    p = B.make_params(Q, K, 64, 2)
+    O = torch.empty_like(Q)
+    ws = B.Workspace()
+    wptr, wbytes = ws.get(B.workspace_bytes(p, B.OP_ATTENTION_PREFILL))
+    import ctypes
+    st = lib.sl_span_attention_combined_prefill(ctypes.byref(p), Q.data_ptr(), K.data_ptr(), V.data_ptr(),
+                                                idx.data_ptr(), None, O.data_ptr(), wptr, wbytes, None)
+    assert st == 1   # SL_ERR_INVALID_ARG: scores missing
