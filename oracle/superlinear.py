@@ -253,3 +253,87 @@ def span_attention_combined(Q, K, V, idx, scores, S: int, scale: float | None = 
         for r in range(Lq):
             O[h, r] = combined_row(Q[h, r], K, V, h // G, q_pos0 + r, S, idx[h, r], scores[h, r], scale)
     return O
+
+
+# ---------------------------------------------------------------------------------------------
+# The paper's own geometry (Section 3.3; Fig. 3; Algorithm 1), for one query position i:
+# anchors on a quadratic stride pattern, spans of a length that grows with sqrt(i) around the
+# selected anchors, a sliding window W, anchors inside W dropped.  p = 1/2 (the N = 2 case).
+
+def anchor_positions(i: int):
+    """Anchor tokens of query position i for p = 1/2: t_s = i - (s+1)^2 + 1, s = 0, 1, ...,
+    as long as t_s >= 0 (Section 3.3: "i, i-3, i-8, i-15, ...")."""
+    out = []
+    s = 0
+    while i - (s + 1) * (s + 1) + 1 >= 0:
+        out.append(i - (s + 1) * (s + 1) + 1)
+        s += 1
+    return out
+
+
+def base_span_length(i: int) -> int:
+    """l(i) = ceil(i^(1-p)) = ceil(sqrt(i)) for p = 1/2 (Section 3.3), in exact integer arithmetic."""
+    r = math.isqrt(int(i))
+    return r if r * r == i else r + 1
+
+
+def window_range(i: int, w: int):
+    """W = [max(0, i-w+1), i] (Algorithm 1); None if w = 0."""
+    return None if w <= 0 else (max(0, i - w + 1), i)
+
+
+def anchor_candidates(i: int, w: int):
+    """T = Anchors(i) minus W (Algorithm 1): (stride index s, anchor t_s) pairs, ascending s."""
+    lo = i - w + 1 if w > 0 else i + 1
+    return [(s, t) for s, t in enumerate(anchor_positions(i)) if t < lo]
+
+
+def anchor_span(t: int, i: int, b: int, f: int):
+    """S_t = [max(0, t - b*l(i)), min(i, t + f*l(i))] (Algorithm 1), inclusive bounds."""
+    l = base_span_length(i)
+    return max(0, t - b * l), min(i, t + f * l)
+
+
+def anchor_search_row(qs, Krow, i: int, w: int, topk: int):
+    """Scores <Q_s(i), K_a(t)> (eq. (2), K_a = K) of the candidate anchors of position i and the
+    top-k of them (eq. (3)); ties go to the lower stride index (the anchor nearer to the query).
+    Krow: anything indexable as Krow[t] -> [D].  Returns (stride indices ascending, their anchor
+    positions, their scores), each of length min(topk, number of candidates)."""
+    cand = anchor_candidates(i, w)
+    qs = _f64(qs)
+    sc = np.array([float(_f64(Krow[t]) @ qs) for _, t in cand], dtype=F64)
+    order = select_topk(sc, topk)          # ascending candidate number = ascending stride index
+    return [cand[n][0] for n in order], [cand[n][1] for n in order], [float(sc[n]) for n in order]
+
+
+def anchor_combined_row(q, K, V, kv: int, i: int, w: int, b: int, f: int, sel_t, sel_scores, scale: float,
+                        return_parts=False):
+    """Algorithm 1 for one query row on the paper's geometry: for every selected anchor t,
+    J_t = DedupConcat(S_t, W) (the set union, every token once), A_t = softmax attention over
+    J_t (eq. (4)); O = sum_t alpha_t A_t with alpha = softmax of the selected scores (eq. (5)-(6));
+    nothing selected: attention over W.  Entries of sel_t < 0 are empty slots."""
+    q = _f64(q)
+    W = window_range(i, w)
+
+    def attend(tokens):
+        Kj = np.stack([_f64(K[kv, t:t + 1])[0] for t in tokens])
+        Vj = np.stack([_f64(V[kv, t:t + 1])[0] for t in tokens])
+        z = scale * (Kj @ q)
+        e = np.exp(z - np.max(z))
+        return (e @ Vj) / np.sum(e)
+
+    wtok = list(range(W[0], W[1] + 1)) if W else []
+    slots = [n for n, t in enumerate(sel_t) if int(t) >= 0]
+    if not slots:
+        o = attend(wtok)
+        return (o, np.zeros(0), []) if return_parts else o
+    A = []
+    for n in slots:
+        a, e = anchor_span(int(sel_t[n]), i, b, f)
+        tokens = sorted(set(range(a, e + 1)) | set(wtok))
+        A.append(attend(tokens))
+    alpha = gate_weights([sel_scores[n] for n in slots])
+    o = np.zeros_like(A[0])
+    for g, At in zip(alpha, A):
+        o = o + g * At
+    return (o, alpha, A) if return_parts else o

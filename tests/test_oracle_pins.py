@@ -352,3 +352,111 @@ def test_combination_identical_spans_collapse():
     o = orc.combined_row(Q[0, i], K, V, 0, i, S, [0, 1, 2], [5.0, -1.0, 0.2], 0.6)
     one = orc.combined_row(Q[0, i], K, V, 0, i, S, [2], [0.0], 0.6)
     assert np.allclose(o, one, rtol=1e-13, atol=1e-14)
+
+
+# ---------------------------------------------------------------- the paper's own geometry (Section 3.3, Fig. 3)
+
+def _gold_geometry():
+    g = {}
+    for kind, vals in _rows(os.path.join(GOLD, "anchor_geometry.txt")):
+        g[kind] = [int(v) for v in vals.split(",")]
+    return g
+
+
+def test_golden_fig3_anchors_span_length_and_cover():
+    g = _gold_geometry()
+    i, b, f = g["fig3_i"][0], g["fig3_b"][0], g["fig3_f"][0]
+    assert orc.anchor_positions(i) == g["fig3_anchors"]
+    assert (b + f) * orc.base_span_length(i) == g["fig3_span_length"][0]
+    # every position 0..i lies in at least one candidate span (no window in the figure)
+    covered = set()
+    for t in orc.anchor_positions(i):
+        a, e = orc.anchor_span(t, i, b, f)
+        assert e == t and t - a == min(t, g["fig3_span_length"][0])      # f = 0: the span ends at its anchor
+        covered |= set(range(a, e + 1))
+    assert covered == set(range(i + 1))
+
+
+def test_golden_anchor_offsets_and_gaps():
+    g = _gold_geometry()
+    for i in (15, 100, 4097):
+        a = orc.anchor_positions(i)
+        assert [i - t for t in a[:4]] == g["text_offsets"]
+        assert [a[n] - a[n + 1] for n in range(3)] == g["text_gaps"]
+
+
+@pytest.mark.parametrize("i", [0, 1, 2, 3, 8, 24, 99, 1000, 65535, 1048575])
+def test_anchor_count_and_base_length_closed_forms(i):
+    a = orc.anchor_positions(i)
+    assert len(a) == math.isqrt(i + 1)                 # (s+1)^2 <= i + 1
+    assert a[0] == i and all(x > y for x, y in zip(a, a[1:])) and a[-1] >= 0
+    l = orc.base_span_length(i)
+    assert (l - 1) ** 2 < max(i, 1) <= l * l or i == 0 and l == 0
+    assert l == math.ceil(math.sqrt(i)) or i > 2 ** 40   # float sqrt is exact enough at these sizes
+
+
+@pytest.mark.parametrize("i,w,b", [(30, 0, 2), (500, 48, 2), (4095, 99, 2), (100000, 1088, 4)])
+def test_random_context_access_on_paper_geometry(i, w, b):
+    # Section 3.3: with b >= 1/p = 2 every key j <= i is reachable: it lies in W or in the span of a
+    # candidate.  The window is "chosen based on the stride index" so that the search starts right
+    # after it: w = m^2 - 1 (the paper's 1088 = 33^2 - 1), the first candidate anchor is i - w.
+    covered = set()
+    W = orc.window_range(i, w)
+    if W:
+        covered |= set(range(W[0], W[1] + 1))
+    cand = orc.anchor_candidates(i, w)
+    assert W is None or cand[0][1] == W[0] - 1
+    for _, t in cand:
+        assert W is None or t < W[0]
+        a, e = orc.anchor_span(t, i, b, 0)
+        covered |= set(range(a, e + 1))
+    assert covered == set(range(i + 1))
+
+
+def test_anchor_search_equals_bruteforce_argsort():
+    rng = np.random.default_rng(50)
+    i, w, k, D = 777, 50, 4, 8
+    K = rng.standard_normal((i + 1, D))
+    q = rng.standard_normal(D)
+    s_sel, t_sel, sc_sel = orc.anchor_search_row(q, K, i, w, k)
+    cand_t = [t for t in (i - (s + 1) ** 2 + 1 for s in range(100)) if 0 <= t < i - w + 1]
+    scores = K[cand_t] @ q
+    want = brute.argsort_topk(scores, k)
+    assert t_sel == [cand_t[n] for n in want]
+    assert np.allclose(sc_sel, scores[want], rtol=1e-13)
+    assert s_sel == sorted(s_sel) and t_sel == sorted(t_sel, reverse=True)
+    # a duplicated key: the nearer anchor (lower stride index) wins the tie
+    K2 = K.copy()
+    K2[cand_t[5]] = K2[cand_t[2]] = 10.0 * q
+    s2, t2, _ = orc.anchor_search_row(q, K2, i, w, 1)
+    assert t2 == [cand_t[2]]
+
+
+def test_anchor_combined_equals_dense_masked_bruteforce():
+    # per selected anchor one dense masked softmax over (S_t | W), gate by a library softmax
+    rng = np.random.default_rng(51)
+    L, D, w, b, f, k = 400, 8, 30, 4, 2, 3
+    i = L - 1
+    Q = rng.standard_normal((1, 1, D))
+    K = rng.standard_normal((1, L, D))
+    V = rng.standard_normal((1, L, D))
+    _, t_sel, sc_sel = orc.anchor_search_row(Q[0, 0], K[0], i, w, k)
+    o, alpha, A = orc.anchor_combined_row(Q[0, 0], K, V, 0, i, w, b, f, t_sel, sc_sel, 0.5, return_parts=True)
+    from scipy.special import softmax as sp_softmax
+    l = math.ceil(math.sqrt(i))
+    want = np.zeros(D)
+    a_ref = sp_softmax(np.array(sc_sel))
+    for g, t in zip(a_ref, t_sel):
+        mask = np.zeros((1, 1, L), dtype=bool)
+        mask[0, 0, max(0, t - b * l):min(i, t + f * l) + 1] = True      # spans of close anchors overlap: fine, each has its own softmax
+        mask[0, 0, i - w + 1:i + 1] = True
+        At, _, _ = brute.dense_masked_attention(Q, K, V, mask, 0.5)
+        want += g * At[0, 0]
+    assert np.allclose(alpha, a_ref, atol=1e-15)
+    assert np.allclose(o, want, rtol=1e-12, atol=1e-13)
+    # nothing selected -> window attention
+    o0 = orc.anchor_combined_row(Q[0, 0], K, V, 0, i, w, b, f, [-1, -1], [0.0, 0.0], 0.5)
+    mask = np.zeros((1, 1, L), dtype=bool)
+    mask[0, 0, i - w + 1:i + 1] = True
+    Aw, _, _ = brute.dense_masked_attention(Q, K, V, mask, 0.5)
+    assert np.allclose(o0, Aw[0, 0], rtol=1e-12, atol=1e-13)
