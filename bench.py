@@ -143,6 +143,67 @@ def bench_decode(cfg, steps, warmup, torch, B, W):
         cgraph.replay()
     torch.cuda.synchronize()
     dt_combined = (time.perf_counter() - tc) / (nrep * N_DECODE_QUERIES)
+    # The paper's own geometry on the same cache (anchors on the quadratic stride pattern, window
+    # 1088, top-2, b = 4, f = 2: Section 4.3's kernel configuration), same replay.
+    PW, PK, PB, PF = 1088, 2, 4, 2
+    outs_p = [torch.empty((cfg.Hq, 1, cfg.D), dtype=K.dtype, device=dev) for _ in range(N_DECODE_QUERIES)]
+
+    def step_paper(i, prof=None):
+        q = Qs[i % N_DECODE_QUERIES]
+        an, sc = B.sl_anchor_search_decode(q, K, PK, PW, want_scores=True)
+        B.sl_anchor_attention_decode(q, K, V, an, sc, PW, PB, PF, ws=ws, prof=prof, out=outs_p[i % N_DECODE_QUERIES])
+        return an
+
+    an0 = [step_paper(i).cpu().numpy() for i in range(N_DECODE_QUERIES)]
+    torch.cuda.synchronize()
+    pgraph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(pgraph):
+        for i in range(N_DECODE_QUERIES):
+            step_paper(i)
+    pgraph.replay()
+    torch.cuda.synchronize()
+    tc = time.perf_counter()
+    for _ in range(nrep):
+        pgraph.replay()
+    torch.cuda.synchronize()
+    dt_paper = (time.perf_counter() - tc) / (nrep * N_DECODE_QUERIES)
+    # its K/V streaming kernel and algorithmic bytes: per kv head the union of the heads' token
+    # ranges (span minus window, plus the window once), K and V rows
+    ell = math.isqrt(q_pos) + (0 if math.isqrt(q_pos) ** 2 == q_pos else 1)
+    G = cfg.Hq // cfg.Hkv
+    pbytes = []
+    for an in an0[:N_DECODE_QUERIES // 2]:
+        tokens = 0
+        for kv in range(cfg.Hkv):
+            cover = set()
+            for h in range(kv * G, (kv + 1) * G):
+                for t in an[h, 0].tolist():
+                    if t >= 0:
+                        cover.add((max(0, t - PB * ell), min(min(q_pos, t + PF * ell), q_pos - PW) + 1))
+            ivs = sorted(cover)
+            end = -1
+            for a0, a1 in ivs:          # union of intervals
+                a0 = max(a0, end)
+                if a1 > a0:
+                    tokens += a1 - a0
+                    end = a1
+            tokens += PW
+        pbytes.append(tokens * cfg.D * 2 * 2)
+    evp = [ProfEvents(torch) for _ in range(16)]
+    for i, ev in enumerate(evp):
+        qi = i % (N_DECODE_QUERIES // 2)
+        pgraph.replay()
+        an, sc = B.sl_anchor_search_decode(Qs[qi], K, PK, PW, want_scores=True)
+        B.sl_anchor_attention_decode(Qs[qi], K, V, an, sc, PW, PB, PF, ws=ws, prof=ev.handles(), out=outs_p[qi])
+    torch.cuda.synchronize()
+    pms = sum(ev.ms() for ev in evp) / len(evp)
+    paper_geometry = {"workload": f"anchors i-(s+1)^2+1, window {PW}, top-{PK}, b={PB}, f={PF}, combination gate",
+                      "ms_per_step": dt_paper * 1e3, "value": 1.0 / dt_paper, "unit": "steps/s",
+                      "roofline": {"bound": "hbm", "kernel": "decode_split_kernel", "kernel_ms": pms,
+                                   "algorithmic_bytes": sum(pbytes) / len(pbytes),
+                                   "achieved": sum(pbytes) / len(pbytes) / (pms * 1e-3) / 1e9,
+                                   "peak": PEAK_HBM / 1e9, "unit": "GB/s",
+                                   "frac": sum(pbytes) / len(pbytes) / (pms * 1e-3) / PEAK_HBM}}
     # Dominant kernel (K/V streaming + fused merge): a graph of N_DECODE_QUERIES back-to-back
     # span-attention launches, timed with HIP events on the launch stream.
     idx_dev = [torch.from_numpy(ix).to(dev) for ix in idxs]
@@ -181,6 +242,7 @@ def bench_decode(cfg, steps, warmup, torch, B, W):
         "metric": "decode steps/s (span-search + span-attention)", "value": steps / dt, "unit": "steps/s",
         "ms_per_step": dt / steps * 1e3, "steps": steps, "dtype": cfg.dtype, "launch": "hip-graph replay",
         "combined_form": {"ms_per_step": dt_combined * 1e3, "value": 1.0 / dt_combined, "unit": "steps/s"},
+        "paper_geometry": paper_geometry,
         "roofline": {"bound": "hbm", "kernel": "decode_split_kernel", "achieved": achieved / 1e9, "peak": PEAK_HBM / 1e9,
                      "unit": "GB/s", "frac": achieved / PEAK_HBM, "traffic": MEASURED_TRAFFIC.get(cfg.name),
                      "kernel_ms": kms_avg, "kernel_ms_min": min(kms), "algorithmic_bytes": sum(kbytes) / len(kbytes),

@@ -167,6 +167,44 @@ sl_status sl_span_attention_combined_decode(const sl_params* p, const void* Q, c
                                             const void* V, const int32_t* idx, const float* scores,
                                             void* O, void* ws, size_t ws_bytes, void* hip_stream);
 
+/* ---- The paper's own geometry, decode form (Section 3.3 with Fig. 3; Algorithm 1), p = 1/2.
+ * For the query at position i = q_pos0 = L - 1 (Lq must be 1; S of sl_params is ignored):
+ *   anchors      t_s = i - (s+1)^2 + 1, s = 0, 1, ..., t_s >= 0;
+ *   window       W = [max(0, i - window + 1), i]  (window = 0: none); anchors inside W are not
+ *                candidates.  For gap-free coverage choose window = m^2 - 1 (the paper's 1088), so
+ *                that the first candidate is the token just before W;
+ *   spans        S_t = [max(0, t - backward_factor * l), min(i, t + forward_factor * l)],
+ *                l = ceil(sqrt(i)). */
+typedef struct sl_anchor_geometry {
+  int64_t window;
+  int32_t backward_factor; /* b >= 0 */
+  int32_t forward_factor;  /* f >= 0 */
+} sl_anchor_geometry;
+
+/* Bytes of scratch sl_anchor_attention_decode needs (0 if the arguments are invalid). */
+size_t sl_anchor_workspace_bytes(const sl_params* p, const sl_anchor_geometry* g);
+
+/* Span-search over the candidate anchors (eq. (2)-(3) with K_a = K: the key of anchor t is
+ * K[kv][t]).
+ *   anchors out: [Hq][topk] int32, the token positions of the min(topk, #candidates) best
+ *           anchors per head, nearest anchor (lowest stride index) first, remaining slots -1.
+ *           Ties in score go to the nearer anchor.
+ *   scores  out, optional: fp32 score of the anchor in the same slot, -inf in empty slots.
+ * At most 4096 candidate anchors (i < 2^24). */
+sl_status sl_anchor_search_decode(const sl_params* p, const sl_anchor_geometry* g, const void* Qs,
+                                  const void* K, int32_t* anchors, float* scores, void* hip_stream);
+
+/* Span-attention and combination over the selected anchors (Algorithm 1): per non-empty slot,
+ * A_t = softmax attention over DedupConcat(S_t, W) (every token once, logits scale * <Q, K_j>),
+ * O = sum_t alpha_t A_t with alpha = softmax of scores over the non-empty slots; no non-empty
+ * slot: attention over W (zeros if there is no window either).
+ *   anchors in: as produced by sl_anchor_search_decode (entries < 0 or > i are empty slots).
+ *   scores  in: [Hq][topk] float, finite in non-empty slots.   O out: [Hq][1][D]. */
+sl_status sl_anchor_attention_decode(const sl_params* p, const sl_anchor_geometry* g, const void* Q,
+                                     const void* K, const void* V, const int32_t* anchors,
+                                     const float* scores, void* O, void* ws, size_t ws_bytes,
+                                     void* hip_stream);
+
 /* Static, human-readable name of a status code. */
 const char* sl_status_string(int status);
 

@@ -22,7 +22,13 @@ SL_MAX_TOPK = 32
 
 EXPORTS = ("sl_workspace_bytes", "sl_span_keys", "sl_span_search_prefill", "sl_span_search_decode",
            "sl_span_attention_prefill", "sl_span_attention_decode", "sl_span_attention_combined_prefill",
-           "sl_span_attention_combined_decode", "sl_status_string", "sl_version")
+           "sl_span_attention_combined_decode", "sl_anchor_workspace_bytes", "sl_anchor_search_decode",
+           "sl_anchor_attention_decode", "sl_status_string", "sl_version")
+
+
+class SlAnchorGeometry(ctypes.Structure):
+    _fields_ = [("window", ctypes.c_int64), ("backward_factor", ctypes.c_int32),
+                ("forward_factor", ctypes.c_int32)]
 
 
 class SlParams(ctypes.Structure):
@@ -74,6 +80,13 @@ def load():
         fn = getattr(lib, name)
         fn.restype = ctypes.c_int
         fn.argtypes = [pp, vp, vp, vp, i32p, f32p, vp, vp, ctypes.c_size_t, vp]
+    gp = ctypes.POINTER(SlAnchorGeometry)
+    lib.sl_anchor_workspace_bytes.restype = ctypes.c_size_t
+    lib.sl_anchor_workspace_bytes.argtypes = [pp, gp]
+    lib.sl_anchor_search_decode.restype = ctypes.c_int
+    lib.sl_anchor_search_decode.argtypes = [pp, gp, vp, vp, i32p, f32p, vp]
+    lib.sl_anchor_attention_decode.restype = ctypes.c_int
+    lib.sl_anchor_attention_decode.argtypes = [pp, gp, vp, vp, vp, i32p, f32p, vp, vp, ctypes.c_size_t, vp]
     lib.sl_status_string.restype = ctypes.c_char_p
     lib.sl_status_string.argtypes = [ctypes.c_int]
     lib.sl_version.restype = ctypes.c_int
@@ -237,6 +250,39 @@ def sl_span_attention_combined_decode(Q, K, V, idx, scores, S, q_pos0=None, scal
     q_pos0 = K.shape[1] - 1 if q_pos0 is None else q_pos0
     return _combined("sl_span_attention_combined_decode", OP_ATTENTION_DECODE, Q, K, V, idx, scores, S,
                      q_pos0, scale, ws, out)
+
+
+def sl_anchor_search_decode(Qs, K, topk, window, want_scores=False, prof=None):
+    """Top-k anchors of the query at the end of the cache on the paper's stride pattern."""
+    lib = load()
+    p = make_params(Qs, K, 1, topk, K.shape[1] - 1, prof=prof)
+    g = SlAnchorGeometry(window, 0, 0)
+    Hq = Qs.shape[0]
+    anchors = torch.empty((Hq, 1, topk), dtype=torch.int32, device=Qs.device)
+    scores = torch.empty((Hq, 1, topk), dtype=torch.float32, device=Qs.device) if want_scores else None
+    st = lib.sl_anchor_search_decode(ctypes.byref(p), ctypes.byref(g), _ptr(Qs), _ptr(K), _ptr(anchors),
+                                     _ptr(scores), _stream())
+    _check(st, "sl_anchor_search_decode")
+    return (anchors, scores) if want_scores else anchors
+
+
+def sl_anchor_attention_decode(Q, K, V, anchors, scores, window, backward_factor, forward_factor,
+                               scale=0.0, ws=None, prof=None, out=None):
+    """Algorithm 1's span-attention + combination for the query at the end of the cache."""
+    lib = load()
+    topk = 0 if anchors is None else anchors.shape[2]
+    p = make_params(Q, K, 1, topk, K.shape[1] - 1, scale, prof=prof)
+    g = SlAnchorGeometry(window, backward_factor, forward_factor)
+    if V.shape != K.shape or V.stride() != K.stride():
+        raise ValueError("V must have the shape and strides of K")
+    Hq, Lq, D = Q.shape
+    O = torch.empty((Hq, Lq, D), dtype=Q.dtype, device=Q.device) if out is None else out
+    need = lib.sl_anchor_workspace_bytes(ctypes.byref(p), ctypes.byref(g))
+    wptr, wbytes = _ws(ws).get(need)
+    st = lib.sl_anchor_attention_decode(ctypes.byref(p), ctypes.byref(g), _ptr(Q), _ptr(K), _ptr(V),
+                                        _ptr(anchors), _ptr(scores), _ptr(O), wptr, wbytes, _stream())
+    _check(st, "sl_anchor_attention_decode")
+    return O
 
 
 def sl_span_attention_prefill(Q, K, V, idx, S, q_pos0=0, scale=0.0, ws=None, prof=None, out=None):

@@ -185,6 +185,45 @@ sl_status sl_span_attention_combined_decode(const sl_params* p, const void* Q, c
                              ws_bytes, hip_stream);
 }
 
+size_t sl_anchor_workspace_bytes(const sl_params* p, const sl_anchor_geometry* g) {
+  sl::Problem pb;
+  if (!g || g->window < 0 || g->backward_factor < 0 || g->forward_factor < 0) return 0;
+  if (sl::make_problem(p, SL_OP_ATTENTION_DECODE, &pb) != SL_OK) return 0;
+  return sl::anchor_attention_ws_bytes(pb, g->window, g->backward_factor, g->forward_factor);
+}
+
+sl_status sl_anchor_search_decode(const sl_params* p, const sl_anchor_geometry* g, const void* Qs,
+                                  const void* K, int32_t* anchors, float* scores, void* hip_stream) {
+  sl::Problem pb;
+  sl_status s = sl::make_problem(p, SL_OP_SEARCH_DECODE, &pb);
+  if (s != SL_OK) return s;
+  if (!g || g->window < 0 || !Qs || !K || !anchors) return SL_ERR_INVALID_ARG;
+  if (!sl::aligned16(Qs) || !sl::aligned16(K) || !sl::aligned16(anchors) || !sl::aligned16(scores))
+    return SL_ERR_INVALID_ARG;
+  return sl::anchor_search_decode(pb, g->window, Qs, K, anchors, scores,
+                                  static_cast<hipStream_t>(hip_stream));
+}
+
+sl_status sl_anchor_attention_decode(const sl_params* p, const sl_anchor_geometry* g, const void* Q,
+                                     const void* K, const void* V, const int32_t* anchors,
+                                     const float* scores, void* O, void* ws, size_t ws_bytes,
+                                     void* hip_stream) {
+  sl::Problem pb;
+  sl_status s = sl::make_problem(p, SL_OP_ATTENTION_DECODE, &pb);
+  if (s != SL_OK) return s;
+  if (!g || g->window < 0 || g->backward_factor < 0 || g->forward_factor < 0) return SL_ERR_INVALID_ARG;
+  if (!Q || !K || !V || !O || (pb.topk > 0 && (!anchors || !scores))) return SL_ERR_INVALID_ARG;
+  if (!sl::aligned16(Q) || !sl::aligned16(K) || !sl::aligned16(V) || !sl::aligned16(O) ||
+      !sl::aligned16(anchors) || !sl::aligned16(scores))
+    return SL_ERR_INVALID_ARG;
+  const size_t need = sl::anchor_attention_ws_bytes(pb, g->window, g->backward_factor, g->forward_factor);
+  if (!ws || ws_bytes < need || (reinterpret_cast<uintptr_t>(ws) & 255u)) return SL_ERR_WORKSPACE;
+  pb.combined = true;
+  pb.gate = scores;
+  return sl::anchor_attention_decode(pb, g->window, g->backward_factor, g->forward_factor, Q, K, V,
+                                     anchors, O, ws, static_cast<hipStream_t>(hip_stream));
+}
+
 const char* sl_status_string(int status) {
   switch (status) {
     case SL_OK: return "SL_OK";

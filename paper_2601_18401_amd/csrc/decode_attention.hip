@@ -6,6 +6,8 @@
 // (head, slot, chunk) items of CT tokens so that thousands of workgroups are in flight.
 #include <hip/hip_ext.h>
 
+#include <cmath>
+
 #include "kernels.h"
 #include "stream_attend.h"
 
@@ -21,7 +23,9 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_split_kernel(
     const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
     const int32_t* __restrict__ idx, float* __restrict__ part, int64_t q_pos, int Hq, int Hkv,
     int S, int topk, int nchunks, int CT, float scale_log2e, int64_t qsh, int64_t kvsh,
-    int64_t kvst, int n_routed_blocks, int local_stride) {
+    int64_t kvst, int n_routed_blocks, int local_stride, const int64_t* __restrict__ ranges) {
+  // ranges != nullptr: slot s of head h attends tokens [ranges[2u], ranges[2u+1]) with
+  // u = h * (topk + 1) + s (slot topk = the window), instead of grid span idx[h][s] / [c*S, q_pos].
   using RL = RowLayout<T, D>;
   constexpr int EPL = RL::EPL, LPR = RL::LPR, RPW = RL::RPW;
   constexpr int NG = (kDecodeThreads / 64) * RPW;  // row groups per workgroup
@@ -38,8 +42,9 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_split_kernel(
   if (bid >= 0) {
     ck = bid % nchunks;
     const int u = bid / nchunks;
-    h = u / topk;
-    slot = u % topk;
+    const int ns = ranges ? topk + 1 : topk;  // with ranges the window is slot topk of every head
+    h = u / ns;
+    slot = u % ns;
   } else {
     // The G heads of one kv head read the same rows; their block ids differ by a multiple of 8
     // so that they run on the same XCD and share its L2.
@@ -54,7 +59,12 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_split_kernel(
   const int kv = h / G;
 
   int64_t t0, t1;
-  if (slot < topk) {
+  if (ranges) {
+    const int64_t r0 = ranges[2 * ((int64_t)h * (topk + 1) + slot)];
+    const int64_t r1 = ranges[2 * ((int64_t)h * (topk + 1) + slot) + 1];
+    t0 = r0 + (int64_t)ck * CT;
+    t1 = t0 + CT < r1 ? t0 + CT : r1;
+  } else if (slot < topk) {
     const int64_t j = idx[(int64_t)h * topk + slot];
     if (j >= 0 && j < c) {
       t0 = j * S + (int64_t)ck * CT;
@@ -309,7 +319,7 @@ __global__ __launch_bounds__(256) void decode_reduce_combined_kernel(const float
       asum += a;
       acc = fmaf(a, (slot_o(slot) * wa + ow * wb) / (s_ls[slot] * wa + lw * wb), acc);
     }
-    Elem<T>::store1(O + (int64_t)h * D + d0 + tid, asum > 0.f ? acc / asum : ow / lw);
+    Elem<T>::store1(O + (int64_t)h * D + d0 + tid, asum > 0.f ? acc / asum : (lw > 0.f ? ow / lw : 0.f));
   }
 }
 
@@ -340,12 +350,13 @@ sl_status launch_decode(const Problem& pb, const void* Q, const void* K, const v
                           pb.prof_start, pb.prof_stop, 0, static_cast<const T*>(Q),
                           static_cast<const T*>(K), static_cast<const T*>(V), idx, part, pb.q_pos0,
                           pb.Hq, pb.Hkv, pb.S, pb.topk, nchunks, CT, scale_log2e, pb.qsh, pb.kvsh,
-                          pb.kvst, n_routed, local_stride);
+                          pb.kvst, n_routed, local_stride, static_cast<const int64_t*>(nullptr));
   } else {
     hipLaunchKernelGGL((decode_split_kernel<T, D>), dim3(grid), dim3(kDecodeThreads), 0, st,
                        static_cast<const T*>(Q), static_cast<const T*>(K), static_cast<const T*>(V),
                        idx, part, pb.q_pos0, pb.Hq, pb.Hkv, pb.S, pb.topk, nchunks, CT,
-                       scale_log2e, pb.qsh, pb.kvsh, pb.kvst, n_routed, local_stride);
+                       scale_log2e, pb.qsh, pb.kvsh, pb.kvst, n_routed, local_stride,
+                       static_cast<const int64_t*>(nullptr));
   }
   if (hipGetLastError() != hipSuccess) return SL_ERR_LAUNCH;
   const int nrec = (pb.topk + 1) * nchunks;
@@ -359,6 +370,101 @@ sl_status launch_decode(const Problem& pb, const void* Q, const void* K, const v
                      (size_t)nrec * sizeof(float), st, part, static_cast<T*>(O), LSE, nrec);
   if (hipGetLastError() != hipSuccess) return SL_ERR_LAUNCH;
   return SL_OK;
+}
+
+
+// ------------------------------------------------------------------ the paper's own geometry
+// Token ranges of one decode step on the paper's geometry (Section 3.3, Algorithm 1): slot s of
+// head h holds S_t minus W for the selected anchor t = anchors[h][s] (W is a suffix of [0, i], so
+// the set difference is a clip; DedupConcat(S_t, W) is then the slot's range plus the window's),
+// S_t = [max(0, t - back), min(i, t + fwd)]; slot topk holds W = [wlo, i].
+__global__ void anchor_ranges_kernel(const int32_t* __restrict__ anchors, int64_t* __restrict__ ranges,
+                                     int Hq, int topk, int64_t i, int64_t wlo, int64_t back,
+                                     int64_t fwd) {
+  const int u = blockIdx.x * blockDim.x + threadIdx.x;
+  if (u >= Hq * (topk + 1)) return;
+  const int h = u / (topk + 1), slot = u % (topk + 1);
+  int64_t r0 = 0, r1 = 0;
+  if (slot == topk) {
+    r0 = wlo;
+    r1 = i + 1;
+  } else {
+    const int64_t t = anchors[h * topk + slot];
+    if (t >= 0 && t <= i) {
+      r0 = t - back > 0 ? t - back : 0;
+      const int64_t e = t + fwd < i ? t + fwd : i;
+      r1 = (e < wlo - 1 ? e : wlo - 1) + 1;
+      if (r1 < r0) r1 = r0;
+    }
+  }
+  ranges[2 * u] = r0;
+  ranges[2 * u + 1] = r1;
+}
+
+struct AnchorPlan {
+  int64_t back, fwd, wlo, maxlen;
+  int CT, nchunks;
+  size_t part_bytes, total_bytes;
+};
+
+int64_t isqrt_ceil(int64_t x) {
+  int64_t r = (int64_t)std::sqrt((double)x);
+  while (r * r > x) --r;
+  while ((r + 1) * (r + 1) <= x) ++r;
+  return r * r == x ? r : r + 1;
+}
+
+AnchorPlan plan_anchor(const Problem& pb, int64_t window, int b, int f) {
+  AnchorPlan a;
+  const int64_t i = pb.q_pos0;
+  const int64_t ell = isqrt_ceil(i);  // l(i) = ceil(sqrt(i))
+  a.back = (int64_t)b * ell;
+  a.fwd = (int64_t)f * ell;
+  a.wlo = window > 0 ? (i - window + 1 > 0 ? i - window + 1 : 0) : i + 1;
+  const int64_t wlen = i + 1 - a.wlo;
+  a.maxlen = a.back + a.fwd + 1 > wlen ? a.back + a.fwd + 1 : wlen;
+  if (a.maxlen > i + 1) a.maxlen = i + 1;
+  const int64_t units = (int64_t)pb.Hq * (pb.topk + 1);
+  int ct = 512;
+  while (ct > 64 && units * ((a.maxlen + ct - 1) / ct) < 4096) ct >>= 1;
+  a.CT = ct;
+  a.nchunks = (int)((a.maxlen + ct - 1) / ct);
+  a.part_bytes = align_up((size_t)units * a.nchunks * (pb.D + 2) * sizeof(float), 256);
+  a.total_bytes = a.part_bytes + align_up((size_t)units * 2 * sizeof(int64_t), 256);
+  return a;
+}
+
+template <typename T, int D>
+sl_status launch_anchor_attention(const Problem& pb, const AnchorPlan& a, const void* Q,
+                                  const void* K, const void* V, const int32_t* anchors, void* O,
+                                  void* ws, hipStream_t st) {
+  float* part = static_cast<float*>(ws);
+  int64_t* ranges = reinterpret_cast<int64_t*>(static_cast<char*>(ws) + a.part_bytes);
+  const int units = pb.Hq * (pb.topk + 1);
+  hipLaunchKernelGGL(anchor_ranges_kernel, dim3((units + 255) / 256), dim3(256), 0, st, anchors,
+                     ranges, pb.Hq, pb.topk, pb.q_pos0, a.wlo, a.back, a.fwd);
+  // every (head, slot, chunk) is a routed item here: the window is slot topk of every head
+  const int grid = units * a.nchunks;
+  const float scale_log2e = pb.scale * kLog2e;
+  if (pb.prof_start) {
+    hipExtLaunchKernelGGL((decode_split_kernel<T, D>), dim3(grid), dim3(kDecodeThreads), 0, st,
+                          pb.prof_start, pb.prof_stop, 0, static_cast<const T*>(Q),
+                          static_cast<const T*>(K), static_cast<const T*>(V), anchors, part, pb.q_pos0,
+                          pb.Hq, pb.Hkv, 1, pb.topk, a.nchunks, a.CT, scale_log2e, pb.qsh, pb.kvsh,
+                          pb.kvst, grid, 8, static_cast<const int64_t*>(ranges));
+  } else {
+    hipLaunchKernelGGL((decode_split_kernel<T, D>), dim3(grid), dim3(kDecodeThreads), 0, st,
+                       static_cast<const T*>(Q), static_cast<const T*>(K), static_cast<const T*>(V),
+                       anchors, part, pb.q_pos0, pb.Hq, pb.Hkv, 1, pb.topk, a.nchunks, a.CT,
+                       scale_log2e, pb.qsh, pb.kvsh, pb.kvst, grid, 8,
+                       static_cast<const int64_t*>(ranges));
+  }
+  if (hipGetLastError() != hipSuccess) return SL_ERR_LAUNCH;
+  const int nrec = (pb.topk + 1) * a.nchunks;
+  hipLaunchKernelGGL((decode_reduce_combined_kernel<T, D>), dim3(pb.Hq, D / kReduceDims), dim3(256),
+                     (size_t)2 * nrec * sizeof(float), st, part, pb.gate, static_cast<T*>(O), pb.topk,
+                     a.nchunks);
+  return hipGetLastError() == hipSuccess ? SL_OK : SL_ERR_LAUNCH;
 }
 
 }  // namespace
@@ -377,6 +483,26 @@ sl_status decode_attention(const Problem& pb, const void* Q, const void* K, cons
   }
   if (pb.D == 128) return launch_decode<float, 128>(pb, Q, K, V, idx, O, LSE, ws, st);
   return launch_decode<float, 64>(pb, Q, K, V, idx, O, LSE, ws, st);
+}
+
+}  // namespace sl
+
+namespace sl {
+
+size_t anchor_attention_ws_bytes(const Problem& pb, int64_t window, int b, int f) {
+  return plan_anchor(pb, window, b, f).total_bytes;
+}
+
+sl_status anchor_attention_decode(const Problem& pb, int64_t window, int b, int f, const void* Q,
+                                  const void* K, const void* V, const int32_t* anchors, void* O,
+                                  void* ws, hipStream_t st) {
+  const AnchorPlan a = plan_anchor(pb, window, b, f);
+  if (pb.dtype == SL_BF16) {
+    if (pb.D == 128) return launch_anchor_attention<bf16_t, 128>(pb, a, Q, K, V, anchors, O, ws, st);
+    return launch_anchor_attention<bf16_t, 64>(pb, a, Q, K, V, anchors, O, ws, st);
+  }
+  if (pb.D == 128) return launch_anchor_attention<float, 128>(pb, a, Q, K, V, anchors, O, ws, st);
+  return launch_anchor_attention<float, 64>(pb, a, Q, K, V, anchors, O, ws, st);
 }
 
 }  // namespace sl

@@ -18,6 +18,15 @@ size_t decode_attention_ws_bytes(const Problem& pb);
 sl_status decode_attention(const Problem& pb, const void* Q, const void* K, const void* V,
                            const int32_t* idx, void* O, float* LSE, void* ws, hipStream_t st);
 
+// The paper's own geometry, decode form (Section 3.3, Algorithm 1): anchors on the quadratic
+// stride pattern, spans of b*l(i) / f*l(i) tokens around the selected anchors, window w.
+sl_status anchor_search_decode(const Problem& pb, int64_t window, const void* Qs, const void* K,
+                               int32_t* anchors, float* scores, hipStream_t st);
+size_t anchor_attention_ws_bytes(const Problem& pb, int64_t window, int b, int f);
+sl_status anchor_attention_decode(const Problem& pb, int64_t window, int b, int f, const void* Q,
+                                  const void* K, const void* V, const int32_t* anchors, void* O,
+                                  void* ws, hipStream_t st);
+
 // a1 + a2: prefill span-search
 size_t prefill_search_ws_bytes(const Problem& pb);
 sl_status prefill_search(const Problem& pb, const void* Qs, const void* K, const void* Ks,

@@ -4,6 +4,8 @@
 // MFMA path does not cover.
 //
 // Scores are eq. (2): raw dot products, accumulated in fp32 from exact products.
+#include <cmath>
+
 #include "kernels.h"
 #include "select.h"
 
@@ -98,10 +100,17 @@ template <typename T, int D, int RMAX>
 __global__ __launch_bounds__(kDecodeSearchThreads) void decode_search_block_kernel(
     const T* __restrict__ Qs, const T* __restrict__ K, const T* __restrict__ Ks,
     int32_t* __restrict__ idx, float* __restrict__ scores, int64_t c, int64_t n, int G, int S,
-    int topk, int64_t qsh, int64_t kvsh, int64_t kvst) {
+    int topk, int64_t qsh, int64_t kvsh, int64_t kvst, int64_t anchor_i, int anchor_s0) {
+  // anchor_i >= 0: the candidates are the anchors of query position anchor_i on the paper's
+  // quadratic stride pattern (Section 3.3): candidate j is stride index s = anchor_s0 + j at token
+  // anchor_i - (s+1)^2 + 1, its key is K at that token, and the output lists tokens, not numbers.
   using RL = RowLayout<T, D>;
   constexpr int EPL = RL::EPL, LPR = RL::LPR, RPW = RL::RPW;
   constexpr int U = 16, NW = kDecodeSearchThreads / 64;
+  auto anchor_token = [&](int64_t j) {
+    const int64_t s1 = anchor_s0 + j + 1;
+    return anchor_i - s1 * s1 + 1;
+  };
   __shared__ float s_sc[kDecodeSearchThreads * RMAX];
   __shared__ __align__(16) unsigned s_hist[256];
   __shared__ int s_wave_tot[NW];
@@ -119,7 +128,9 @@ __global__ __launch_bounds__(kDecodeSearchThreads) void decode_search_block_kern
     for (int u = 0; u < U; ++u) {
       int64_t j = jb + u * RPW + g;
       j = j < c ? j : c - 1;
-      kr[u] = load16(span_key_ptr<T, D>(K, Ks, kv, j, n, S, kvsh, kvst) + lr * EPL);
+      const T* kp = anchor_i >= 0 ? K + kv * kvsh + anchor_token(j) * kvst
+                                  : span_key_ptr<T, D>(K, Ks, kv, j, n, S, kvsh, kvst);
+      kr[u] = load16(kp + lr * EPL);
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
@@ -215,7 +226,7 @@ __global__ __launch_bounds__(kDecodeSearchThreads) void decode_search_block_kern
     const bool is_eq = v[r] == Tval && v[r] > -INFINITY;
     if (is_gt || (is_eq && eq_before < need_eq)) {
       const int pos = gt_before + (eq_before < need_eq ? eq_before : need_eq);
-      oi[pos] = tid * R + r;
+      oi[pos] = anchor_i >= 0 ? (int32_t)anchor_token(tid * R + r) : tid * R + r;
       if (os) os[pos] = v[r];
     }
     gt_before += is_gt ? 1 : 0;
@@ -301,12 +312,12 @@ sl_status launch_decode_search(const Problem& pb, const void* Qs, const void* K,
       hipLaunchKernelGGL((decode_search_block_kernel<T, D, 1>), dim3(pb.Hq),
                          dim3(kDecodeSearchThreads), 0, st, static_cast<const T*>(Qs),
                          static_cast<const T*>(K), static_cast<const T*>(Ks), idx, scores, c, pb.n,
-                         pb.G, pb.S, pb.topk, pb.qsh, pb.kvsh, pb.kvst);
+                         pb.G, pb.S, pb.topk, pb.qsh, pb.kvsh, pb.kvst, (int64_t)-1, 0);
     else
       hipLaunchKernelGGL((decode_search_block_kernel<T, D, 4>), dim3(pb.Hq),
                          dim3(kDecodeSearchThreads), 0, st, static_cast<const T*>(Qs),
                          static_cast<const T*>(K), static_cast<const T*>(Ks), idx, scores, c, pb.n,
-                         pb.G, pb.S, pb.topk, pb.qsh, pb.kvsh, pb.kvst);
+                         pb.G, pb.S, pb.topk, pb.qsh, pb.kvsh, pb.kvst, (int64_t)-1, 0);
     if (pb.prof_stop) (void)hipEventRecord(pb.prof_stop, st);
     return hipGetLastError() == hipSuccess ? SL_OK : SL_ERR_LAUNCH;
   }
@@ -315,6 +326,24 @@ sl_status launch_decode_search(const Problem& pb, const void* Qs, const void* K,
                      static_cast<const T*>(Qs),
                      static_cast<const T*>(K), static_cast<const T*>(Ks), idx, scores, c, pb.n,
                      pb.G, pb.S, pb.topk, pb.qsh, pb.kvsh, pb.kvst);
+  if (pb.prof_stop) (void)hipEventRecord(pb.prof_stop, st);
+  return hipGetLastError() == hipSuccess ? SL_OK : SL_ERR_LAUNCH;
+}
+
+template <typename T, int D>
+sl_status launch_anchor_search(const Problem& pb, const void* Qs, const void* K, int32_t* anchors,
+                               float* scores, int64_t c, int s0, hipStream_t st) {
+  if (pb.prof_start) (void)hipEventRecord(pb.prof_start, st);
+  if (c <= kDecodeSearchThreads)
+    hipLaunchKernelGGL((decode_search_block_kernel<T, D, 1>), dim3(pb.Hq), dim3(kDecodeSearchThreads),
+                       0, st, static_cast<const T*>(Qs), static_cast<const T*>(K),
+                       static_cast<const T*>(nullptr), anchors, scores, c, (int64_t)0, pb.G, 1,
+                       pb.topk, pb.qsh, pb.kvsh, pb.kvst, pb.q_pos0, s0);
+  else
+    hipLaunchKernelGGL((decode_search_block_kernel<T, D, 4>), dim3(pb.Hq), dim3(kDecodeSearchThreads),
+                       0, st, static_cast<const T*>(Qs), static_cast<const T*>(K),
+                       static_cast<const T*>(nullptr), anchors, scores, c, (int64_t)0, pb.G, 1,
+                       pb.topk, pb.qsh, pb.kvsh, pb.kvst, pb.q_pos0, s0);
   if (pb.prof_stop) (void)hipEventRecord(pb.prof_stop, st);
   return hipGetLastError() == hipSuccess ? SL_OK : SL_ERR_LAUNCH;
 }
@@ -359,6 +388,33 @@ sl_status span_keys(const Problem& pb, const void* K, void* Ks, hipStream_t st) 
 }
 
 size_t decode_search_ws_bytes(const Problem&) { return 0; }
+
+// Integer square root (floor), exact.
+static int64_t isqrt64(int64_t x) {
+  int64_t r = (int64_t)std::sqrt((double)x);
+  while (r * r > x) --r;
+  while ((r + 1) * (r + 1) <= x) ++r;
+  return r;
+}
+
+// Candidate anchors of query position i = pb.q_pos0 with window w (Section 3.3, Algorithm 1):
+// stride indices s0 .. s_max, where t_s = i - (s+1)^2 + 1 >= 0 and t_s < i - w + 1.
+void anchor_candidates(const Problem& pb, int64_t window, int64_t* c, int* s0) {
+  const int64_t i = pb.q_pos0;
+  const int64_t s_max = isqrt64(i + 1) - 1;     // (s+1)^2 <= i + 1
+  const int64_t first = window > 0 ? isqrt64(window) : 0;  // (s+1)^2 > w  <=>  s >= isqrt(w)
+  *s0 = (int)first;
+  *c = s_max >= first ? s_max - first + 1 : 0;
+}
+
+sl_status anchor_search_decode(const Problem& pb, int64_t window, const void* Qs, const void* K,
+                               int32_t* anchors, float* scores, hipStream_t st) {
+  int64_t c;
+  int s0;
+  anchor_candidates(pb, window, &c, &s0);
+  if (c > (int64_t)kDecodeSearchThreads * 4) return SL_ERR_UNSUPPORTED;
+  SL_DISPATCH(launch_anchor_search, pb, Qs, K, anchors, scores, c, s0, st);
+}
 
 sl_status decode_search(const Problem& pb, const void* Qs, const void* K, const void* Ks,
                         int32_t* idx, float* scores, void* /*ws*/, hipStream_t st) {

@@ -10,7 +10,9 @@ import torch
 from oracle import superlinear as orc
 from paper_2601_18401_amd import binding as B
 from paper_2601_18401_amd import workloads as W
-from tests.test_parity_gpu import DEV, check_attention, check_combined, check_idx, f64
+import math
+
+from tests.test_parity_gpu import DEV, TOL, DevKV, DevRows, check_attention, check_combined, check_idx, f64
 
 pytestmark = pytest.mark.gpu
 
@@ -111,5 +113,30 @@ def test_decode_configs_full_cache(name):
             Oc = B.sl_span_attention_combined_decode(Q, K, V, idx_g, sc_g, cfg.S)
             torch.cuda.synchronize()
             check_combined(Oc, Q, K, V, idx_g, sc_g, cfg.S, cfg.L - 1, 0.0, [(0, 0), (13, 0), (31, 0)])
+    del data, K, V
+    torch.cuda.empty_cache()
+
+
+def test_paper_geometry_decode_at_1m():
+    # config 3's cache with the paper's kernel configuration (window 1088, top-2, b = 4, f = 2)
+    cfg = W.CONFIGS["C3"]
+    data = W.generate(cfg, device=DEV, n_queries=1)
+    K, V, Q = data["K"], data["V"], data["Q"][0]
+    w, k, b, f = 1088, 2, 4, 2
+    i = cfg.L - 1
+    G = cfg.Hq // cfg.Hkv
+    anchors, sc = B.sl_anchor_search_decode(Q, K, k, w, want_scores=True)
+    O = B.sl_anchor_attention_decode(Q, K, V, anchors, sc, w, b, f)
+    torch.cuda.synchronize()
+    an, scn, Qn, On = anchors.cpu().numpy(), sc.cpu().numpy().astype(np.float64), f64(Q), f64(O)
+    Kd, Vd = DevKV(K), DevKV(V)
+    for h in range(cfg.Hq):
+        _, t_o, _ = orc.anchor_search_row(Qn[h, 0], DevRows(K[h // G]), i, w, k)
+        if an[h, 0].tolist() != t_o:
+            cand = orc.anchor_candidates(i, w)
+            allsc = [float(f64(K[h // G, t]) @ Qn[h, 0]) for _, t in cand]
+            assert orc.selection_margin(allsc, k) < 1e-3
+        o = orc.anchor_combined_row(Qn[h, 0], Kd, Vd, h // G, i, w, b, f, an[h, 0], scn[h, 0], 1.0 / math.sqrt(cfg.D))
+        assert float(np.max(np.abs(On[h, 0] - o))) <= TOL[torch.bfloat16]
     del data, K, V
     torch.cuda.empty_cache()

@@ -416,3 +416,64 @@ def test_combined_invalid_arguments():
     st = lib.sl_span_attention_combined_prefill(ctypes.byref(p), Q.data_ptr(), K.data_ptr(), V.data_ptr(),
                                                 idx.data_ptr(), None, O.data_ptr(), wptr, wbytes, None)
     assert st == 1   # SL_ERR_INVALID_ARG: scores missing
+
+
+# ------------------------------------------------------------------------------ the paper's own geometry (decode form)
+
+ANCHOR_DECODE = [
+    # seed Hq Hkv L       D    k  w     b  f  dtype
+    (41, 8, 2, 70000, 128, 2, 1088, 4, 2, torch.bfloat16),   # the paper's kernel configuration
+    (42, 4, 4, 31, 64, 3, 0, 2, 0, torch.float32),           # Fig. 3's shape: i = 30, no window
+    (43, 4, 1, 5000, 128, 4, 48, 2, 0, torch.bfloat16),      # w = 7^2 - 1, adjacent anchors -> overlapping spans
+    (44, 2, 2, 900, 64, 8, 899, 4, 2, torch.float32),        # the window swallows every anchor but the last ones
+    (45, 2, 1, 20, 128, 2, 24, 4, 2, torch.bfloat16),        # window longer than the cache: no candidate
+    (46, 4, 2, 300000, 128, 16, 575, 3, 1, torch.bfloat16),  # long cache, 16 anchors
+]
+
+
+@pytest.mark.parametrize("seed,Hq,Hkv,L,D,k,w,b,f,dtype", ANCHOR_DECODE)
+def test_anchor_decode(seed, Hq, Hkv, L, D, k, w, b, f, dtype):
+    Q, K, V = make(seed, Hq, Hkv, L, D, dtype, Lq=1, scale=0.5)
+    i = L - 1
+    G = Hq // Hkv
+    anchors, sc = B.sl_anchor_search_decode(Q, K, k, w, want_scores=True)
+    torch.cuda.synchronize()
+    an, scn = anchors.cpu().numpy(), sc.cpu().numpy()
+    Qn = f64(Q)
+    Kh = [f64(K[kv]) if L <= 100000 else None for kv in range(Hkv)]
+    for h in range(Hq):
+        kv = h // G
+        Krow = Kh[kv] if Kh[kv] is not None else DevRows(K[kv])
+        s_o, t_o, sc_o = orc.anchor_search_row(Qn[h, 0], Krow, i, w, k)
+        want = t_o + [-1] * (k - len(t_o))
+        got = an[h, 0].tolist()
+        if got != want:
+            cand = orc.anchor_candidates(i, w)
+            allsc = [float(f64(K[kv, t]) @ Qn[h, 0]) for _, t in cand]
+            assert orc.selection_margin(allsc, k) < MARGIN, (h, got, want)
+        for slot, t in enumerate(got):
+            if t >= 0:
+                assert abs(scn[h, 0, slot] - float(f64(K[kv, t]) @ Qn[h, 0])) <= 1e-3
+            else:
+                assert scn[h, 0, slot] == -np.inf
+    # attention + combination on the library's own selection
+    sc_in = torch.where(torch.isfinite(sc), sc, torch.zeros_like(sc))
+    O = B.sl_anchor_attention_decode(Q, K, V, anchors, sc_in, w, b, f)
+    torch.cuda.synchronize()
+    On = f64(O)
+    Kd, Vd = DevKV(K), DevKV(V)
+    scale = 1.0 / math.sqrt(D)
+    for h in range(Hq):
+        o = orc.anchor_combined_row(Qn[h, 0], Kd, Vd, h // G, i, w, b, f, an[h, 0], scn[h, 0].astype(np.float64), scale)
+        err = float(np.max(np.abs(On[h, 0] - o)))
+        assert err <= TOL[dtype], (h, err)
+
+
+class DevRows:
+    """Row access K[t] -> fp64 [D] on a device tensor [L, D] (for the oracle's anchor scoring)."""
+
+    def __init__(self, t):
+        self.t = t
+
+    def __getitem__(self, t):
+        return f64(self.t[t])
