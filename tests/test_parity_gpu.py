@@ -200,6 +200,33 @@ def test_prefill_search_ties_lower_index_wins():
     assert np.mean(idx.cpu().numpy() == want) > 0.98
 
 
+@pytest.mark.parametrize("S,n,k", [(64, 40, 8), (64, 70, 16), (128, 33, 32)])
+def test_prefill_search_heavy_ties_exact(S, n, k):
+    # every span key is one of 5 distinct rows: most of a query's candidates tie exactly, on both
+    # sides of the k-th score, so the selection is decided by the tie rule (lower index) alone
+    Hq, Hkv, D = 4, 2, 128
+    L = S * n + 17
+    Q, K, V = make(21, Hq, Hkv, L, D, torch.bfloat16)
+    g = torch.Generator().manual_seed(4)
+    base = torch.randn((Hkv, 5, D), generator=g).to(torch.bfloat16).to(DEV)
+    which = torch.randint(0, 5, (n,), generator=g)
+    for j in range(n):
+        K[:, (j + 1) * S - 1] = base[:, which[j]]
+    idx, sc = B.sl_span_search_prefill(Q, K, None, S, k, want_scores=True)
+    torch.cuda.synchronize()
+    want, wsc = orc.span_search(f64(Q), orc.span_keys(f64(K), S), S, k, return_scores=True)
+    got = idx.cpu().numpy()
+    # a row may differ only where two DISTINCT keys score within the tie margin of each other
+    qb = f64(Q).reshape(Hkv, Hq // Hkv, L, D)
+    five = np.einsum("vgld,vbd->vglb", qb, f64(base)).reshape(Hq, L, 5)
+    gaps = np.diff(np.sort(five, axis=-1), axis=-1).min(axis=-1)
+    bad = (got != want).any(axis=-1)
+    assert not (bad & (gaps >= 1e-3)).any()
+    assert bad.mean() < 0.02
+    ok = ~bad
+    assert np.allclose(np.where(got >= 0, sc.cpu().numpy(), 0.0)[ok], np.where(want >= 0, wsc, 0.0)[ok], atol=1e-3)
+
+
 def test_strided_inputs():
     # Q and K/V taken as views of wider buffers (non-packed strides)
     Hq, Hkv, L, D, S, k = 4, 2, 512, 128, 64, 3
