@@ -253,7 +253,9 @@ struct TileDesc {
   int kv;
   int64_t kv_begin, kv_end;
   int64_t q_off;      // element offset of the lane's Q vector
-  int64_t row_out;    // partial record index of the lane's column, -1 = no row
+  int64_t row_out;    // partial record index of the lane's column (fused merge: its row index
+                      // h*Lq + r), -1 = no row
+  int64_t row_base;   // fused merge: h*Lq of the tile's head
   int64_t i_q, lo_q;  // LOCAL: query position and start of its window
 };
 
@@ -278,7 +280,7 @@ struct FlashCarry {
 // other group's MFMAs instead of both groups asking for the matrix pipe at the same time.
 // When the kv loop is over, the first K/V stage and the Q fragments of the next tile are
 // requested before the output tile is normalised and written.
-template <bool LOCAL>
+template <bool LOCAL, bool FUSED>
 __device__ __forceinline__ void flash_tile(const FlashArgs& a, char* lds, const TileDesc& cur,
                                            const TileDesc& next, bool has_next, FlashCarry& c) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -486,22 +488,91 @@ __device__ __forceinline__ void flash_tile(const FlashArgs& a, char* lds, const 
       *reinterpret_cast<bf16x4*>(&ost[srow * HD + unit * 8 + 4 * hf]) = w;
     }
   __builtin_amdgcn_wave_barrier();
+  if constexpr (FUSED) {
+    // Local-window tile with the merge fused in (topk <= 8): the lane that would store 16 bytes
+    // of the window's partial instead loads the same 16 bytes of the row's routed partials
+    // (written by the routed kernel, which ran before on the stream), does the log-sum-exp merge
+    // and stores the final output.  Every load is issued before the first dependent use; slots
+    // that take no part may hold anything and are discarded by selects, never by arithmetic.
+    const int topk = a.topk, nslot = topk + 1;
 #pragma unroll
-  for (int half = 0; half < 2; ++half) {
-    int64_t outs[4];
-    uint4 vals[4];
+    for (int half = 0; half < 2; ++half) {
+      int64_t outs[4];
+      int js[4][8];
+      float ls[4][8];
+      uint4 ov[4][8];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      const int row = w4 * 32 + (half * 4 + u) * 4 + (lane >> 4), piece = lane & 15;
-      outs[u] = row_out[row];
-      vals[u] = *reinterpret_cast<const uint4*>(&ost[row * HD + ((piece ^ (row & 15)) << 3)]);
+      for (int u = 0; u < 4; ++u) {
+        const int row = w4 * 32 + (half * 4 + u) * 4 + (lane >> 4), piece = lane & 15;
+        outs[u] = row_out[row];
+        const int64_t rg = outs[u] >= 0 ? outs[u] : 0;
+#pragma unroll
+        for (int sl = 0; sl < 8; ++sl) {
+          const bool in = sl < topk;
+          js[u][sl] = in ? a.idx[rg * topk + sl] : -1;
+          ls[u][sl] = in ? a.part_lse[rg * nslot + sl] : 0.f;
+          ov[u][sl] = in ? load16(a.part_o + (rg * nslot + sl) * HD + piece * 8) : make_uint4(0, 0, 0, 0);
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int row = w4 * 32 + (half * 4 + u) * 4 + (lane >> 4), piece = lane & 15;
+        const int cq = (int)((a.q_pos0 + (outs[u] - cur.row_base)) / a.S);
+        const float lw = row_lse[row];
+        float M = lw;
+#pragma unroll
+        for (int sl = 0; sl < 8; ++sl) {
+          // a slot takes part if its span is a candidate and no earlier slot lists the same span
+          bool ok = js[u][sl] >= 0 && js[u][sl] < cq;
+#pragma unroll
+          for (int v = 0; v < sl; ++v) ok = ok && js[u][v] != js[u][sl];
+          ls[u][sl] = ok ? ls[u][sl] : -INFINITY;
+          M = fmaxf(M, ls[u][sl]);
+        }
+        float acc[8], f[8];
+        float wsum = __expf(lw - M);
+        Elem<bf16_t>::unpack(*reinterpret_cast<const uint4*>(&ost[row * HD + ((piece ^ (row & 15)) << 3)]), f);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[e] = wsum * f[e];
+#pragma unroll
+        for (int sl = 0; sl < 8; ++sl) {
+          const bool ok = ls[u][sl] > -INFINITY;
+          const float w = ok ? __expf(ls[u][sl] - M) : 0.f;
+          wsum += w;
+          Elem<bf16_t>::unpack(ok ? ov[u][sl] : make_uint4(0, 0, 0, 0), f);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) acc[e] = fmaf(w, f[e], acc[e]);
+        }
+        const float winv = 1.f / wsum;
+        uint4 res;
+        res.x = (uint32_t)f32_to_bf16(acc[0] * winv) | ((uint32_t)f32_to_bf16(acc[1] * winv) << 16);
+        res.y = (uint32_t)f32_to_bf16(acc[2] * winv) | ((uint32_t)f32_to_bf16(acc[3] * winv) << 16);
+        res.z = (uint32_t)f32_to_bf16(acc[4] * winv) | ((uint32_t)f32_to_bf16(acc[5] * winv) << 16);
+        res.w = (uint32_t)f32_to_bf16(acc[6] * winv) | ((uint32_t)f32_to_bf16(acc[7] * winv) << 16);
+        if (outs[u] >= 0) {
+          *reinterpret_cast<uint4*>(a.O + outs[u] * HD + piece * 8) = res;
+          if (piece == 0) a.LSE[outs[u]] = M + __logf(wsum);
+        }
+      }
     }
+  } else {
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      const int row = w4 * 32 + (half * 4 + u) * 4 + (lane >> 4), piece = lane & 15;
-      if (outs[u] >= 0) {
-        *reinterpret_cast<uint4*>(a.part_o + outs[u] * HD + piece * 8) = vals[u];
-        if (piece == 0) a.part_lse[outs[u]] = row_lse[row];
+    for (int half = 0; half < 2; ++half) {
+      int64_t outs[4];
+      uint4 vals[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int row = w4 * 32 + (half * 4 + u) * 4 + (lane >> 4), piece = lane & 15;
+        outs[u] = row_out[row];
+        vals[u] = *reinterpret_cast<const uint4*>(&ost[row * HD + ((piece ^ (row & 15)) << 3)]);
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int row = w4 * 32 + (half * 4 + u) * 4 + (lane >> 4), piece = lane & 15;
+        if (outs[u] >= 0) {
+          *reinterpret_cast<uint4*>(a.part_o + outs[u] * HD + piece * 8) = vals[u];
+          if (piece == 0) a.part_lse[outs[u]] = row_lse[row];
+        }
       }
     }
   }
@@ -539,6 +610,7 @@ __global__ __launch_bounds__(kFlashThreads, 1) void span_flash_routed_kernel(con
     d.q_off = h * a.qsh + r * a.qst;
     d.row_out = qrow < info.z ? ((int64_t)h * a.Lq + r) * (a.topk + 1) + slot : -1;
     d.i_q = d.lo_q = 0;
+    d.row_base = 0;
     return d;
   };
   FlashCarry carry;
@@ -553,12 +625,17 @@ __global__ __launch_bounds__(kFlashThreads, 1) void span_flash_routed_kernel(con
       const int4 ninfo = a.tile_info[t + NWL];
       nxt = describe(ninfo, a.items[ninfo.y + min(qrow, ninfo.z - 1)]);
     }
-    flash_tile<false>(a, lds, cur, nxt, has_next, carry);
+    flash_tile<false, false>(a, lds, cur, nxt, has_next, carry);
     cur = nxt;
   }
 }
 
 // Local window [c*S, i]: regular 256-row tiles of one head with the causal / window mask.
+// FUSED = false: writes the window's partial into the row's last slot (a merge kernel follows).
+// FUSED = true (joint softmax, topk <= 8): merges the row's routed partials in the epilogue and
+// writes the final output, which takes the merge's HBM traffic off the critical path of a
+// separate kernel and saves the window partial's round trip.
+template <bool FUSED>
 __global__ __launch_bounds__(kFlashThreads, 1) void span_flash_local_kernel(const FlashArgs a) {
   extern __shared__ __align__(16) char lds[];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -571,7 +648,9 @@ __global__ __launch_bounds__(kFlashThreads, 1) void span_flash_local_kernel(cons
   TileDesc d;
   d.kv = h / a.G;
   d.q_off = h * a.qsh + rc * a.qst;
-  d.row_out = r < a.Lq ? ((int64_t)h * a.Lq + r) * (a.topk + 1) + a.topk : -1;
+  d.row_base = (int64_t)h * a.Lq;
+  if (FUSED) d.row_out = r < a.Lq ? d.row_base + r : -1;
+  else d.row_out = r < a.Lq ? (d.row_base + r) * (a.topk + 1) + a.topk : -1;
   d.i_q = a.q_pos0 + rc;
   d.lo_q = (d.i_q / a.S) * a.S;
   const int64_t i_first = a.q_pos0 + r0;
@@ -581,7 +660,7 @@ __global__ __launch_bounds__(kFlashThreads, 1) void span_flash_local_kernel(cons
   FlashCarry carry;
   carry.kb = carry.vb = 0;
   carry.primed = false;
-  flash_tile<true>(a, lds, d, d, false, carry);
+  flash_tile<true, FUSED>(a, lds, d, d, false, carry);
 }
 
 // ------------------------------------------------------------------ merge
@@ -745,7 +824,9 @@ bool allow_large_lds() {
     const bool ok =
         hipFuncSetAttribute(reinterpret_cast<const void*>(span_flash_routed_kernel),
                             hipFuncAttributeMaxDynamicSharedMemorySize, kFlashLdsBytes) == hipSuccess &&
-        hipFuncSetAttribute(reinterpret_cast<const void*>(span_flash_local_kernel),
+        hipFuncSetAttribute(reinterpret_cast<const void*>(span_flash_local_kernel<false>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, kFlashLdsBytes) == hipSuccess &&
+        hipFuncSetAttribute(reinterpret_cast<const void*>(span_flash_local_kernel<true>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, kFlashLdsBytes) == hipSuccess;
     done = ok ? 1 : -1;
   }
@@ -858,8 +939,13 @@ sl_status prefill_attention_mfma(const Problem& pb, const void* Q, const void* K
     if (pb.prof_stop) (void)hipEventRecord(pb.prof_stop, st);
   }
   const int tiles_per_head = (int)((pb.Lq + TM - 1) / TM);
-  hipLaunchKernelGGL(span_flash_local_kernel, dim3(pb.Hq * tiles_per_head), dim3(kFlashThreads),
-                     kFlashLdsBytes, st, a);
+  if (!pb.combined && pb.topk <= 8) {  // the window kernel merges and writes the final output
+    hipLaunchKernelGGL(span_flash_local_kernel<true>, dim3(pb.Hq * tiles_per_head),
+                       dim3(kFlashThreads), kFlashLdsBytes, st, a);
+    return hipGetLastError() == hipSuccess ? SL_OK : SL_ERR_LAUNCH;
+  }
+  hipLaunchKernelGGL(span_flash_local_kernel<false>, dim3(pb.Hq * tiles_per_head),
+                     dim3(kFlashThreads), kFlashLdsBytes, st, a);
   const int64_t rows = (int64_t)pb.Hq * pb.Lq;
   const dim3 mgrid((unsigned)((rows + 15) / 16));
 #define SL_MERGE(KM)                                                                             \
