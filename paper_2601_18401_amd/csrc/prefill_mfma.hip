@@ -11,10 +11,12 @@
 //                                   gathered Q rows against the span's K/V tiles staged through
 //                                   LDS, flash softmax, MFMA QK^T and PV; writes a normalised
 //                                   partial (o, lse) per (row, slot)
-//   span_flash_local                the local window [c*S, i]: regular 256-row tiles of one
-//                                   head with the causal mask; writes the row's last partial
-//   merge_partials                  streaming log-sum-exp merge of the <= topk + 1 partials of
-//                                   every row; writes O and LSE
+//   span_flash_local                the local window [c*S, i]: regular 128-row tiles of one
+//                                   head with the causal mask; joint form with topk <= 8: merges
+//                                   the row's routed partials in its epilogue (log-sum-exp) and
+//                                   writes O and LSE; otherwise writes the row's last partial
+//   merge_partials / merge_combined streaming merge of the <= topk + 1 partials of every row
+//                                   (topk > 8, and the gated combination of Section 3.4)
 //
 // MFMA formulation.  Both products are computed transposed so that a lane owns a query column:
 //   S^T[kv][q] = K[kv][:] . Q[q][:]      A = K tile (LDS), B = Q rows (registers)
@@ -34,31 +36,42 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x8 __attribute__((ext_vector_type(8)));
 
-constexpr int TM = 256;            // query rows per workgroup: two groups of 4 wavefronts x 32 columns
-constexpr int TG = 128;            // rows of one wavefront group
+constexpr int TG = 128;            // rows of one wavefront group (4 wavefronts x 32 columns)
 constexpr int TN = 64;             // kv positions per staged tile
 constexpr int HD = 128;            // head dimension of this path
-constexpr int kFlashThreads = 512;
 constexpr int kBucketRows = 1024;  // query rows of one head per bucketing workgroup
 
-// LDS of the flash kernel (dynamic, 150528 bytes, one workgroup per compute unit).
-// Main loop: three stages of the V^T tile and two of the K tile, filled by direct global->LDS
-// loads (16 bytes per lane, a wavefront instruction fills 1 KB contiguously); rows are unpadded
-// and their 16-byte pieces XOR-swizzled so that the MFMA operand reads of 16 consecutive lanes
-// hit 16 distinct bank groups:
+// LDS of the flash kernels (dynamic).  Main loop: stages of the V^T tile and of the K tile, filled
+// by direct global->LDS loads (16 bytes per lane, a wavefront instruction fills 1 KB
+// contiguously); rows are unpadded and their 16-byte pieces XOR-swizzled so that the MFMA
+// operand reads of 16 consecutive lanes hit 16 distinct bank groups:
 //   K tile  [64][128]: piece p of row r at position p ^ (r & 15)
 //   V^T tile [128][64]: piece p of row d at position p ^ ((d >> 1) & 7)
-// Epilogue: each wavefront group stages its output tile [128][128] bf16 in a region of its own
-// (piece p of row r at p ^ (r & 15)), so the first K/V tile of the next 256-row tile can be
-// fetched while the current one is written out.
-constexpr int kStageElems = TN * HD;                        // 8192 bf16 = 16 KB
-constexpr int kStagesK = 2, kStagesV = 3;
-constexpr int kLdsV = 0;
-constexpr int kLdsK = kStagesV * kStageElems * 2;           // byte offset 49152
-constexpr int kLdsOut = (kStagesV + kStagesK) * kStageElems * 2;  // bf16[2][TG][HD], byte offset 81920
-constexpr int kLdsRowOut = kLdsOut + 2 * TG * HD * 2;       // int64[2][TG], byte offset 147456
-constexpr int kLdsRowLse = kLdsRowOut + 2 * TG * 8;         // float[2][TG]
-constexpr int kFlashLdsBytes = kLdsRowLse + 2 * TG * 4;     // 150528
+// Epilogue: each wavefront group stages its output tile [128][128] bf16 (piece p of row r at
+// p ^ (r & 15)).
+//   NG = 2 (routed, 512 threads, 256 rows, one workgroup per compute unit, 150528 bytes): two K
+//     and three V^T stages (the late group reads a V^T tile one step after the early group); the
+//     output region is separate, so the first K/V tile of the next 256-row tile can be fetched
+//     while the current one is written out.
+//   NG = 1 (local window, 256 threads, 128 rows, 67072 bytes: two workgroups per compute unit, so
+//     one's epilogue runs beside the other's main loop): two stages each; the output region
+//     lies over the V^T stages, which are dead by then.
+constexpr int kStageElems = TN * HD;  // 8192 bf16 = 16 KB
+template <int NG>
+struct FlashLds {
+  static constexpr int kStagesK = 2, kStagesV = NG == 2 ? 3 : 2;
+  static constexpr int kV = 0;
+  static constexpr int kK = kStagesV * kStageElems * 2;
+  static constexpr int kStagesEnd = (kStagesV + kStagesK) * kStageElems * 2;
+  static constexpr int kOut = NG == 2 ? kStagesEnd : 0;                             // bf16[NG][TG][HD]
+  static constexpr int kRowOut = NG == 2 ? kOut + NG * TG * HD * 2 : kStagesEnd;    // int64[NG][TG]
+  static constexpr int kRowLse = kRowOut + NG * TG * 8;                             // float[NG][TG]
+  static constexpr int kBytes = kRowLse + NG * TG * 4;
+  static constexpr int kThreads = NG * 256;
+  static constexpr int kRows = NG * TG;  // query rows per workgroup
+  static constexpr int kBlocksPerWave = 16 / (4 * NG);  // 1 KB blocks of a staged tile per wavefront
+};
+constexpr int TM = FlashLds<2>::kRows;  // rows of a routed tile
 
 #define SL_LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
 #define SL_GLOBAL_PTR(p) ((const __attribute__((address_space(1))) void*)(p))
@@ -280,47 +293,49 @@ struct FlashCarry {
 // other group's MFMAs instead of both groups asking for the matrix pipe at the same time.
 // When the kv loop is over, the first K/V stage and the Q fragments of the next tile are
 // requested before the output tile is normalised and written.
-template <bool LOCAL, bool FUSED>
+template <int NG, bool LOCAL, bool FUSED>
 __device__ __forceinline__ void flash_tile(const FlashArgs& a, char* lds, const TileDesc& cur,
                                            const TileDesc& next, bool has_next, FlashCarry& c) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int grp = wave >> 2, w4 = wave & 3;  // grp 0 = early, 1 = late
   const int qc = lane & 31, hf = lane >> 5;
   const int srow = w4 * 32 + qc;             // row inside the group's 128-row half tile
-  bf16_t* const ldsV = reinterpret_cast<bf16_t*>(lds + kLdsV);
-  bf16_t* const ldsK = reinterpret_cast<bf16_t*>(lds + kLdsK);
+  using Lds = FlashLds<NG>;
+  constexpr int kStagesK = Lds::kStagesK, kStagesV = Lds::kStagesV, BPW = Lds::kBlocksPerWave;
+  bf16_t* const ldsV = reinterpret_cast<bf16_t*>(lds + Lds::kV);
+  bf16_t* const ldsK = reinterpret_cast<bf16_t*>(lds + Lds::kK);
 
   // Direct global -> LDS staging of one (K, V^T) tile pair in 1 KB blocks (4 K rows or 8 V^T rows
   // each); lane L of a block lands at byte 16*L.
   // Per-lane byte offsets are loop-invariant 32-bit values; the kv head and the tile position
   // go into the wave-uniform base pointer.
-  uint32_t koff[2], voff[2];
+  uint32_t koff[BPW], voff[BPW];
 #pragma unroll
-  for (int i = 0; i < 2; ++i) {
-    const int blk = wave * 2 + i;
+  for (int i = 0; i < BPW; ++i) {
+    const int blk = wave * BPW + i;
     const int row = blk * 4 + (lane >> 4), pc = lane & 15, gp = pc ^ (row & 15);
     koff[i] = (uint32_t)((row * a.kvst + gp * 8) * sizeof(bf16_t));
     const int d = blk * 8 + (lane >> 3), pv = lane & 7, gv = pv ^ ((d >> 1) & 7);
     voff[i] = (uint32_t)((d * a.Lp + gv * 8) * sizeof(bf16_t));
   }
-  // wavefront w fills blocks 2w, 2w+1 of both tiles
+  // wavefront w fills blocks w*BPW .. w*BPW + BPW-1 of both tiles
   auto stage = [&](int kvh, int64_t t0, int kb, int vb) {
     const char* kbase = reinterpret_cast<const char*>(a.K + (int64_t)kvh * a.kvsh + t0 * a.kvst);
     const char* vbase = reinterpret_cast<const char*>(a.Vt + (int64_t)kvh * HD * a.Lp + t0);
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
+    for (int i = 0; i < BPW; ++i) {
       uint32_t off = koff[i];
       if (LOCAL) {  // rows past the end of the sequence re-read the last row (masked later)
-        const int row = (wave * 2 + i) * 4 + (lane >> 4);
+        const int row = (wave * BPW + i) * 4 + (lane >> 4);
         if (t0 + row >= a.L) off -= (uint32_t)((t0 + row - (a.L - 1)) * a.kvst * sizeof(bf16_t));
       }
       __builtin_amdgcn_global_load_lds(SL_GLOBAL_PTR(kbase + off),
-                                       SL_LDS_PTR(ldsK + kb * kStageElems + (wave * 2 + i) * 512), 16, 0, 0);
+                                       SL_LDS_PTR(ldsK + kb * kStageElems + (wave * BPW + i) * 512), 16, 0, 0);
     }
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < BPW; ++i)
       __builtin_amdgcn_global_load_lds(SL_GLOBAL_PTR(vbase + voff[i]),
-                                       SL_LDS_PTR(ldsV + vb * kStageElems + (wave * 2 + i) * 512), 16, 0, 0);
+                                       SL_LDS_PTR(ldsV + vb * kStageElems + (wave * BPW + i) * 512), 16, 0, 0);
   };
   // Q row of a lane's column, as the B operand of S^T = K Q^T
   auto load_q = [&](int64_t q_off) {
@@ -456,8 +471,8 @@ __device__ __forceinline__ void flash_tile(const FlashArgs& a, char* lds, const 
   __syncthreads();
   c.kb = kb;
   c.vb = vb;
-  c.primed = has_next;
-  if (has_next) {
+  c.primed = NG == 2 && has_next;  // NG = 1: the output region lies over the stages, nothing is fetched ahead
+  if (NG == 2 && has_next) {
     stage(next.kv, next.kv_begin, kb, vb);
     load_q(next.q_off);
   }
@@ -469,9 +484,9 @@ __device__ __forceinline__ void flash_tile(const FlashArgs& a, char* lds, const 
   // issue order, so the reads below see the writes of the other lanes.
   const float lt = pair_sum(l);
   const float inv = 1.f / lt;
-  bf16_t* const ost = reinterpret_cast<bf16_t*>(lds + kLdsOut) + grp * TG * HD;
-  int64_t* const row_out = reinterpret_cast<int64_t*>(lds + kLdsRowOut) + grp * TG;
-  float* const row_lse = reinterpret_cast<float*>(lds + kLdsRowLse) + grp * TG;
+  bf16_t* const ost = reinterpret_cast<bf16_t*>(lds + Lds::kOut) + grp * TG * HD;
+  int64_t* const row_out = reinterpret_cast<int64_t*>(lds + Lds::kRowOut) + grp * TG;
+  float* const row_lse = reinterpret_cast<float*>(lds + Lds::kRowLse) + grp * TG;
   if (hf == 0) {
     row_lse[srow] = (m + __log2f(lt)) * kLn2;
     row_out[srow] = cur.row_out;
@@ -586,7 +601,7 @@ __device__ __forceinline__ void flash_tile(const FlashArgs& a, char* lds, const 
 // workgroups walk the chunk interleaved, so at any moment they sit on neighbouring tiles -- the
 // same one or two buckets -- and share the span through that XCD's L2.  The record and the item
 // of a workgroup's next tile are fetched while its current tile is computed.
-__global__ __launch_bounds__(kFlashThreads, 1) void span_flash_routed_kernel(const FlashArgs a) {
+__global__ __launch_bounds__(FlashLds<2>::kThreads, 1) void span_flash_routed_kernel(const FlashArgs a) {
   extern __shared__ __align__(16) char lds[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int qrow = (wave >> 2) * TG + (wave & 3) * 32 + (lane & 31);
@@ -625,7 +640,7 @@ __global__ __launch_bounds__(kFlashThreads, 1) void span_flash_routed_kernel(con
       const int4 ninfo = a.tile_info[t + NWL];
       nxt = describe(ninfo, a.items[ninfo.y + min(qrow, ninfo.z - 1)]);
     }
-    flash_tile<false, false>(a, lds, cur, nxt, has_next, carry);
+    flash_tile<2, false, false>(a, lds, cur, nxt, has_next, carry);
     cur = nxt;
   }
 }
@@ -636,13 +651,14 @@ __global__ __launch_bounds__(kFlashThreads, 1) void span_flash_routed_kernel(con
 // writes the final output, which takes the merge's HBM traffic off the critical path of a
 // separate kernel and saves the window partial's round trip.
 template <bool FUSED>
-__global__ __launch_bounds__(kFlashThreads, 1) void span_flash_local_kernel(const FlashArgs a) {
+__global__ __launch_bounds__(FlashLds<1>::kThreads, 2) void span_flash_local_kernel(const FlashArgs a) {
   extern __shared__ __align__(16) char lds[];
+  constexpr int TML = FlashLds<1>::kRows;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int qrow = (wave >> 2) * TG + (wave & 3) * 32 + (lane & 31);
-  const int tiles_per_head = (int)((a.Lq + TM - 1) / TM);
+  const int qrow = wave * 32 + (lane & 31);
+  const int tiles_per_head = (int)((a.Lq + TML - 1) / TML);
   const int h = blockIdx.x / tiles_per_head;
-  const int64_t r0 = (int64_t)(blockIdx.x % tiles_per_head) * TM;
+  const int64_t r0 = (int64_t)(blockIdx.x % tiles_per_head) * TML;
   const int64_t r = r0 + qrow;
   const int64_t rc = r < a.Lq ? r : a.Lq - 1;
   TileDesc d;
@@ -654,13 +670,13 @@ __global__ __launch_bounds__(kFlashThreads, 1) void span_flash_local_kernel(cons
   d.i_q = a.q_pos0 + rc;
   d.lo_q = (d.i_q / a.S) * a.S;
   const int64_t i_first = a.q_pos0 + r0;
-  const int64_t i_last = min(a.q_pos0 + r0 + TM - 1, a.q_pos0 + a.Lq - 1);
+  const int64_t i_last = min(a.q_pos0 + r0 + TML - 1, a.q_pos0 + a.Lq - 1);
   d.kv_begin = (i_first / a.S) * a.S;
   d.kv_end = d.kv_begin + ((i_last - d.kv_begin) / TN + 1) * TN;
   FlashCarry carry;
   carry.kb = carry.vb = 0;
   carry.primed = false;
-  flash_tile<true, FUSED>(a, lds, d, d, false, carry);
+  flash_tile<1, true, FUSED>(a, lds, d, d, false, carry);
 }
 
 // ------------------------------------------------------------------ merge
@@ -823,11 +839,11 @@ bool allow_large_lds() {
   if (done == 0) {
     const bool ok =
         hipFuncSetAttribute(reinterpret_cast<const void*>(span_flash_routed_kernel),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, kFlashLdsBytes) == hipSuccess &&
+                            hipFuncAttributeMaxDynamicSharedMemorySize, FlashLds<2>::kBytes) == hipSuccess &&
         hipFuncSetAttribute(reinterpret_cast<const void*>(span_flash_local_kernel<false>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, kFlashLdsBytes) == hipSuccess &&
+                            hipFuncAttributeMaxDynamicSharedMemorySize, FlashLds<1>::kBytes) == hipSuccess &&
         hipFuncSetAttribute(reinterpret_cast<const void*>(span_flash_local_kernel<true>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, kFlashLdsBytes) == hipSuccess;
+                            hipFuncAttributeMaxDynamicSharedMemorySize, FlashLds<1>::kBytes) == hipSuccess;
     done = ok ? 1 : -1;
   }
   return done == 1;
@@ -934,18 +950,18 @@ sl_status prefill_attention_mfma(const Problem& pb, const void* Q, const void* K
                        counts, cursor, items, pb.Lq, pb.q_pos0, pb.G, pb.S, pb.topk, n);
     if (hipGetLastError() != hipSuccess) return SL_ERR_LAUNCH;
     if (pb.prof_start) (void)hipEventRecord(pb.prof_start, st);
-    hipLaunchKernelGGL(span_flash_routed_kernel, dim3(persistent_grid()), dim3(kFlashThreads),
-                       kFlashLdsBytes, st, a);
+    hipLaunchKernelGGL(span_flash_routed_kernel, dim3(persistent_grid()),
+                       dim3(FlashLds<2>::kThreads), FlashLds<2>::kBytes, st, a);
     if (pb.prof_stop) (void)hipEventRecord(pb.prof_stop, st);
   }
-  const int tiles_per_head = (int)((pb.Lq + TM - 1) / TM);
+  const int tiles_per_head = (int)((pb.Lq + FlashLds<1>::kRows - 1) / FlashLds<1>::kRows);
   if (!pb.combined && pb.topk <= 8) {  // the window kernel merges and writes the final output
     hipLaunchKernelGGL(span_flash_local_kernel<true>, dim3(pb.Hq * tiles_per_head),
-                       dim3(kFlashThreads), kFlashLdsBytes, st, a);
+                       dim3(FlashLds<1>::kThreads), FlashLds<1>::kBytes, st, a);
     return hipGetLastError() == hipSuccess ? SL_OK : SL_ERR_LAUNCH;
   }
   hipLaunchKernelGGL(span_flash_local_kernel<false>, dim3(pb.Hq * tiles_per_head),
-                     dim3(kFlashThreads), kFlashLdsBytes, st, a);
+                     dim3(FlashLds<1>::kThreads), FlashLds<1>::kBytes, st, a);
   const int64_t rows = (int64_t)pb.Hq * pb.Lq;
   const dim3 mgrid((unsigned)((rows + 15) / 16));
 #define SL_MERGE(KM)                                                                             \
