@@ -49,7 +49,7 @@ constexpr int kBucketRows = 1024;  // query rows of one head per bucketing workg
 //   V^T tile [128][64]: piece p of row d at position p ^ ((d >> 1) & 7)
 // Epilogue: each wavefront group stages its output tile [128][128] bf16 (piece p of row r at
 // p ^ (r & 15)).
-//   NG = 2 (routed, 512 threads, 256 rows, one workgroup per compute unit, 150528 bytes): two K
+//   NG = 2 (routed, 512 threads, 256 rows, one workgroup per compute unit, 154624 bytes): two K
 //     and three V^T stages (the late group reads a V^T tile one step after the early group); the
 //     output region is separate, so the first K/V tile of the next 256-row tile can be fetched
 //     while the current one is written out.
@@ -66,7 +66,10 @@ struct FlashLds {
   static constexpr int kOut = NG == 2 ? kStagesEnd : 0;                             // bf16[NG][TG][HD]
   static constexpr int kRowOut = NG == 2 ? kOut + NG * TG * HD * 2 : kStagesEnd;    // int64[NG][TG]
   static constexpr int kRowLse = kRowOut + NG * TG * 8;                             // float[NG][TG]
-  static constexpr int kBytes = kRowLse + NG * TG * 4;
+  // NG = 2: per wavefront 256 bytes for the next tile's record and 256 for its items, fetched by
+  // direct global->LDS loads while the current tile runs (they hold no registers meanwhile)
+  static constexpr int kAhead = kRowLse + NG * TG * 4;
+  static constexpr int kBytes = kAhead + (NG == 2 ? 8 * 512 : 0);
   static constexpr int kThreads = NG * 256;
   static constexpr int kRows = NG * TG;  // query rows per workgroup
   static constexpr int kBlocksPerWave = 16 / (4 * NG);  // 1 KB blocks of a staged tile per wavefront
@@ -175,7 +178,9 @@ __global__ __launch_bounds__(256) void bucket_kernel(const int32_t* __restrict__
 }
 
 // One workgroup: exclusive scans of the item counts and of the tile counts over the B buckets.
-// item_off[B] / tile_off[B] receive the totals; cursor[b] = item_off[b] for the fill pass.
+// item_off[B] / tile_off[B] receive the totals.  The item list is laid out tile by tile, TM
+// entries per tile (a bucket's last tile is padded), so that the items of tile t start at t*TM
+// whatever its record says: cursor[b] = tile_off[b] * TM for the fill pass.
 __global__ __launch_bounds__(1024) void bucket_scan_kernel(const int* __restrict__ g_count,
                                                            int* __restrict__ item_off,
                                                            int* __restrict__ tile_off,
@@ -206,7 +211,7 @@ __global__ __launch_bounds__(1024) void bucket_scan_kernel(const int* __restrict
     const int cnt = g_count[b];
     item_off[b] = io;
     tile_off[b] = to;
-    g_cursor[b] = io;
+    g_cursor[b] = to * TM;
     io += cnt;
     to += (cnt + TM - 1) / TM;
   }
@@ -216,17 +221,22 @@ __global__ __launch_bounds__(1024) void bucket_scan_kernel(const int* __restrict
   }
 }
 
-// One workgroup per bucket writes the record of each of its tiles:
-// {bucket, first item, number of items (1..TM), unused}.
+// One workgroup per bucket writes the record of each of its tiles,
+// {bucket, first item = t*TM, number of items (1..TM), unused}, and fills the padding of the
+// bucket's last tile with item 0 (row 0, slot 0 of the kv head's first query head: a valid row to
+// read, whose result the flash kernel drops because the lane lies beyond the tile's item count).
 __global__ __launch_bounds__(256) void bucket_tiles_kernel(const int* __restrict__ tile_off,
                                                            const int* __restrict__ item_off,
-                                                           int4* __restrict__ tile_info) {
+                                                           int4* __restrict__ tile_info,
+                                                           int* __restrict__ items) {
   const int b = blockIdx.x;
   const int t0 = tile_off[b], t1 = tile_off[b + 1];
-  const int i0 = item_off[b], i1 = item_off[b + 1];
-  for (int t = t0 + threadIdx.x; t < t1; t += 256) {
-    const int first = i0 + (t - t0) * TM;
-    tile_info[t] = make_int4(b, first, min(TM, i1 - first), 0);
+  const int cnt = item_off[b + 1] - item_off[b];
+  for (int t = t0 + threadIdx.x; t < t1; t += 256)
+    tile_info[t] = make_int4(b, t * TM, min(TM, cnt - (t - t0) * TM), 0);
+  if (t1 > t0) {
+    const int last = cnt - (t1 - 1 - t0) * TM;  // items of the last tile, 1..TM
+    for (int e = last + threadIdx.x; e < TM; e += 256) items[(int64_t)(t1 - 1) * TM + e] = 0;
   }
 }
 
@@ -281,8 +291,10 @@ struct FlashCarry {
   bf16x8 qf[8];
 };
 
-// One 256-row tile.  All 512 threads call.  `next` (if has_next) is the tile this workgroup
-// processes afterwards.
+// One tile of NG*128 rows.  All threads call.  If has_next, request_next() issues the caller's
+// loads for the tile this workgroup processes afterwards and describe_next() turns them into
+// `next`: the first is called right after the first kv step's barrier (next to that step's K/V
+// loads, so the wait before the second step covers it), the second after the kv loop.
 //
 // The eight wavefronts form two groups of four (each group owns 128 rows, a wavefront 32
 // columns); SIMD s hosts wavefront s of both groups.  Both groups consume the same staged K/V
@@ -293,9 +305,10 @@ struct FlashCarry {
 // other group's MFMAs instead of both groups asking for the matrix pipe at the same time.
 // When the kv loop is over, the first K/V stage and the Q fragments of the next tile are
 // requested before the output tile is normalised and written.
-template <int NG, bool LOCAL, bool FUSED>
+template <int NG, bool LOCAL, bool FUSED, typename RequestNext, typename DescribeNext>
 __device__ __forceinline__ void flash_tile(const FlashArgs& a, char* lds, const TileDesc& cur,
-                                           const TileDesc& next, bool has_next, FlashCarry& c) {
+                                           TileDesc& next, bool has_next, RequestNext&& request_next,
+                                           DescribeNext&& describe_next, FlashCarry& c) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int grp = wave >> 2, w4 = wave & 3;  // grp 0 = early, 1 = late
   const int qc = lane & 31, hf = lane >> 5;
@@ -454,6 +467,7 @@ __device__ __forceinline__ void flash_tile(const FlashArgs& a, char* lds, const 
     __syncthreads();
     const int kb1 = kb == kStagesK - 1 ? 0 : kb + 1, vb1 = vb == kStagesV - 1 ? 0 : vb + 1;
     if (t0 + TN < cur.kv_end) stage(cur.kv, t0 + TN, kb1, vb1);
+    if (NG == 2 && has_next && t0 == cur.kv_begin) request_next();
     if (grp == 0) {
       qk_softmax(ldsK + kb * kStageElems, t0);
       pv(ldsV + vb * kStageElems);
@@ -473,6 +487,7 @@ __device__ __forceinline__ void flash_tile(const FlashArgs& a, char* lds, const 
   c.vb = vb;
   c.primed = NG == 2 && has_next;  // NG = 1: the output region lies over the stages, nothing is fetched ahead
   if (NG == 2 && has_next) {
+    next = describe_next();
     stage(next.kv, next.kv_begin, kb, vb);
     load_q(next.q_off);
   }
@@ -571,23 +586,30 @@ __device__ __forceinline__ void flash_tile(const FlashArgs& a, char* lds, const 
       }
     }
   } else {
+    // Every LDS read comes before the first store, and the values are pinned there: the compiler
+    // orders an LDS read after all outstanding vector-memory operations once direct global->LDS
+    // loads are in flight (the next tile's), so a read between two stores would wait for the
+    // earlier store to be acknowledged.
+    int64_t outs[8];
+    uint4 vals[8];
+    float lses[8];
 #pragma unroll
-    for (int half = 0; half < 2; ++half) {
-      int64_t outs[4];
-      uint4 vals[4];
+    for (int u = 0; u < 8; ++u) {
+      const int row = w4 * 32 + u * 4 + (lane >> 4), piece = lane & 15;
+      outs[u] = row_out[row];
+      lses[u] = row_lse[row];
+      vals[u] = *reinterpret_cast<const uint4*>(&ost[row * HD + ((piece ^ (row & 15)) << 3)]);
+    }
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        const int row = w4 * 32 + (half * 4 + u) * 4 + (lane >> 4), piece = lane & 15;
-        outs[u] = row_out[row];
-        vals[u] = *reinterpret_cast<const uint4*>(&ost[row * HD + ((piece ^ (row & 15)) << 3)]);
-      }
+    for (int u = 0; u < 8; ++u)
+      asm volatile("" : "+v"(vals[u].x), "+v"(vals[u].y), "+v"(vals[u].z), "+v"(vals[u].w), "+v"(lses[u]),
+                   "+v"(outs[u]));
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        const int row = w4 * 32 + (half * 4 + u) * 4 + (lane >> 4), piece = lane & 15;
-        if (outs[u] >= 0) {
-          *reinterpret_cast<uint4*>(a.part_o + outs[u] * HD + piece * 8) = vals[u];
-          if (piece == 0) a.part_lse[outs[u]] = row_lse[row];
-        }
+    for (int u = 0; u < 8; ++u) {
+      const int piece = lane & 15;
+      if (outs[u] >= 0) {
+        *reinterpret_cast<uint4*>(a.part_o + outs[u] * HD + piece * 8) = vals[u];
+        if (piece == 0) a.part_lse[outs[u]] = lses[u];
       }
     }
   }
@@ -631,16 +653,28 @@ __global__ __launch_bounds__(FlashLds<2>::kThreads, 1) void span_flash_routed_ke
   FlashCarry carry;
   carry.kb = carry.vb = 0;
   carry.primed = false;
-  int4 info = a.tile_info[t_begin];
-  TileDesc cur = describe(info, a.items[info.y + min(qrow, info.z - 1)]);
+  // The record and the items of a workgroup's next tile are requested during the current tile's
+  // first kv step as direct global->LDS loads into the wavefront's own 512 bytes (the items of tile t sit
+  // at t*TM, so the two do not depend on each other) and read back at its tail.
+  int* const ahead = reinterpret_cast<int*>(lds + FlashLds<2>::kAhead) + wave * 128;
+  const int4 info0 = a.tile_info[t_begin];
+  TileDesc cur = describe(info0, a.items[t_begin * TM + qrow]);
   for (int64_t t = t_begin; t < t_end; t += NWL) {
     const bool has_next = t + NWL < t_end;
     TileDesc nxt = cur;
-    if (has_next) {
-      const int4 ninfo = a.tile_info[t + NWL];
-      nxt = describe(ninfo, a.items[ninfo.y + min(qrow, ninfo.z - 1)]);
-    }
-    flash_tile<2, false, false>(a, lds, cur, nxt, has_next, carry);
+    flash_tile<2, false, false>(
+        a, lds, cur, nxt, has_next,
+        [&] {
+          const int* rec = reinterpret_cast<const int*>(a.tile_info + (t + NWL)) + (lane & 3);
+          const int* itm = a.items + (t + NWL) * TM + wave * 32 + (lane & 31);
+          __builtin_amdgcn_global_load_lds(SL_GLOBAL_PTR(rec), SL_LDS_PTR(ahead), 4, 0, 0);
+          __builtin_amdgcn_global_load_lds(SL_GLOBAL_PTR(itm), SL_LDS_PTR(ahead + 64), 4, 0, 0);
+        },
+        [&] {
+          const int4 ninfo = make_int4(ahead[0], ahead[1], ahead[2], 0);
+          return describe(ninfo, ahead[64 + lane]);
+        },
+        carry);
     cur = nxt;
   }
 }
@@ -676,7 +710,8 @@ __global__ __launch_bounds__(FlashLds<1>::kThreads, 2) void span_flash_local_ker
   FlashCarry carry;
   carry.kb = carry.vb = 0;
   carry.primed = false;
-  flash_tile<1, true, FUSED>(a, lds, d, d, false, carry);
+  TileDesc unused = d;
+  flash_tile<1, true, FUSED>(a, lds, d, unused, false, [] {}, [&] { return d; }, carry);
 }
 
 // ------------------------------------------------------------------ merge
@@ -867,7 +902,7 @@ MfmaWs carve(const Problem& pb) {
   w.tile_off = take((size_t)(w.B + 1) * sizeof(int));
   w.cursor = take((size_t)w.B * sizeof(int));
   w.tile_info = take((size_t)w.max_tiles * sizeof(int4));
-  w.items = take((size_t)w.max_items * sizeof(int));
+  w.items = take((size_t)w.max_tiles * TM * sizeof(int));  // tile by tile, TM entries each
   const size_t nparts = (size_t)pb.Hq * pb.Lq * (pb.topk + 1);  // routed slots + the local window
   w.part_lse = take(nparts * sizeof(float));
   w.part_o = take(nparts * HD * sizeof(bf16_t));
@@ -884,6 +919,8 @@ bool prefill_attention_mfma_supported(const Problem& pb) {
          (int64_t)HD * (int64_t)align_up((size_t)pb.L, 64) * 2 < ((int64_t)1 << 32) &&
          64 * pb.kvst * 2 < ((int64_t)1 << 31) &&
          (int64_t)pb.Hq * pb.Lq * (pb.topk + 1) < ((int64_t)1 << 31) &&
+         // 32-bit positions in the tile-by-tile item list
+         (int64_t)pb.Hq * pb.Lq * pb.topk + ((int64_t)pb.Hkv * pb.n + 1) * TM < ((int64_t)1 << 31) &&
          // row_q holds 32-bit element offsets into Q
          (int64_t)pb.Hq * pb.qsh + pb.Lq * pb.qst < ((int64_t)1 << 31);
 }
@@ -945,7 +982,8 @@ sl_status prefill_attention_mfma(const Problem& pb, const void* Q, const void* K
                        counts, cursor, items, pb.Lq, pb.q_pos0, pb.G, pb.S, pb.topk, n);
     hipLaunchKernelGGL(bucket_scan_kernel, dim3(1), dim3(1024), 0, st, counts, item_off, tile_off,
                        cursor, w.B);
-    hipLaunchKernelGGL(bucket_tiles_kernel, dim3(w.B), dim3(256), 0, st, tile_off, item_off, tile_info);
+    hipLaunchKernelGGL(bucket_tiles_kernel, dim3(w.B), dim3(256), 0, st, tile_off, item_off, tile_info,
+                       items);
     hipLaunchKernelGGL(bucket_kernel<true>, bgrid, dim3(256), (size_t)2 * n * sizeof(int), st, idx,
                        counts, cursor, items, pb.Lq, pb.q_pos0, pb.G, pb.S, pb.topk, n);
     if (hipGetLastError() != hipSuccess) return SL_ERR_LAUNCH;
