@@ -401,6 +401,9 @@ __device__ __forceinline__ void flash_tile(const FlashArgs& a, char* lds, const 
       __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
     }
     __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+    // The softmax arithmetic below competes for issue slots with the MFMA stream of the SIMD's
+    // other wavefront; that one needs a slot every 32 cycles, this one needs most of them.
+    __builtin_amdgcn_s_setprio(3);
 
     float mx = -INFINITY;
 #pragma unroll
@@ -438,6 +441,7 @@ __device__ __forceinline__ void flash_tile(const FlashArgs& a, char* lds, const 
       }
       pb[ks] = __builtin_convertvector(p, bf16x8);
     }
+    __builtin_amdgcn_s_setprio(0);
   };
   // O^T += V^T P^T with the P^T fragments in pb
   auto pv = [&](const bf16_t* vt) {
