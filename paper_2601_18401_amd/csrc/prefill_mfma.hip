@@ -683,7 +683,32 @@ __global__ __launch_bounds__(FlashLds<2>::kThreads, 1) void span_flash_routed_ke
   }
 }
 
-// Local window [c*S, i]: regular 256-row tiles of one head with the causal / window mask.
+// Row tiles of the local-window kernel and their grouping into chunks of `tps` tiles (the tiles
+// of one span when S is a multiple of the tile height).
+struct LocalMap {
+  int tiles_per_head, tps, chunks;
+};
+__host__ __device__ inline LocalMap local_map(int64_t Lq, int S) {
+  LocalMap m;
+  m.tiles_per_head = (int)((Lq + FlashLds<1>::kRows - 1) / FlashLds<1>::kRows);
+  m.tps = S / FlashLds<1>::kRows > 0 ? S / FlashLds<1>::kRows : 1;
+  m.chunks = (m.tiles_per_head + m.tps - 1) / m.tps;
+  return m;
+}
+// Blocks to launch: 8 x the largest per-XCD share.
+inline unsigned local_grid(int64_t Lq, int S, int Hkv, int G) {
+  const LocalMap m = local_map(Lq, S);
+  int best = 0;
+  for (int x = 0; x < 8; ++x) {
+    const int cx = (m.chunks - x + 7) / 8;
+    const bool lx = m.chunks > 0 && (m.chunks - 1) % 8 == x;
+    const int tx = cx * m.tps - (lx ? m.chunks * m.tps - m.tiles_per_head : 0);
+    best = tx > best ? tx : best;
+  }
+  return (unsigned)(8 * Hkv * best * G);
+}
+
+// Local window [c*S, i]: regular 128-row tiles of one head with the causal / window mask.
 // FUSED = false: writes the window's partial into the row's last slot (a merge kernel follows).
 // FUSED = true (joint softmax, topk <= 8): merges the row's routed partials in the epilogue and
 // writes the final output, which takes the merge's HBM traffic off the critical path of a
@@ -694,9 +719,21 @@ __global__ __launch_bounds__(FlashLds<1>::kThreads, 2) void span_flash_local_ker
   constexpr int TML = FlashLds<1>::kRows;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int qrow = wave * 32 + (lane & 31);
-  const int tiles_per_head = (int)((a.Lq + TML - 1) / TML);
-  const int h = blockIdx.x / tiles_per_head;
-  const int64_t r0 = (int64_t)(blockIdx.x % tiles_per_head) * TML;
+  // Workgroup -> (head, row tile), XCD-aware: blocks are dealt round-robin to the 8 XCDs, each
+  // with its own L2.  A run of `tps` consecutive row tiles (one span's worth) goes to one XCD,
+  // and inside an XCD the G query heads of a kv head take the same row tile back to back, so the
+  // window's K/V tiles are fetched from HBM about once instead of once per head and row tile.
+  const LocalMap lm = local_map(a.Lq, a.S);
+  const int xcd = blockIdx.x % 8, slot = blockIdx.x / 8;
+  const int chunks_x = (lm.chunks - xcd + 7) / 8;                 // chunks xcd, xcd+8, ... of a kv head
+  const bool has_last = lm.chunks > 0 && (lm.chunks - 1) % 8 == xcd;  // the only chunk that may be short
+  const int tiles_x = chunks_x * lm.tps - (has_last ? lm.chunks * lm.tps - lm.tiles_per_head : 0);
+  if (slot >= (a.Hq / a.G) * tiles_x * a.G) return;  // uniform: the grid is padded to 8 * the largest share
+  const int kvh = slot / (tiles_x * a.G), rem = slot % (tiles_x * a.G);
+  const int tile_local = rem / a.G, g = rem % a.G;
+  const int tile = (xcd + 8 * (tile_local / lm.tps)) * lm.tps + tile_local % lm.tps;
+  const int h = kvh * a.G + g;
+  const int64_t r0 = (int64_t)tile * TML;
   const int64_t r = r0 + qrow;
   const int64_t rc = r < a.Lq ? r : a.Lq - 1;
   TileDesc d;
@@ -996,14 +1033,14 @@ sl_status prefill_attention_mfma(const Problem& pb, const void* Q, const void* K
                        dim3(FlashLds<2>::kThreads), FlashLds<2>::kBytes, st, a);
     if (pb.prof_stop) (void)hipEventRecord(pb.prof_stop, st);
   }
-  const int tiles_per_head = (int)((pb.Lq + FlashLds<1>::kRows - 1) / FlashLds<1>::kRows);
+  const unsigned lgrid = local_grid(pb.Lq, pb.S, pb.Hkv, pb.G);
   if (!pb.combined && pb.topk <= 8) {  // the window kernel merges and writes the final output
-    hipLaunchKernelGGL(span_flash_local_kernel<true>, dim3(pb.Hq * tiles_per_head),
-                       dim3(FlashLds<1>::kThreads), FlashLds<1>::kBytes, st, a);
+    hipLaunchKernelGGL(span_flash_local_kernel<true>, dim3(lgrid), dim3(FlashLds<1>::kThreads),
+                       FlashLds<1>::kBytes, st, a);
     return hipGetLastError() == hipSuccess ? SL_OK : SL_ERR_LAUNCH;
   }
-  hipLaunchKernelGGL(span_flash_local_kernel<false>, dim3(pb.Hq * tiles_per_head),
-                     dim3(FlashLds<1>::kThreads), FlashLds<1>::kBytes, st, a);
+  hipLaunchKernelGGL(span_flash_local_kernel<false>, dim3(lgrid), dim3(FlashLds<1>::kThreads),
+                     FlashLds<1>::kBytes, st, a);
   const int64_t rows = (int64_t)pb.Hq * pb.Lq;
   const dim3 mgrid((unsigned)((rows + 15) / 16));
 #define SL_MERGE(KM)                                                                             \
