@@ -294,6 +294,31 @@ def bench_prefill(cfg, steps, warmup, torch, B, W):
         step_combined()
     torch.cuda.synchronize()
     dt_combined = (time.perf_counter() - tc) / nc
+    # the same prefill in chunks of 32K query rows against the growing cache (Section 5's chunked
+    # prefill): chunk c sees the first (c + 1) * 32K tokens through q_pos0 / Lq
+    chunked = None
+    CH = 32768
+    if cfg.L % CH == 0 and cfg.L > CH:
+        och = (torch.empty((cfg.Hq, CH, cfg.D), dtype=Q.dtype, device=dev),
+               torch.empty((cfg.Hq, CH), dtype=torch.float32, device=dev))
+
+        def step_chunked():
+            for c in range(cfg.L // CH):
+                p0, vis = c * CH, (c + 1) * CH
+                Kc, Vc = K[:, :vis], V[:, :vis]
+                # span keys are read from the cache itself (no gathered copy per chunk)
+                idx = B.sl_span_search_prefill(Qs[:, p0:vis], Kc, None, cfg.S, cfg.topk, q_pos0=p0, ws=ws)
+                B.sl_span_attention_prefill(Q[:, p0:vis], Kc, Vc, idx, cfg.S, q_pos0=p0, ws=ws, out=och)
+
+        step_chunked()
+        torch.cuda.synchronize()
+        tch = time.perf_counter()
+        nch = max(1, min(steps, 3))
+        for _ in range(nch):
+            step_chunked()
+        torch.cuda.synchronize()
+        dt_ch = (time.perf_counter() - tch) / nch
+        chunked = {"chunk_rows": CH, "ms_per_step": dt_ch * 1e3, "value": cfg.L / dt_ch, "unit": "tokens/s"}
     f_search, f_routed, f_local = prefill_flops(cfg)
     f_attn = f_routed + f_local
     ka = sum(ms_a) / len(ms_a)
@@ -310,6 +335,7 @@ def bench_prefill(cfg, steps, warmup, torch, B, W):
         "ms_per_step": dt / steps * 1e3, "steps": steps, "dtype": cfg.dtype,
         "step_frac_of_peak": (f_search + f_attn) / (dt / steps) / peak,
         "combined_form": {"ms_per_step": dt_combined * 1e3, "value": cfg.L / dt_combined, "unit": "tokens/s"},
+        "chunked_prefill": chunked,
         "roofline": {"bound": bound, "kernel": kernel, "achieved": tflops_attn / 1e12,
                      "peak": peak / 1e12, "unit": "TFLOP/s", "frac": tflops_attn / peak,
                      "traffic": MEASURED_TRAFFIC.get(cfg.name),
