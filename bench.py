@@ -319,6 +319,27 @@ def bench_prefill(cfg, steps, warmup, torch, B, W):
         torch.cuda.synchronize()
         dt_ch = (time.perf_counter() - tch) / nch
         chunked = {"chunk_rows": CH, "ms_per_step": dt_ch * 1e3, "value": cfg.L / dt_ch, "unit": "tokens/s"}
+    # the paper's own geometry in prefill form (row-stationary kernels: every row has its own
+    # anchors and span length): the last 4K rows of the cache at the paper's kernel configuration
+    paper = None
+    if cfg.dtype == "bf16" and cfg.L >= 16384:
+        PR, PW, PK, PB, PF = 4096, 1088, 2, 4, 2
+        p0 = cfg.L - PR
+        Qp, Qsp = Q[:, p0:], Qs[:, p0:]
+        op = torch.empty((cfg.Hq, PR, cfg.D), dtype=Q.dtype, device=dev)
+
+        def step_paper():
+            an, sc = B.sl_anchor_search_prefill(Qsp, K, PK, PW, q_pos0=p0, want_scores=True)
+            B.sl_anchor_attention_prefill(Qp, K, V, an, sc, PW, PB, PF, q_pos0=p0, out=op)
+
+        step_paper()
+        torch.cuda.synchronize()
+        tp = time.perf_counter()
+        step_paper()
+        torch.cuda.synchronize()
+        dt_p = time.perf_counter() - tp
+        paper = {"rows": PR, "q_pos0": p0, "window": PW, "topk": PK, "backward_factor": PB, "forward_factor": PF,
+                 "ms_per_step": dt_p * 1e3, "value": PR / dt_p, "unit": "tokens/s"}
     f_search, f_routed, f_local = prefill_flops(cfg)
     f_attn = f_routed + f_local
     ka = sum(ms_a) / len(ms_a)
@@ -336,6 +357,7 @@ def bench_prefill(cfg, steps, warmup, torch, B, W):
         "step_frac_of_peak": (f_search + f_attn) / (dt / steps) / peak,
         "combined_form": {"ms_per_step": dt_combined * 1e3, "value": cfg.L / dt_combined, "unit": "tokens/s"},
         "chunked_prefill": chunked,
+        "paper_geometry_prefill": paper,
         "roofline": {"bound": bound, "kernel": kernel, "achieved": tflops_attn / 1e12,
                      "peak": peak / 1e12, "unit": "TFLOP/s", "frac": tflops_attn / peak,
                      "traffic": MEASURED_TRAFFIC.get(cfg.name),

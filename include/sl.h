@@ -205,6 +205,18 @@ sl_status sl_anchor_attention_decode(const sl_params* p, const sl_anchor_geometr
                                      const float* scores, void* O, void* ws, size_t ws_bytes,
                                      void* hip_stream);
 
+/* ---- The same geometry, prefill form: every query row r (position i = q_pos0 + r) has its own
+ * anchors, its own l = ceil(sqrt(i)) and its own window, exactly as in the decode form above
+ * (Section 3.3, Algorithm 1).  Row-stationary kernels (one wavefront per query row), fp32 or bf16;
+ * no workspace.  S of sl_params is ignored.
+ *   anchors: [Hq][Lq][topk] int32, scores: [Hq][Lq][topk] float, O: [Hq][Lq][D]; slot meaning and
+ *   tie rule as in the decode form.  At most 12288 candidate anchors per row. */
+sl_status sl_anchor_search_prefill(const sl_params* p, const sl_anchor_geometry* g, const void* Qs,
+                                   const void* K, int32_t* anchors, float* scores, void* hip_stream);
+sl_status sl_anchor_attention_prefill(const sl_params* p, const sl_anchor_geometry* g, const void* Q,
+                                      const void* K, const void* V, const int32_t* anchors,
+                                      const float* scores, void* O, void* hip_stream);
+
 /* Static, human-readable name of a status code. */
 const char* sl_status_string(int status);
 

@@ -23,7 +23,8 @@ SL_MAX_TOPK = 32
 EXPORTS = ("sl_workspace_bytes", "sl_span_keys", "sl_span_search_prefill", "sl_span_search_decode",
            "sl_span_attention_prefill", "sl_span_attention_decode", "sl_span_attention_combined_prefill",
            "sl_span_attention_combined_decode", "sl_anchor_workspace_bytes", "sl_anchor_search_decode",
-           "sl_anchor_attention_decode", "sl_status_string", "sl_version")
+           "sl_anchor_attention_decode", "sl_anchor_search_prefill", "sl_anchor_attention_prefill",
+           "sl_status_string", "sl_version")
 
 
 class SlAnchorGeometry(ctypes.Structure):
@@ -87,6 +88,10 @@ def load():
     lib.sl_anchor_search_decode.argtypes = [pp, gp, vp, vp, i32p, f32p, vp]
     lib.sl_anchor_attention_decode.restype = ctypes.c_int
     lib.sl_anchor_attention_decode.argtypes = [pp, gp, vp, vp, vp, i32p, f32p, vp, vp, ctypes.c_size_t, vp]
+    lib.sl_anchor_search_prefill.restype = ctypes.c_int
+    lib.sl_anchor_search_prefill.argtypes = [pp, gp, vp, vp, i32p, f32p, vp]
+    lib.sl_anchor_attention_prefill.restype = ctypes.c_int
+    lib.sl_anchor_attention_prefill.argtypes = [pp, gp, vp, vp, vp, i32p, f32p, vp, vp]
     lib.sl_status_string.restype = ctypes.c_char_p
     lib.sl_status_string.argtypes = [ctypes.c_int]
     lib.sl_version.restype = ctypes.c_int
@@ -282,6 +287,37 @@ def sl_anchor_attention_decode(Q, K, V, anchors, scores, window, backward_factor
     st = lib.sl_anchor_attention_decode(ctypes.byref(p), ctypes.byref(g), _ptr(Q), _ptr(K), _ptr(V),
                                         _ptr(anchors), _ptr(scores), _ptr(O), wptr, wbytes, _stream())
     _check(st, "sl_anchor_attention_decode")
+    return O
+
+
+def sl_anchor_search_prefill(Qs, K, topk, window, q_pos0=0, want_scores=False, prof=None):
+    """Top-k anchors of every query row on the paper's stride pattern (row r sits at q_pos0 + r)."""
+    lib = load()
+    p = make_params(Qs, K, 1, topk, q_pos0, prof=prof)
+    g = SlAnchorGeometry(window, 0, 0)
+    Hq, Lq, _ = Qs.shape
+    anchors = torch.empty((Hq, Lq, topk), dtype=torch.int32, device=Qs.device)
+    scores = torch.empty((Hq, Lq, topk), dtype=torch.float32, device=Qs.device) if want_scores else None
+    st = lib.sl_anchor_search_prefill(ctypes.byref(p), ctypes.byref(g), _ptr(Qs), _ptr(K), _ptr(anchors),
+                                      _ptr(scores), _stream())
+    _check(st, "sl_anchor_search_prefill")
+    return (anchors, scores) if want_scores else anchors
+
+
+def sl_anchor_attention_prefill(Q, K, V, anchors, scores, window, backward_factor, forward_factor,
+                                q_pos0=0, scale=0.0, prof=None, out=None):
+    """Algorithm 1's span-attention + combination for every query row."""
+    lib = load()
+    topk = 0 if anchors is None else anchors.shape[2]
+    p = make_params(Q, K, 1, topk, q_pos0, scale, prof=prof)
+    g = SlAnchorGeometry(window, backward_factor, forward_factor)
+    if V.shape != K.shape or V.stride() != K.stride():
+        raise ValueError("V must have the shape and strides of K")
+    Hq, Lq, D = Q.shape
+    O = torch.empty((Hq, Lq, D), dtype=Q.dtype, device=Q.device) if out is None else out
+    st = lib.sl_anchor_attention_prefill(ctypes.byref(p), ctypes.byref(g), _ptr(Q), _ptr(K), _ptr(V),
+                                         _ptr(anchors), _ptr(scores), _ptr(O), _stream())
+    _check(st, "sl_anchor_attention_prefill")
     return O
 
 

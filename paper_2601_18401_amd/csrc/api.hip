@@ -224,6 +224,36 @@ sl_status sl_anchor_attention_decode(const sl_params* p, const sl_anchor_geometr
                                      anchors, O, ws, static_cast<hipStream_t>(hip_stream));
 }
 
+sl_status sl_anchor_search_prefill(const sl_params* p, const sl_anchor_geometry* g, const void* Qs,
+                                   const void* K, int32_t* anchors, float* scores, void* hip_stream) {
+  sl::Problem pb;
+  sl_status s = sl::make_problem(p, SL_OP_SEARCH_PREFILL, &pb);
+  if (s != SL_OK) return s;
+  if (!g || g->window < 0 || !Qs || !K || !anchors) return SL_ERR_INVALID_ARG;
+  if (!sl::aligned16(Qs) || !sl::aligned16(K) || !sl::aligned16(anchors) || !sl::aligned16(scores))
+    return SL_ERR_INVALID_ARG;
+  if (pb.L > ((int64_t)1 << 31) - 1) return SL_ERR_UNSUPPORTED;  // anchors are int32 token positions
+  return sl::anchor_search_prefill(pb, g->window, Qs, K, anchors, scores,
+                                   static_cast<hipStream_t>(hip_stream));
+}
+
+sl_status sl_anchor_attention_prefill(const sl_params* p, const sl_anchor_geometry* g, const void* Q,
+                                      const void* K, const void* V, const int32_t* anchors,
+                                      const float* scores, void* O, void* hip_stream) {
+  sl::Problem pb;
+  sl_status s = sl::make_problem(p, SL_OP_ATTENTION_PREFILL, &pb);
+  if (s != SL_OK) return s;
+  if (!g || g->window < 0 || g->backward_factor < 0 || g->forward_factor < 0) return SL_ERR_INVALID_ARG;
+  if (!Q || !K || !V || !O || (pb.topk > 0 && (!anchors || !scores))) return SL_ERR_INVALID_ARG;
+  if (!sl::aligned16(Q) || !sl::aligned16(K) || !sl::aligned16(V) || !sl::aligned16(O) ||
+      !sl::aligned16(anchors) || !sl::aligned16(scores))
+    return SL_ERR_INVALID_ARG;
+  pb.combined = true;
+  pb.gate = scores;
+  return sl::anchor_attention_prefill(pb, g->window, g->backward_factor, g->forward_factor, Q, K, V,
+                                      anchors, O, static_cast<hipStream_t>(hip_stream));
+}
+
 const char* sl_status_string(int status) {
   switch (status) {
     case SL_OK: return "SL_OK";

@@ -27,6 +27,14 @@ sl_status anchor_attention_decode(const Problem& pb, int64_t window, int b, int 
                                   const void* K, const void* V, const int32_t* anchors, void* O,
                                   void* ws, hipStream_t st);
 
+// The same geometry, prefill form (one wavefront per query row; every row has its own anchors,
+// span length and window)
+sl_status anchor_search_prefill(const Problem& pb, int64_t window, const void* Qs, const void* K,
+                                int32_t* anchors, float* scores, hipStream_t st);
+sl_status anchor_attention_prefill(const Problem& pb, int64_t window, int b, int f, const void* Q,
+                                   const void* K, const void* V, const int32_t* anchors, void* O,
+                                   hipStream_t st);
+
 // a1 + a2: prefill span-search
 size_t prefill_search_ws_bytes(const Problem& pb);
 sl_status prefill_search(const Problem& pb, const void* Qs, const void* K, const void* Ks,

@@ -289,6 +289,69 @@ __global__ __launch_bounds__(256) void prefill_search_rows_kernel(
                    scores ? scores + row * topk : nullptr);
 }
 
+// Exact floor(sqrt(x)) for 0 <= x < 2^52.
+__device__ __forceinline__ int64_t isqrt_floor_dev(int64_t x) {
+  int64_t r = (int64_t)sqrt((double)x);
+  while (r * r > x) --r;
+  while ((r + 1) * (r + 1) <= x) ++r;
+  return r;
+}
+
+// The paper's geometry, prefill form, search (Section 3.3, Algorithm 1; eq. (2)-(3) with
+// K_a = K): one wavefront per (head, query row).  The candidates of the query at position i are
+// the anchors t_s = i - (s+1)^2 + 1 with s0 <= s and t_s >= 0 (s0 = floor(sqrt(window)): anchors
+// inside the window are left out); candidate number j is stride index s0 + j.
+template <typename T, int D>
+__global__ __launch_bounds__(256) void prefill_anchor_search_rows_kernel(
+    const T* __restrict__ Qs, const T* __restrict__ K, int32_t* __restrict__ anchors,
+    float* __restrict__ scores, int64_t Lq, int64_t q_pos0, int Hq, int G, int topk, int s0, int W,
+    int lds_per_wave, int64_t qsh, int64_t qst, int64_t kvsh, int64_t kvst) {
+  using RL = RowLayout<T, D>;
+  constexpr int EPL = RL::EPL, LPR = RL::LPR, RPW = RL::RPW;
+  extern __shared__ float s_all[];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int64_t row = (int64_t)blockIdx.x * W + wave;
+  if (wave >= W || row >= (int64_t)Hq * Lq) return;
+  float* sc = s_all + (int64_t)wave * lds_per_wave;
+  const int h = (int)(row / Lq);
+  const int64_t r = row % Lq, i = q_pos0 + r;
+  const int kv = h / G;
+  const int64_t s_max = isqrt_floor_dev(i + 1) - 1;  // (s+1)^2 <= i + 1
+  const int64_t c = s_max >= s0 ? s_max - s0 + 1 : 0;
+  const int g = lane / LPR, lr = lane % LPR;
+  const LaneMajor lm = LaneMajor::make(c);
+  select_clear(sc, lm, lane);
+  __builtin_amdgcn_wave_barrier();
+  float qf[EPL];
+  Elem<T>::unpack(load16(Qs + h * qsh + r * qst + lr * EPL), qf);
+  const T* Kb = K + kv * kvsh;
+  constexpr int U = 4;
+  for (int64_t jb = 0; jb < c; jb += RPW * U) {
+    uint4 kr[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      int64_t j = jb + u * RPW + g;
+      j = j < c ? j : c - 1;
+      const int64_t step = s0 + j + 1;
+      kr[u] = load16(Kb + (i - step * step + 1) * kvst + lr * EPL);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      float kf[EPL];
+      Elem<T>::unpack(kr[u], kf);
+      float acc = 0.f;
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) acc = fmaf(qf[e], kf[e], acc);
+      acc = group_sum<LPR>(acc);
+      const int64_t j = jb + u * RPW + g;
+      if (lr == 0 && j < c) sc[lm.slot((int)j)] = acc;
+    }
+  }
+  __builtin_amdgcn_wave_barrier();
+  wave_select_topk(sc, lm, (int)c, topk, lane, anchors + row * topk,
+                   scores ? scores + row * topk : nullptr, i, s0);
+}
+
 template <typename T, int D>
 sl_status launch_span_keys(const Problem& pb, const void* K, void* Ks, hipStream_t st) {
   using RL = RowLayout<T, D>;
@@ -368,6 +431,24 @@ sl_status launch_prefill_search_rows(const Problem& pb, const void* Qs, const vo
   return hipGetLastError() == hipSuccess ? SL_OK : SL_ERR_LAUNCH;
 }
 
+template <typename T, int D>
+sl_status launch_anchor_search_rows(const Problem& pb, const void* Qs, const void* K,
+                                    int32_t* anchors, float* scores, int64_t c_max, int s0,
+                                    hipStream_t st) {
+  const int lds_per_wave = LaneMajor::make(c_max).lds_floats();
+  int W = 4;
+  while (W > 1 && (size_t)W * lds_per_wave * sizeof(float) > 64 * 1024) W >>= 1;
+  const int64_t rows = (int64_t)pb.Hq * pb.Lq;
+  const int64_t grid = (rows + W - 1) / W;
+  if (pb.prof_start) (void)hipEventRecord(pb.prof_start, st);
+  hipLaunchKernelGGL((prefill_anchor_search_rows_kernel<T, D>), dim3((unsigned)grid), dim3(256),
+                     (size_t)W * lds_per_wave * sizeof(float), st, static_cast<const T*>(Qs),
+                     static_cast<const T*>(K), anchors, scores, pb.Lq, pb.q_pos0, pb.Hq, pb.G,
+                     pb.topk, s0, W, lds_per_wave, pb.qsh, pb.qst, pb.kvsh, pb.kvst);
+  if (pb.prof_stop) (void)hipEventRecord(pb.prof_stop, st);
+  return hipGetLastError() == hipSuccess ? SL_OK : SL_ERR_LAUNCH;
+}
+
 #define SL_DISPATCH(FN, ...)                                                   \
   do {                                                                         \
     if (pb.dtype == SL_BF16) {                                                 \
@@ -414,6 +495,18 @@ sl_status anchor_search_decode(const Problem& pb, int64_t window, const void* Qs
   anchor_candidates(pb, window, &c, &s0);
   if (c > (int64_t)kDecodeSearchThreads * 4) return SL_ERR_UNSUPPORTED;
   SL_DISPATCH(launch_anchor_search, pb, Qs, K, anchors, scores, c, s0, st);
+}
+
+sl_status anchor_search_prefill(const Problem& pb, int64_t window, const void* Qs, const void* K,
+                                int32_t* anchors, float* scores, hipStream_t st) {
+  // the last query row has the most candidates
+  Problem last = pb;
+  last.q_pos0 = pb.q_pos0 + pb.Lq - 1;
+  int64_t c_max;
+  int s0;
+  anchor_candidates(last, window, &c_max, &s0);
+  if (c_max > kMaxSpansLds) return SL_ERR_UNSUPPORTED;
+  SL_DISPATCH(launch_anchor_search_rows, pb, Qs, K, anchors, scores, c_max, s0, st);
 }
 
 sl_status decode_search(const Problem& pb, const void* Qs, const void* K, const void* Ks,

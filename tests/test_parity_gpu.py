@@ -496,6 +496,77 @@ def test_anchor_decode(seed, Hq, Hkv, L, D, k, w, b, f, dtype):
         assert err <= TOL[dtype], (h, err)
 
 
+# ------------------------------------------------------------------------------ the paper's own geometry (prefill form)
+
+ANCHOR_PREFILL = [
+    # seed Hq Hkv L     D    k  w    b  f  dtype           q_pos0 Lq
+    (51, 4, 2, 700, 128, 2, 24, 4, 2, torch.bfloat16, 0, None),     # every row from i = 0 on: no candidates at first
+    (52, 2, 2, 400, 64, 3, 0, 2, 0, torch.float32, 0, None),        # no window (Fig. 3's setting), fp32
+    (53, 4, 1, 3000, 128, 4, 48, 2, 1, torch.bfloat16, 2600, 300),  # a chunk at the end of a longer cache
+    (54, 2, 1, 1500, 64, 8, 99, 3, 0, torch.float32, 1000, 77),     # 8 anchors, ragged chunk
+]
+
+
+@pytest.mark.parametrize("seed,Hq,Hkv,L,D,k,w,b,f,dtype,q_pos0,Lq", ANCHOR_PREFILL)
+def test_anchor_prefill(seed, Hq, Hkv, L, D, k, w, b, f, dtype, q_pos0, Lq):
+    Q, K, V = make(seed, Hq, Hkv, L, D, dtype, Lq=Lq, scale=0.5)
+    Lq = Q.shape[1]
+    G = Hq // Hkv
+    anchors, sc = B.sl_anchor_search_prefill(Q, K, k, w, q_pos0=q_pos0, want_scores=True)
+    torch.cuda.synchronize()
+    an, scn = anchors.cpu().numpy(), sc.cpu().numpy()
+    Qn = f64(Q)
+    Kh = [f64(K[kv]) for kv in range(Hkv)]
+    rows = sorted(set(list(range(0, Lq, max(1, Lq // 40))) + [0, 1, 2, 3, Lq - 1]))
+    ambiguous = 0
+    for h in range(Hq):
+        kv = h // G
+        for r in rows:
+            i = q_pos0 + r
+            s_o, t_o, sc_o = orc.anchor_search_row(Qn[h, r], Kh[kv], i, w, k)
+            want = t_o + [-1] * (k - len(t_o))
+            got = an[h, r].tolist()
+            if got != want:
+                cand = orc.anchor_candidates(i, w)
+                allsc = [float(Kh[kv][t] @ Qn[h, r]) for _, t in cand]
+                assert orc.selection_margin(allsc, k) < MARGIN, (h, r, got, want)
+                ambiguous += 1
+            for slot, t in enumerate(got):
+                if t >= 0:
+                    assert abs(scn[h, r, slot] - float(Kh[kv][t] @ Qn[h, r])) <= 1e-3
+                else:
+                    assert scn[h, r, slot] == -np.inf
+    assert ambiguous <= max(1, len(rows) * Hq // 50)
+    sc_in = torch.where(torch.isfinite(sc), sc, torch.zeros_like(sc))
+    O = B.sl_anchor_attention_prefill(Q, K, V, anchors, sc_in, w, b, f, q_pos0=q_pos0)
+    torch.cuda.synchronize()
+    On = f64(O)
+    Kn, Vn = f64(K), f64(V)
+    scale = 1.0 / math.sqrt(D)
+    for h in range(Hq):
+        for r in rows:
+            i = q_pos0 + r
+            o = orc.anchor_combined_row(Qn[h, r], Kn, Vn, h // G, i, w, b, f, an[h, r],
+                                        scn[h, r].astype(np.float64), scale)
+            err = float(np.max(np.abs(On[h, r] - o)))
+            assert err <= TOL[dtype], (h, r, err)
+
+
+def test_anchor_prefill_last_row_equals_decode():
+    # the decode form is the prefill form's last row
+    Hq, Hkv, L, D, k, w, b, f = 8, 2, 5000, 128, 2, 1088, 4, 2
+    Q, K, V = make(55, Hq, Hkv, L, D, torch.bfloat16, Lq=64, scale=0.5)
+    a_p, s_p = B.sl_anchor_search_prefill(Q, K, k, w, q_pos0=L - 64, want_scores=True)
+    a_d, s_d = B.sl_anchor_search_decode(Q[:, -1:].contiguous(), K, k, w, want_scores=True)
+    torch.cuda.synchronize()
+    assert torch.equal(a_p[:, -1], a_d[:, 0])
+    assert torch.allclose(s_p[:, -1], s_d[:, 0], atol=1e-3)
+    O_p = B.sl_anchor_attention_prefill(Q, K, V, a_p, s_p, w, b, f, q_pos0=L - 64)
+    O_d = B.sl_anchor_attention_decode(Q[:, -1:].contiguous(), K, V, a_d, s_d, w, b, f)
+    torch.cuda.synchronize()
+    assert float((O_p[:, -1].float() - O_d[:, 0].float()).abs().max()) <= 2 * TOL[torch.bfloat16]
+
+
 class DevRows:
     """Row access K[t] -> fp64 [D] on a device tensor [L, D] (for the oracle's anchor scoring)."""
 
