@@ -179,6 +179,11 @@ typedef struct sl_anchor_geometry {
   int64_t window;
   int32_t backward_factor; /* b >= 0 */
   int32_t forward_factor;  /* f >= 0 */
+  int32_t search_root;     /* 1/p: 0 or 2 = the geometry above (p = 1/2); 3 = the exponent split
+                              (1/3, 2/3) of Section 5 in the general-p formulas of Section 3.3:
+                              anchors t_s = i - (s+1)^3 + 1, l = ceil(i^(2/3)), window = m^3 - 1
+                              for gap-free coverage, b >= 3 to reach every key */
+  int32_t reserved;        /* 0 */
 } sl_anchor_geometry;
 
 /* Bytes of scratch sl_anchor_attention_decode needs (0 if the arguments are invalid). */

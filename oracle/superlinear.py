@@ -260,21 +260,31 @@ def span_attention_combined(Q, K, V, idx, scores, S: int, scale: float | None = 
 # anchors on a quadratic stride pattern, spans of a length that grows with sqrt(i) around the
 # selected anchors, a sliding window W, anchors inside W dropped.  p = 1/2 (the N = 2 case).
 
-def anchor_positions(i: int):
-    """Anchor tokens of query position i for p = 1/2: t_s = i - (s+1)^2 + 1, s = 0, 1, ...,
-    as long as t_s >= 0 (Section 3.3: "i, i-3, i-8, i-15, ...")."""
+def anchor_positions(i: int, root: int = 2):
+    """Anchor tokens of query position i for search exponent p = 1/root:
+    t_s = i - (s+1)^(1/p) + 1 = i - (s+1)^root + 1, s = 0, 1, ..., as long as t_s >= 0
+    (Section 3.3; for p = 1/2: "i, i-3, i-8, i-15, ...")."""
     out = []
     s = 0
-    while i - (s + 1) * (s + 1) + 1 >= 0:
-        out.append(i - (s + 1) * (s + 1) + 1)
+    while i - (s + 1) ** root + 1 >= 0:
+        out.append(i - (s + 1) ** root + 1)
         s += 1
     return out
 
 
-def base_span_length(i: int) -> int:
-    """l(i) = ceil(i^(1-p)) = ceil(sqrt(i)) for p = 1/2 (Section 3.3), in exact integer arithmetic."""
-    r = math.isqrt(int(i))
-    return r if r * r == i else r + 1
+def base_span_length(i: int, root: int = 2) -> int:
+    """l(i) = ceil(i^(1-p)) for p = 1/root (Section 3.3), in exact integer arithmetic: the
+    smallest integer m with m^root >= i^(root-1).  root = 2: ceil(sqrt(i)); root = 3 is the
+    (1/3, 2/3) split of search and span exponents (Section 5)."""
+    target = int(i) ** (root - 1)
+    lo, hi = 0, max(1, int(i))          # hi^root >= i^(root-1) for every i >= 0
+    while lo < hi:                      # smallest m in [0, hi] with m^root >= target
+        mid = (lo + hi) // 2
+        if mid ** root >= target:
+            hi = mid
+        else:
+            lo = mid + 1
+    return lo
 
 
 def window_range(i: int, w: int):
@@ -282,24 +292,24 @@ def window_range(i: int, w: int):
     return None if w <= 0 else (max(0, i - w + 1), i)
 
 
-def anchor_candidates(i: int, w: int):
+def anchor_candidates(i: int, w: int, root: int = 2):
     """T = Anchors(i) minus W (Algorithm 1): (stride index s, anchor t_s) pairs, ascending s."""
     lo = i - w + 1 if w > 0 else i + 1
-    return [(s, t) for s, t in enumerate(anchor_positions(i)) if t < lo]
+    return [(s, t) for s, t in enumerate(anchor_positions(i, root)) if t < lo]
 
 
-def anchor_span(t: int, i: int, b: int, f: int):
+def anchor_span(t: int, i: int, b: int, f: int, root: int = 2):
     """S_t = [max(0, t - b*l(i)), min(i, t + f*l(i))] (Algorithm 1), inclusive bounds."""
-    l = base_span_length(i)
+    l = base_span_length(i, root)
     return max(0, t - b * l), min(i, t + f * l)
 
 
-def anchor_search_row(qs, Krow, i: int, w: int, topk: int):
+def anchor_search_row(qs, Krow, i: int, w: int, topk: int, root: int = 2):
     """Scores <Q_s(i), K_a(t)> (eq. (2), K_a = K) of the candidate anchors of position i and the
     top-k of them (eq. (3)); ties go to the lower stride index (the anchor nearer to the query).
     Krow: anything indexable as Krow[t] -> [D].  Returns (stride indices ascending, their anchor
     positions, their scores), each of length min(topk, number of candidates)."""
-    cand = anchor_candidates(i, w)
+    cand = anchor_candidates(i, w, root)
     qs = _f64(qs)
     sc = np.array([float(_f64(Krow[t]) @ qs) for _, t in cand], dtype=F64)
     order = select_topk(sc, topk)          # ascending candidate number = ascending stride index
@@ -307,7 +317,7 @@ def anchor_search_row(qs, Krow, i: int, w: int, topk: int):
 
 
 def anchor_combined_row(q, K, V, kv: int, i: int, w: int, b: int, f: int, sel_t, sel_scores, scale: float,
-                        return_parts=False):
+                        return_parts=False, root: int = 2):
     """Algorithm 1 for one query row on the paper's geometry: for every selected anchor t,
     J_t = DedupConcat(S_t, W) (the set union, every token once), A_t = softmax attention over
     J_t (eq. (4)); O = sum_t alpha_t A_t with alpha = softmax of the selected scores (eq. (5)-(6));
@@ -329,7 +339,7 @@ def anchor_combined_row(q, K, V, kv: int, i: int, w: int, b: int, f: int, sel_t,
         return (o, np.zeros(0), []) if return_parts else o
     A = []
     for n in slots:
-        a, e = anchor_span(int(sel_t[n]), i, b, f)
+        a, e = anchor_span(int(sel_t[n]), i, b, f, root)
         tokens = sorted(set(range(a, e + 1)) | set(wtok))
         A.append(attend(tokens))
     alpha = gate_weights([sel_scores[n] for n in slots])

@@ -29,7 +29,8 @@ EXPORTS = ("sl_workspace_bytes", "sl_span_keys", "sl_span_search_prefill", "sl_s
 
 class SlAnchorGeometry(ctypes.Structure):
     _fields_ = [("window", ctypes.c_int64), ("backward_factor", ctypes.c_int32),
-                ("forward_factor", ctypes.c_int32)]
+                ("forward_factor", ctypes.c_int32), ("search_root", ctypes.c_int32),
+                ("reserved", ctypes.c_int32)]
 
 
 class SlParams(ctypes.Structure):
@@ -257,11 +258,11 @@ def sl_span_attention_combined_decode(Q, K, V, idx, scores, S, q_pos0=None, scal
                      q_pos0, scale, ws, out)
 
 
-def sl_anchor_search_decode(Qs, K, topk, window, want_scores=False, prof=None):
+def sl_anchor_search_decode(Qs, K, topk, window, want_scores=False, prof=None, search_root=2):
     """Top-k anchors of the query at the end of the cache on the paper's stride pattern."""
     lib = load()
     p = make_params(Qs, K, 1, topk, K.shape[1] - 1, prof=prof)
-    g = SlAnchorGeometry(window, 0, 0)
+    g = SlAnchorGeometry(window, 0, 0, search_root, 0)
     Hq = Qs.shape[0]
     anchors = torch.empty((Hq, 1, topk), dtype=torch.int32, device=Qs.device)
     scores = torch.empty((Hq, 1, topk), dtype=torch.float32, device=Qs.device) if want_scores else None
@@ -272,12 +273,12 @@ def sl_anchor_search_decode(Qs, K, topk, window, want_scores=False, prof=None):
 
 
 def sl_anchor_attention_decode(Q, K, V, anchors, scores, window, backward_factor, forward_factor,
-                               scale=0.0, ws=None, prof=None, out=None):
+                               scale=0.0, ws=None, prof=None, out=None, search_root=2):
     """Algorithm 1's span-attention + combination for the query at the end of the cache."""
     lib = load()
     topk = 0 if anchors is None else anchors.shape[2]
     p = make_params(Q, K, 1, topk, K.shape[1] - 1, scale, prof=prof)
-    g = SlAnchorGeometry(window, backward_factor, forward_factor)
+    g = SlAnchorGeometry(window, backward_factor, forward_factor, search_root, 0)
     if V.shape != K.shape or V.stride() != K.stride():
         raise ValueError("V must have the shape and strides of K")
     Hq, Lq, D = Q.shape
@@ -290,11 +291,11 @@ def sl_anchor_attention_decode(Q, K, V, anchors, scores, window, backward_factor
     return O
 
 
-def sl_anchor_search_prefill(Qs, K, topk, window, q_pos0=0, want_scores=False, prof=None):
+def sl_anchor_search_prefill(Qs, K, topk, window, q_pos0=0, want_scores=False, prof=None, search_root=2):
     """Top-k anchors of every query row on the paper's stride pattern (row r sits at q_pos0 + r)."""
     lib = load()
     p = make_params(Qs, K, 1, topk, q_pos0, prof=prof)
-    g = SlAnchorGeometry(window, 0, 0)
+    g = SlAnchorGeometry(window, 0, 0, search_root, 0)
     Hq, Lq, _ = Qs.shape
     anchors = torch.empty((Hq, Lq, topk), dtype=torch.int32, device=Qs.device)
     scores = torch.empty((Hq, Lq, topk), dtype=torch.float32, device=Qs.device) if want_scores else None
@@ -305,12 +306,12 @@ def sl_anchor_search_prefill(Qs, K, topk, window, q_pos0=0, want_scores=False, p
 
 
 def sl_anchor_attention_prefill(Q, K, V, anchors, scores, window, backward_factor, forward_factor,
-                                q_pos0=0, scale=0.0, prof=None, out=None):
+                                q_pos0=0, scale=0.0, prof=None, out=None, search_root=2):
     """Algorithm 1's span-attention + combination for every query row."""
     lib = load()
     topk = 0 if anchors is None else anchors.shape[2]
     p = make_params(Q, K, 1, topk, q_pos0, scale, prof=prof)
-    g = SlAnchorGeometry(window, backward_factor, forward_factor)
+    g = SlAnchorGeometry(window, backward_factor, forward_factor, search_root, 0)
     if V.shape != K.shape or V.stride() != K.stride():
         raise ValueError("V must have the shape and strides of K")
     Hq, Lq, D = Q.shape

@@ -185,11 +185,19 @@ sl_status sl_span_attention_combined_decode(const sl_params* p, const void* Q, c
                              ws_bytes, hip_stream);
 }
 
+// 0 if the geometry is invalid, else the root 1/p (2 or 3; search_root = 0 means 2)
+static int anchor_root(const sl_anchor_geometry* g) {
+  if (!g || g->window < 0 || g->backward_factor < 0 || g->forward_factor < 0) return 0;
+  if (g->search_root == 0 || g->search_root == 2) return 2;
+  return g->search_root == 3 ? 3 : 0;
+}
+
 size_t sl_anchor_workspace_bytes(const sl_params* p, const sl_anchor_geometry* g) {
   sl::Problem pb;
-  if (!g || g->window < 0 || g->backward_factor < 0 || g->forward_factor < 0) return 0;
+  const int root = anchor_root(g);
+  if (!root) return 0;
   if (sl::make_problem(p, SL_OP_ATTENTION_DECODE, &pb) != SL_OK) return 0;
-  return sl::anchor_attention_ws_bytes(pb, g->window, g->backward_factor, g->forward_factor);
+  return sl::anchor_attention_ws_bytes(pb, g->window, g->backward_factor, g->forward_factor, root);
 }
 
 sl_status sl_anchor_search_decode(const sl_params* p, const sl_anchor_geometry* g, const void* Qs,
@@ -197,10 +205,12 @@ sl_status sl_anchor_search_decode(const sl_params* p, const sl_anchor_geometry* 
   sl::Problem pb;
   sl_status s = sl::make_problem(p, SL_OP_SEARCH_DECODE, &pb);
   if (s != SL_OK) return s;
-  if (!g || g->window < 0 || !Qs || !K || !anchors) return SL_ERR_INVALID_ARG;
+  const int root = anchor_root(g);
+  if (!root || !Qs || !K || !anchors) return SL_ERR_INVALID_ARG;
   if (!sl::aligned16(Qs) || !sl::aligned16(K) || !sl::aligned16(anchors) || !sl::aligned16(scores))
     return SL_ERR_INVALID_ARG;
-  return sl::anchor_search_decode(pb, g->window, Qs, K, anchors, scores,
+  if (pb.L > ((int64_t)1 << 31) - 1) return SL_ERR_UNSUPPORTED;  // anchors are int32 token positions
+  return sl::anchor_search_decode(pb, g->window, root, Qs, K, anchors, scores,
                                   static_cast<hipStream_t>(hip_stream));
 }
 
@@ -211,17 +221,19 @@ sl_status sl_anchor_attention_decode(const sl_params* p, const sl_anchor_geometr
   sl::Problem pb;
   sl_status s = sl::make_problem(p, SL_OP_ATTENTION_DECODE, &pb);
   if (s != SL_OK) return s;
-  if (!g || g->window < 0 || g->backward_factor < 0 || g->forward_factor < 0) return SL_ERR_INVALID_ARG;
+  const int root = anchor_root(g);
+  if (!root) return SL_ERR_INVALID_ARG;
   if (!Q || !K || !V || !O || (pb.topk > 0 && (!anchors || !scores))) return SL_ERR_INVALID_ARG;
   if (!sl::aligned16(Q) || !sl::aligned16(K) || !sl::aligned16(V) || !sl::aligned16(O) ||
       !sl::aligned16(anchors) || !sl::aligned16(scores))
     return SL_ERR_INVALID_ARG;
-  const size_t need = sl::anchor_attention_ws_bytes(pb, g->window, g->backward_factor, g->forward_factor);
+  if (pb.L > ((int64_t)1 << 31) - 1) return SL_ERR_UNSUPPORTED;
+  const size_t need = sl::anchor_attention_ws_bytes(pb, g->window, g->backward_factor, g->forward_factor, root);
   if (!ws || ws_bytes < need || (reinterpret_cast<uintptr_t>(ws) & 255u)) return SL_ERR_WORKSPACE;
   pb.combined = true;
   pb.gate = scores;
-  return sl::anchor_attention_decode(pb, g->window, g->backward_factor, g->forward_factor, Q, K, V,
-                                     anchors, O, ws, static_cast<hipStream_t>(hip_stream));
+  return sl::anchor_attention_decode(pb, g->window, g->backward_factor, g->forward_factor, root, Q, K,
+                                     V, anchors, O, ws, static_cast<hipStream_t>(hip_stream));
 }
 
 sl_status sl_anchor_search_prefill(const sl_params* p, const sl_anchor_geometry* g, const void* Qs,
@@ -229,11 +241,12 @@ sl_status sl_anchor_search_prefill(const sl_params* p, const sl_anchor_geometry*
   sl::Problem pb;
   sl_status s = sl::make_problem(p, SL_OP_SEARCH_PREFILL, &pb);
   if (s != SL_OK) return s;
-  if (!g || g->window < 0 || !Qs || !K || !anchors) return SL_ERR_INVALID_ARG;
+  const int root = anchor_root(g);
+  if (!root || !Qs || !K || !anchors) return SL_ERR_INVALID_ARG;
   if (!sl::aligned16(Qs) || !sl::aligned16(K) || !sl::aligned16(anchors) || !sl::aligned16(scores))
     return SL_ERR_INVALID_ARG;
   if (pb.L > ((int64_t)1 << 31) - 1) return SL_ERR_UNSUPPORTED;  // anchors are int32 token positions
-  return sl::anchor_search_prefill(pb, g->window, Qs, K, anchors, scores,
+  return sl::anchor_search_prefill(pb, g->window, root, Qs, K, anchors, scores,
                                    static_cast<hipStream_t>(hip_stream));
 }
 
@@ -243,15 +256,17 @@ sl_status sl_anchor_attention_prefill(const sl_params* p, const sl_anchor_geomet
   sl::Problem pb;
   sl_status s = sl::make_problem(p, SL_OP_ATTENTION_PREFILL, &pb);
   if (s != SL_OK) return s;
-  if (!g || g->window < 0 || g->backward_factor < 0 || g->forward_factor < 0) return SL_ERR_INVALID_ARG;
+  const int root = anchor_root(g);
+  if (!root) return SL_ERR_INVALID_ARG;
   if (!Q || !K || !V || !O || (pb.topk > 0 && (!anchors || !scores))) return SL_ERR_INVALID_ARG;
   if (!sl::aligned16(Q) || !sl::aligned16(K) || !sl::aligned16(V) || !sl::aligned16(O) ||
       !sl::aligned16(anchors) || !sl::aligned16(scores))
     return SL_ERR_INVALID_ARG;
+  if (pb.L > ((int64_t)1 << 31) - 1) return SL_ERR_UNSUPPORTED;
   pb.combined = true;
   pb.gate = scores;
-  return sl::anchor_attention_prefill(pb, g->window, g->backward_factor, g->forward_factor, Q, K, V,
-                                      anchors, O, static_cast<hipStream_t>(hip_stream));
+  return sl::anchor_attention_prefill(pb, g->window, g->backward_factor, g->forward_factor, root, Q, K,
+                                      V, anchors, O, static_cast<hipStream_t>(hip_stream));
 }
 
 const char* sl_status_string(int status) {

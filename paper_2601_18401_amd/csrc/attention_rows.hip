@@ -143,16 +143,8 @@ __global__ __launch_bounds__(256) void prefill_combined_rows_kernel(
   }
 }
 
-// Exact ceil(sqrt(x)) for 0 <= x < 2^52.
-__device__ __forceinline__ int64_t isqrt_ceil_dev(int64_t x) {
-  int64_t r = (int64_t)sqrt((double)x);
-  while (r * r > x) --r;
-  while ((r + 1) * (r + 1) <= x) ++r;
-  return r * r == x ? r : r + 1;
-}
-
 // The paper's geometry, prefill form, attention + combination (Section 3.3-3.4, Algorithm 1):
-// for the query at position i, l = ceil(sqrt(i)), W = [max(0, i - window + 1), i], and per
+// for the query at position i, l = ceil(i^(1-p)) with p = 1/root, W = [max(0, i - window + 1), i], and per
 // selected anchor t the span S_t = [max(0, t - b*l), min(i, t + f*l)].  DedupConcat(S_t, W) is S_t
 // clipped at the start of W followed by W (W is a suffix of [0, i]); A_t has its own softmax and
 // O = sum_t alpha_t A_t with alpha = softmax of the slots' search scores; no valid slot: W alone
@@ -161,7 +153,7 @@ template <typename T, int D>
 __global__ __launch_bounds__(256) void prefill_anchor_combined_rows_kernel(
     const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
     const int32_t* __restrict__ anchors, const float* __restrict__ gate, T* __restrict__ O,
-    int64_t Lq, int64_t q_pos0, int Hq, int G, int topk, int64_t window, int b, int f,
+    int64_t Lq, int64_t q_pos0, int Hq, int G, int topk, int64_t window, int b, int f, int root,
     float scale_log2e, int64_t qsh, int64_t qst, int64_t kvsh, int64_t kvst) {
   using RL = RowLayout<T, D>;
   constexpr int EPL = RL::EPL, LPR = RL::LPR;
@@ -171,7 +163,7 @@ __global__ __launch_bounds__(256) void prefill_anchor_combined_rows_kernel(
   const int h = (int)(row / Lq);
   const int64_t r = row % Lq, i = q_pos0 + r;
   const int kv = h / G;
-  const int64_t ell = isqrt_ceil_dev(i);
+  const int64_t ell = span_base_length(i, root);
   const int64_t back = b * ell, fwd = f * ell;
   const int64_t wlo = window > 0 ? (i - window + 1 > 0 ? i - window + 1 : 0) : i + 1;
   const int lr = lane % LPR;
@@ -229,7 +221,7 @@ __global__ __launch_bounds__(256) void prefill_anchor_combined_rows_kernel(
 }
 
 template <typename T, int D>
-sl_status launch_anchor_rows(const Problem& pb, int64_t window, int b, int f, const void* Q,
+sl_status launch_anchor_rows(const Problem& pb, int64_t window, int b, int f, int root, const void* Q,
                              const void* K, const void* V, const int32_t* anchors, void* O,
                              hipStream_t st) {
   const int64_t rows = (int64_t)pb.Hq * pb.Lq;
@@ -237,7 +229,7 @@ sl_status launch_anchor_rows(const Problem& pb, int64_t window, int b, int f, co
   hipLaunchKernelGGL((prefill_anchor_combined_rows_kernel<T, D>), dim3((unsigned)((rows + 3) / 4)),
                      dim3(256), 0, st, static_cast<const T*>(Q), static_cast<const T*>(K),
                      static_cast<const T*>(V), anchors, pb.gate, static_cast<T*>(O), pb.Lq, pb.q_pos0,
-                     pb.Hq, pb.G, pb.topk, window, b, f, pb.scale * kLog2e, pb.qsh, pb.qst, pb.kvsh,
+                     pb.Hq, pb.G, pb.topk, window, b, f, root, pb.scale * kLog2e, pb.qsh, pb.qst, pb.kvsh,
                      pb.kvst);
   if (pb.prof_stop) (void)hipEventRecord(pb.prof_stop, st);
   return hipGetLastError() == hipSuccess ? SL_OK : SL_ERR_LAUNCH;
@@ -278,15 +270,16 @@ sl_status prefill_attention_rows(const Problem& pb, const void* Q, const void* K
   return launch_rows<float, 64>(pb, Q, K, V, idx, O, LSE, st);
 }
 
-sl_status anchor_attention_prefill(const Problem& pb, int64_t window, int b, int f, const void* Q,
+sl_status anchor_attention_prefill(const Problem& pb, int64_t window, int b, int f, int root,
+                                   const void* Q,
                                    const void* K, const void* V, const int32_t* anchors, void* O,
                                    hipStream_t st) {
   if (pb.dtype == SL_BF16) {
-    if (pb.D == 128) return launch_anchor_rows<bf16_t, 128>(pb, window, b, f, Q, K, V, anchors, O, st);
-    return launch_anchor_rows<bf16_t, 64>(pb, window, b, f, Q, K, V, anchors, O, st);
+    if (pb.D == 128) return launch_anchor_rows<bf16_t, 128>(pb, window, b, f, root, Q, K, V, anchors, O, st);
+    return launch_anchor_rows<bf16_t, 64>(pb, window, b, f, root, Q, K, V, anchors, O, st);
   }
-  if (pb.D == 128) return launch_anchor_rows<float, 128>(pb, window, b, f, Q, K, V, anchors, O, st);
-  return launch_anchor_rows<float, 64>(pb, window, b, f, Q, K, V, anchors, O, st);
+  if (pb.D == 128) return launch_anchor_rows<float, 128>(pb, window, b, f, root, Q, K, V, anchors, O, st);
+  return launch_anchor_rows<float, 64>(pb, window, b, f, root, Q, K, V, anchors, O, st);
 }
 
 }  // namespace sl

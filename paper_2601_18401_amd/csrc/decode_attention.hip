@@ -407,17 +407,10 @@ struct AnchorPlan {
   size_t part_bytes, total_bytes;
 };
 
-int64_t isqrt_ceil(int64_t x) {
-  int64_t r = (int64_t)std::sqrt((double)x);
-  while (r * r > x) --r;
-  while ((r + 1) * (r + 1) <= x) ++r;
-  return r * r == x ? r : r + 1;
-}
-
-AnchorPlan plan_anchor(const Problem& pb, int64_t window, int b, int f) {
+AnchorPlan plan_anchor(const Problem& pb, int64_t window, int b, int f, int root) {
   AnchorPlan a;
   const int64_t i = pb.q_pos0;
-  const int64_t ell = isqrt_ceil(i);  // l(i) = ceil(sqrt(i))
+  const int64_t ell = span_base_length(i, root);  // l(i) = ceil(i^(1-p)), p = 1/root
   a.back = (int64_t)b * ell;
   a.fwd = (int64_t)f * ell;
   a.wlo = window > 0 ? (i - window + 1 > 0 ? i - window + 1 : 0) : i + 1;
@@ -489,14 +482,15 @@ sl_status decode_attention(const Problem& pb, const void* Q, const void* K, cons
 
 namespace sl {
 
-size_t anchor_attention_ws_bytes(const Problem& pb, int64_t window, int b, int f) {
-  return plan_anchor(pb, window, b, f).total_bytes;
+size_t anchor_attention_ws_bytes(const Problem& pb, int64_t window, int b, int f, int root) {
+  return plan_anchor(pb, window, b, f, root).total_bytes;
 }
 
-sl_status anchor_attention_decode(const Problem& pb, int64_t window, int b, int f, const void* Q,
+sl_status anchor_attention_decode(const Problem& pb, int64_t window, int b, int f, int root,
+                                  const void* Q,
                                   const void* K, const void* V, const int32_t* anchors, void* O,
                                   void* ws, hipStream_t st) {
-  const AnchorPlan a = plan_anchor(pb, window, b, f);
+  const AnchorPlan a = plan_anchor(pb, window, b, f, root);
   if (pb.dtype == SL_BF16) {
     if (pb.D == 128) return launch_anchor_attention<bf16_t, 128>(pb, a, Q, K, V, anchors, O, ws, st);
     return launch_anchor_attention<bf16_t, 64>(pb, a, Q, K, V, anchors, O, ws, st);

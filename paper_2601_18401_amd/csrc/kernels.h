@@ -20,20 +20,21 @@ sl_status decode_attention(const Problem& pb, const void* Q, const void* K, cons
 
 // The paper's own geometry, decode form (Section 3.3, Algorithm 1): anchors on the quadratic
 // stride pattern, spans of b*l(i) / f*l(i) tokens around the selected anchors, window w.
-sl_status anchor_search_decode(const Problem& pb, int64_t window, const void* Qs, const void* K,
-                               int32_t* anchors, float* scores, hipStream_t st);
-size_t anchor_attention_ws_bytes(const Problem& pb, int64_t window, int b, int f);
-sl_status anchor_attention_decode(const Problem& pb, int64_t window, int b, int f, const void* Q,
-                                  const void* K, const void* V, const int32_t* anchors, void* O,
-                                  void* ws, hipStream_t st);
+// root = 1/p: 2 (anchors i-(s+1)^2+1, l = ceil(sqrt(i))) or 3 (anchors i-(s+1)^3+1, l = ceil(i^(2/3))).
+sl_status anchor_search_decode(const Problem& pb, int64_t window, int root, const void* Qs,
+                               const void* K, int32_t* anchors, float* scores, hipStream_t st);
+size_t anchor_attention_ws_bytes(const Problem& pb, int64_t window, int b, int f, int root);
+sl_status anchor_attention_decode(const Problem& pb, int64_t window, int b, int f, int root,
+                                  const void* Q, const void* K, const void* V,
+                                  const int32_t* anchors, void* O, void* ws, hipStream_t st);
 
 // The same geometry, prefill form (one wavefront per query row; every row has its own anchors,
 // span length and window)
-sl_status anchor_search_prefill(const Problem& pb, int64_t window, const void* Qs, const void* K,
-                                int32_t* anchors, float* scores, hipStream_t st);
-sl_status anchor_attention_prefill(const Problem& pb, int64_t window, int b, int f, const void* Q,
-                                   const void* K, const void* V, const int32_t* anchors, void* O,
-                                   hipStream_t st);
+sl_status anchor_search_prefill(const Problem& pb, int64_t window, int root, const void* Qs,
+                                const void* K, int32_t* anchors, float* scores, hipStream_t st);
+sl_status anchor_attention_prefill(const Problem& pb, int64_t window, int b, int f, int root,
+                                   const void* Q, const void* K, const void* V,
+                                   const int32_t* anchors, void* O, hipStream_t st);
 
 // a1 + a2: prefill span-search
 size_t prefill_search_ws_bytes(const Problem& pb);

@@ -100,17 +100,15 @@ template <typename T, int D, int RMAX>
 __global__ __launch_bounds__(kDecodeSearchThreads) void decode_search_block_kernel(
     const T* __restrict__ Qs, const T* __restrict__ K, const T* __restrict__ Ks,
     int32_t* __restrict__ idx, float* __restrict__ scores, int64_t c, int64_t n, int G, int S,
-    int topk, int64_t qsh, int64_t kvsh, int64_t kvst, int64_t anchor_i, int anchor_s0) {
+    int topk, int64_t qsh, int64_t kvsh, int64_t kvst, int64_t anchor_i, int anchor_s0,
+    int anchor_root) {
   // anchor_i >= 0: the candidates are the anchors of query position anchor_i on the paper's
-  // quadratic stride pattern (Section 3.3): candidate j is stride index s = anchor_s0 + j at token
-  // anchor_i - (s+1)^2 + 1, its key is K at that token, and the output lists tokens, not numbers.
+  // stride pattern (Section 3.3, p = 1/anchor_root): candidate j is stride index s = anchor_s0 + j
+  // at token anchor_i - (s+1)^root + 1, its key is K at that token, and the output lists tokens.
   using RL = RowLayout<T, D>;
   constexpr int EPL = RL::EPL, LPR = RL::LPR, RPW = RL::RPW;
   constexpr int U = 16, NW = kDecodeSearchThreads / 64;
-  auto anchor_token = [&](int64_t j) {
-    const int64_t s1 = anchor_s0 + j + 1;
-    return anchor_i - s1 * s1 + 1;
-  };
+  auto anchor_token = [&](int64_t j) { return anchor_token_of(anchor_i, anchor_s0 + j, anchor_root); };
   __shared__ float s_sc[kDecodeSearchThreads * RMAX];
   __shared__ __align__(16) unsigned s_hist[256];
   __shared__ int s_wave_tot[NW];
@@ -289,23 +287,15 @@ __global__ __launch_bounds__(256) void prefill_search_rows_kernel(
                    scores ? scores + row * topk : nullptr);
 }
 
-// Exact floor(sqrt(x)) for 0 <= x < 2^52.
-__device__ __forceinline__ int64_t isqrt_floor_dev(int64_t x) {
-  int64_t r = (int64_t)sqrt((double)x);
-  while (r * r > x) --r;
-  while ((r + 1) * (r + 1) <= x) ++r;
-  return r;
-}
-
 // The paper's geometry, prefill form, search (Section 3.3, Algorithm 1; eq. (2)-(3) with
 // K_a = K): one wavefront per (head, query row).  The candidates of the query at position i are
-// the anchors t_s = i - (s+1)^2 + 1 with s0 <= s and t_s >= 0 (s0 = floor(sqrt(window)): anchors
-// inside the window are left out); candidate number j is stride index s0 + j.
+// the anchors t_s = i - (s+1)^root + 1 with s0 <= s and t_s >= 0 (s0 = floor(window^(1/root)):
+// anchors inside the window are left out); candidate number j is stride index s0 + j.
 template <typename T, int D>
 __global__ __launch_bounds__(256) void prefill_anchor_search_rows_kernel(
     const T* __restrict__ Qs, const T* __restrict__ K, int32_t* __restrict__ anchors,
-    float* __restrict__ scores, int64_t Lq, int64_t q_pos0, int Hq, int G, int topk, int s0, int W,
-    int lds_per_wave, int64_t qsh, int64_t qst, int64_t kvsh, int64_t kvst) {
+    float* __restrict__ scores, int64_t Lq, int64_t q_pos0, int Hq, int G, int topk, int s0, int root,
+    int W, int lds_per_wave, int64_t qsh, int64_t qst, int64_t kvsh, int64_t kvst) {
   using RL = RowLayout<T, D>;
   constexpr int EPL = RL::EPL, LPR = RL::LPR, RPW = RL::RPW;
   extern __shared__ float s_all[];
@@ -316,7 +306,7 @@ __global__ __launch_bounds__(256) void prefill_anchor_search_rows_kernel(
   const int h = (int)(row / Lq);
   const int64_t r = row % Lq, i = q_pos0 + r;
   const int kv = h / G;
-  const int64_t s_max = isqrt_floor_dev(i + 1) - 1;  // (s+1)^2 <= i + 1
+  const int64_t s_max = iroot_floor(i + 1, root) - 1;  // (s+1)^root <= i + 1
   const int64_t c = s_max >= s0 ? s_max - s0 + 1 : 0;
   const int g = lane / LPR, lr = lane % LPR;
   const LaneMajor lm = LaneMajor::make(c);
@@ -332,8 +322,7 @@ __global__ __launch_bounds__(256) void prefill_anchor_search_rows_kernel(
     for (int u = 0; u < U; ++u) {
       int64_t j = jb + u * RPW + g;
       j = j < c ? j : c - 1;
-      const int64_t step = s0 + j + 1;
-      kr[u] = load16(Kb + (i - step * step + 1) * kvst + lr * EPL);
+      kr[u] = load16(Kb + anchor_token_of(i, s0 + j, root) * kvst + lr * EPL);
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
@@ -349,7 +338,7 @@ __global__ __launch_bounds__(256) void prefill_anchor_search_rows_kernel(
   }
   __builtin_amdgcn_wave_barrier();
   wave_select_topk(sc, lm, (int)c, topk, lane, anchors + row * topk,
-                   scores ? scores + row * topk : nullptr, i, s0);
+                   scores ? scores + row * topk : nullptr, i, s0, root);
 }
 
 template <typename T, int D>
@@ -375,12 +364,12 @@ sl_status launch_decode_search(const Problem& pb, const void* Qs, const void* K,
       hipLaunchKernelGGL((decode_search_block_kernel<T, D, 1>), dim3(pb.Hq),
                          dim3(kDecodeSearchThreads), 0, st, static_cast<const T*>(Qs),
                          static_cast<const T*>(K), static_cast<const T*>(Ks), idx, scores, c, pb.n,
-                         pb.G, pb.S, pb.topk, pb.qsh, pb.kvsh, pb.kvst, (int64_t)-1, 0);
+                         pb.G, pb.S, pb.topk, pb.qsh, pb.kvsh, pb.kvst, (int64_t)-1, 0, 2);
     else
       hipLaunchKernelGGL((decode_search_block_kernel<T, D, 4>), dim3(pb.Hq),
                          dim3(kDecodeSearchThreads), 0, st, static_cast<const T*>(Qs),
                          static_cast<const T*>(K), static_cast<const T*>(Ks), idx, scores, c, pb.n,
-                         pb.G, pb.S, pb.topk, pb.qsh, pb.kvsh, pb.kvst, (int64_t)-1, 0);
+                         pb.G, pb.S, pb.topk, pb.qsh, pb.kvsh, pb.kvst, (int64_t)-1, 0, 2);
     if (pb.prof_stop) (void)hipEventRecord(pb.prof_stop, st);
     return hipGetLastError() == hipSuccess ? SL_OK : SL_ERR_LAUNCH;
   }
@@ -395,18 +384,18 @@ sl_status launch_decode_search(const Problem& pb, const void* Qs, const void* K,
 
 template <typename T, int D>
 sl_status launch_anchor_search(const Problem& pb, const void* Qs, const void* K, int32_t* anchors,
-                               float* scores, int64_t c, int s0, hipStream_t st) {
+                               float* scores, int64_t c, int s0, int root, hipStream_t st) {
   if (pb.prof_start) (void)hipEventRecord(pb.prof_start, st);
   if (c <= kDecodeSearchThreads)
     hipLaunchKernelGGL((decode_search_block_kernel<T, D, 1>), dim3(pb.Hq), dim3(kDecodeSearchThreads),
                        0, st, static_cast<const T*>(Qs), static_cast<const T*>(K),
                        static_cast<const T*>(nullptr), anchors, scores, c, (int64_t)0, pb.G, 1,
-                       pb.topk, pb.qsh, pb.kvsh, pb.kvst, pb.q_pos0, s0);
+                       pb.topk, pb.qsh, pb.kvsh, pb.kvst, pb.q_pos0, s0, root);
   else
     hipLaunchKernelGGL((decode_search_block_kernel<T, D, 4>), dim3(pb.Hq), dim3(kDecodeSearchThreads),
                        0, st, static_cast<const T*>(Qs), static_cast<const T*>(K),
                        static_cast<const T*>(nullptr), anchors, scores, c, (int64_t)0, pb.G, 1,
-                       pb.topk, pb.qsh, pb.kvsh, pb.kvst, pb.q_pos0, s0);
+                       pb.topk, pb.qsh, pb.kvsh, pb.kvst, pb.q_pos0, s0, root);
   if (pb.prof_stop) (void)hipEventRecord(pb.prof_stop, st);
   return hipGetLastError() == hipSuccess ? SL_OK : SL_ERR_LAUNCH;
 }
@@ -434,7 +423,7 @@ sl_status launch_prefill_search_rows(const Problem& pb, const void* Qs, const vo
 template <typename T, int D>
 sl_status launch_anchor_search_rows(const Problem& pb, const void* Qs, const void* K,
                                     int32_t* anchors, float* scores, int64_t c_max, int s0,
-                                    hipStream_t st) {
+                                    int root, hipStream_t st) {
   const int lds_per_wave = LaneMajor::make(c_max).lds_floats();
   int W = 4;
   while (W > 1 && (size_t)W * lds_per_wave * sizeof(float) > 64 * 1024) W >>= 1;
@@ -444,7 +433,7 @@ sl_status launch_anchor_search_rows(const Problem& pb, const void* Qs, const voi
   hipLaunchKernelGGL((prefill_anchor_search_rows_kernel<T, D>), dim3((unsigned)grid), dim3(256),
                      (size_t)W * lds_per_wave * sizeof(float), st, static_cast<const T*>(Qs),
                      static_cast<const T*>(K), anchors, scores, pb.Lq, pb.q_pos0, pb.Hq, pb.G,
-                     pb.topk, s0, W, lds_per_wave, pb.qsh, pb.qst, pb.kvsh, pb.kvst);
+                     pb.topk, s0, root, W, lds_per_wave, pb.qsh, pb.qst, pb.kvsh, pb.kvst);
   if (pb.prof_stop) (void)hipEventRecord(pb.prof_stop, st);
   return hipGetLastError() == hipSuccess ? SL_OK : SL_ERR_LAUNCH;
 }
@@ -470,43 +459,35 @@ sl_status span_keys(const Problem& pb, const void* K, void* Ks, hipStream_t st) 
 
 size_t decode_search_ws_bytes(const Problem&) { return 0; }
 
-// Integer square root (floor), exact.
-static int64_t isqrt64(int64_t x) {
-  int64_t r = (int64_t)std::sqrt((double)x);
-  while (r * r > x) --r;
-  while ((r + 1) * (r + 1) <= x) ++r;
-  return r;
-}
-
 // Candidate anchors of query position i = pb.q_pos0 with window w (Section 3.3, Algorithm 1):
-// stride indices s0 .. s_max, where t_s = i - (s+1)^2 + 1 >= 0 and t_s < i - w + 1.
-void anchor_candidates(const Problem& pb, int64_t window, int64_t* c, int* s0) {
+// stride indices s0 .. s_max, where t_s = i - (s+1)^root + 1 >= 0 and t_s < i - w + 1.
+void anchor_candidates(const Problem& pb, int64_t window, int root, int64_t* c, int* s0) {
   const int64_t i = pb.q_pos0;
-  const int64_t s_max = isqrt64(i + 1) - 1;     // (s+1)^2 <= i + 1
-  const int64_t first = window > 0 ? isqrt64(window) : 0;  // (s+1)^2 > w  <=>  s >= isqrt(w)
+  const int64_t s_max = iroot_floor(i + 1, root) - 1;               // (s+1)^root <= i + 1
+  const int64_t first = window > 0 ? iroot_floor(window, root) : 0;  // (s+1)^root > w  <=>  s >= floor(w^(1/root))
   *s0 = (int)first;
   *c = s_max >= first ? s_max - first + 1 : 0;
 }
 
-sl_status anchor_search_decode(const Problem& pb, int64_t window, const void* Qs, const void* K,
-                               int32_t* anchors, float* scores, hipStream_t st) {
+sl_status anchor_search_decode(const Problem& pb, int64_t window, int root, const void* Qs,
+                               const void* K, int32_t* anchors, float* scores, hipStream_t st) {
   int64_t c;
   int s0;
-  anchor_candidates(pb, window, &c, &s0);
+  anchor_candidates(pb, window, root, &c, &s0);
   if (c > (int64_t)kDecodeSearchThreads * 4) return SL_ERR_UNSUPPORTED;
-  SL_DISPATCH(launch_anchor_search, pb, Qs, K, anchors, scores, c, s0, st);
+  SL_DISPATCH(launch_anchor_search, pb, Qs, K, anchors, scores, c, s0, root, st);
 }
 
-sl_status anchor_search_prefill(const Problem& pb, int64_t window, const void* Qs, const void* K,
-                                int32_t* anchors, float* scores, hipStream_t st) {
+sl_status anchor_search_prefill(const Problem& pb, int64_t window, int root, const void* Qs,
+                                const void* K, int32_t* anchors, float* scores, hipStream_t st) {
   // the last query row has the most candidates
   Problem last = pb;
   last.q_pos0 = pb.q_pos0 + pb.Lq - 1;
   int64_t c_max;
   int s0;
-  anchor_candidates(last, window, &c_max, &s0);
+  anchor_candidates(last, window, root, &c_max, &s0);
   if (c_max > kMaxSpansLds) return SL_ERR_UNSUPPORTED;
-  SL_DISPATCH(launch_anchor_search_rows, pb, Qs, K, anchors, scores, c_max, s0, st);
+  SL_DISPATCH(launch_anchor_search_rows, pb, Qs, K, anchors, scores, c_max, s0, root, st);
 }
 
 sl_status decode_search(const Problem& pb, const void* Qs, const void* K, const void* Ks,

@@ -57,12 +57,13 @@ __device__ __forceinline__ void select_clear(float* sc, const LaneMajor& lm, int
 // sc: lane-major LDS array with the c candidate scores of one query row (private to this
 // wavefront), unused entries -inf.  Scores are assumed finite.  All 64 lanes must call.
 // out_idx / out_scores point at the row's topk output slots.
-// anchor_i >= 0: candidate j stands for the anchor token anchor_i - (anchor_s0 + j + 1)^2 + 1 of
-// the quadratic stride pattern (Section 3.3) and that token is what is written to out_idx.
+// anchor_i >= 0: candidate j stands for the anchor token anchor_i - (anchor_s0 + j + 1)^root + 1
+// of the stride pattern (Section 3.3, p = 1/root) and that token is what is written to out_idx.
 __device__ __forceinline__ void wave_select_topk(float* sc, const LaneMajor& lm, int c, int topk,
                                                  int lane, int32_t* __restrict__ out_idx,
                                                  float* __restrict__ out_scores,
-                                                 int64_t anchor_i = -1, int anchor_s0 = 0) {
+                                                 int64_t anchor_i = -1, int anchor_s0 = 0,
+                                                 int anchor_root = 2) {
   const int kk = topk < c ? topk : c;
   float* colf = sc + lane * lm.Rp;
   const float4* col = reinterpret_cast<const float4*>(colf);
@@ -107,8 +108,8 @@ __device__ __forceinline__ void wave_select_topk(float* sc, const LaneMajor& lm,
   }
   if (lane < kk) {
     if (anchor_i >= 0 && myj != 0x7fffffff) {
-      const int64_t step = (int64_t)anchor_s0 + myj + 1;
-      myj = (int)(anchor_i - step * step + 1);  // rank stays: ascending candidate = nearest anchor first
+      // rank stays: ascending candidate = nearest anchor first
+      myj = (int)anchor_token_of(anchor_i, (int64_t)anchor_s0 + myj, anchor_root);
     }
     out_idx[rank] = myj == 0x7fffffff ? -1 : myj;
     if (out_scores) out_scores[rank] = mys;

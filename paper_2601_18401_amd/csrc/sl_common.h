@@ -1,6 +1,8 @@
 // Shared host/device helpers for the gfx950 kernels of the span-search / span-attention library.
 #pragma once
 
+#include <cmath>
+
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -85,6 +87,29 @@ struct RowLayout {
 };
 
 __device__ __forceinline__ uint4 load16(const void* p) { return *reinterpret_cast<const uint4*>(p); }
+
+// ---- the paper's anchor geometry (Section 3.3) for p = 1/root, root = 2 or 3, in exact integer
+// arithmetic.  Valid for 0 <= x < 2^62.
+__host__ __device__ inline int64_t ipow_root(int64_t v, int root) { return root == 2 ? v * v : v * v * v; }
+// floor(x^(1/root))
+__host__ __device__ inline int64_t iroot_floor(int64_t x, int root) {
+  if (x <= 0) return 0;
+  int64_t m = (int64_t)(root == 2 ? sqrt((double)x) : cbrt((double)x));
+  while (m > 0 && ipow_root(m, root) > x) --m;
+  while (ipow_root(m + 1, root) <= x) ++m;
+  return m;
+}
+// anchor token of stride index s for the query at position i: i - (s+1)^root + 1
+__host__ __device__ inline int64_t anchor_token_of(int64_t i, int64_t s, int root) {
+  return i - ipow_root(s + 1, root) + 1;
+}
+// l(i) = ceil(i^(1-p)) = the smallest m with m^root >= i^(root-1); i < 2^31
+__host__ __device__ inline int64_t span_base_length(int64_t i, int root) {
+  if (i <= 0) return 0;
+  const int64_t target = root == 2 ? i : i * i;
+  const int64_t m = iroot_floor(target, root);
+  return ipow_root(m, root) == target ? m : m + 1;
+}
 
 // DPP lane exchange (no LDS traffic). ctrl: quad_perm 0x00-0xFF, row_mirror 0x140,
 // row_half_mirror 0x141.

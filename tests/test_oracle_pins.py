@@ -413,6 +413,45 @@ def test_random_context_access_on_paper_geometry(i, w, b):
     assert covered == set(range(i + 1))
 
 
+@pytest.mark.parametrize("i", [0, 1, 6, 7, 8, 26, 27, 999, 1000, 262143, 10 ** 6])
+def test_anchor_closed_forms_for_one_third_two_thirds(i):
+    # the general-p formulas of Section 3.3 at p = 1/3: anchors i - (s+1)^3 + 1 (offsets 0, 7, 26,
+    # 63, ...; gaps 3s^2 + 9s + 7), floor((i+1)^(1/3)) of them; l(i) = ceil(i^(2/3)), the exponent
+    # split (1/3, 2/3) of Section 5
+    a = orc.anchor_positions(i, 3)
+    n = len(a)
+    assert n ** 3 <= i + 1 < (n + 1) ** 3
+    assert [i - t for t in a] == [(s + 1) ** 3 - 1 for s in range(n)]
+    assert [a[s] - a[s + 1] for s in range(n - 1)] == [3 * s * s + 9 * s + 7 for s in range(n - 1)]
+    l = orc.base_span_length(i, 3)
+    assert l ** 3 >= i * i and (l == 0 or (l - 1) ** 3 < i * i)
+    if 0 < i < 10 ** 5:
+        assert abs(l - i ** (2.0 / 3.0)) < 1.0 + 1e-6
+
+
+@pytest.mark.parametrize("i,w", [(200, 0), (5000, 26), (100000, 342)])
+def test_random_context_access_for_one_third_two_thirds(i, w):
+    # b >= 1/p = 3 reaches every key (Section 3.3): gaps between adjacent anchors are at most
+    # 3 (s+1)^2 + 3 (s+1) + 1 <= 3 i^(2/3) for (s+2)^3 <= i + 1.  Windows w = m^3 - 1 put the first
+    # candidate right before W.
+    covered = set()
+    W = orc.window_range(i, w)
+    if W:
+        covered |= set(range(W[0], W[1] + 1))
+    cand = orc.anchor_candidates(i, w, 3)
+    assert W is None or cand[0][1] == W[0] - 1
+    for _, t in cand:
+        a, e = orc.anchor_span(t, i, 3, 0, 3)
+        covered |= set(range(a, e + 1))
+    assert covered == set(range(i + 1))
+    # ... and b = 2 is not enough there
+    short = set(range(W[0], W[1] + 1)) if W else set()
+    for _, t in cand:
+        a, e = orc.anchor_span(t, i, 2, 0, 3)
+        short |= set(range(a, e + 1))
+    assert short != set(range(i + 1))
+
+
 def test_anchor_search_equals_bruteforce_argsort():
     rng = np.random.default_rng(50)
     i, w, k, D = 777, 50, 4, 8

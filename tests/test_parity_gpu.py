@@ -567,6 +567,63 @@ def test_anchor_prefill_last_row_equals_decode():
     assert float((O_p[:, -1].float() - O_d[:, 0].float()).abs().max()) <= 2 * TOL[torch.bfloat16]
 
 
+# search exponent 1/3, span exponent 2/3 (Section 5) in the general-p formulas of Section 3.3
+ANCHOR_SPLIT = [
+    # seed Hq Hkv L      D    k  w    b  f  dtype           q_pos0 Lq
+    (61, 4, 2, 60000, 128, 2, 342, 3, 0, torch.bfloat16, 59999, 1),    # decode form, w = 7^3 - 1
+    (62, 2, 1, 3000, 64, 3, 26, 3, 1, torch.float32, 0, 3000),         # prefill form from i = 0 on
+    (63, 4, 1, 9000, 128, 4, 0, 4, 0, torch.bfloat16, 8800, 200),      # no window, chunk at the end
+]
+
+
+@pytest.mark.parametrize("seed,Hq,Hkv,L,D,k,w,b,f,dtype,q_pos0,Lq", ANCHOR_SPLIT)
+def test_anchor_split_exponents(seed, Hq, Hkv, L, D, k, w, b, f, dtype, q_pos0, Lq):
+    Q, K, V = make(seed, Hq, Hkv, L, D, dtype, Lq=Lq, scale=0.5)
+    G = Hq // Hkv
+    if Lq == 1:
+        anchors, sc = B.sl_anchor_search_decode(Q, K, k, w, want_scores=True, search_root=3)
+    else:
+        anchors, sc = B.sl_anchor_search_prefill(Q, K, k, w, q_pos0=q_pos0, want_scores=True, search_root=3)
+    torch.cuda.synchronize()
+    an, scn = anchors.cpu().numpy(), sc.cpu().numpy()
+    Qn = f64(Q)
+    Kh = [f64(K[kv]) for kv in range(Hkv)]
+    rows = sorted(set(list(range(0, Lq, max(1, Lq // 30))) + [0, min(7, Lq - 1), min(8, Lq - 1), Lq - 1]))
+    for h in range(Hq):
+        kv = h // G
+        for r in rows:
+            i = q_pos0 + r
+            s_o, t_o, sc_o = orc.anchor_search_row(Qn[h, r], Kh[kv], i, w, k, root=3)
+            want = t_o + [-1] * (k - len(t_o))
+            got = an[h, r].tolist()
+            if got != want:
+                cand = orc.anchor_candidates(i, w, 3)
+                allsc = [float(Kh[kv][t] @ Qn[h, r]) for _, t in cand]
+                assert orc.selection_margin(allsc, k) < MARGIN, (h, r, got, want)
+    sc_in = torch.where(torch.isfinite(sc), sc, torch.zeros_like(sc))
+    if Lq == 1:
+        O = B.sl_anchor_attention_decode(Q, K, V, anchors, sc_in, w, b, f, search_root=3)
+    else:
+        O = B.sl_anchor_attention_prefill(Q, K, V, anchors, sc_in, w, b, f, q_pos0=q_pos0, search_root=3)
+    torch.cuda.synchronize()
+    On = f64(O)
+    Kn, Vn = f64(K), f64(V)
+    scale = 1.0 / math.sqrt(D)
+    for h in range(Hq):
+        for r in rows:
+            i = q_pos0 + r
+            o = orc.anchor_combined_row(Qn[h, r], Kn, Vn, h // G, i, w, b, f, an[h, r],
+                                        scn[h, r].astype(np.float64), scale, root=3)
+            err = float(np.max(np.abs(On[h, r] - o)))
+            assert err <= TOL[dtype], (h, r, err)
+
+
+def test_anchor_geometry_rejects_unknown_root():
+    Q, K, V = make(64, 2, 1, 500, 64, torch.float32, Lq=1)
+    with pytest.raises(B.SlError):
+        B.sl_anchor_search_decode(Q, K, 2, 24, search_root=4)
+
+
 class DevRows:
     """Row access K[t] -> fp64 [D] on a device tensor [L, D] (for the oracle's anchor scoring)."""
 
