@@ -350,6 +350,39 @@ def test_decode_search_ties_lower_index_wins(L, S, k):
     assert np.allclose(sc.cpu().numpy(), wsc, atol=1e-3)
 
 
+@pytest.mark.parametrize("case_seed", [101, 102, 103])
+def test_prefill_randomized_shapes(case_seed):
+    # seeded random shapes inside the envelope of the matrix-core path (bf16, D = 128, S % 64 == 0):
+    # head grouping, span length, top-k list size, chunk position and raggedness all vary
+    import random
+    rng = random.Random(case_seed)
+    for _ in range(8):
+        G, Hkv = rng.choice([1, 2, 4, 8]), rng.choice([1, 2, 3])
+        Hq = G * Hkv
+        S, k = rng.choice([64, 128, 192, 256, 320, 512]), rng.choice([1, 2, 3, 5, 8, 8, 12, 16, 32])
+        L = rng.randint(1, 5000)
+        Lq = L if rng.random() < 0.5 else rng.randint(1, L)
+        q0 = L - Lq if rng.random() < 0.5 else rng.randint(0, L - Lq)
+        seed = rng.randint(0, 10 ** 6)
+        Q, K, V = make(seed, Hq, Hkv, q0 + Lq, 128, torch.bfloat16, Lq=Lq)
+        Ks = B.sl_span_keys(K, S)
+        idx, sc = B.sl_span_search_prefill(Q, K, Ks, S, k, q_pos0=q0, want_scores=True)
+        torch.cuda.synchronize()
+        rows = [(h, r) for h in range(Hq) for r in sorted(set(rng.sample(range(Lq), min(Lq, 25)) + [0, Lq - 1]))]
+        where = (seed, Hq, Hkv, q0 + Lq, S, k, q0, Lq)
+        try:
+            check_idx(idx, Q, Ks, S, k, q0, rows)
+            O, LSE = B.sl_span_attention_prefill(Q, K, V, idx, S, q_pos0=q0)
+            torch.cuda.synchronize()
+            check_attention(O, LSE, Q, K, V, idx, S, q0, 0.0, rows)
+            scf = torch.where(torch.isfinite(sc), sc, torch.zeros_like(sc))
+            Oc = B.sl_span_attention_combined_prefill(Q, K, V, idx, scf, S, q_pos0=q0)
+            torch.cuda.synchronize()
+            check_combined(Oc, Q, K, V, idx, scf, S, q0, 0.0, rows)
+        except AssertionError as e:
+            raise AssertionError(f"case {where}: {e}") from e
+
+
 # ------------------------------------------------------------------------------ combination (Section 3.4)
 
 def check_combined(O, Q, K, V, idx, scores, S, q_pos0, scale, rows=None):
