@@ -234,7 +234,7 @@ __global__ __launch_bounds__(256) void decode_reduce_kernel(const float* __restr
 // scores; no valid slot: the window alone.  Record p = slot * nchunks + chunk (slot topk = window)
 // holds (o[D] unnormalised, m, l), m in log2 units; a slot without a span has m = -inf in all
 // its records.  grid (Hq, D / 32) like decode_reduce_kernel: 256 threads = 8 chunk subsets x 32
-// dims; a thread's record loads are issued before the statistics they are weighted with arrive.
+// dims.
 constexpr int kMaxSlots = SL_MAX_TOPK + 1;
 
 template <typename T, int D>
@@ -253,13 +253,25 @@ __global__ __launch_bounds__(256) void decode_reduce_combined_kernel(const float
   float* s_l = s_dyn + nrec;
   const float* base = part + (int64_t)h * nrec * (D + 2);
 
-  // first chunk batch of every slot: independent of the statistics, issued first
-  float ov[kMaxSlots];
+  // A thread owns dim d and the chunks sub, sub + 8, ... of every slot.  Its record loads do not
+  // depend on the statistics, so (if they fit kMaxPre registers) all of them are issued first.
+  constexpr int kMaxPre = 36;
+  const int per_slot = (nchunks + kReduceSub - 1) / kReduceSub;
+  const int nload = nslot * per_slot;
+  const bool pre = nload <= kMaxPre;
+  float ov[kMaxPre];
+  if (pre) {
+    int slot = 0, it = 0;
 #pragma unroll
-  for (int slot = 0; slot < kMaxSlots; ++slot)
-    ov[slot] = (slot < nslot && sub < nchunks)
-                   ? base[(int64_t)(slot * nchunks + sub) * (D + 2) + d0 + d]
-                   : 0.f;
+    for (int u = 0; u < kMaxPre; ++u) {
+      const int ck = sub + it * kReduceSub;
+      ov[u] = (u < nload && ck < nchunks) ? base[(int64_t)(slot * nchunks + ck) * (D + 2) + d0 + d] : 0.f;
+      if (++it == per_slot) {
+        it = 0;
+        ++slot;
+      }
+    }
+  }
   for (int p = tid; p < nrec; p += 256) {
     s_m[p] = base[(int64_t)p * (D + 2) + D];
     s_l[p] = base[(int64_t)p * (D + 2) + D + 1];
@@ -277,17 +289,32 @@ __global__ __launch_bounds__(256) void decode_reduce_combined_kernel(const float
     s_ls[tid] = l;
   }
   __syncthreads();
+  if (pre) {
+    int slot = 0, it = 0;
+    float acc = 0.f;
 #pragma unroll
-  for (int slot = 0; slot < kMaxSlots; ++slot) {
-    if (slot < nslot) {
+    for (int u = 0; u < kMaxPre; ++u) {
+      if (u < nload) {
+        const int ck = sub + it * kReduceSub;
+        const float ms = s_ms[slot];
+        if (ck < nchunks && ms > -INFINITY) {
+          const float mp = s_m[slot * nchunks + ck];
+          if (mp > -INFINITY) acc = fmaf(fast_exp2(mp - ms), ov[u], acc);
+        }
+        if (++it == per_slot) {
+          s_part[slot][sub][d] = acc;
+          acc = 0.f;
+          it = 0;
+          ++slot;
+        }
+      }
+    }
+  } else {
+    for (int slot = 0; slot < nslot; ++slot) {
       const float ms = s_ms[slot];
       float acc = 0.f;
       if (ms > -INFINITY) {
-        if (sub < nchunks) {
-          const float mp = s_m[slot * nchunks + sub];
-          if (mp > -INFINITY) acc = fast_exp2(mp - ms) * ov[slot];
-        }
-        for (int ck = sub + kReduceSub; ck < nchunks; ck += kReduceSub) {  // more than 8 chunks
+        for (int ck = sub; ck < nchunks; ck += kReduceSub) {
           const float mp = s_m[slot * nchunks + ck];
           if (mp > -INFINITY)
             acc = fmaf(fast_exp2(mp - ms), base[(int64_t)(slot * nchunks + ck) * (D + 2) + d0 + d], acc);
