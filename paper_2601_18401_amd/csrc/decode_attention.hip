@@ -17,15 +17,23 @@ namespace {
 
 constexpr int kDecodeThreads = 256;
 
+// Span extents of the paper's geometry for one decode step (l = ceil(i^(1-p)): back = b*l, fwd = f*l).
+struct AnchorRanges {
+  bool on;
+  int64_t wlo, back, fwd;
+};
+
 // Partial record of one (head, slot, chunk): o[D] (unnormalised, relative to m), m (log2 units), l.
 template <typename T, int D>
 __global__ __launch_bounds__(kDecodeThreads) void decode_split_kernel(
     const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
     const int32_t* __restrict__ idx, float* __restrict__ part, int64_t q_pos, int Hq, int Hkv,
     int S, int topk, int nchunks, int CT, float scale_log2e, int64_t qsh, int64_t kvsh,
-    int64_t kvst, int n_routed_blocks, int local_stride, const int64_t* __restrict__ ranges) {
-  // ranges != nullptr: slot s of head h attends tokens [ranges[2u], ranges[2u+1]) with
-  // u = h * (topk + 1) + s (slot topk = the window), instead of grid span idx[h][s] / [c*S, q_pos].
+    int64_t kvst, int n_routed_blocks, int local_stride, const AnchorRanges ar) {
+  // ar.on: the paper's geometry (Section 3.3, Algorithm 1) instead of the grid: idx holds anchor
+  // tokens, slot s of head h attends S_t minus W for t = idx[h][s] (W is a suffix of [0, q_pos], so
+  // the set difference is a clip; DedupConcat(S_t, W) is then the slot's range plus the window's),
+  // S_t = [max(0, t - back), min(q_pos, t + fwd)], and slot topk of every head is W = [wlo, q_pos].
   using RL = RowLayout<T, D>;
   constexpr int EPL = RL::EPL, LPR = RL::LPR, RPW = RL::RPW;
   constexpr int NG = (kDecodeThreads / 64) * RPW;  // row groups per workgroup
@@ -42,7 +50,7 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_split_kernel(
   if (bid >= 0) {
     ck = bid % nchunks;
     const int u = bid / nchunks;
-    const int ns = ranges ? topk + 1 : topk;  // with ranges the window is slot topk of every head
+    const int ns = ar.on ? topk + 1 : topk;  // on the paper's geometry the window is slot topk of every head
     h = u / ns;
     slot = u % ns;
   } else {
@@ -59,9 +67,20 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_split_kernel(
   const int kv = h / G;
 
   int64_t t0, t1;
-  if (ranges) {
-    const int64_t r0 = ranges[2 * ((int64_t)h * (topk + 1) + slot)];
-    const int64_t r1 = ranges[2 * ((int64_t)h * (topk + 1) + slot) + 1];
+  if (ar.on) {
+    int64_t r0 = 0, r1 = 0;
+    if (slot == topk) {
+      r0 = ar.wlo;
+      r1 = q_pos + 1;
+    } else {
+      const int64_t t = idx[(int64_t)h * topk + slot];
+      if (t >= 0 && t <= q_pos) {
+        r0 = t - ar.back > 0 ? t - ar.back : 0;
+        const int64_t e = t + ar.fwd < q_pos ? t + ar.fwd : q_pos;
+        r1 = (e < ar.wlo - 1 ? e : ar.wlo - 1) + 1;
+        if (r1 < r0) r1 = r0;
+      }
+    }
     t0 = r0 + (int64_t)ck * CT;
     t1 = t0 + CT < r1 ? t0 + CT : r1;
   } else if (slot < topk) {
@@ -377,13 +396,13 @@ sl_status launch_decode(const Problem& pb, const void* Q, const void* K, const v
                           pb.prof_start, pb.prof_stop, 0, static_cast<const T*>(Q),
                           static_cast<const T*>(K), static_cast<const T*>(V), idx, part, pb.q_pos0,
                           pb.Hq, pb.Hkv, pb.S, pb.topk, nchunks, CT, scale_log2e, pb.qsh, pb.kvsh,
-                          pb.kvst, n_routed, local_stride, static_cast<const int64_t*>(nullptr));
+                          pb.kvst, n_routed, local_stride, AnchorRanges{false, 0, 0, 0});
   } else {
     hipLaunchKernelGGL((decode_split_kernel<T, D>), dim3(grid), dim3(kDecodeThreads), 0, st,
                        static_cast<const T*>(Q), static_cast<const T*>(K), static_cast<const T*>(V),
                        idx, part, pb.q_pos0, pb.Hq, pb.Hkv, pb.S, pb.topk, nchunks, CT,
                        scale_log2e, pb.qsh, pb.kvsh, pb.kvst, n_routed, local_stride,
-                       static_cast<const int64_t*>(nullptr));
+                       AnchorRanges{false, 0, 0, 0});
   }
   if (hipGetLastError() != hipSuccess) return SL_ERR_LAUNCH;
   const int nrec = (pb.topk + 1) * nchunks;
@@ -401,33 +420,6 @@ sl_status launch_decode(const Problem& pb, const void* Q, const void* K, const v
 
 
 // ------------------------------------------------------------------ the paper's own geometry
-// Token ranges of one decode step on the paper's geometry (Section 3.3, Algorithm 1): slot s of
-// head h holds S_t minus W for the selected anchor t = anchors[h][s] (W is a suffix of [0, i], so
-// the set difference is a clip; DedupConcat(S_t, W) is then the slot's range plus the window's),
-// S_t = [max(0, t - back), min(i, t + fwd)]; slot topk holds W = [wlo, i].
-__global__ void anchor_ranges_kernel(const int32_t* __restrict__ anchors, int64_t* __restrict__ ranges,
-                                     int Hq, int topk, int64_t i, int64_t wlo, int64_t back,
-                                     int64_t fwd) {
-  const int u = blockIdx.x * blockDim.x + threadIdx.x;
-  if (u >= Hq * (topk + 1)) return;
-  const int h = u / (topk + 1), slot = u % (topk + 1);
-  int64_t r0 = 0, r1 = 0;
-  if (slot == topk) {
-    r0 = wlo;
-    r1 = i + 1;
-  } else {
-    const int64_t t = anchors[h * topk + slot];
-    if (t >= 0 && t <= i) {
-      r0 = t - back > 0 ? t - back : 0;
-      const int64_t e = t + fwd < i ? t + fwd : i;
-      r1 = (e < wlo - 1 ? e : wlo - 1) + 1;
-      if (r1 < r0) r1 = r0;
-    }
-  }
-  ranges[2 * u] = r0;
-  ranges[2 * u + 1] = r1;
-}
-
 struct AnchorPlan {
   int64_t back, fwd, wlo, maxlen;
   int CT, nchunks;
@@ -450,7 +442,7 @@ AnchorPlan plan_anchor(const Problem& pb, int64_t window, int b, int f, int root
   a.CT = ct;
   a.nchunks = (int)((a.maxlen + ct - 1) / ct);
   a.part_bytes = align_up((size_t)units * a.nchunks * (pb.D + 2) * sizeof(float), 256);
-  a.total_bytes = a.part_bytes + align_up((size_t)units * 2 * sizeof(int64_t), 256);
+  a.total_bytes = a.part_bytes;
   return a;
 }
 
@@ -459,10 +451,8 @@ sl_status launch_anchor_attention(const Problem& pb, const AnchorPlan& a, const 
                                   const void* K, const void* V, const int32_t* anchors, void* O,
                                   void* ws, hipStream_t st) {
   float* part = static_cast<float*>(ws);
-  int64_t* ranges = reinterpret_cast<int64_t*>(static_cast<char*>(ws) + a.part_bytes);
   const int units = pb.Hq * (pb.topk + 1);
-  hipLaunchKernelGGL(anchor_ranges_kernel, dim3((units + 255) / 256), dim3(256), 0, st, anchors,
-                     ranges, pb.Hq, pb.topk, pb.q_pos0, a.wlo, a.back, a.fwd);
+  const AnchorRanges ar{true, a.wlo, a.back, a.fwd};
   // every (head, slot, chunk) is a routed item here: the window is slot topk of every head
   const int grid = units * a.nchunks;
   const float scale_log2e = pb.scale * kLog2e;
@@ -471,13 +461,12 @@ sl_status launch_anchor_attention(const Problem& pb, const AnchorPlan& a, const 
                           pb.prof_start, pb.prof_stop, 0, static_cast<const T*>(Q),
                           static_cast<const T*>(K), static_cast<const T*>(V), anchors, part, pb.q_pos0,
                           pb.Hq, pb.Hkv, 1, pb.topk, a.nchunks, a.CT, scale_log2e, pb.qsh, pb.kvsh,
-                          pb.kvst, grid, 8, static_cast<const int64_t*>(ranges));
+                          pb.kvst, grid, 8, ar);
   } else {
     hipLaunchKernelGGL((decode_split_kernel<T, D>), dim3(grid), dim3(kDecodeThreads), 0, st,
                        static_cast<const T*>(Q), static_cast<const T*>(K), static_cast<const T*>(V),
                        anchors, part, pb.q_pos0, pb.Hq, pb.Hkv, 1, pb.topk, a.nchunks, a.CT,
-                       scale_log2e, pb.qsh, pb.kvsh, pb.kvst, grid, 8,
-                       static_cast<const int64_t*>(ranges));
+                       scale_log2e, pb.qsh, pb.kvsh, pb.kvst, grid, 8, ar);
   }
   if (hipGetLastError() != hipSuccess) return SL_ERR_LAUNCH;
   const int nrec = (pb.topk + 1) * a.nchunks;
