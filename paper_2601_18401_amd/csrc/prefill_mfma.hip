@@ -495,6 +495,9 @@ __device__ __forceinline__ void flash_tile(const FlashArgs& a, char* lds, const 
     stage(next.kv, next.kv_begin, kb, vb);
     load_q(next.q_off);
   }
+  // From here to the end of the tile the late group is the critical path (it still owes a PV):
+  // its wavefronts go first wherever both groups want an issue slot.
+  if (NG == 2 && grp == 1) __builtin_amdgcn_s_setprio(2);
   if (grp == 1) pv(ldsV + vb_prev * kStageElems);  // the late group's last PV
 
   // epilogue, wavefront-local (no workgroup barrier): normalise, stage the wavefront's 32 rows as
@@ -617,6 +620,7 @@ __device__ __forceinline__ void flash_tile(const FlashArgs& a, char* lds, const 
       }
     }
   }
+  __builtin_amdgcn_s_setprio(0);
   __builtin_amdgcn_wave_barrier();
   // No trailing barrier: a wavefront's output slice is private to it, and the K/V stages are
   // handed over through c.kb / c.vb.
