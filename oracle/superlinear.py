@@ -33,9 +33,16 @@ window, scale 1/sqrt(D) unless given; LSE is the natural-log sum of exp(logit) o
   nothing selected, attention over the window alone.  (The joint softmax above is what the
   task statement fixes for span-attention; the gate is the paper's own output rule.)
 
+* the paper's own geometry -- Section 3.3 with Fig. 3, Algorithm 1, for p = 1/root (root = 2, or
+  3 for the (1/3, 2/3) exponent split of Section 5): anchors t_s = i - (s+1)^root + 1, base span
+  length l(i) = ceil(i^(1-p)) in exact integer arithmetic, spans [t - b*l, min(i, t + f*l)],
+  window [i - w + 1, i] whose indices are removed from the candidates; search, span-attention
+  and combination per query row (anchor_* functions).  Ties go to the nearer anchor.
+
 Every function is pinned by tests that do not call it back: brute-force dense causal
-attention, brute-force argsort, closed forms, a library softmax with an explicit mask, and
-hand-derived values stored under tests/golden/.
+attention, brute-force argsort, closed forms, a library softmax with an explicit mask, the
+values the paper prints for its worked example and hand-derived values stored under
+tests/golden/.
 """
 from __future__ import annotations
 
