@@ -140,3 +140,34 @@ def test_paper_geometry_decode_at_1m():
         assert float(np.max(np.abs(On[h, 0] - o))) <= TOL[torch.bfloat16]
     del data, K, V
     torch.cuda.empty_cache()
+
+
+def test_paper_geometry_prefill_rows_of_the_256k_cache():
+    # the configuration bench.py times: the last rows of config 4's cache on the paper's geometry
+    # (window 1088, top-2, b = 4, f = 2), sampled rows against the oracle
+    cfg = W.CONFIGS["C4"]
+    data = W.generate(cfg, device=DEV)
+    K, V = data["K"], data["V"]
+    w, k, b, f, rows_n = 1088, 2, 4, 2, 512
+    p0 = cfg.L - rows_n
+    Q = data["Q"][:, p0:]
+    del data
+    G = cfg.Hq // cfg.Hkv
+    anchors, sc = B.sl_anchor_search_prefill(Q, K, k, w, q_pos0=p0, want_scores=True)
+    O = B.sl_anchor_attention_prefill(Q, K, V, anchors, sc, w, b, f, q_pos0=p0)
+    torch.cuda.synchronize()
+    an, scn, Qn, On = anchors.cpu().numpy(), sc.cpu().numpy().astype(np.float64), f64(Q), f64(O)
+    Kd, Vd = DevKV(K), DevKV(V)
+    for h in (0, 9, 31):
+        for r in (0, 1, 255, rows_n - 1):
+            i = p0 + r
+            _, t_o, _ = orc.anchor_search_row(Qn[h, r], DevRows(K[h // G]), i, w, k)
+            if an[h, r].tolist() != t_o:
+                cand = orc.anchor_candidates(i, w)
+                allsc = [float(f64(K[h // G, t]) @ Qn[h, r]) for _, t in cand]
+                assert orc.selection_margin(allsc, k) < 1e-3
+            o = orc.anchor_combined_row(Qn[h, r], Kd, Vd, h // G, i, w, b, f, an[h, r], scn[h, r],
+                                        1.0 / math.sqrt(cfg.D))
+            assert float(np.max(np.abs(On[h, r] - o))) <= TOL[torch.bfloat16], (h, r)
+    del K, V
+    torch.cuda.empty_cache()
