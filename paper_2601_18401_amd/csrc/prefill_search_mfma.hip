@@ -51,7 +51,9 @@ struct TopVals {
 //           (ties go to the lower index), and writes them in ascending span order.
 // Tracking values only makes the per-candidate cost of pass 1 k median instructions instead of
 // the compare-and-select chains that carrying the indices along would need.
-template <int KMAX>
+// WS: the scores of the selected spans are written too (their list costs LDS, which limits the
+// resident workgroups; most callers only want the indices).
+template <int KMAX, bool WS>
 __global__ __launch_bounds__(256) void prefill_search_mfma_kernel(
     const bf16_t* __restrict__ Qs, const bf16_t* __restrict__ K, const bf16_t* __restrict__ Ks,
     int32_t* __restrict__ idx, float* __restrict__ scores, int64_t Lq, int64_t q_pos0, int G, int S,
@@ -60,7 +62,7 @@ __global__ __launch_bounds__(256) void prefill_search_mfma_kernel(
   __shared__ __align__(16) bf16_t s_k[TNS * KSTR];
   __shared__ int s_cnt[TMQ];
   __shared__ int s_j[TMQ][CAP + 1];  // odd row stride: the lanes of a wavefront read their own rows
-  __shared__ float s_x[TMQ][CAP + 1];
+  __shared__ float s_x[WS ? TMQ : 1][CAP + 1];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int qc = lane & 31, hf = lane >> 5;
   const int col = wave * 32 + qc;
@@ -172,7 +174,7 @@ __global__ __launch_bounds__(256) void prefill_search_mfma_kernel(
       if (!eq || n_eq < need_eq) {
         const int pos = atomicAdd(&s_cnt[col], 1);
         s_j[col][pos] = eq ? (j | 0x40000000) : j;
-        s_x[col][pos] = x;
+        if (WS) s_x[col][pos] = x;
         n_eq += eq ? 1 : 0;
       }
     }
@@ -185,7 +187,7 @@ __global__ __launch_bounds__(256) void prefill_search_mfma_kernel(
   if (r < Lq) {
     const int cnt = s_cnt[col];
     int32_t* oi = idx + ((int64_t)h * Lq + r) * topk;
-    float* os = scores ? scores + ((int64_t)h * Lq + r) * topk : nullptr;
+    float* os = WS ? scores + ((int64_t)h * Lq + r) * topk : nullptr;
     for (int u = hf; u < cnt; u += 2) {
       const int eu = s_j[col][u], ju = eu & 0x3fffffff;
       int lower_gt = 0, lower_eq = 0;
@@ -198,13 +200,13 @@ __global__ __launch_bounds__(256) void prefill_search_mfma_kernel(
       if ((eu & 0x40000000) == 0 || lower_eq < need_eq) {
         const int rank = lower_gt + (lower_eq < need_eq ? lower_eq : need_eq);
         oi[rank] = ju;
-        if (os) os[rank] = s_x[col][u];
+        if (WS) os[rank] = s_x[col][u];
       }
     }
   }
   if (hf == 0 && r < Lq) {
     int32_t* oi = idx + ((int64_t)h * Lq + r) * topk;
-    float* os = scores ? scores + ((int64_t)h * Lq + r) * topk : nullptr;
+    float* os = WS ? scores + ((int64_t)h * Lq + r) * topk : nullptr;
     for (int e = kq; e < topk; ++e) {
       oi[e] = -1;
       if (os) os[e] = -INFINITY;
@@ -217,10 +219,16 @@ sl_status launch(const Problem& pb, const void* Qs, const void* K, const void* K
                  float* scores, hipStream_t st) {
   const int tiles_per_head = (int)((pb.Lq + TMQ - 1) / TMQ);
   if (pb.prof_start) (void)hipEventRecord(pb.prof_start, st);
-  hipLaunchKernelGGL((prefill_search_mfma_kernel<KMAX>), dim3(pb.Hq * tiles_per_head), dim3(256), 0,
-                     st, static_cast<const bf16_t*>(Qs), static_cast<const bf16_t*>(K),
-                     static_cast<const bf16_t*>(Ks), idx, scores, pb.Lq, pb.q_pos0, pb.G, pb.S,
-                     pb.topk, pb.n, pb.qsh, pb.qst, pb.kvsh, pb.kvst);
+  if (scores)
+    hipLaunchKernelGGL((prefill_search_mfma_kernel<KMAX, true>), dim3(pb.Hq * tiles_per_head), dim3(256),
+                       0, st, static_cast<const bf16_t*>(Qs), static_cast<const bf16_t*>(K),
+                       static_cast<const bf16_t*>(Ks), idx, scores, pb.Lq, pb.q_pos0, pb.G, pb.S,
+                       pb.topk, pb.n, pb.qsh, pb.qst, pb.kvsh, pb.kvst);
+  else
+    hipLaunchKernelGGL((prefill_search_mfma_kernel<KMAX, false>), dim3(pb.Hq * tiles_per_head), dim3(256),
+                       0, st, static_cast<const bf16_t*>(Qs), static_cast<const bf16_t*>(K),
+                       static_cast<const bf16_t*>(Ks), idx, scores, pb.Lq, pb.q_pos0, pb.G, pb.S,
+                       pb.topk, pb.n, pb.qsh, pb.qst, pb.kvsh, pb.kvst);
   if (pb.prof_stop) (void)hipEventRecord(pb.prof_stop, st);
   return hipGetLastError() == hipSuccess ? SL_OK : SL_ERR_LAUNCH;
 }
