@@ -204,6 +204,45 @@ def bench_decode(cfg, steps, warmup, torch, B, W):
                                    "achieved": sum(pbytes) / len(pbytes) / (pms * 1e-3) / 1e9,
                                    "peak": PEAK_HBM / 1e9, "unit": "GB/s",
                                    "frac": sum(pbytes) / len(pbytes) / (pms * 1e-3) / PEAK_HBM}}
+    # Batched decode: NB sequences with caches of their own (copies of the cache, cut to different
+    # lengths, each with a different query) advance one step in three launches.
+    esz = 2 if cfg.dtype == "bf16" else 4
+    NB = 8 if 8 * 2 * cfg.Hkv * cfg.L * cfg.D * esz <= 64e9 else 4
+    lens = [cfg.L - b * (cfg.S + 37) for b in range(NB)]
+    Kc = [K.clone()[:, :lens[b]] for b in range(NB)]
+    Vc = [V.clone()[:, :lens[b]] for b in range(NB)]
+    Ksc = [B.sl_span_keys(Kc[b], cfg.S) for b in range(NB)]
+    nrot = max(1, N_DECODE_QUERIES // NB)
+    batches = [B.DecodeBatch([Qs[(r * NB + b) % N_DECODE_QUERIES] for b in range(NB)],
+                             [Qs[(r * NB + b) % N_DECODE_QUERIES] for b in range(NB)], Kc, Vc, Ksc,
+                             cfg.S, cfg.topk) for r in range(nrot)]
+
+    def step_batched(r):
+        B.sl_span_search_decode_batched(batches[r])
+        B.sl_span_attention_decode_batched(batches[r], ws=ws)
+
+    bbytes = 0
+    for r in range(nrot):
+        step_batched(r)
+        torch.cuda.synchronize()
+        ix = batches[r].idx.cpu().numpy()
+        bbytes += sum(decode_bytes(cfg, ix[b], lens[b] - 1) for b in range(NB))
+    bgraph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(bgraph):
+        for r in range(nrot):
+            step_batched(r)
+    bgraph.replay()
+    torch.cuda.synchronize()
+    tc = time.perf_counter()
+    for _ in range(nrep):
+        bgraph.replay()
+    torch.cuda.synchronize()
+    dt_batched = (time.perf_counter() - tc) / (nrep * nrot)
+    batched = {"workload": f"{NB} sequences, caches of {lens[-1]}..{lens[0]} tokens, one query each",
+               "ms_per_step": dt_batched * 1e3, "value": NB / dt_batched, "unit": "sequence-steps/s",
+               "algorithmic_bytes": bbytes / nrot,
+               "step_hbm_frac": bbytes / nrot / dt_batched / PEAK_HBM}
+    del Kc, Vc, Ksc, batches, bgraph
     # Dominant kernel (K/V streaming + fused merge): a graph of N_DECODE_QUERIES back-to-back
     # span-attention launches, timed with HIP events on the launch stream.
     idx_dev = [torch.from_numpy(ix).to(dev) for ix in idxs]
@@ -243,6 +282,7 @@ def bench_decode(cfg, steps, warmup, torch, B, W):
         "ms_per_step": dt / steps * 1e3, "steps": steps, "dtype": cfg.dtype, "launch": "hip-graph replay",
         "combined_form": {"ms_per_step": dt_combined * 1e3, "value": 1.0 / dt_combined, "unit": "steps/s"},
         "paper_geometry": paper_geometry,
+        "batched_decode": batched,
         "roofline": {"bound": "hbm", "kernel": "decode_split_kernel", "achieved": achieved / 1e9, "peak": PEAK_HBM / 1e9,
                      "unit": "GB/s", "frac": achieved / PEAK_HBM, "traffic": MEASURED_TRAFFIC.get(cfg.name),
                      "kernel_ms": kms_avg, "kernel_ms_min": min(kms), "algorithmic_bytes": sum(kbytes) / len(kbytes),

@@ -222,6 +222,40 @@ sl_status sl_anchor_attention_prefill(const sl_params* p, const sl_anchor_geomet
                                       const void* K, const void* V, const int32_t* anchors,
                                       const float* scores, void* O, void* hip_stream);
 
+/* ---- Batched decode: one step for B independent sequences in three launches (Section 4.3's
+ * decoding path serves a batch of sequences; the grid gains a sequence dimension).  Every
+ * sequence b has its own cache of seq[b].L tokens (its query sits at position L - 1) and its own
+ * tensors; heads, D, S, topk, dtype, scale and the element strides are common and come from p
+ * (p->L must be the largest L of the batch, p->Lq = 1, p->q_pos0 = p->L - 1; a head stride given
+ * as 0 means "packed for this sequence's own L").  `seqs` is an array of B records in DEVICE
+ * memory, read by the kernels: its contents cannot be validated by the host, so every pointer in
+ * it must be valid and 16-byte aligned and 1 <= L <= p->L must hold -- that is the caller's
+ * responsibility.  Joint softmax form only. */
+typedef struct sl_decode_seq {
+  const void* Qs;  /* search query   [Hq][1][D]                                   */
+  const void* Q;   /* attention query [Hq][1][D]                                  */
+  const void* K;   /* [Hkv][L][D]                                                 */
+  const void* V;   /* [Hkv][L][D]                                                 */
+  const void* Ks;  /* packed span keys [Hkv][ceil(L/S)][D], or NULL (keys from K) */
+  int32_t* idx;    /* out (search) / in (attention): [Hq][1][topk]                */
+  float* scores;   /* out, optional: [Hq][1][topk]                                */
+  void* O;         /* out: [Hq][1][D]                                             */
+  float* LSE;      /* out: [Hq][1]                                                */
+  int64_t L;       /* tokens in this sequence's cache, current token included     */
+} sl_decode_seq;
+
+/* Scratch bytes of sl_span_attention_decode_batched for B sequences (0 if invalid). */
+size_t sl_decode_batched_workspace_bytes(const sl_params* p, int32_t B);
+
+/* sl_span_search_decode for every sequence of the batch: fills seq[b].idx (and scores).
+ * At most 4096 candidate spans per sequence ((p->L - 1) / S <= 4096). */
+sl_status sl_span_search_decode_batched(const sl_params* p, const sl_decode_seq* seqs, int32_t B,
+                                        void* hip_stream);
+
+/* sl_span_attention_decode for every sequence of the batch on seq[b].idx: fills seq[b].O, LSE. */
+sl_status sl_span_attention_decode_batched(const sl_params* p, const sl_decode_seq* seqs, int32_t B,
+                                           void* ws, size_t ws_bytes, void* hip_stream);
+
 /* Static, human-readable name of a status code. */
 const char* sl_status_string(int status);
 

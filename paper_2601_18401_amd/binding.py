@@ -24,13 +24,21 @@ EXPORTS = ("sl_workspace_bytes", "sl_span_keys", "sl_span_search_prefill", "sl_s
            "sl_span_attention_prefill", "sl_span_attention_decode", "sl_span_attention_combined_prefill",
            "sl_span_attention_combined_decode", "sl_anchor_workspace_bytes", "sl_anchor_search_decode",
            "sl_anchor_attention_decode", "sl_anchor_search_prefill", "sl_anchor_attention_prefill",
-           "sl_status_string", "sl_version")
+           "sl_decode_batched_workspace_bytes", "sl_span_search_decode_batched",
+           "sl_span_attention_decode_batched", "sl_status_string", "sl_version")
 
 
 class SlAnchorGeometry(ctypes.Structure):
     _fields_ = [("window", ctypes.c_int64), ("backward_factor", ctypes.c_int32),
                 ("forward_factor", ctypes.c_int32), ("search_root", ctypes.c_int32),
                 ("reserved", ctypes.c_int32)]
+
+
+class SlDecodeSeq(ctypes.Structure):
+    _fields_ = [("Qs", ctypes.c_void_p), ("Q", ctypes.c_void_p), ("K", ctypes.c_void_p),
+                ("V", ctypes.c_void_p), ("Ks", ctypes.c_void_p), ("idx", ctypes.c_void_p),
+                ("scores", ctypes.c_void_p), ("O", ctypes.c_void_p), ("LSE", ctypes.c_void_p),
+                ("L", ctypes.c_int64)]
 
 
 class SlParams(ctypes.Structure):
@@ -93,6 +101,12 @@ def load():
     lib.sl_anchor_search_prefill.argtypes = [pp, gp, vp, vp, i32p, f32p, vp]
     lib.sl_anchor_attention_prefill.restype = ctypes.c_int
     lib.sl_anchor_attention_prefill.argtypes = [pp, gp, vp, vp, vp, i32p, f32p, vp, vp]
+    lib.sl_decode_batched_workspace_bytes.restype = ctypes.c_size_t
+    lib.sl_decode_batched_workspace_bytes.argtypes = [pp, ctypes.c_int32]
+    lib.sl_span_search_decode_batched.restype = ctypes.c_int
+    lib.sl_span_search_decode_batched.argtypes = [pp, vp, ctypes.c_int32, vp]
+    lib.sl_span_attention_decode_batched.restype = ctypes.c_int
+    lib.sl_span_attention_decode_batched.argtypes = [pp, vp, ctypes.c_int32, vp, ctypes.c_size_t, vp]
     lib.sl_status_string.restype = ctypes.c_char_p
     lib.sl_status_string.argtypes = [ctypes.c_int]
     lib.sl_version.restype = ctypes.c_int
@@ -331,3 +345,73 @@ def sl_span_attention_decode(Q, K, V, idx, S, q_pos0=None, scale=0.0, ws=None, p
     q_pos0 = K.shape[1] - 1 if q_pos0 is None else q_pos0
     return _attention("sl_span_attention_decode", OP_ATTENTION_DECODE, Q, K, V, idx, S, q_pos0,
                       scale, ws, prof, out)
+
+
+class DecodeBatch:
+    """The device array of sl_decode_seq records for B sequences, and the tensors it points at.
+
+    Qs, Q: lists of [Hq, 1, D]; K, V: lists of [Hkv, L_b, D] (V with K's strides); Ks: list of packed
+    span keys [Hkv, ceil(L_b / S), D] or None.  idx / scores / O / LSE are allocated here and filled
+    by the two batched calls.  The kv head stride is passed to the library when every sequence has
+    the same one (caches cut from one [B, Hkv, Lmax, D] buffer); otherwise every cache must be
+    contiguous and the library takes L_b * D."""
+
+    def __init__(self, Qs, Q, K, V, Ks, S, topk, want_scores=False):
+        B = len(Q)
+        if not (len(Qs) == len(K) == len(V) == B) or (Ks is not None and len(Ks) != B) or B < 1:
+            raise ValueError("one Qs, Q, K, V (and Ks) per sequence")
+        dev, Hq, D = Q[0].device, Q[0].shape[0], Q[0].shape[2]
+        self.B, self.S, self.topk = B, int(S), int(topk)
+        self.tensors = (Qs, Q, K, V, Ks)  # kept alive: the records hold raw pointers
+        self.idx = torch.empty((B, Hq, 1, topk), dtype=torch.int32, device=dev)
+        self.scores = torch.empty((B, Hq, 1, topk), dtype=torch.float32, device=dev) if want_scores else None
+        self.O = torch.empty((B, Hq, 1, D), dtype=Q[0].dtype, device=dev)
+        self.LSE = torch.empty((B, Hq, 1), dtype=torch.float32, device=dev)
+        self.longest = max(range(B), key=lambda b: K[b].shape[1])
+        same = all(k.stride(0) == K[0].stride(0) for k in K)
+        recs = (SlDecodeSeq * B)()
+        for b in range(B):
+            if (Q[b].shape != Q[0].shape or Qs[b].shape != Q[0].shape or Q[b].stride() != Q[0].stride()
+                    or Qs[b].stride() != Q[0].stride() or Q[b].dtype != Q[0].dtype or K[b].dtype != Q[0].dtype):
+                raise ValueError("queries of a batch share shape, strides and dtype")
+            if (K[b].shape[0] != K[0].shape[0] or K[b].shape[2] != D or V[b].shape != K[b].shape
+                    or V[b].stride() != K[b].stride() or K[b].stride(1) != K[0].stride(1) or K[b].stride(2) != 1):
+                raise ValueError("caches of a batch share heads, D and the token stride; V has K's strides")
+            if not same and not K[b].is_contiguous():
+                raise ValueError("caches with different head strides must each be contiguous")
+            Lb = K[b].shape[1]
+            if Ks is not None and (tuple(Ks[b].shape) != (K[b].shape[0], -(-Lb // self.S), D)
+                                   or not Ks[b].is_contiguous()):
+                raise ValueError("Ks[b] must be contiguous [Hkv, ceil(L_b / S), D]")
+            r = recs[b]
+            r.Qs, r.Q, r.K, r.V = Qs[b].data_ptr(), Q[b].data_ptr(), K[b].data_ptr(), V[b].data_ptr()
+            r.Ks = Ks[b].data_ptr() if Ks is not None else None
+            r.idx = self.idx[b].data_ptr()
+            r.scores = self.scores[b].data_ptr() if want_scores else None
+            r.O, r.LSE, r.L = self.O[b].data_ptr(), self.LSE[b].data_ptr(), Lb
+        host = torch.frombuffer(bytearray(bytes(recs)), dtype=torch.int64).clone()
+        self.records = host.to(dev)
+        m = self.longest
+        self.params = make_params(Q[m], K[m], S, topk, K[m].shape[1] - 1)
+        if not same:
+            self.params.kv_stride_h = 0
+
+
+def sl_span_search_decode_batched(batch: DecodeBatch):
+    """Fills batch.idx (and batch.scores) for every sequence; returns them."""
+    st = load().sl_span_search_decode_batched(ctypes.byref(batch.params), _ptr(batch.records), batch.B,
+                                              _stream())
+    _check(st, "sl_span_search_decode_batched")
+    return (batch.idx, batch.scores) if batch.scores is not None else batch.idx
+
+
+def sl_span_attention_decode_batched(batch: DecodeBatch, scale=0.0, ws=None):
+    """Joint span-attention of every sequence on batch.idx; returns (batch.O, batch.LSE)."""
+    lib = load()
+    batch.params.scale = float(scale)
+    need = lib.sl_decode_batched_workspace_bytes(ctypes.byref(batch.params), batch.B)
+    wptr, wbytes = _ws(ws).get(need)
+    st = lib.sl_span_attention_decode_batched(ctypes.byref(batch.params), _ptr(batch.records), batch.B,
+                                              wptr, wbytes, _stream())
+    _check(st, "sl_span_attention_decode_batched")
+    return batch.O, batch.LSE

@@ -53,6 +53,7 @@ sl_status make_problem(const sl_params* p, int op, Problem* pb) {
   pb->qsh = qsh;
   pb->qst = qst;
   pb->kvsh = kvsh;
+  pb->kvsh_given = p->kv_stride_h != 0;
   pb->kvst = kvst;
   pb->n = (p->L + p->S - 1) / p->S;
   const bool prof = p->prof_start && p->prof_stop;
@@ -267,6 +268,32 @@ sl_status sl_anchor_attention_prefill(const sl_params* p, const sl_anchor_geomet
   pb.gate = scores;
   return sl::anchor_attention_prefill(pb, g->window, g->backward_factor, g->forward_factor, root, Q, K,
                                       V, anchors, O, static_cast<hipStream_t>(hip_stream));
+}
+
+size_t sl_decode_batched_workspace_bytes(const sl_params* p, int32_t B) {
+  sl::Problem pb;
+  if (B < 1 || sl::make_problem(p, SL_OP_ATTENTION_DECODE, &pb) != SL_OK) return 0;
+  return sl::decode_attention_batched_ws_bytes(pb, B);
+}
+
+sl_status sl_span_search_decode_batched(const sl_params* p, const sl_decode_seq* seqs, int32_t B,
+                                        void* hip_stream) {
+  sl::Problem pb;
+  sl_status s = sl::make_problem(p, SL_OP_SEARCH_DECODE, &pb);
+  if (s != SL_OK) return s;
+  if (!seqs || B < 1 || B > 65535 || (reinterpret_cast<uintptr_t>(seqs) & 7u)) return SL_ERR_INVALID_ARG;
+  return sl::decode_search_batched(pb, seqs, B, static_cast<hipStream_t>(hip_stream));
+}
+
+sl_status sl_span_attention_decode_batched(const sl_params* p, const sl_decode_seq* seqs, int32_t B,
+                                           void* ws, size_t ws_bytes, void* hip_stream) {
+  sl::Problem pb;
+  sl_status s = sl::make_problem(p, SL_OP_ATTENTION_DECODE, &pb);
+  if (s != SL_OK) return s;
+  if (!seqs || B < 1 || B > 65535 || (reinterpret_cast<uintptr_t>(seqs) & 7u)) return SL_ERR_INVALID_ARG;
+  const size_t need = sl::decode_attention_batched_ws_bytes(pb, B);
+  if (!ws || ws_bytes < need || (reinterpret_cast<uintptr_t>(ws) & 255u)) return SL_ERR_WORKSPACE;
+  return sl::decode_attention_batched(pb, seqs, B, ws, static_cast<hipStream_t>(hip_stream));
 }
 
 const char* sl_status_string(int status) {

@@ -25,7 +25,7 @@ struct AnchorRanges {
 
 // Partial record of one (head, slot, chunk): o[D] (unnormalised, relative to m), m (log2 units), l.
 template <typename T, int D>
-__global__ __launch_bounds__(kDecodeThreads) void decode_split_kernel(
+__device__ __forceinline__ void decode_split_body(
     const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
     const int32_t* __restrict__ idx, float* __restrict__ part, int64_t q_pos, int Hq, int Hkv,
     int S, int topk, int nchunks, int CT, float scale_log2e, int64_t qsh, int64_t kvsh,
@@ -157,6 +157,31 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_split_kernel(
   }
 }
 
+template <typename T, int D>
+__global__ __launch_bounds__(kDecodeThreads) void decode_split_kernel(
+    const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
+    const int32_t* __restrict__ idx, float* __restrict__ part, int64_t q_pos, int Hq, int Hkv,
+    int S, int topk, int nchunks, int CT, float scale_log2e, int64_t qsh, int64_t kvsh,
+    int64_t kvst, int n_routed_blocks, int local_stride, const AnchorRanges ar) {
+  decode_split_body<T, D>(Q, K, V, idx, part, q_pos, Hq, Hkv, S, topk, nchunks, CT, scale_log2e, qsh,
+                          kvsh, kvst, n_routed_blocks, local_stride, ar);
+}
+
+// Batched decode: blockIdx.y is the sequence; its tensors and length come from the device array.
+// kvsh = 0: the cache of every sequence is packed for its own length.
+template <typename T, int D>
+__global__ __launch_bounds__(kDecodeThreads) void decode_split_batched_kernel(
+    const sl_decode_seq* __restrict__ seqs, float* __restrict__ part, int64_t part_stride, int Hq,
+    int Hkv, int S, int topk, int nchunks, int CT, float scale_log2e, int64_t qsh, int64_t kvsh,
+    int64_t kvst, int n_routed_blocks, int local_stride) {
+  const sl_decode_seq sq = seqs[blockIdx.y];
+  decode_split_body<T, D>(static_cast<const T*>(sq.Q), static_cast<const T*>(sq.K),
+                          static_cast<const T*>(sq.V), sq.idx, part + blockIdx.y * part_stride,
+                          sq.L - 1, Hq, Hkv, S, topk, nchunks, CT, scale_log2e, qsh,
+                          kvsh ? kvsh : sq.L * kvst, kvst, n_routed_blocks, local_stride,
+                          AnchorRanges{false, 0, 0, 0});
+}
+
 // Merges the (topk + 1) * nchunks partial records of a head.  grid (Hq, D / 32): each workgroup
 // produces 32 output dims; its 256 threads are 8 record subsets x 32 dims.  All record loads of a
 // thread are issued before the first dependent use, so the kernel costs about two memory round
@@ -166,9 +191,8 @@ constexpr int kReduceSub = 256 / kReduceDims;
 constexpr int kReduceBatch = 16;  // records per thread held in registers at a time
 
 template <typename T, int D>
-__global__ __launch_bounds__(256) void decode_reduce_kernel(const float* __restrict__ part,
-                                                            T* __restrict__ O,
-                                                            float* __restrict__ LSE, int nrec) {
+__device__ __forceinline__ void decode_reduce_body(const float* __restrict__ part, T* __restrict__ O,
+                                                   float* __restrict__ LSE, int nrec) {
   extern __shared__ float s_w[];  // nrec weights
   __shared__ float s_red[4];
   __shared__ float s_acc[256];
@@ -244,6 +268,21 @@ __global__ __launch_bounds__(256) void decode_reduce_kernel(const float* __restr
     Elem<T>::store1(O + (int64_t)h * D + d0 + tid, tot / lt);
     if (tid == 0 && blockIdx.y == 0) LSE[h] = (M + __log2f(lt)) * kLn2;
   }
+}
+
+template <typename T, int D>
+__global__ __launch_bounds__(256) void decode_reduce_kernel(const float* __restrict__ part,
+                                                            T* __restrict__ O,
+                                                            float* __restrict__ LSE, int nrec) {
+  decode_reduce_body<T, D>(part, O, LSE, nrec);
+}
+
+// Batched decode: blockIdx.z is the sequence.
+template <typename T, int D>
+__global__ __launch_bounds__(256) void decode_reduce_batched_kernel(
+    const sl_decode_seq* __restrict__ seqs, const float* __restrict__ part, int64_t part_stride, int nrec) {
+  const sl_decode_seq sq = seqs[blockIdx.z];
+  decode_reduce_body<T, D>(part + blockIdx.z * part_stride, static_cast<T*>(sq.O), sq.LSE, nrec);
 }
 
 
@@ -369,10 +408,10 @@ __global__ __launch_bounds__(256) void decode_reduce_combined_kernel(const float
   }
 }
 
-int pick_chunk_tokens(const Problem& pb) {
+int pick_chunk_tokens(const Problem& pb, int batch = 1) {
   // Aim for a few thousand workgroups so the 256 CUs keep enough loads in flight, without
   // going below 64 tokens per item.
-  const int64_t units = (int64_t)pb.Hq * (pb.topk + 1);
+  const int64_t units = (int64_t)batch * pb.Hq * (pb.topk + 1);
   int ct = 512;
   while (ct > 64 && units * ((pb.S + ct - 1) / ct) < 4096) ct >>= 1;
   return ct;
@@ -476,7 +515,45 @@ sl_status launch_anchor_attention(const Problem& pb, const AnchorPlan& a, const 
   return hipGetLastError() == hipSuccess ? SL_OK : SL_ERR_LAUNCH;
 }
 
+template <typename T, int D>
+sl_status launch_decode_batched(const Problem& pb, const sl_decode_seq* seqs, int B, void* ws,
+                                hipStream_t st) {
+  const int CT = pick_chunk_tokens(pb, B);
+  const int nchunks = (pb.S + CT - 1) / CT;
+  const int nrec = (pb.topk + 1) * nchunks;
+  const int64_t part_stride = (int64_t)pb.Hq * nrec * (D + 2);
+  float* part = static_cast<float*>(ws);
+  // same grid as the single-sequence launch in x, the sequence in y
+  const int n_routed = pb.Hq * pb.topk * nchunks;
+  const int local_stride = (int)align_up((size_t)pb.Hkv * nchunks, 8);
+  const int grid = n_routed + pb.G * local_stride;
+  hipLaunchKernelGGL((decode_split_batched_kernel<T, D>), dim3(grid, B), dim3(kDecodeThreads), 0, st,
+                     seqs, part, part_stride, pb.Hq, pb.Hkv, pb.S, pb.topk, nchunks, CT,
+                     pb.scale * kLog2e, pb.qsh, pb.kvsh_given ? pb.kvsh : (int64_t)0, pb.kvst, n_routed,
+                     local_stride);
+  if (hipGetLastError() != hipSuccess) return SL_ERR_LAUNCH;
+  hipLaunchKernelGGL((decode_reduce_batched_kernel<T, D>), dim3(pb.Hq, D / kReduceDims, B), dim3(256),
+                     (size_t)nrec * sizeof(float), st, seqs, part, part_stride, nrec);
+  return hipGetLastError() == hipSuccess ? SL_OK : SL_ERR_LAUNCH;
+}
+
 }  // namespace
+
+size_t decode_attention_batched_ws_bytes(const Problem& pb, int B) {
+  const int CT = pick_chunk_tokens(pb, B);
+  const int nchunks = (pb.S + CT - 1) / CT;
+  return (size_t)B * pb.Hq * (pb.topk + 1) * nchunks * (pb.D + 2) * sizeof(float);
+}
+
+sl_status decode_attention_batched(const Problem& pb, const sl_decode_seq* seqs, int B, void* ws,
+                                   hipStream_t st) {
+  if (pb.dtype == SL_BF16) {
+    if (pb.D == 128) return launch_decode_batched<bf16_t, 128>(pb, seqs, B, ws, st);
+    return launch_decode_batched<bf16_t, 64>(pb, seqs, B, ws, st);
+  }
+  if (pb.D == 128) return launch_decode_batched<float, 128>(pb, seqs, B, ws, st);
+  return launch_decode_batched<float, 64>(pb, seqs, B, ws, st);
+}
 
 size_t decode_attention_ws_bytes(const Problem& pb) {
   const int CT = pick_chunk_tokens(pb);

@@ -18,6 +18,13 @@ size_t decode_attention_ws_bytes(const Problem& pb);
 sl_status decode_attention(const Problem& pb, const void* Q, const void* K, const void* V,
                            const int32_t* idx, void* O, float* LSE, void* ws, hipStream_t st);
 
+// a7 .. a9 for a batch of sequences (one more grid dimension; tensors and lengths per sequence
+// come from a device array)
+sl_status decode_search_batched(const Problem& pb, const sl_decode_seq* seqs, int B, hipStream_t st);
+size_t decode_attention_batched_ws_bytes(const Problem& pb, int B);
+sl_status decode_attention_batched(const Problem& pb, const sl_decode_seq* seqs, int B, void* ws,
+                                   hipStream_t st);
+
 // The paper's own geometry, decode form (Section 3.3, Algorithm 1): anchors on the quadratic
 // stride pattern, spans of b*l(i) / f*l(i) tokens around the selected anchors, window w.
 // root = 1/p: 2 (anchors i-(s+1)^2+1, l = ceil(sqrt(i))) or 3 (anchors i-(s+1)^3+1, l = ceil(i^(2/3))).

@@ -97,7 +97,7 @@ __global__ __launch_bounds__(kDecodeSearchThreads) void decode_search_kernel(
 //      reach k (ties to the lower index); the output slot of a selected candidate is the number
 //      of selected candidates below it, from one block-wide prefix sum of (count > T, count == T).
 template <typename T, int D, int RMAX>
-__global__ __launch_bounds__(kDecodeSearchThreads) void decode_search_block_kernel(
+__device__ __forceinline__ void decode_search_block_body(
     const T* __restrict__ Qs, const T* __restrict__ K, const T* __restrict__ Ks,
     int32_t* __restrict__ idx, float* __restrict__ scores, int64_t c, int64_t n, int G, int S,
     int topk, int64_t qsh, int64_t kvsh, int64_t kvst, int64_t anchor_i, int anchor_s0,
@@ -234,6 +234,29 @@ __global__ __launch_bounds__(kDecodeSearchThreads) void decode_search_block_kern
     oi[tid] = -1;
     if (os) os[tid] = -INFINITY;
   }
+}
+
+template <typename T, int D, int RMAX>
+__global__ __launch_bounds__(kDecodeSearchThreads) void decode_search_block_kernel(
+    const T* __restrict__ Qs, const T* __restrict__ K, const T* __restrict__ Ks,
+    int32_t* __restrict__ idx, float* __restrict__ scores, int64_t c, int64_t n, int G, int S,
+    int topk, int64_t qsh, int64_t kvsh, int64_t kvst, int64_t anchor_i, int anchor_s0,
+    int anchor_root) {
+  decode_search_block_body<T, D, RMAX>(Qs, K, Ks, idx, scores, c, n, G, S, topk, qsh, kvsh, kvst,
+                                       anchor_i, anchor_s0, anchor_root);
+}
+
+// Batched decode: blockIdx.y is the sequence; candidates c = (L - 1) / S and the span-key row count
+// n = ceil(L / S) follow from its own length.  kvsh = 0: the cache is packed for its own length.
+template <typename T, int D, int RMAX>
+__global__ __launch_bounds__(kDecodeSearchThreads) void decode_search_block_batched_kernel(
+    const sl_decode_seq* __restrict__ seqs, int G, int S, int topk, int64_t qsh, int64_t kvsh,
+    int64_t kvst) {
+  const sl_decode_seq sq = seqs[blockIdx.y];
+  decode_search_block_body<T, D, RMAX>(static_cast<const T*>(sq.Qs), static_cast<const T*>(sq.K),
+                                       static_cast<const T*>(sq.Ks), sq.idx, sq.scores, (sq.L - 1) / S,
+                                       (sq.L + S - 1) / S, G, S, topk, qsh, kvsh ? kvsh : sq.L * kvst,
+                                       kvst, (int64_t)-1, 0, 2);
 }
 
 // ------------------------------------------------------------------ a1 + a2: prefill, row-stationary
@@ -383,6 +406,22 @@ sl_status launch_decode_search(const Problem& pb, const void* Qs, const void* K,
 }
 
 template <typename T, int D>
+sl_status launch_decode_search_batched(const Problem& pb, const sl_decode_seq* seqs, int B,
+                                       hipStream_t st) {
+  const int64_t c_max = pb.q_pos0 / pb.S;  // of the longest sequence
+  const int64_t kvsh = pb.kvsh_given ? pb.kvsh : 0;
+  if (c_max <= kDecodeSearchThreads)
+    hipLaunchKernelGGL((decode_search_block_batched_kernel<T, D, 1>), dim3(pb.Hq, B),
+                       dim3(kDecodeSearchThreads), 0, st, seqs, pb.G, pb.S, pb.topk, pb.qsh, kvsh,
+                       pb.kvst);
+  else
+    hipLaunchKernelGGL((decode_search_block_batched_kernel<T, D, 4>), dim3(pb.Hq, B),
+                       dim3(kDecodeSearchThreads), 0, st, seqs, pb.G, pb.S, pb.topk, pb.qsh, kvsh,
+                       pb.kvst);
+  return hipGetLastError() == hipSuccess ? SL_OK : SL_ERR_LAUNCH;
+}
+
+template <typename T, int D>
 sl_status launch_anchor_search(const Problem& pb, const void* Qs, const void* K, int32_t* anchors,
                                float* scores, int64_t c, int s0, int root, hipStream_t st) {
   if (pb.prof_start) (void)hipEventRecord(pb.prof_start, st);
@@ -488,6 +527,11 @@ sl_status anchor_search_prefill(const Problem& pb, int64_t window, int root, con
   anchor_candidates(last, window, root, &c_max, &s0);
   if (c_max > kMaxSpansLds) return SL_ERR_UNSUPPORTED;
   SL_DISPATCH(launch_anchor_search_rows, pb, Qs, K, anchors, scores, c_max, s0, root, st);
+}
+
+sl_status decode_search_batched(const Problem& pb, const sl_decode_seq* seqs, int B, hipStream_t st) {
+  if (pb.q_pos0 / pb.S > (int64_t)kDecodeSearchThreads * 4) return SL_ERR_UNSUPPORTED;
+  SL_DISPATCH(launch_decode_search_batched, pb, seqs, B, st);
 }
 
 sl_status decode_search(const Problem& pb, const void* Qs, const void* K, const void* Ks,

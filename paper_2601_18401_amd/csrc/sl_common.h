@@ -17,6 +17,7 @@ struct Problem {
   int dtype;
   float scale;  // resolved softmax scale
   int64_t qsh, qst, kvsh, kvst;
+  bool kvsh_given;  // the caller gave a kv head stride (else kvsh = L * kvst: packed)
   int64_t n;  // ceil(L / S)
   hipEvent_t prof_start, prof_stop;
   // Combination (Section 3.4) instead of one joint softmax over the selected spans and the

@@ -285,6 +285,55 @@ def test_decode_small(seed, Hq, Hkv, L, D, S, k, dtype):
     check_attention(Op, LSEp, Q, K, V, idx_o, S, L - 1, 0.0)
 
 
+DECODE_BATCHED = [
+    # seed Hq Hkv D    S    k   dtype           lengths                      shared-buffer caches, span keys given
+    (1, 32, 4, 128, 256, 16, torch.bfloat16, [65536, 1000, 30000, 257], False, True),
+    (2, 4, 4, 64, 64, 4, torch.float32, [4096, 40, 1, 3000, 64], True, False),
+    (3, 8, 2, 128, 64, 8, torch.bfloat16, [64 * 700, 64 * 300 + 5], False, False),   # > 256 candidates
+    (4, 8, 1, 128, 96, 6, torch.bfloat16, [5000], True, True),                       # batch of one
+]
+
+
+@pytest.mark.parametrize("seed,Hq,Hkv,D,S,k,dtype,lengths,shared,with_ks", DECODE_BATCHED)
+def test_decode_batched(seed, Hq, Hkv, D, S, k, dtype, lengths, shared, with_ks):
+    """One batched call per step against the single-sequence entry points and the oracle."""
+    nb, Lmax = len(lengths), max(lengths)
+    Qs, Ksrc, Vsrc = [], [], []
+    if shared:   # every cache is the head of a slot of one [B, Hkv, Lmax, D] buffer: common head stride
+        Kbuf = torch.zeros((nb, Hkv, Lmax, D), dtype=dtype, device=DEV)
+        Vbuf = torch.zeros_like(Kbuf)
+    for b, Lb in enumerate(lengths):
+        Q, K, V = make(seed * 100 + b, Hq, Hkv, Lb, D, dtype, Lq=1)
+        if shared:
+            Kbuf[b, :, :Lb] = K
+            Vbuf[b, :, :Lb] = V
+            K, V = Kbuf[b, :, :Lb], Vbuf[b, :, :Lb]
+        Qs.append(Q), Ksrc.append(K), Vsrc.append(V)
+    Kss = [B.sl_span_keys(K, S) for K in Ksrc]
+    batch = B.DecodeBatch(Qs, Qs, Ksrc, Vsrc, Kss if with_ks else None, S, k, want_scores=True)
+    idx, sc = B.sl_span_search_decode_batched(batch)
+    O, LSE = B.sl_span_attention_decode_batched(batch)
+    torch.cuda.synchronize()
+    for b, Lb in enumerate(lengths):
+        idx1, sc1 = B.sl_span_search_decode(Qs[b], Ksrc[b], Kss[b], S, k, want_scores=True)
+        torch.cuda.synchronize()
+        assert torch.equal(idx[b], idx1), f"sequence {b}"
+        assert torch.equal(sc[b], sc1), f"sequence {b}"
+        check_idx(idx[b], Qs[b], Kss[b], S, k, Lb - 1)
+        check_attention(O[b], LSE[b], Qs[b], Ksrc[b].contiguous(), Vsrc[b].contiguous(), idx[b], S, Lb - 1, 0.0)
+
+
+def test_decode_batched_rejects_what_it_cannot_serve():
+    Hq, Hkv, D, S, k = 4, 2, 64, 16, 4
+    Q, K, V = make(5, Hq, Hkv, 16 * 5000, D, torch.bfloat16, Lq=1)
+    batch = B.DecodeBatch([Q], [Q], [K], [V], None, S, k)
+    with pytest.raises(B.SlError):                     # more than 4096 candidate spans
+        B.sl_span_search_decode_batched(batch)
+    batch.B = 0
+    with pytest.raises(B.SlError):
+        B.sl_span_attention_decode_batched(batch)
+
+
 def test_decode_mid_cache_position_and_garbage_idx():
     Hq, Hkv, L, D, S, k = 8, 2, 16384, 128, 128, 8
     Q, K, V = make(21, Hq, Hkv, L, D, torch.bfloat16, Lq=1)
