@@ -230,7 +230,7 @@ sl_status sl_anchor_attention_prefill(const sl_params* p, const sl_anchor_geomet
  * as 0 means "packed for this sequence's own L").  `seqs` is an array of B records in DEVICE
  * memory, read by the kernels: its contents cannot be validated by the host, so every pointer in
  * it must be valid and 16-byte aligned and 1 <= L <= p->L must hold -- that is the caller's
- * responsibility.  Joint softmax form only. */
+ * responsibility.  Joint softmax form only; p->prof_start / prof_stop are not recorded. */
 typedef struct sl_decode_seq {
   const void* Qs;  /* search query   [Hq][1][D]                                   */
   const void* Q;   /* attention query [Hq][1][D]                                  */

@@ -102,6 +102,25 @@ def test_workspace_checks():
     assert lib.sl_workspace_bytes(ctypes.byref(p), B.OP_SEARCH_DECODE) == 0   # scores stay in LDS
 
 
+def test_batched_decode_argument_checks():
+    lib = B.load()
+    assert ctypes.sizeof(B.SlDecodeSeq) == 80          # 9 pointers + int64
+    p = good(Lq=1, q_pos0=4095)
+    need = lib.sl_decode_batched_workspace_bytes(ctypes.byref(p), 3)
+    assert need > 0 and need % 3 == 0
+    assert lib.sl_decode_batched_workspace_bytes(ctypes.byref(p), 0) == 0
+    assert lib.sl_decode_batched_workspace_bytes(ctypes.byref(good()), 3) == 0     # Lq != 1
+    assert lib.sl_span_search_decode_batched(ctypes.byref(p), None, 3, None) == 1
+    assert lib.sl_span_search_decode_batched(ctypes.byref(p), FAKE, 0, None) == 1
+    assert lib.sl_span_search_decode_batched(ctypes.byref(p), ctypes.c_void_p(0x1004), 3, None) == 1
+    assert lib.sl_span_search_decode_batched(ctypes.byref(good()), FAKE, 3, None) == 1
+    big = good(L=64 * 5000, Lq=1, q_pos0=64 * 5000 - 1)                              # > 4096 candidates
+    assert lib.sl_span_search_decode_batched(ctypes.byref(big), FAKE, 3, None) == 2
+    assert lib.sl_span_attention_decode_batched(ctypes.byref(p), FAKE, 3, None, 0, None) == 3
+    assert lib.sl_span_attention_decode_batched(ctypes.byref(p), FAKE, 3, FAKE_WS, need - 1, None) == 3
+    assert lib.sl_span_attention_decode_batched(ctypes.byref(p), FAKE, 0, FAKE_WS, need, None) == 1
+
+
 def test_binding_fails_loudly_without_library(monkeypatch, tmp_path):
     monkeypatch.setattr(B, "_lib", None)
     monkeypatch.setattr(B, "LIB_PATH", str(tmp_path / "missing.so"))
