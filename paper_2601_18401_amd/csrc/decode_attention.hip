@@ -125,7 +125,12 @@ __device__ __forceinline__ void decode_split_body(
   int64_t w1 = w0 + per_wave < t1 ? w0 + per_wave : t1;
   AttendState<T, D> st;
   st.init();
-  attend_range<T, D, 8>(q2, Kb, Vb, kvst, w0, w1, lane, st);
+  // A selected span is read by few heads and once; the window is read by all G heads of its kv
+  // head and stays cacheable.
+  if (slot != topk)
+    attend_range<T, D, 8, true>(q2, Kb, Vb, kvst, w0, w1, lane, st);
+  else
+    attend_range<T, D, 8, false>(q2, Kb, Vb, kvst, w0, w1, lane, st);
 
   const int gi = wave * RPW + g;
 #pragma unroll

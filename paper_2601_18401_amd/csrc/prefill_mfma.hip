@@ -615,8 +615,10 @@ __device__ __forceinline__ void flash_tile(const FlashArgs& a, char* lds, const 
     for (int u = 0; u < 8; ++u) {
       const int piece = lane & 15;
       if (outs[u] >= 0) {
-        *reinterpret_cast<uint4*>(a.part_o + outs[u] * HD + piece * 8) = vals[u];
-        if (piece == 0) a.part_lse[outs[u]] = lses[u];
+        // streamed past the caches: the partials (gigabytes) are read back by a later kernel, and
+        // the K/V tiles keep the L2
+        store16_stream(a.part_o + outs[u] * HD + piece * 8, vals[u]);
+        if (piece == 0) __builtin_nontemporal_store(lses[u], &a.part_lse[outs[u]]);
       }
     }
   }
@@ -790,10 +792,10 @@ __global__ __launch_bounds__(256) void merge_partials_kernel(
 #pragma unroll
     for (int u = 0; u < s; ++u) ok = ok && js[u] != js[s];
     ls[s] = ok ? lrow[s] : -INFINITY;
-    ov[s] = ok ? load16(orow + (int64_t)s * HD) : make_uint4(0, 0, 0, 0);
+    ov[s] = ok ? load16_stream(orow + (int64_t)s * HD) : make_uint4(0, 0, 0, 0);
   }
   ls[KMAX] = lrow[topk];
-  ov[KMAX] = load16(orow + (int64_t)topk * HD);
+  ov[KMAX] = load16_stream(orow + (int64_t)topk * HD);
 
   float M = ls[KMAX];
 #pragma unroll
@@ -855,11 +857,11 @@ __global__ __launch_bounds__(256) void merge_combined_kernel(
     for (int u = 0; u < s; ++u) ok = ok && js[u] != js[s];
     ls[s] = ok ? lrow[s] : -INFINITY;
     gs[s] = ok ? grow[s] : -INFINITY;
-    ov[s] = ok ? load16(orow + (int64_t)s * HD) : make_uint4(0, 0, 0, 0);
+    ov[s] = ok ? load16_stream(orow + (int64_t)s * HD) : make_uint4(0, 0, 0, 0);
     gmax = fmaxf(gmax, gs[s]);
   }
   const float lw = lrow[topk];
-  ov[KMAX] = load16(orow + (int64_t)topk * HD);
+  ov[KMAX] = load16_stream(orow + (int64_t)topk * HD);
 
   float acc[8], fw[8], f[8];
   Elem<bf16_t>::unpack(ov[KMAX], fw);

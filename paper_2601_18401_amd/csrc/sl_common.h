@@ -88,6 +88,19 @@ struct RowLayout {
 };
 
 __device__ __forceinline__ uint4 load16(const void* p) { return *reinterpret_cast<const uint4*>(p); }
+// 16-byte load with the non-temporal hint, for data that is read once
+__device__ __forceinline__ uint4 load16_stream(const void* p) {
+  typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+  const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+
+// 16-byte store with the non-temporal hint, for data that is not read again soon
+__device__ __forceinline__ void store16_stream(void* p, uint4 v) {
+  typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+  const u32x4 w = {v.x, v.y, v.z, v.w};
+  __builtin_nontemporal_store(w, reinterpret_cast<u32x4*>(p));
+}
 
 // ---- the paper's anchor geometry (Section 3.3) for p = 1/root, root = 2 or 3, in exact integer
 // arithmetic.  Valid for 0 <= x < 2^62.
