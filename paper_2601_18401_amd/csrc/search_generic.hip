@@ -110,11 +110,12 @@ __device__ __forceinline__ void decode_search_block_body(
   constexpr int U = 16, NW = kDecodeSearchThreads / 64;
   auto anchor_token = [&](int64_t j) { return anchor_token_of(anchor_i, anchor_s0 + j, anchor_root); };
   __shared__ float s_sc[kDecodeSearchThreads * RMAX];
-  __shared__ __align__(16) unsigned s_hist[256];
+  __shared__ __align__(16) unsigned s_hist[4][256];  // one histogram per radix pass
   __shared__ int s_wave_tot[NW];
-  __shared__ int s_digit, s_krem;
   const int h = blockIdx.x, kv = h / G;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  static_assert(kDecodeSearchThreads == 4 * 256, "one histogram bin per thread");
+  s_hist[tid >> 8][tid & 255] = 0u;  // visible after the barrier that follows the scoring loop
   const int g = lane / LPR, lr = lane % LPR;
   const int kk = topk < c ? topk : (int)c;
 
@@ -164,32 +165,34 @@ __device__ __forceinline__ void decode_search_block_body(
     int krem = kk;
     for (int pass = 0; pass < 4; ++pass) {
       const int shift = 24 - 8 * pass;
-      if (tid < 256) s_hist[tid] = 0u;
-      __syncthreads();
 #pragma unroll
       for (int r = 0; r < RMAX; ++r)
-        if (key[r] != 0u && (key[r] & mask) == prefix) atomicAdd(&s_hist[(key[r] >> shift) & 255u], 1u);
+        if (key[r] != 0u && (key[r] & mask) == prefix) atomicAdd(&s_hist[pass][(key[r] >> shift) & 255u], 1u);
       __syncthreads();
-      if (wave == 0) {
-        const uint4 c4 = *reinterpret_cast<const uint4*>(&s_hist[4 * lane]);
-        const int lane_sum = (int)(c4.x + c4.y + c4.z + c4.w);
-        const int incl = wave_inclusive_scan(lane_sum);
-        const int total = __builtin_amdgcn_readlane(incl, 63);
-        int above = total - incl;  // candidates in bins above this lane's four
-        const unsigned cnt[4] = {c4.x, c4.y, c4.z, c4.w};
+      // every wavefront finds the bin of the krem-th largest key by itself (one barrier per pass)
+      const uint4 c4 = *reinterpret_cast<const uint4*>(&s_hist[pass][4 * lane]);
+      const int lane_sum = (int)(c4.x + c4.y + c4.z + c4.w);
+      const int incl = wave_inclusive_scan(lane_sum);
+      const int total = __builtin_amdgcn_readlane(incl, 63);
+      int above = total - incl;  // candidates in bins above this lane's four
+      const unsigned cnt[4] = {c4.x, c4.y, c4.z, c4.w};
+      int digit = -1, kleft = 0;
 #pragma unroll
-        for (int b4 = 3; b4 >= 0; --b4) {
-          if (above < krem && krem <= above + (int)cnt[b4]) {
-            s_digit = 4 * lane + b4;
-            s_krem = krem - above;
-          }
-          above += (int)cnt[b4];
+      for (int b4 = 3; b4 >= 0; --b4) {
+        if (above < krem && krem <= above + (int)cnt[b4]) {
+          digit = 4 * lane + b4;
+          kleft = krem - above;
         }
+        above += (int)cnt[b4];
       }
-      __syncthreads();
-      prefix |= (unsigned)s_digit << shift;
+      // exactly one lane holds the bin when 1 <= krem <= number of matching keys; NaN scores
+      // (which never match) can leave none: bin 0 then, the result is unspecified but in bounds
+      const unsigned long long found = __ballot(digit >= 0);
+      const int src = found ? __builtin_ctzll(found) : 0;
+      digit = found ? __builtin_amdgcn_readlane(digit, src) : 0;
+      krem = found ? __builtin_amdgcn_readlane(kleft, src) : krem;
+      prefix |= (unsigned)digit << shift;
       mask |= 255u << shift;
-      krem = s_krem;
     }
     const unsigned tu = (prefix & 0x80000000u) ? (prefix & 0x7fffffffu) : ~prefix;
     Tval = __uint_as_float(tu);
@@ -224,8 +227,10 @@ __device__ __forceinline__ void decode_search_block_body(
     const bool is_eq = v[r] == Tval && v[r] > -INFINITY;
     if (is_gt || (is_eq && eq_before < need_eq)) {
       const int pos = gt_before + (eq_before < need_eq ? eq_before : need_eq);
-      oi[pos] = anchor_i >= 0 ? (int32_t)anchor_token(tid * R + r) : tid * R + r;
-      if (os) os[pos] = v[r];
+      if ((unsigned)pos < (unsigned)kk) {  // always true unless scores are NaN
+        oi[pos] = anchor_i >= 0 ? (int32_t)anchor_token(tid * R + r) : tid * R + r;
+        if (os) os[pos] = v[r];
+      }
     }
     gt_before += is_gt ? 1 : 0;
     eq_before += is_eq ? 1 : 0;
