@@ -117,6 +117,30 @@ def test_decode_configs_full_cache(name):
     torch.cuda.empty_cache()
 
 
+def test_batched_decode_at_the_benchmark_configuration():
+    """8 sequences with caches of about 1M tokens each, as bench.py's batched_decode line runs them:
+    every sequence against the oracle (search on every head, attention on the batch's indices)."""
+    cfg = W.CONFIGS["C3"]
+    data = W.generate(cfg, device=DEV, n_queries=8)
+    K, V = data["K"], data["V"]
+    NB = 8
+    lens = [cfg.L - b * (cfg.S + 37) for b in range(NB)]
+    Kc = [K.clone()[:, :lens[b]] for b in range(NB)]
+    Vc = [V.clone()[:, :lens[b]] for b in range(NB)]
+    Ksc = [B.sl_span_keys(Kc[b], cfg.S) for b in range(NB)]
+    Qs = [data["Q"][b] for b in range(NB)]
+    batch = B.DecodeBatch(Qs, Qs, Kc, Vc, Ksc, cfg.S, cfg.topk)
+    idx = B.sl_span_search_decode_batched(batch)
+    O, LSE = B.sl_span_attention_decode_batched(batch)
+    torch.cuda.synchronize()
+    for b in range(NB):
+        amb = check_idx(idx[b], Qs[b], Ksc[b], cfg.S, cfg.topk, lens[b] - 1)
+        assert amb <= 2                                    # rows whose k / k+1 margin is below 1e-3
+        check_attention(O[b], LSE[b], Qs[b], Kc[b], Vc[b], idx[b], cfg.S, lens[b] - 1, 0.0)
+    del data, K, V, Kc, Vc
+    torch.cuda.empty_cache()
+
+
 def test_paper_geometry_decode_at_1m():
     # config 3's cache with the paper's kernel configuration (window 1088, top-2, b = 4, f = 2)
     cfg = W.CONFIGS["C3"]
