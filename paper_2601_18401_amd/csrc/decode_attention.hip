@@ -96,69 +96,116 @@ __device__ __forceinline__ void decode_split_body(
     t1 = t0 + CT < q_pos + 1 ? t0 + CT : q_pos + 1;
   }
 
-  float* prec = part + (((int64_t)h * (topk + 1) + slot) * nchunks + ck) * (D + 2);
   const int tid = threadIdx.x;
-  if (t0 >= t1) {  // empty slot or chunk past the end of the range (uniform over the workgroup)
-    if (tid < D) prec[tid] = 0.f;
-    if (tid == 0) {
-      prec[D] = -INFINITY;
-      prec[D + 1] = 0.f;
-    }
-    return;
-  }
-
   const int lane = tid & 63, wave = tid >> 6;
-  const int g = lane / LPR, lr = lane % LPR;
-  float q2[EPL];
-  {
-    float qf[EPL];
-    Elem<T>::unpack(load16(Q + (int64_t)h * qsh + lr * EPL), qf);
-#pragma unroll
-    for (int e = 0; e < EPL; ++e) q2[e] = qf[e] * scale_log2e;
-  }
-  const T* Kb = K + (int64_t)kv * kvsh;
-  const T* Vb = V + (int64_t)kv * kvsh;
 
-  // each wave takes a contiguous quarter of the chunk
-  const int per_wave = CT / (kDecodeThreads / 64);
-  int64_t w0 = t0 + (int64_t)wave * per_wave;
-  int64_t w1 = w0 + per_wave < t1 ? w0 + per_wave : t1;
-  AttendState<T, D> st;
-  st.init();
-  // A selected span is read by few heads and once; the window is read by all G heads of its kv
-  // head and stays cacheable.
-  if (slot != topk)
-    attend_range<T, D, 8, true>(q2, Kb, Vb, kvst, w0, w1, lane, st);
-  else
-    attend_range<T, D, 8, false>(q2, Kb, Vb, kvst, w0, w1, lane, st);
-
-  const int gi = wave * RPW + g;
+  // Spans on the grid that several heads of a kv head select are read once: the entry (head,
+  // slot) that comes first in the group's index rows owns the chunk and computes the partial of
+  // every other entry that lists the same span from the rows it has just pulled through the L2;
+  // the workgroups of those entries leave at once.  Needs the group's G * topk indices in one
+  // pass of a wavefront (larger groups: every entry reads its own span, as before).
+  constexpr int kShareWords = 4;  // up to 256 (head, slot) entries per kv head
+  const bool dedup = !ar.on && slot < topk && G * topk <= 64 * kShareWords && G > 1;
+  unsigned long long share[kShareWords] = {0ull, 0ull, 0ull, 0ull};
+  const int my_entry = (h - kv * G) * topk + slot;
+  bool shared_span = false;
+  if (dedup) {
+    // every wavefront builds the masks by itself (no LDS, no barrier): lane l looks at entries
+    // l, l + 64, ... of the group's index rows, which are contiguous
+    const int64_t jmine = idx[(int64_t)h * topk + slot];
+    int first = -1, count = 0;
 #pragma unroll
-  for (int e = 0; e < EPL; ++e) s_o[gi][lr * EPL + e] = st.o[e];
-  if (lr == 0) {
-    s_m[gi] = st.m;
-    s_l[gi] = st.l;
+    for (int w = kShareWords - 1; w >= 0; --w) {
+      const int e = 64 * w + lane;
+      int64_t jother = -1;
+      if (e < G * topk) jother = idx[(int64_t)kv * G * topk + e];
+      share[w] = __ballot(jmine >= 0 && jmine < c && jother == jmine);
+      if (share[w]) first = 64 * w + __builtin_ctzll(share[w]);
+      count += __builtin_popcountll(share[w]);
+    }
+    if (count > 1) {
+      if (first != my_entry) return;  // the owner writes this entry's record
+      shared_span = true;
+    }
   }
-  __syncthreads();
-  if (tid < D) {
-    float M = -INFINITY;
+
+  // Entries served by this workgroup: its own, then (owner of a shared span) the others.
+  int entry = my_entry;
+  while (true) {
+    const int he = shared_span ? kv * G + entry / topk : h;
+    const int se = shared_span ? entry % topk : slot;
+    float* prec = part + (((int64_t)he * (topk + 1) + se) * nchunks + ck) * (D + 2);
+    if (t0 >= t1) {  // empty slot or chunk past the end of the range (uniform over the workgroup)
+      if (tid < D) prec[tid] = 0.f;
+      if (tid == 0) {
+        prec[D] = -INFINITY;
+        prec[D + 1] = 0.f;
+      }
+    } else {
+      const int g = lane / LPR, lr = lane % LPR;
+      float q2[EPL];
+      {
+        float qf[EPL];
+        Elem<T>::unpack(load16(Q + (int64_t)he * qsh + lr * EPL), qf);
 #pragma unroll
-    for (int i = 0; i < NG; ++i) M = fmaxf(M, s_m[i]);
-    float acc = 0.f, lt = 0.f;
+        for (int e = 0; e < EPL; ++e) q2[e] = qf[e] * scale_log2e;
+      }
+      const T* Kb = K + (int64_t)kv * kvsh;
+      const T* Vb = V + (int64_t)kv * kvsh;
+
+      // each wave takes a contiguous quarter of the chunk
+      const int per_wave = CT / (kDecodeThreads / 64);
+      int64_t w0 = t0 + (int64_t)wave * per_wave;
+      int64_t w1 = w0 + per_wave < t1 ? w0 + per_wave : t1;
+      AttendState<T, D> st;
+      st.init();
+      // A span that one entry reads is streamed past the caches; the window (read by all G heads
+      // of its kv head) and a shared span (read again right away) stay cacheable.
+      if (slot != topk && !shared_span)
+        attend_range<T, D, 8, true>(q2, Kb, Vb, kvst, w0, w1, lane, st);
+      else
+        attend_range<T, D, 8, false>(q2, Kb, Vb, kvst, w0, w1, lane, st);
+
+      const int gi = wave * RPW + g;
 #pragma unroll
-    for (int i = 0; i < NG; ++i) {
-      const float mi = s_m[i];
-      if (mi > -INFINITY) {
-        const float w = fast_exp2(mi - M);
-        acc = fmaf(w, s_o[i][tid], acc);
-        lt = fmaf(w, s_l[i], lt);
+      for (int e = 0; e < EPL; ++e) s_o[gi][lr * EPL + e] = st.o[e];
+      if (lr == 0) {
+        s_m[gi] = st.m;
+        s_l[gi] = st.l;
+      }
+      __syncthreads();
+      if (tid < D) {
+        float M = -INFINITY;
+#pragma unroll
+        for (int i = 0; i < NG; ++i) M = fmaxf(M, s_m[i]);
+        float acc = 0.f, lt = 0.f;
+#pragma unroll
+        for (int i = 0; i < NG; ++i) {
+          const float mi = s_m[i];
+          if (mi > -INFINITY) {
+            const float w = fast_exp2(mi - M);
+            acc = fmaf(w, s_o[i][tid], acc);
+            lt = fmaf(w, s_l[i], lt);
+          }
+        }
+        prec[tid] = acc;
+        if (tid == 0) {
+          prec[D] = M;
+          prec[D + 1] = lt;
+        }
       }
     }
-    prec[tid] = acc;
-    if (tid == 0) {
-      prec[D] = M;
-      prec[D + 1] = lt;
+    if (!shared_span) break;
+    // next entry that lists the span (all threads hold the same masks)
+    int next = -1;
+#pragma unroll
+    for (int w = kShareWords - 1; w >= 0; --w) {
+      if (w == (entry >> 6)) share[w] &= ~(1ull << (entry & 63));
+      if (share[w]) next = 64 * w + __builtin_ctzll(share[w]);
     }
+    if (next < 0) break;
+    entry = next;
+    __syncthreads();  // the merge above has read s_o / s_m / s_l
   }
 }
 

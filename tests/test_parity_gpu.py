@@ -334,6 +334,40 @@ def test_decode_batched_rejects_what_it_cannot_serve():
         B.sl_span_attention_decode_batched(batch)
 
 
+@pytest.mark.parametrize("dtype,Hq,Hkv,D,S,k", [(torch.bfloat16, 32, 4, 128, 256, 16), (torch.float32, 8, 2, 64, 64, 4),
+                                                (torch.bfloat16, 16, 1, 128, 128, 32)])
+def test_decode_heads_of_a_group_sharing_spans(dtype, Hq, Hkv, D, S, k):
+    """Several heads of a kv head list the same span: one of their workgroups reads it for all."""
+    L = S * 70 + 33
+    Q, K, V = make(71, Hq, Hkv, L, D, dtype, Lq=1)
+    c, G = (L - 1) // S, Hq // Hkv
+    rng = np.random.default_rng(5)
+    idx = np.full((Hq, 1, k), -1, np.int32)
+    for kv in range(Hkv):
+        common = rng.choice(c, size=k, replace=False)
+        for g in range(G):
+            h = kv * G + g
+            if g % 3 == 0:      # the same spans as the group's first head, in ascending order
+                sel = np.sort(common)
+            elif g % 3 == 1:    # half shared, half own, unsorted, one empty slot
+                own = rng.choice(np.setdiff1d(np.arange(c), common), size=k - k // 2, replace=False)
+                sel = np.concatenate([common[:k // 2], own])
+                rng.shuffle(sel)
+                sel[0] = -1
+            else:               # shares nothing
+                sel = rng.choice(np.setdiff1d(np.arange(c), common), size=k, replace=False)
+            idx[h, 0] = sel
+    idx_t = torch.from_numpy(idx).to(DEV)
+    O, LSE = B.sl_span_attention_decode(Q, K, V, idx_t, S)
+    torch.cuda.synchronize()
+    check_attention(O, LSE, Q, K, V, idx_t, S, L - 1, 0.0)
+    # every head of every group on exactly the same spans
+    idx_same = torch.from_numpy(np.sort(idx[::G].repeat(G, axis=0), axis=2)).to(DEV)
+    O, LSE = B.sl_span_attention_decode(Q, K, V, idx_same, S)
+    torch.cuda.synchronize()
+    check_attention(O, LSE, Q, K, V, idx_same, S, L - 1, 0.0)
+
+
 def test_decode_mid_cache_position_and_garbage_idx():
     Hq, Hkv, L, D, S, k = 8, 2, 16384, 128, 128, 8
     Q, K, V = make(21, Hq, Hkv, L, D, torch.bfloat16, Lq=1)
