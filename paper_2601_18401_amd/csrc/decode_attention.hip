@@ -99,13 +99,14 @@ __device__ __forceinline__ void decode_split_body(
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
 
-  // Spans on the grid that several heads of a kv head select are read once: the entry (head,
+  // Spans (grid indices or anchor tokens) that several heads of a kv head select are read once: the entry (head,
   // slot) that comes first in the group's index rows owns the chunk and computes the partial of
   // every other entry that lists the same span from the rows it has just pulled through the L2;
   // the workgroups of those entries leave at once.  Needs the group's G * topk indices in one
   // pass of a wavefront (larger groups: every entry reads its own span, as before).
   constexpr int kShareWords = 4;  // up to 256 (head, slot) entries per kv head
-  const bool dedup = !ar.on && slot < topk && G * topk <= 64 * kShareWords && G > 1;
+  const bool dedup = slot < topk && G * topk <= 64 * kShareWords && G > 1;
+  const int64_t jlimit = ar.on ? q_pos + 1 : c;  // valid entries: anchor tokens <= q_pos, resp. spans < c
   unsigned long long share[kShareWords] = {0ull, 0ull, 0ull, 0ull};
   const int my_entry = (h - kv * G) * topk + slot;
   bool shared_span = false;
@@ -119,7 +120,7 @@ __device__ __forceinline__ void decode_split_body(
       const int e = 64 * w + lane;
       int64_t jother = -1;
       if (e < G * topk) jother = idx[(int64_t)kv * G * topk + e];
-      share[w] = __ballot(jmine >= 0 && jmine < c && jother == jmine);
+      share[w] = __ballot(jmine >= 0 && jmine < jlimit && jother == jmine);
       if (share[w]) first = 64 * w + __builtin_ctzll(share[w]);
       count += __builtin_popcountll(share[w]);
     }

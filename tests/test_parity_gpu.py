@@ -652,6 +652,27 @@ def test_anchor_decode(seed, Hq, Hkv, L, D, k, w, b, f, dtype):
         assert err <= TOL[dtype], (h, err)
 
 
+def test_anchor_decode_heads_sharing_anchors():
+    """Heads of a kv head that list the same anchor token share one read of its span."""
+    Hq, Hkv, L, D, k, w, b, f = 8, 2, 40000, 128, 4, 120, 4, 2
+    Q, K, V = make(47, Hq, Hkv, L, D, torch.bfloat16, Lq=1, scale=0.5)
+    i, G = L - 1, Hq // Hkv
+    anchors, sc = B.sl_anchor_search_decode(Q, K, k, w, want_scores=True)
+    torch.cuda.synchronize()
+    an = anchors.clone()
+    for kv in range(Hkv):               # heads 1 and 2 of each group take head 0's anchors (all, resp. two of them)
+        an[kv * G + 1] = an[kv * G]
+        an[kv * G + 2, 0, :2] = an[kv * G, 0, 2:]
+    sc_in = torch.randn(sc.shape, generator=torch.Generator().manual_seed(3)).to(DEV)
+    O = B.sl_anchor_attention_decode(Q, K, V, an, sc_in, w, b, f)
+    torch.cuda.synchronize()
+    On, Qn, ann, scn = f64(O), f64(Q), an.cpu().numpy(), sc_in.cpu().numpy().astype(np.float64)
+    Kd, Vd = DevKV(K), DevKV(V)
+    for h in range(Hq):
+        o = orc.anchor_combined_row(Qn[h, 0], Kd, Vd, h // G, i, w, b, f, ann[h, 0], scn[h, 0], 1.0 / math.sqrt(D))
+        assert float(np.max(np.abs(On[h, 0] - o))) <= TOL[torch.bfloat16], h
+
+
 # ------------------------------------------------------------------------------ the paper's own geometry (prefill form)
 
 ANCHOR_PREFILL = [
