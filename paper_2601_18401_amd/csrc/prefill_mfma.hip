@@ -435,11 +435,16 @@ __device__ __forceinline__ void flash_tile(const FlashArgs& a, char* lds, const 
     for (int ks = 0; ks < 4; ++ks) {
       f32x8 p;
 #pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        p[e] = fast_exp2(fmaf(s[ks >> 1][8 * (ks & 1) + e], sc, nm));
-        l += p[e];
-      }
+      for (int e = 0; e < 8; ++e) p[e] = fast_exp2(fmaf(s[ks >> 1][8 * (ks & 1) + e], sc, nm));
       pb[ks] = __builtin_convertvector(p, bf16x8);
+      // the row sum is taken over the rounded weights, the ones the PV product uses
+#pragma unroll
+      for (int e = 0; e < 8; e += 2) {
+        typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+        const bf16x2 pr = {pb[ks][e], pb[ks][e + 1]};
+        const bf16x2 one = {(__bf16)1.0f, (__bf16)1.0f};
+        l = __builtin_amdgcn_fdot2_f32_bf16(pr, one, l, false);
+      }
     }
     __builtin_amdgcn_s_setprio(0);
   };
