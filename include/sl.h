@@ -256,6 +256,25 @@ sl_status sl_span_search_decode_batched(const sl_params* p, const sl_decode_seq*
 sl_status sl_span_attention_decode_batched(const sl_params* p, const sl_decode_seq* seqs, int32_t B,
                                            void* ws, size_t ws_bytes, void* hip_stream);
 
+/* The combination form (sl_span_attention_combined_decode) for every sequence of the batch: the
+ * gate is seq[b].scores as written by sl_span_search_decode_batched (required), O is written, LSE
+ * is not.  Workspace: sl_decode_batched_workspace_bytes. */
+sl_status sl_span_attention_combined_decode_batched(const sl_params* p, const sl_decode_seq* seqs,
+                                                    int32_t B, void* ws, size_t ws_bytes,
+                                                    void* hip_stream);
+
+/* The paper's own geometry (sl_anchor_search_decode / sl_anchor_attention_decode) for a batch:
+ * window, span factors and exponent are common (g), every sequence's query sits at its own
+ * L - 1, so its anchors, its span base length l(L - 1) and its window follow from its own
+ * length.  p->S is ignored, seq[b].Ks is not read; seq[b].idx receives / supplies anchor TOKEN
+ * positions, seq[b].scores the gate (required); O is written, LSE is not. */
+size_t sl_anchor_batched_workspace_bytes(const sl_params* p, const sl_anchor_geometry* g, int32_t B);
+sl_status sl_anchor_search_decode_batched(const sl_params* p, const sl_anchor_geometry* g,
+                                          const sl_decode_seq* seqs, int32_t B, void* hip_stream);
+sl_status sl_anchor_attention_decode_batched(const sl_params* p, const sl_anchor_geometry* g,
+                                             const sl_decode_seq* seqs, int32_t B, void* ws,
+                                             size_t ws_bytes, void* hip_stream);
+
 /* Static, human-readable name of a status code. */
 const char* sl_status_string(int status);
 

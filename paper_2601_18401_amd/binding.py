@@ -25,7 +25,9 @@ EXPORTS = ("sl_workspace_bytes", "sl_span_keys", "sl_span_search_prefill", "sl_s
            "sl_span_attention_combined_decode", "sl_anchor_workspace_bytes", "sl_anchor_search_decode",
            "sl_anchor_attention_decode", "sl_anchor_search_prefill", "sl_anchor_attention_prefill",
            "sl_decode_batched_workspace_bytes", "sl_span_search_decode_batched",
-           "sl_span_attention_decode_batched", "sl_status_string", "sl_version")
+           "sl_span_attention_decode_batched", "sl_span_attention_combined_decode_batched",
+           "sl_anchor_batched_workspace_bytes", "sl_anchor_search_decode_batched",
+           "sl_anchor_attention_decode_batched", "sl_status_string", "sl_version")
 
 
 class SlAnchorGeometry(ctypes.Structure):
@@ -107,6 +109,14 @@ def load():
     lib.sl_span_search_decode_batched.argtypes = [pp, vp, ctypes.c_int32, vp]
     lib.sl_span_attention_decode_batched.restype = ctypes.c_int
     lib.sl_span_attention_decode_batched.argtypes = [pp, vp, ctypes.c_int32, vp, ctypes.c_size_t, vp]
+    lib.sl_span_attention_combined_decode_batched.restype = ctypes.c_int
+    lib.sl_span_attention_combined_decode_batched.argtypes = [pp, vp, ctypes.c_int32, vp, ctypes.c_size_t, vp]
+    lib.sl_anchor_batched_workspace_bytes.restype = ctypes.c_size_t
+    lib.sl_anchor_batched_workspace_bytes.argtypes = [pp, gp, ctypes.c_int32]
+    lib.sl_anchor_search_decode_batched.restype = ctypes.c_int
+    lib.sl_anchor_search_decode_batched.argtypes = [pp, gp, vp, ctypes.c_int32, vp]
+    lib.sl_anchor_attention_decode_batched.restype = ctypes.c_int
+    lib.sl_anchor_attention_decode_batched.argtypes = [pp, gp, vp, ctypes.c_int32, vp, ctypes.c_size_t, vp]
     lib.sl_status_string.restype = ctypes.c_char_p
     lib.sl_status_string.argtypes = [ctypes.c_int]
     lib.sl_version.restype = ctypes.c_int
@@ -415,3 +425,42 @@ def sl_span_attention_decode_batched(batch: DecodeBatch, scale=0.0, ws=None):
                                               wptr, wbytes, _stream())
     _check(st, "sl_span_attention_decode_batched")
     return batch.O, batch.LSE
+
+
+def sl_span_attention_combined_decode_batched(batch: DecodeBatch, scale=0.0, ws=None):
+    """Gated combination of every sequence on batch.idx / batch.scores; returns batch.O."""
+    lib = load()
+    if batch.scores is None:
+        raise ValueError("the combination form needs the search scores: DecodeBatch(..., want_scores=True)")
+    batch.params.scale = float(scale)
+    need = lib.sl_decode_batched_workspace_bytes(ctypes.byref(batch.params), batch.B)
+    wptr, wbytes = _ws(ws).get(need)
+    st = lib.sl_span_attention_combined_decode_batched(ctypes.byref(batch.params), _ptr(batch.records),
+                                                       batch.B, wptr, wbytes, _stream())
+    _check(st, "sl_span_attention_combined_decode_batched")
+    return batch.O
+
+
+def sl_anchor_search_decode_batched(batch: DecodeBatch, window, search_root=2):
+    """Top-k anchors (token positions) of every sequence's last position into batch.idx / batch.scores."""
+    g = SlAnchorGeometry(window, 0, 0, search_root, 0)
+    st = load().sl_anchor_search_decode_batched(ctypes.byref(batch.params), ctypes.byref(g),
+                                                _ptr(batch.records), batch.B, _stream())
+    _check(st, "sl_anchor_search_decode_batched")
+    return (batch.idx, batch.scores) if batch.scores is not None else batch.idx
+
+
+def sl_anchor_attention_decode_batched(batch: DecodeBatch, window, backward_factor, forward_factor,
+                                       scale=0.0, ws=None, search_root=2):
+    """Algorithm 1's span-attention + combination for every sequence; returns batch.O."""
+    lib = load()
+    if batch.scores is None:
+        raise ValueError("the combination needs the search scores: DecodeBatch(..., want_scores=True)")
+    batch.params.scale = float(scale)
+    g = SlAnchorGeometry(window, backward_factor, forward_factor, search_root, 0)
+    need = lib.sl_anchor_batched_workspace_bytes(ctypes.byref(batch.params), ctypes.byref(g), batch.B)
+    wptr, wbytes = _ws(ws).get(need)
+    st = lib.sl_anchor_attention_decode_batched(ctypes.byref(batch.params), ctypes.byref(g),
+                                                _ptr(batch.records), batch.B, wptr, wbytes, _stream())
+    _check(st, "sl_anchor_attention_decode_batched")
+    return batch.O

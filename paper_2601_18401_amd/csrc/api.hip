@@ -296,6 +296,59 @@ sl_status sl_span_attention_decode_batched(const sl_params* p, const sl_decode_s
   return sl::decode_attention_batched(pb, seqs, B, ws, static_cast<hipStream_t>(hip_stream));
 }
 
+static bool good_batch(const sl_decode_seq* seqs, int32_t B) {
+  return seqs && B >= 1 && B <= 65535 && (reinterpret_cast<uintptr_t>(seqs) & 7u) == 0;
+}
+
+sl_status sl_span_attention_combined_decode_batched(const sl_params* p, const sl_decode_seq* seqs,
+                                                    int32_t B, void* ws, size_t ws_bytes,
+                                                    void* hip_stream) {
+  sl::Problem pb;
+  sl_status s = sl::make_problem(p, SL_OP_ATTENTION_DECODE, &pb);
+  if (s != SL_OK) return s;
+  if (!good_batch(seqs, B)) return SL_ERR_INVALID_ARG;
+  const size_t need = sl::decode_attention_batched_ws_bytes(pb, B);
+  if (!ws || ws_bytes < need || (reinterpret_cast<uintptr_t>(ws) & 255u)) return SL_ERR_WORKSPACE;
+  pb.combined = true;
+  return sl::decode_attention_batched(pb, seqs, B, ws, static_cast<hipStream_t>(hip_stream));
+}
+
+size_t sl_anchor_batched_workspace_bytes(const sl_params* p, const sl_anchor_geometry* g, int32_t B) {
+  sl::Problem pb;
+  const int root = anchor_root(g);
+  if (!root || B < 1) return 0;
+  if (sl::make_problem(p, SL_OP_ATTENTION_DECODE, &pb) != SL_OK) return 0;
+  return sl::anchor_attention_batched_ws_bytes(pb, g->window, g->backward_factor, g->forward_factor, root, B);
+}
+
+sl_status sl_anchor_search_decode_batched(const sl_params* p, const sl_anchor_geometry* g,
+                                          const sl_decode_seq* seqs, int32_t B, void* hip_stream) {
+  sl::Problem pb;
+  sl_status s = sl::make_problem(p, SL_OP_SEARCH_DECODE, &pb);
+  if (s != SL_OK) return s;
+  const int root = anchor_root(g);
+  if (!root || !good_batch(seqs, B)) return SL_ERR_INVALID_ARG;
+  if (pb.L > ((int64_t)1 << 31) - 1) return SL_ERR_UNSUPPORTED;  // anchors are int32 token positions
+  return sl::anchor_search_decode_batched(pb, g->window, root, seqs, B, static_cast<hipStream_t>(hip_stream));
+}
+
+sl_status sl_anchor_attention_decode_batched(const sl_params* p, const sl_anchor_geometry* g,
+                                             const sl_decode_seq* seqs, int32_t B, void* ws,
+                                             size_t ws_bytes, void* hip_stream) {
+  sl::Problem pb;
+  sl_status s = sl::make_problem(p, SL_OP_ATTENTION_DECODE, &pb);
+  if (s != SL_OK) return s;
+  const int root = anchor_root(g);
+  if (!root || !good_batch(seqs, B)) return SL_ERR_INVALID_ARG;
+  if (pb.L > ((int64_t)1 << 31) - 1) return SL_ERR_UNSUPPORTED;
+  const size_t need =
+      sl::anchor_attention_batched_ws_bytes(pb, g->window, g->backward_factor, g->forward_factor, root, B);
+  if (!ws || ws_bytes < need || (reinterpret_cast<uintptr_t>(ws) & 255u)) return SL_ERR_WORKSPACE;
+  pb.combined = true;
+  return sl::anchor_attention_decode_batched(pb, g->window, g->backward_factor, g->forward_factor, root,
+                                             seqs, B, ws, static_cast<hipStream_t>(hip_stream));
+}
+
 const char* sl_status_string(int status) {
   switch (status) {
     case SL_OK: return "SL_OK";

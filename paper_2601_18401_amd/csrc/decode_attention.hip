@@ -222,17 +222,33 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_split_kernel(
 
 // Batched decode: blockIdx.y is the sequence; its tensors and length come from the device array.
 // kvsh = 0: the cache of every sequence is packed for its own length.
+// The paper's geometry for a batch: window, span factors and exponent are common, the span base
+// length l(L - 1) and the window's first token follow from each sequence's own length.
+struct AnchorBatch {
+  bool on;
+  int64_t window;
+  int b, f, root;
+};
+
 template <typename T, int D>
 __global__ __launch_bounds__(kDecodeThreads) void decode_split_batched_kernel(
     const sl_decode_seq* __restrict__ seqs, float* __restrict__ part, int64_t part_stride, int Hq,
     int Hkv, int S, int topk, int nchunks, int CT, float scale_log2e, int64_t qsh, int64_t kvsh,
-    int64_t kvst, int n_routed_blocks, int local_stride) {
+    int64_t kvst, int n_routed_blocks, int local_stride, const AnchorBatch ab) {
   const sl_decode_seq sq = seqs[blockIdx.y];
+  const int64_t i = sq.L - 1;
+  AnchorRanges ar{false, 0, 0, 0};
+  if (ab.on) {
+    const int64_t ell = span_base_length(i, ab.root);
+    ar.on = true;
+    ar.wlo = ab.window > 0 ? (i - ab.window + 1 > 0 ? i - ab.window + 1 : 0) : i + 1;
+    ar.back = (int64_t)ab.b * ell;
+    ar.fwd = (int64_t)ab.f * ell;
+  }
   decode_split_body<T, D>(static_cast<const T*>(sq.Q), static_cast<const T*>(sq.K),
-                          static_cast<const T*>(sq.V), sq.idx, part + blockIdx.y * part_stride,
-                          sq.L - 1, Hq, Hkv, S, topk, nchunks, CT, scale_log2e, qsh,
-                          kvsh ? kvsh : sq.L * kvst, kvst, n_routed_blocks, local_stride,
-                          AnchorRanges{false, 0, 0, 0});
+                          static_cast<const T*>(sq.V), sq.idx, part + blockIdx.y * part_stride, i, Hq,
+                          Hkv, S, topk, nchunks, CT, scale_log2e, qsh, kvsh ? kvsh : sq.L * kvst, kvst,
+                          n_routed_blocks, local_stride, ar);
 }
 
 // Merges the (topk + 1) * nchunks partial records of a head.  grid (Hq, D / 32): each workgroup
@@ -349,10 +365,9 @@ __global__ __launch_bounds__(256) void decode_reduce_batched_kernel(
 constexpr int kMaxSlots = SL_MAX_TOPK + 1;
 
 template <typename T, int D>
-__global__ __launch_bounds__(256) void decode_reduce_combined_kernel(const float* __restrict__ part,
-                                                                    const float* __restrict__ gate,
-                                                                    T* __restrict__ O, int topk,
-                                                                    int nchunks) {
+__device__ __forceinline__ void decode_reduce_combined_body(const float* __restrict__ part,
+                                                            const float* __restrict__ gate,
+                                                            T* __restrict__ O, int topk, int nchunks) {
   extern __shared__ float s_dyn[];  // [nrec] m, [nrec] l
   __shared__ float s_ms[kMaxSlots], s_ls[kMaxSlots];           // per slot: max m, l relative to it
   __shared__ float s_part[kMaxSlots][kReduceSub][kReduceDims];  // per slot and subset: o relative to it
@@ -461,6 +476,24 @@ __global__ __launch_bounds__(256) void decode_reduce_combined_kernel(const float
   }
 }
 
+template <typename T, int D>
+__global__ __launch_bounds__(256) void decode_reduce_combined_kernel(const float* __restrict__ part,
+                                                                    const float* __restrict__ gate,
+                                                                    T* __restrict__ O, int topk,
+                                                                    int nchunks) {
+  decode_reduce_combined_body<T, D>(part, gate, O, topk, nchunks);
+}
+
+// Batched decode: blockIdx.z is the sequence; the gate is the sequence's own score array.
+template <typename T, int D>
+__global__ __launch_bounds__(256) void decode_reduce_combined_batched_kernel(
+    const sl_decode_seq* __restrict__ seqs, const float* __restrict__ part, int64_t part_stride, int topk,
+    int nchunks) {
+  const sl_decode_seq sq = seqs[blockIdx.z];
+  decode_reduce_combined_body<T, D>(part + blockIdx.z * part_stride, sq.scores, static_cast<T*>(sq.O), topk,
+                                    nchunks);
+}
+
 int pick_chunk_tokens(const Problem& pb, int batch = 1) {
   // Aim for a few thousand workgroups so the 256 CUs keep enough loads in flight, without
   // going below 64 tokens per item.
@@ -518,7 +551,7 @@ struct AnchorPlan {
   size_t part_bytes, total_bytes;
 };
 
-AnchorPlan plan_anchor(const Problem& pb, int64_t window, int b, int f, int root) {
+AnchorPlan plan_anchor(const Problem& pb, int64_t window, int b, int f, int root, int batch = 1) {
   AnchorPlan a;
   const int64_t i = pb.q_pos0;
   const int64_t ell = span_base_length(i, root);  // l(i) = ceil(i^(1-p)), p = 1/root
@@ -530,10 +563,10 @@ AnchorPlan plan_anchor(const Problem& pb, int64_t window, int b, int f, int root
   if (a.maxlen > i + 1) a.maxlen = i + 1;
   const int64_t units = (int64_t)pb.Hq * (pb.topk + 1);
   int ct = 512;
-  while (ct > 64 && units * ((a.maxlen + ct - 1) / ct) < 4096) ct >>= 1;
+  while (ct > 64 && batch * units * ((a.maxlen + ct - 1) / ct) < 4096) ct >>= 1;
   a.CT = ct;
   a.nchunks = (int)((a.maxlen + ct - 1) / ct);
-  a.part_bytes = align_up((size_t)units * a.nchunks * (pb.D + 2) * sizeof(float), 256);
+  a.part_bytes = align_up((size_t)batch * units * a.nchunks * (pb.D + 2) * sizeof(float), 256);
   a.total_bytes = a.part_bytes;
   return a;
 }
@@ -583,10 +616,33 @@ sl_status launch_decode_batched(const Problem& pb, const sl_decode_seq* seqs, in
   hipLaunchKernelGGL((decode_split_batched_kernel<T, D>), dim3(grid, B), dim3(kDecodeThreads), 0, st,
                      seqs, part, part_stride, pb.Hq, pb.Hkv, pb.S, pb.topk, nchunks, CT,
                      pb.scale * kLog2e, pb.qsh, pb.kvsh_given ? pb.kvsh : (int64_t)0, pb.kvst, n_routed,
-                     local_stride);
+                     local_stride, AnchorBatch{false, 0, 0, 0, 2});
   if (hipGetLastError() != hipSuccess) return SL_ERR_LAUNCH;
-  hipLaunchKernelGGL((decode_reduce_batched_kernel<T, D>), dim3(pb.Hq, D / kReduceDims, B), dim3(256),
-                     (size_t)nrec * sizeof(float), st, seqs, part, part_stride, nrec);
+  if (pb.combined)
+    hipLaunchKernelGGL((decode_reduce_combined_batched_kernel<T, D>), dim3(pb.Hq, D / kReduceDims, B),
+                       dim3(256), (size_t)2 * nrec * sizeof(float), st, seqs, part, part_stride, pb.topk,
+                       nchunks);
+  else
+    hipLaunchKernelGGL((decode_reduce_batched_kernel<T, D>), dim3(pb.Hq, D / kReduceDims, B), dim3(256),
+                       (size_t)nrec * sizeof(float), st, seqs, part, part_stride, nrec);
+  return hipGetLastError() == hipSuccess ? SL_OK : SL_ERR_LAUNCH;
+}
+
+template <typename T, int D>
+sl_status launch_anchor_batched(const Problem& pb, const AnchorPlan& a, const AnchorBatch& ab,
+                                const sl_decode_seq* seqs, int B, void* ws, hipStream_t st) {
+  const int units = pb.Hq * (pb.topk + 1);
+  const int nrec = (pb.topk + 1) * a.nchunks;
+  const int64_t part_stride = (int64_t)pb.Hq * nrec * (D + 2);
+  float* part = static_cast<float*>(ws);
+  const int grid = units * a.nchunks;  // every (head, slot, chunk) is a routed item, as for one sequence
+  hipLaunchKernelGGL((decode_split_batched_kernel<T, D>), dim3(grid, B), dim3(kDecodeThreads), 0, st,
+                     seqs, part, part_stride, pb.Hq, pb.Hkv, 1, pb.topk, a.nchunks, a.CT,
+                     pb.scale * kLog2e, pb.qsh, pb.kvsh_given ? pb.kvsh : (int64_t)0, pb.kvst, grid, 8, ab);
+  if (hipGetLastError() != hipSuccess) return SL_ERR_LAUNCH;
+  hipLaunchKernelGGL((decode_reduce_combined_batched_kernel<T, D>), dim3(pb.Hq, D / kReduceDims, B),
+                     dim3(256), (size_t)2 * nrec * sizeof(float), st, seqs, part, part_stride, pb.topk,
+                     a.nchunks);
   return hipGetLastError() == hipSuccess ? SL_OK : SL_ERR_LAUNCH;
 }
 
@@ -606,6 +662,23 @@ sl_status decode_attention_batched(const Problem& pb, const sl_decode_seq* seqs,
   }
   if (pb.D == 128) return launch_decode_batched<float, 128>(pb, seqs, B, ws, st);
   return launch_decode_batched<float, 64>(pb, seqs, B, ws, st);
+}
+
+size_t anchor_attention_batched_ws_bytes(const Problem& pb, int64_t window, int b, int f, int root,
+                                         int B) {
+  return plan_anchor(pb, window, b, f, root, B).total_bytes;
+}
+
+sl_status anchor_attention_decode_batched(const Problem& pb, int64_t window, int b, int f, int root,
+                                          const sl_decode_seq* seqs, int B, void* ws, hipStream_t st) {
+  const AnchorPlan a = plan_anchor(pb, window, b, f, root, B);
+  const AnchorBatch ab{true, window, b, f, root};
+  if (pb.dtype == SL_BF16) {
+    if (pb.D == 128) return launch_anchor_batched<bf16_t, 128>(pb, a, ab, seqs, B, ws, st);
+    return launch_anchor_batched<bf16_t, 64>(pb, a, ab, seqs, B, ws, st);
+  }
+  if (pb.D == 128) return launch_anchor_batched<float, 128>(pb, a, ab, seqs, B, ws, st);
+  return launch_anchor_batched<float, 64>(pb, a, ab, seqs, B, ws, st);
 }
 
 size_t decode_attention_ws_bytes(const Problem& pb) {

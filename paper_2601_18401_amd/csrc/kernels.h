@@ -25,6 +25,13 @@ size_t decode_attention_batched_ws_bytes(const Problem& pb, int B);
 sl_status decode_attention_batched(const Problem& pb, const sl_decode_seq* seqs, int B, void* ws,
                                    hipStream_t st);
 
+// ... and on the paper's own geometry (anchors as candidates, gated combination)
+sl_status anchor_search_decode_batched(const Problem& pb, int64_t window, int root,
+                                       const sl_decode_seq* seqs, int B, hipStream_t st);
+size_t anchor_attention_batched_ws_bytes(const Problem& pb, int64_t window, int b, int f, int root, int B);
+sl_status anchor_attention_decode_batched(const Problem& pb, int64_t window, int b, int f, int root,
+                                          const sl_decode_seq* seqs, int B, void* ws, hipStream_t st);
+
 // The paper's own geometry, decode form (Section 3.3, Algorithm 1): anchors on the quadratic
 // stride pattern, spans of b*l(i) / f*l(i) tokens around the selected anchors, window w.
 // root = 1/p: 2 (anchors i-(s+1)^2+1, l = ceil(sqrt(i))) or 3 (anchors i-(s+1)^3+1, l = ceil(i^(2/3))).

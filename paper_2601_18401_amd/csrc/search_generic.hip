@@ -264,6 +264,22 @@ __global__ __launch_bounds__(kDecodeSearchThreads) void decode_search_block_batc
                                        kvst, (int64_t)-1, 0, 2);
 }
 
+// Batched decode on the paper's geometry: every sequence has its own query position L - 1 and so
+// its own candidate range (stride indices s0 .. s_max of that position).
+template <typename T, int D, int RMAX>
+__global__ __launch_bounds__(kDecodeSearchThreads) void anchor_search_block_batched_kernel(
+    const sl_decode_seq* __restrict__ seqs, int G, int topk, int64_t qsh, int64_t kvsh, int64_t kvst,
+    int64_t window, int root) {
+  const sl_decode_seq sq = seqs[blockIdx.y];
+  const int64_t i = sq.L - 1;
+  const int64_t s_max = iroot_floor(i + 1, root) - 1;
+  const int64_t first = window > 0 ? iroot_floor(window, root) : 0;
+  const int64_t c = s_max >= first ? s_max - first + 1 : 0;
+  decode_search_block_body<T, D, RMAX>(static_cast<const T*>(sq.Qs), static_cast<const T*>(sq.K),
+                                       static_cast<const T*>(nullptr), sq.idx, sq.scores, c, (int64_t)0, G,
+                                       1, topk, qsh, kvsh ? kvsh : sq.L * kvst, kvst, i, (int)first, root);
+}
+
 // ------------------------------------------------------------------ a1 + a2: prefill, row-stationary
 // One wavefront per (head, query row); W rows per workgroup; dynamic LDS = W lane-major score arrays.
 template <typename T, int D>
@@ -427,6 +443,21 @@ sl_status launch_decode_search_batched(const Problem& pb, const sl_decode_seq* s
 }
 
 template <typename T, int D>
+sl_status launch_anchor_search_batched(const Problem& pb, const sl_decode_seq* seqs, int B, int64_t c_max,
+                                       int64_t window, int root, hipStream_t st) {
+  const int64_t kvsh = pb.kvsh_given ? pb.kvsh : 0;
+  if (c_max <= kDecodeSearchThreads)
+    hipLaunchKernelGGL((anchor_search_block_batched_kernel<T, D, 1>), dim3(pb.Hq, B),
+                       dim3(kDecodeSearchThreads), 0, st, seqs, pb.G, pb.topk, pb.qsh, kvsh, pb.kvst,
+                       window, root);
+  else
+    hipLaunchKernelGGL((anchor_search_block_batched_kernel<T, D, 4>), dim3(pb.Hq, B),
+                       dim3(kDecodeSearchThreads), 0, st, seqs, pb.G, pb.topk, pb.qsh, kvsh, pb.kvst,
+                       window, root);
+  return hipGetLastError() == hipSuccess ? SL_OK : SL_ERR_LAUNCH;
+}
+
+template <typename T, int D>
 sl_status launch_anchor_search(const Problem& pb, const void* Qs, const void* K, int32_t* anchors,
                                float* scores, int64_t c, int s0, int root, hipStream_t st) {
   if (pb.prof_start) (void)hipEventRecord(pb.prof_start, st);
@@ -532,6 +563,15 @@ sl_status anchor_search_prefill(const Problem& pb, int64_t window, int root, con
   anchor_candidates(last, window, root, &c_max, &s0);
   if (c_max > kMaxSpansLds) return SL_ERR_UNSUPPORTED;
   SL_DISPATCH(launch_anchor_search_rows, pb, Qs, K, anchors, scores, c_max, s0, root, st);
+}
+
+sl_status anchor_search_decode_batched(const Problem& pb, int64_t window, int root,
+                                       const sl_decode_seq* seqs, int B, hipStream_t st) {
+  int64_t c_max;  // of the longest sequence: candidates only grow with the position
+  int s0;
+  anchor_candidates(pb, window, root, &c_max, &s0);
+  if (c_max > (int64_t)kDecodeSearchThreads * 4) return SL_ERR_UNSUPPORTED;
+  SL_DISPATCH(launch_anchor_search_batched, pb, seqs, B, c_max, window, root, st);
 }
 
 sl_status decode_search_batched(const Problem& pb, const sl_decode_seq* seqs, int B, hipStream_t st) {

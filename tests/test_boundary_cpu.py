@@ -121,6 +121,25 @@ def test_batched_decode_argument_checks():
     assert lib.sl_span_attention_decode_batched(ctypes.byref(p), FAKE, 0, FAKE_WS, need, None) == 1
 
 
+def test_batched_combination_and_anchor_argument_checks():
+    lib = B.load()
+    p = good(Lq=1, q_pos0=4095)
+    g = B.SlAnchorGeometry(1088, 4, 2, 2, 0)
+    bad_g = B.SlAnchorGeometry(1088, 4, 2, 5, 0)          # exponent 1/5 is not offered
+    need = lib.sl_anchor_batched_workspace_bytes(ctypes.byref(p), ctypes.byref(g), 2)
+    assert need > 0
+    assert lib.sl_anchor_batched_workspace_bytes(ctypes.byref(p), ctypes.byref(bad_g), 2) == 0
+    assert lib.sl_anchor_batched_workspace_bytes(ctypes.byref(p), ctypes.byref(g), 0) == 0
+    assert lib.sl_anchor_search_decode_batched(ctypes.byref(p), ctypes.byref(g), None, 2, None) == 1
+    assert lib.sl_anchor_search_decode_batched(ctypes.byref(p), ctypes.byref(bad_g), FAKE, 2, None) == 1
+    assert lib.sl_anchor_search_decode_batched(ctypes.byref(good()), ctypes.byref(g), FAKE, 2, None) == 1
+    assert lib.sl_anchor_attention_decode_batched(ctypes.byref(p), ctypes.byref(g), FAKE, 2, FAKE_WS, need - 1, None) == 3
+    assert lib.sl_anchor_attention_decode_batched(ctypes.byref(p), ctypes.byref(g), FAKE, 0, FAKE_WS, need, None) == 1
+    need_c = lib.sl_decode_batched_workspace_bytes(ctypes.byref(p), 2)
+    assert lib.sl_span_attention_combined_decode_batched(ctypes.byref(p), FAKE, 2, None, 0, None) == 3
+    assert lib.sl_span_attention_combined_decode_batched(ctypes.byref(p), None, 2, FAKE_WS, need_c, None) == 1
+
+
 def test_binding_fails_loudly_without_library(monkeypatch, tmp_path):
     monkeypatch.setattr(B, "_lib", None)
     monkeypatch.setattr(B, "LIB_PATH", str(tmp_path / "missing.so"))

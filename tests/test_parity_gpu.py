@@ -323,6 +323,57 @@ def test_decode_batched(seed, Hq, Hkv, D, S, k, dtype, lengths, shared, with_ks)
         check_attention(O[b], LSE[b], Qs[b], Ksrc[b].contiguous(), Vsrc[b].contiguous(), idx[b], S, Lb - 1, 0.0)
 
 
+@pytest.mark.parametrize("seed,Hq,Hkv,D,S,k,dtype,lengths", [
+    (6, 16, 2, 128, 128, 8, torch.bfloat16, [20000, 300, 9000]),
+    (7, 4, 4, 64, 64, 4, torch.float32, [4096, 64, 1]),
+])
+def test_decode_batched_combination_form(seed, Hq, Hkv, D, S, k, dtype, lengths):
+    Qs, Kc, Vc = [], [], []
+    for b, Lb in enumerate(lengths):
+        Q, K, V = make(seed * 100 + b, Hq, Hkv, Lb, D, dtype, Lq=1)
+        Qs.append(Q), Kc.append(K), Vc.append(V)
+    batch = B.DecodeBatch(Qs, Qs, Kc, Vc, None, S, k, want_scores=True)
+    idx, sc = B.sl_span_search_decode_batched(batch)
+    torch.cuda.synchronize()
+    sc.copy_(torch.where(torch.isfinite(sc), sc, torch.zeros_like(sc)))   # empty slots: any finite gate
+    O = B.sl_span_attention_combined_decode_batched(batch)
+    torch.cuda.synchronize()
+    for b, Lb in enumerate(lengths):
+        check_combined(O[b], Qs[b], Kc[b], Vc[b], idx[b], sc[b], S, Lb - 1, 0.0)
+
+
+@pytest.mark.parametrize("seed,Hq,Hkv,D,k,w,bf,ff,root,dtype,lengths", [
+    (8, 8, 2, 128, 2, 1088, 4, 2, 2, torch.bfloat16, [70000, 1500, 20, 33000]),   # the paper's kernel configuration
+    (9, 4, 4, 64, 3, 0, 2, 0, 2, torch.float32, [31, 900, 2]),                    # no window
+    (10, 4, 1, 128, 4, 30, 2, 1, 3, torch.bfloat16, [50000, 4000]),               # exponents 1/3 and 2/3
+])
+def test_anchor_decode_batched(seed, Hq, Hkv, D, k, w, bf, ff, root, dtype, lengths):
+    """The paper's geometry for a batch: anchors bit-equal to the single-sequence entry point,
+    outputs against the oracle's gated combination."""
+    G = Hq // Hkv
+    Qs, Kc, Vc = [], [], []
+    for b, Lb in enumerate(lengths):
+        Q, K, V = make(seed * 100 + b, Hq, Hkv, Lb, D, dtype, Lq=1, scale=0.5)
+        Qs.append(Q), Kc.append(K), Vc.append(V)
+    batch = B.DecodeBatch(Qs, Qs, Kc, Vc, None, 1, k, want_scores=True)
+    an, sc = B.sl_anchor_search_decode_batched(batch, w, search_root=root)
+    torch.cuda.synchronize()
+    for b in range(len(lengths)):
+        a1, s1 = B.sl_anchor_search_decode(Qs[b], Kc[b], k, w, want_scores=True, search_root=root)
+        torch.cuda.synchronize()
+        assert torch.equal(an[b], a1) and torch.equal(sc[b], s1), b
+    sc.copy_(torch.where(torch.isfinite(sc), sc, torch.zeros_like(sc)))
+    O = B.sl_anchor_attention_decode_batched(batch, w, bf, ff, search_root=root)
+    torch.cuda.synchronize()
+    for b, Lb in enumerate(lengths):
+        On, Qn, ann, scn = f64(O[b]), f64(Qs[b]), an[b].cpu().numpy(), sc[b].cpu().numpy().astype(np.float64)
+        Kd, Vd = DevKV(Kc[b]), DevKV(Vc[b])
+        for h in range(Hq):
+            o = orc.anchor_combined_row(Qn[h, 0], Kd, Vd, h // G, Lb - 1, w, bf, ff, ann[h, 0], scn[h, 0],
+                                        1.0 / math.sqrt(D), root=root)
+            assert float(np.max(np.abs(On[h, 0] - o))) <= TOL[dtype], (b, h)
+
+
 def test_decode_batched_rejects_what_it_cannot_serve():
     Hq, Hkv, D, S, k = 4, 2, 64, 16, 4
     Q, K, V = make(5, Hq, Hkv, 16 * 5000, D, torch.bfloat16, Lq=1)
