@@ -242,7 +242,28 @@ def bench_decode(cfg, steps, warmup, torch, B, W):
                "ms_per_step": dt_batched * 1e3, "value": NB / dt_batched, "unit": "sequence-steps/s",
                "algorithmic_bytes": bbytes / nrot,
                "step_hbm_frac": bbytes / nrot / dt_batched / PEAK_HBM}
-    del Kc, Vc, Ksc, batches, bgraph
+    # ... and the same batch on the paper's geometry (anchors, gated combination)
+    pbatch = B.DecodeBatch([Qs[b % N_DECODE_QUERIES] for b in range(NB)], [Qs[b % N_DECODE_QUERIES] for b in range(NB)],
+                           Kc, Vc, None, 1, PK, want_scores=True)
+
+    def step_batched_paper():
+        B.sl_anchor_search_decode_batched(pbatch, PW)
+        B.sl_anchor_attention_decode_batched(pbatch, PW, PB, PF, ws=ws)
+
+    step_batched_paper()
+    torch.cuda.synchronize()
+    pbgraph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(pbgraph):
+        step_batched_paper()
+    pbgraph.replay()
+    torch.cuda.synchronize()
+    tc = time.perf_counter()
+    for _ in range(nrep * 2):
+        pbgraph.replay()
+    torch.cuda.synchronize()
+    dt_bp = (time.perf_counter() - tc) / (nrep * 2)
+    batched["paper_geometry"] = {"ms_per_step": dt_bp * 1e3, "value": NB / dt_bp, "unit": "sequence-steps/s"}
+    del Kc, Vc, Ksc, batches, bgraph, pbatch, pbgraph
     # Dominant kernel (K/V streaming + fused merge): a graph of N_DECODE_QUERIES back-to-back
     # span-attention launches, timed with HIP events on the launch stream.
     idx_dev = [torch.from_numpy(ix).to(dev) for ix in idxs]
