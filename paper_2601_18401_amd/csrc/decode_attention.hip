@@ -99,11 +99,11 @@ __device__ __forceinline__ void decode_split_body(
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
 
-  // Spans (grid indices or anchor tokens) that several heads of a kv head select are read once: the entry (head,
-  // slot) that comes first in the group's index rows owns the chunk and computes the partial of
-  // every other entry that lists the same span from the rows it has just pulled through the L2;
-  // the workgroups of those entries leave at once.  Needs the group's G * topk indices in one
-  // pass of a wavefront (larger groups: every entry reads its own span, as before).
+  // Spans (grid indices, or anchor tokens) that several heads of a kv head select are read once:
+  // the entry (head, slot) that comes first in the group's index rows owns the chunk and computes
+  // the partial of every other entry that lists the same span from the rows it has just pulled
+  // through the L2; the workgroups of those entries leave at once.  Needs the group's G * topk
+  // indices in one pass of a wavefront (larger groups: every entry reads its own span).
   constexpr int kShareWords = 4;  // up to 256 (head, slot) entries per kv head
   const bool dedup = slot < topk && G * topk <= 64 * kShareWords && G > 1;
   const int64_t jlimit = ar.on ? q_pos + 1 : c;  // valid entries: anchor tokens <= q_pos, resp. spans < c
