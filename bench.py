@@ -67,7 +67,7 @@ def prefill_flops(cfg):
 
 # HBM bytes per launch of each configuration's dominant kernel, from the FETCH_SIZE and WRITE_SIZE
 # counter runs whose summaries are under profiles/ (scaled by the 1 GiB copy calibration).
-MEASURED_TRAFFIC = {"C3": 268.1e6, "C5": 1081.0e6, "C4": 37.0e9}
+MEASURED_TRAFFIC = {"C3": 258.5e6, "C5": 1053.5e6, "C4": 37.0e9}
 
 
 def decode_bytes(cfg, idx, q_pos):
