@@ -360,6 +360,6 @@ const char* sl_status_string(int status) {
   return "unknown sl_status";
 }
 
-int sl_version(void) { return 100; }
+int sl_version(void) { return 200; }  // 0.2.0: batched decode entry points
 
 }  // extern "C"
