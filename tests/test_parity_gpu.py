@@ -517,6 +517,87 @@ def test_prefill_randomized_shapes(case_seed):
             raise AssertionError(f"case {where}: {e}") from e
 
 
+@pytest.mark.parametrize("case_seed", [201, 202])
+def test_decode_randomized_shapes(case_seed):
+    # seeded random decode steps: one sequence or a batch, joint or gated form, grid or the paper's
+    # geometry, fp32 or bf16, packed caches or slots of one buffer, heads sharing some of their spans
+    import random
+    rng = random.Random(case_seed)
+    for _ in range(10):
+        G, Hkv = rng.choice([1, 2, 4, 8]), rng.choice([1, 2, 4])
+        Hq = G * Hkv
+        D, dtype = rng.choice([64, 128]), rng.choice([torch.float32, torch.bfloat16])
+        S, k = rng.choice([16, 33, 64, 100, 128, 256]), rng.choice([1, 2, 4, 8, 16])
+        lens = [rng.randint(1, 12000) for _ in range(rng.randint(1, 4))]
+        shared, form = rng.random() < 0.5, rng.choice(["joint", "gated", "anchor"])
+        seed = rng.randint(0, 10 ** 6)
+        where = (seed, Hq, Hkv, D, dtype, S, k, lens, shared, form)
+        Qs, Kc, Vc = [], [], []
+        if shared:
+            Kbuf = torch.zeros((len(lens), Hkv, max(lens), D), dtype=dtype, device=DEV)
+            Vbuf = torch.zeros_like(Kbuf)
+        for b, Lb in enumerate(lens):
+            Q, K, V = make(seed + b, Hq, Hkv, Lb, D, dtype, Lq=1, scale=0.7)
+            if shared:
+                Kbuf[b, :, :Lb], Vbuf[b, :, :Lb] = K, V
+                K, V = Kbuf[b, :, :Lb], Vbuf[b, :, :Lb]
+            Qs.append(Q), Kc.append(K), Vc.append(V)
+        try:
+            if form == "anchor":
+                w, bf, ff, root = rng.choice([0, 5, 48, 300, 1088]), rng.choice([1, 2, 4]), rng.choice([0, 1, 2]), rng.choice([2, 3])
+                batch = B.DecodeBatch(Qs, Qs, Kc, Vc, None, 1, k, want_scores=True)
+                an, sc = B.sl_anchor_search_decode_batched(batch, w, search_root=root)
+                torch.cuda.synchronize()
+                for b in range(len(lens)):
+                    a1, s1 = B.sl_anchor_search_decode(Qs[b], Kc[b], k, w, want_scores=True, search_root=root)
+                    torch.cuda.synchronize()
+                    assert torch.equal(an[b], a1) and torch.equal(sc[b], s1), b
+                sc.copy_(torch.where(torch.isfinite(sc), sc, torch.zeros_like(sc)))
+                O = B.sl_anchor_attention_decode_batched(batch, w, bf, ff, search_root=root)
+                torch.cuda.synchronize()
+                for b, Lb in enumerate(lens):
+                    On, Qn, ann = f64(O[b]), f64(Qs[b]), an[b].cpu().numpy()
+                    scn = sc[b].cpu().numpy().astype(np.float64)
+                    Kd, Vd = DevKV(Kc[b].contiguous()), DevKV(Vc[b].contiguous())
+                    for h in range(Hq):
+                        o = orc.anchor_combined_row(Qn[h, 0], Kd, Vd, h // G, Lb - 1, w, bf, ff, ann[h, 0],
+                                                    scn[h, 0], 1.0 / math.sqrt(D), root=root)
+                        assert float(np.max(np.abs(On[h, 0] - o))) <= TOL[dtype], (b, h)
+                continue
+            Kss = [B.sl_span_keys(K, S) for K in Kc]
+            batch = B.DecodeBatch(Qs, Qs, Kc, Vc, Kss if rng.random() < 0.5 else None, S, k, want_scores=True)
+            idx, sc = B.sl_span_search_decode_batched(batch)
+            torch.cuda.synchronize()
+            for b, Lb in enumerate(lens):
+                check_idx(idx[b], Qs[b], Kss[b], S, k, Lb - 1)
+                if G > 1:    # heads 1.. of every group take over part of head 0's list (later duplicates emptied)
+                    for kv in range(Hkv):
+                        for g in range(1, G):
+                            m = rng.choice([0, 1, k // 2, k])
+                            row = idx[b, kv * G, 0, :m].tolist() + idx[b, kv * G + g, 0, m:].tolist()
+                            seen, out = set(), []
+                            for j in row:
+                                out.append(-1 if (j >= 0 and j in seen) else j)
+                                seen.add(j)
+                            idx[b, kv * G + g, 0] = torch.tensor(out, dtype=torch.int32)
+            sc.copy_(torch.randn(sc.shape, generator=torch.Generator().manual_seed(seed)).to(DEV))
+            if form == "joint":
+                O, LSE = B.sl_span_attention_decode_batched(batch)
+                torch.cuda.synchronize()
+                for b, Lb in enumerate(lens):
+                    check_attention(O[b], LSE[b], Qs[b], Kc[b].contiguous(), Vc[b].contiguous(), idx[b], S, Lb - 1, 0.0)
+                    O1, L1 = B.sl_span_attention_decode(Qs[b], Kc[b], Vc[b], idx[b].contiguous(), S)
+                    torch.cuda.synchronize()
+                    check_attention(O1, L1, Qs[b], Kc[b].contiguous(), Vc[b].contiguous(), idx[b], S, Lb - 1, 0.0)
+            else:
+                O = B.sl_span_attention_combined_decode_batched(batch)
+                torch.cuda.synchronize()
+                for b, Lb in enumerate(lens):
+                    check_combined(O[b], Qs[b], Kc[b].contiguous(), Vc[b].contiguous(), idx[b], sc[b], S, Lb - 1, 0.0)
+        except AssertionError as e:
+            raise AssertionError(f"case {where}: {e}") from e
+
+
 def test_prefill_and_decode_replay_in_a_hip_graph():
     # the entry points enqueue kernels only (no allocation, no memset nodes): a captured step must
     # give the eager result on every replay, with other work on the device between the replays
