@@ -288,8 +288,44 @@ struct TileDesc {
 struct FlashCarry {
   int kb, vb;
   bool primed;
+  bool pending;  // the previous tile's output still sits in LDS (routed tiles write it out a step later)
   bf16x8 qf[8];
 };
+
+// Writes a wavefront's staged output rows (normalised partial o as bf16, lse) of a routed tile
+// from the group's LDS region to the partial buffers: 16 lanes per row, 16 bytes per lane.
+// Called when no direct global->LDS load is in flight (the compiler orders an LDS read after all
+// outstanding vector-memory operations once such loads exist).
+__device__ __forceinline__ void flush_routed_output(const FlashArgs& a, char* lds, int grp, int w4, int lane) {
+  using Lds = FlashLds<2>;
+  const bf16_t* const ost = reinterpret_cast<const bf16_t*>(lds + Lds::kOut) + grp * TG * HD;
+  const int64_t* const row_out = reinterpret_cast<const int64_t*>(lds + Lds::kRowOut) + grp * TG;
+  const float* const row_lse = reinterpret_cast<const float*>(lds + Lds::kRowLse) + grp * TG;
+  const int piece = lane & 15;
+  // two rows per lane at a time: the tile's accumulators are live here, registers are scarce
+#pragma unroll
+  for (int ub = 0; ub < 8; ub += 2) {
+    int64_t outs[2];
+    uint4 vals[2];
+    float lses[2];
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      const int row = w4 * 32 + (ub + u) * 4 + (lane >> 4);
+      outs[u] = row_out[row];
+      lses[u] = row_lse[row];
+      vals[u] = *reinterpret_cast<const uint4*>(&ost[row * HD + ((piece ^ (row & 15)) << 3)]);
+    }
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      if (outs[u] >= 0) {
+        // streamed past the caches: the partials (gigabytes) are read back by a later kernel, and
+        // the K/V tiles keep the L2
+        store16_stream(a.part_o + outs[u] * HD + piece * 8, vals[u]);
+        if (piece == 0) __builtin_nontemporal_store(lses[u], &a.part_lse[outs[u]]);
+      }
+    }
+  }
+}
 
 // One tile of NG*128 rows.  All threads call.  If has_next, request_next() issues the caller's
 // loads for the tile this workgroup processes afterwards and describe_next() turns them into
@@ -475,6 +511,12 @@ __device__ __forceinline__ void flash_tile(const FlashArgs& a, char* lds, const 
     __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
     __syncthreads();
     const int kb1 = kb == kStagesK - 1 ? 0 : kb + 1, vb1 = vb == kStagesV - 1 ? 0 : vb + 1;
+    if (NG == 2 && !LOCAL && c.pending) {
+      // the previous tile's output: written out here, a step after it was staged, so that the wait
+      // at the top of this tile did not have to cover its stores
+      flush_routed_output(a, lds, grp, w4, lane);
+      c.pending = false;
+    }
     if (t0 + TN < cur.kv_end) stage(cur.kv, t0 + TN, kb1, vb1);
     if (NG == 2 && has_next && t0 == cur.kv_begin) request_next();
     if (grp == 0) {
@@ -597,6 +639,8 @@ __device__ __forceinline__ void flash_tile(const FlashArgs& a, char* lds, const 
         }
       }
     }
+  } else if (NG == 2 && !LOCAL) {
+    c.pending = true;  // written out during the next tile's first kv step, or by the caller after the last tile
   } else {
     // Every LDS read comes before the first store, and the values are pinned there: the compiler
     // orders an LDS read after all outstanding vector-memory operations once direct global->LDS
@@ -620,10 +664,8 @@ __device__ __forceinline__ void flash_tile(const FlashArgs& a, char* lds, const 
     for (int u = 0; u < 8; ++u) {
       const int piece = lane & 15;
       if (outs[u] >= 0) {
-        // streamed past the caches: the partials (gigabytes) are read back by a later kernel, and
-        // the K/V tiles keep the L2
-        store16_stream(a.part_o + outs[u] * HD + piece * 8, vals[u]);
-        if (piece == 0) __builtin_nontemporal_store(lses[u], &a.part_lse[outs[u]]);
+        *reinterpret_cast<uint4*>(a.part_o + outs[u] * HD + piece * 8) = vals[u];
+        if (piece == 0) a.part_lse[outs[u]] = lses[u];
       }
     }
   }
@@ -668,6 +710,7 @@ __global__ __launch_bounds__(FlashLds<2>::kThreads, 1) void span_flash_routed_ke
   FlashCarry carry;
   carry.kb = carry.vb = 0;
   carry.primed = false;
+  carry.pending = false;
   // The record and the items of a workgroup's next tile are requested during the current tile's
   // first kv step as direct global->LDS loads into the wavefront's own 512 bytes (the items of tile t sit
   // at t*TM, so the two do not depend on each other) and read back at its tail.
@@ -692,6 +735,8 @@ __global__ __launch_bounds__(FlashLds<2>::kThreads, 1) void span_flash_routed_ke
         carry);
     cur = nxt;
   }
+  // the last tile's output (its epilogue ended with the wavefront's own LDS writes)
+  if (carry.pending) flush_routed_output(a, lds, wave >> 2, wave & 3, lane);
 }
 
 // Row tiles of the local-window kernel and their grouping into chunks of `tps` tiles (the tiles
@@ -762,6 +807,7 @@ __global__ __launch_bounds__(FlashLds<1>::kThreads, 2) void span_flash_local_ker
   FlashCarry carry;
   carry.kb = carry.vb = 0;
   carry.primed = false;
+  carry.pending = false;
   TileDesc unused = d;
   flash_tile<1, true, FUSED>(a, lds, d, unused, false, [] {}, [&] { return d; }, carry);
 }
