@@ -340,7 +340,8 @@ __device__ __forceinline__ void flush_routed_output(const FlashArgs& a, char* ld
 // so that between two barriers the softmax arithmetic of one group runs in the shadow of the
 // other group's MFMAs instead of both groups asking for the matrix pipe at the same time.
 // When the kv loop is over, the first K/V stage and the Q fragments of the next tile are
-// requested before the output tile is normalised and written.
+// requested before the output tile is normalised and staged in LDS; a routed tile's staged
+// output goes to HBM during the next tile's first kv step (c.pending), a window tile's at once.
 template <int NG, bool LOCAL, bool FUSED, typename RequestNext, typename DescribeNext>
 __device__ __forceinline__ void flash_tile(const FlashArgs& a, char* lds, const TileDesc& cur,
                                            TileDesc& next, bool has_next, RequestNext&& request_next,
