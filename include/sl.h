@@ -248,7 +248,7 @@ typedef struct sl_decode_seq {
 size_t sl_decode_batched_workspace_bytes(const sl_params* p, int32_t B);
 
 /* sl_span_search_decode for every sequence of the batch: fills seq[b].idx (and scores).
- * At most 4096 candidate spans per sequence ((p->L - 1) / S <= 4096). */
+ * Limits as for one sequence (at most 12288 spans in the longest cache). */
 sl_status sl_span_search_decode_batched(const sl_params* p, const sl_decode_seq* seqs, int32_t B,
                                         void* hip_stream);
 

@@ -41,7 +41,7 @@ __device__ __forceinline__ const T* span_key_ptr(const T* K, const T* Ks, int kv
 constexpr int kDecodeSearchThreads = 1024;
 
 template <typename T, int D>
-__global__ __launch_bounds__(kDecodeSearchThreads) void decode_search_kernel(
+__device__ __forceinline__ void decode_search_body(
     const T* __restrict__ Qs, const T* __restrict__ K, const T* __restrict__ Ks,
     int32_t* __restrict__ idx, float* __restrict__ scores, int64_t c, int64_t n, int G, int S,
     int topk, int64_t qsh, int64_t kvsh, int64_t kvst) {
@@ -83,6 +83,25 @@ __global__ __launch_bounds__(kDecodeSearchThreads) void decode_search_kernel(
   if (wave == 0)
     wave_select_topk(s_sc, lm, (int)c, topk, lane, idx + (int64_t)h * topk,
                      scores ? scores + (int64_t)h * topk : nullptr);
+}
+
+template <typename T, int D>
+__global__ __launch_bounds__(kDecodeSearchThreads) void decode_search_kernel(
+    const T* __restrict__ Qs, const T* __restrict__ K, const T* __restrict__ Ks,
+    int32_t* __restrict__ idx, float* __restrict__ scores, int64_t c, int64_t n, int G, int S,
+    int topk, int64_t qsh, int64_t kvsh, int64_t kvst) {
+  decode_search_body<T, D>(Qs, K, Ks, idx, scores, c, n, G, S, topk, qsh, kvsh, kvst);
+}
+
+// Batched form (blockIdx.y = sequence); the dynamic LDS is sized for the longest sequence.
+template <typename T, int D>
+__global__ __launch_bounds__(kDecodeSearchThreads) void decode_search_batched_kernel(
+    const sl_decode_seq* __restrict__ seqs, int G, int S, int topk, int64_t qsh, int64_t kvsh,
+    int64_t kvst) {
+  const sl_decode_seq sq = seqs[blockIdx.y];
+  decode_search_body<T, D>(static_cast<const T*>(sq.Qs), static_cast<const T*>(sq.K),
+                           static_cast<const T*>(sq.Ks), sq.idx, sq.scores, (sq.L - 1) / S,
+                           (sq.L + S - 1) / S, G, S, topk, qsh, kvsh ? kvsh : sq.L * kvst, kvst);
 }
 
 // ------------------------------------------------------------------ a7: decode search, block-parallel select
@@ -431,7 +450,11 @@ sl_status launch_decode_search_batched(const Problem& pb, const sl_decode_seq* s
                                        hipStream_t st) {
   const int64_t c_max = pb.q_pos0 / pb.S;  // of the longest sequence
   const int64_t kvsh = pb.kvsh_given ? pb.kvsh : 0;
-  if (c_max <= kDecodeSearchThreads)
+  if (c_max > (int64_t)kDecodeSearchThreads * 4)
+    hipLaunchKernelGGL((decode_search_batched_kernel<T, D>), dim3(pb.Hq, B), dim3(kDecodeSearchThreads),
+                       (size_t)LaneMajor::make(c_max).lds_floats() * sizeof(float), st, seqs, pb.G, pb.S,
+                       pb.topk, pb.qsh, kvsh, pb.kvst);
+  else if (c_max <= kDecodeSearchThreads)
     hipLaunchKernelGGL((decode_search_block_batched_kernel<T, D, 1>), dim3(pb.Hq, B),
                        dim3(kDecodeSearchThreads), 0, st, seqs, pb.G, pb.S, pb.topk, pb.qsh, kvsh,
                        pb.kvst);
@@ -575,7 +598,7 @@ sl_status anchor_search_decode_batched(const Problem& pb, int64_t window, int ro
 }
 
 sl_status decode_search_batched(const Problem& pb, const sl_decode_seq* seqs, int B, hipStream_t st) {
-  if (pb.q_pos0 / pb.S > (int64_t)kDecodeSearchThreads * 4) return SL_ERR_UNSUPPORTED;
+  if (pb.n > kMaxSpansLds) return SL_ERR_UNSUPPORTED;
   SL_DISPATCH(launch_decode_search_batched, pb, seqs, B, st);
 }
 

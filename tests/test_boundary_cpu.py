@@ -114,7 +114,7 @@ def test_batched_decode_argument_checks():
     assert lib.sl_span_search_decode_batched(ctypes.byref(p), FAKE, 0, None) == 1
     assert lib.sl_span_search_decode_batched(ctypes.byref(p), ctypes.c_void_p(0x1004), 3, None) == 1
     assert lib.sl_span_search_decode_batched(ctypes.byref(good()), FAKE, 3, None) == 1
-    big = good(L=64 * 5000, Lq=1, q_pos0=64 * 5000 - 1)                              # > 4096 candidates
+    big = good(L=64 * 13000, Lq=1, q_pos0=64 * 13000 - 1)                            # > 12288 spans
     assert lib.sl_span_search_decode_batched(ctypes.byref(big), FAKE, 3, None) == 2
     assert lib.sl_span_attention_decode_batched(ctypes.byref(p), FAKE, 3, None, 0, None) == 3
     assert lib.sl_span_attention_decode_batched(ctypes.byref(p), FAKE, 3, FAKE_WS, need - 1, None) == 3

@@ -291,6 +291,7 @@ DECODE_BATCHED = [
     (2, 4, 4, 64, 64, 4, torch.float32, [4096, 40, 1, 3000, 64], True, False),
     (3, 8, 2, 128, 64, 8, torch.bfloat16, [64 * 700, 64 * 300 + 5], False, False),   # > 256 candidates
     (4, 8, 1, 128, 96, 6, torch.bfloat16, [5000], True, True),                       # batch of one
+    (5, 4, 2, 64, 16, 8, torch.bfloat16, [16 * 5000 + 3, 16 * 300], False, True),    # > 4096 candidates: wide search kernel
 ]
 
 
@@ -376,9 +377,9 @@ def test_anchor_decode_batched(seed, Hq, Hkv, D, k, w, bf, ff, root, dtype, leng
 
 def test_decode_batched_rejects_what_it_cannot_serve():
     Hq, Hkv, D, S, k = 4, 2, 64, 16, 4
-    Q, K, V = make(5, Hq, Hkv, 16 * 5000, D, torch.bfloat16, Lq=1)
+    Q, K, V = make(5, Hq, Hkv, 16 * 13000, D, torch.bfloat16, Lq=1)
     batch = B.DecodeBatch([Q], [Q], [K], [V], None, S, k)
-    with pytest.raises(B.SlError):                     # more than 4096 candidate spans
+    with pytest.raises(B.SlError):                     # more than 12288 spans
         B.sl_span_search_decode_batched(batch)
     batch.B = 0
     with pytest.raises(B.SlError):
