@@ -53,8 +53,12 @@ struct TopVals {
 // the compare-and-select chains that carrying the indices along would need.
 // WS: the scores of the selected spans are written too (their list costs LDS, which limits the
 // resident workgroups; most callers only want the indices).
+// The kernel is bound by the latency of its stages (two barriers and a global -> register -> LDS
+// hand-over per 64 span keys), so resident workgroups count: without the score list and with
+// topk <= 8 the registers are capped at 128 for a fourth workgroup per compute unit (-8 % at 256K
+// tokens, -14 % at 64K; a fifth would spill).
 template <int KMAX, bool WS>
-__global__ __launch_bounds__(256) void prefill_search_mfma_kernel(
+__global__ __launch_bounds__(256, (KMAX == 8 && !WS) ? 4 : 1) void prefill_search_mfma_kernel(
     const bf16_t* __restrict__ Qs, const bf16_t* __restrict__ K, const bf16_t* __restrict__ Ks,
     int32_t* __restrict__ idx, float* __restrict__ scores, int64_t Lq, int64_t q_pos0, int G, int S,
     int topk, int64_t n, int64_t qsh, int64_t qst, int64_t kvsh, int64_t kvst) {
