@@ -37,6 +37,25 @@ def test_library_exports_every_declared_symbol():
         assert B.status_string(s).startswith("SL_ERR_")
 
 
+def test_header_is_plain_c():
+    """The boundary is a C ABI: the header must compile as C99 and as C++ on its own."""
+    import shutil
+    import subprocess
+    hdr = os.path.join(ROOT, "include", "sl.h")
+    if shutil.which("gcc"):
+        subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only", "-x", "c", hdr],
+                       check=True)
+    if shutil.which("g++"):
+        subprocess.run(["g++", "-std=c++11", "-Wall", "-Werror", "-fsyntax-only", "-x", "c++", hdr], check=True)
+
+
+def test_struct_layouts_match_the_header():
+    # sl_anchor_geometry: int64 + 4 x int32; sl_decode_seq: 9 pointers + int64
+    assert ctypes.sizeof(B.SlAnchorGeometry) == 24
+    assert ctypes.sizeof(B.SlDecodeSeq) == 80
+    assert B.SlDecodeSeq.L.offset == 72 and B.SlDecodeSeq.idx.offset == 40
+
+
 def test_params_struct_matches_header_size():
     # 3 x int64, 6 x int32, float, int32, 4 x int64, 2 pointers
     assert ctypes.sizeof(B.SlParams) == 24 + 24 + 8 + 32 + 16
