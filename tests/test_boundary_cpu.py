@@ -49,6 +49,20 @@ def test_header_is_plain_c():
         subprocess.run(["g++", "-std=c++11", "-Wall", "-Werror", "-fsyntax-only", "-x", "c++", hdr], check=True)
 
 
+def test_library_is_callable_from_plain_c(tmp_path):
+    """A C99 program includes sl.h, loads libsl.so and calls the host-only entry points."""
+    import shutil
+    import subprocess
+    if not shutil.which("gcc"):
+        pytest.skip("no C compiler")
+    B.load()   # raises if the library has not been built
+    exe = str(tmp_path / "call_from_c")
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-I", os.path.join(ROOT, "include"),
+                    os.path.join(ROOT, "tests", "cabi", "call_from_c.c"), "-o", exe, "-ldl"], check=True)
+    out = subprocess.run([exe, B.LIB_PATH], check=True, capture_output=True, text=True).stdout
+    assert "ok=SL_OK" in out and "bad=SL_ERR_INVALID_ARG" in out, out
+
+
 def test_struct_layouts_match_the_header():
     # sl_anchor_geometry: int64 + 4 x int32; sl_decode_seq: 9 pointers + int64
     assert ctypes.sizeof(B.SlAnchorGeometry) == 24
