@@ -550,6 +550,12 @@ void launch_split_batched(int grid, int B, hipStream_t st, const sl_decode_seq* 
                        kvsh, pb.kvst, n_routed, local_stride, ab);
 }
 
+// The reductions keep one weight (joint form) or two statistics (gated form) per partial record of
+// a head in dynamic LDS; a kernel gets 64 KB without asking for more.
+inline bool reduce_fits_lds(int64_t nrec, bool combined) {
+  return nrec * (combined ? 2 : 1) * (int64_t)sizeof(float) <= 64 * 1024;
+}
+
 int pick_chunk_tokens(const Problem& pb, int batch = 1) {
   // Aim for a few thousand workgroups so the 256 CUs keep enough loads in flight, without
   // going below 64 tokens per item.
@@ -568,10 +574,11 @@ sl_status launch_decode(const Problem& pb, const void* Q, const void* K, const v
   const int local_stride = (int)align_up((size_t)pb.Hkv * nchunks, 8);
   const int grid = n_routed + pb.G * local_stride;
   float* part = static_cast<float*>(ws);
+  const int nrec = (pb.topk + 1) * nchunks;
+  if (!reduce_fits_lds(nrec, pb.combined)) return SL_ERR_UNSUPPORTED;  // before anything is enqueued
   launch_split<T, D>(grid, st, Q, K, V, idx, part, pb, pb.S, nchunks, CT, n_routed, local_stride,
                      AnchorRanges{false, 0, 0, 0});
   if (hipGetLastError() != hipSuccess) return SL_ERR_LAUNCH;
-  const int nrec = (pb.topk + 1) * nchunks;
   if (pb.combined) {
     hipLaunchKernelGGL((decode_reduce_combined_kernel<T, D>), dim3(pb.Hq, D / kReduceDims), dim3(256),
                        (size_t)2 * nrec * sizeof(float), st, part, pb.gate, static_cast<T*>(O),
@@ -621,9 +628,10 @@ sl_status launch_anchor_attention(const Problem& pb, const AnchorPlan& a, const 
   const AnchorRanges ar{true, a.wlo, a.back, a.fwd};
   // every (head, slot, chunk) is a routed item here: the window is slot topk of every head
   const int grid = units * a.nchunks;
+  const int nrec = (pb.topk + 1) * a.nchunks;
+  if (!reduce_fits_lds(nrec, true)) return SL_ERR_UNSUPPORTED;
   launch_split<T, D>(grid, st, Q, K, V, anchors, part, pb, 1, a.nchunks, a.CT, grid, 8, ar);
   if (hipGetLastError() != hipSuccess) return SL_ERR_LAUNCH;
-  const int nrec = (pb.topk + 1) * a.nchunks;
   hipLaunchKernelGGL((decode_reduce_combined_kernel<T, D>), dim3(pb.Hq, D / kReduceDims), dim3(256),
                      (size_t)2 * nrec * sizeof(float), st, part, pb.gate, static_cast<T*>(O), pb.topk,
                      a.nchunks);
@@ -636,6 +644,7 @@ sl_status launch_decode_batched(const Problem& pb, const sl_decode_seq* seqs, in
   const int CT = pick_chunk_tokens(pb, B);
   const int nchunks = (pb.S + CT - 1) / CT;
   const int nrec = (pb.topk + 1) * nchunks;
+  if (!reduce_fits_lds(nrec, pb.combined)) return SL_ERR_UNSUPPORTED;
   const int64_t part_stride = (int64_t)pb.Hq * nrec * (D + 2);
   float* part = static_cast<float*>(ws);
   // same grid as the single-sequence launch in x, the sequence in y
@@ -660,6 +669,7 @@ sl_status launch_anchor_batched(const Problem& pb, const AnchorPlan& a, const An
                                 const sl_decode_seq* seqs, int B, void* ws, hipStream_t st) {
   const int units = pb.Hq * (pb.topk + 1);
   const int nrec = (pb.topk + 1) * a.nchunks;
+  if (!reduce_fits_lds(nrec, true)) return SL_ERR_UNSUPPORTED;
   const int64_t part_stride = (int64_t)pb.Hq * nrec * (D + 2);
   float* part = static_cast<float*>(ws);
   const int grid = units * a.nchunks;  // every (head, slot, chunk) is a routed item, as for one sequence

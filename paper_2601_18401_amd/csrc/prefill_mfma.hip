@@ -39,7 +39,7 @@ typedef float f32x8 __attribute__((ext_vector_type(8)));
 constexpr int TG = 128;            // rows of one wavefront group (4 wavefronts x 32 columns)
 constexpr int TN = 64;             // kv positions per staged tile
 constexpr int HD = 128;            // head dimension of this path
-constexpr int kBucketRows = 1024;  // query rows of one head per bucketing workgroup
+constexpr int kBucketRows = 4096;  // query rows of one head per bucketing workgroup
 
 // LDS of the flash kernels (dynamic).  Main loop: stages of the V^T tile and of the K tile, filled
 // by direct global->LDS loads (16 bytes per lane, a wavefront instruction fills 1 KB
@@ -121,60 +121,98 @@ __global__ __launch_bounds__(256) void transpose_v_kernel(const bf16_t* __restri
 }
 
 // ------------------------------------------------------------------ bucketing
-__global__ void zero_i32_kernel(int* p, int n) {
-  const int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n) p[i] = 0;
-}
-
-// grid (ceil(Lq / kBucketRows), Hq).  FILL = false: count items per (kv, span).  FILL = true:
-// reserve a range per non-empty bin with one global atomic, then scatter the row ids.
+// Inverts idx into per-(kv head, span) lists of (row, slot) items without a sort and without
+// global atomics, so that the item order is the same on every run: within a bucket the items come
+// by query head of the group, then by query row.
+//   bucket_kernel<false>      grid (chunks of kBucketRows rows, Hq): LDS histogram of the block's
+//                             items per span -> blk_cnt[h][chunk][span]
+//   bucket_block_scan_kernel  per (kv head, span): exclusive scan of blk_cnt over (head of the
+//                             group, chunk), in place; the total goes to g_count
+//   bucket_scan_kernel / bucket_tiles_kernel   bucket offsets and tile records
+//   bucket_kernel<true>       recounts per wavefront (each owns a contiguous quarter of the block's
+//                             rows), turns the counts into bases behind the block's prefix and
+//                             scatters the items
 template <bool FILL>
 __global__ __launch_bounds__(256) void bucket_kernel(const int32_t* __restrict__ idx,
-                                                     int* __restrict__ g_count,
-                                                     int* __restrict__ g_cursor,
+                                                     int* __restrict__ blk_cnt,
+                                                     const int* __restrict__ g_cursor,
                                                      int* __restrict__ items, int64_t Lq,
                                                      int64_t q_pos0, int G, int S, int topk, int n) {
-  extern __shared__ int s_hist[];  // [n] counts, then (FILL) [n] bases
-  int* s_base = s_hist + n;
-  const int h = blockIdx.y, kv = h / G, hl = h % G, tid = threadIdx.x;
-  const int64_t r0 = (int64_t)blockIdx.x * kBucketRows;
-  for (int b = tid; b < n; b += 256) s_hist[b] = 0;
+  extern __shared__ int s_hist[];  // count pass: [n]; fill pass: [4][n], one histogram per wavefront
+  const int h = blockIdx.y, kv = h / G, hl = h % G;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int64_t r0 = (int64_t)blockIdx.x * kBucketRows + wave * (kBucketRows / 4);
+  int* const blk = blk_cnt + ((int64_t)h * gridDim.x + blockIdx.x) * n;
+  int* const hist = FILL ? s_hist + wave * n : s_hist;
+  for (int b = tid; b < (FILL ? 4 : 1) * n; b += 256) s_hist[b] = 0;
   __syncthreads();
-  for (int i = 0; i < kBucketRows / 256; ++i) {
-    const int64_t r = r0 + tid + 256 * i;
-    if (r < Lq) {
-      const int64_t c = (q_pos0 + r) / S;
-      const int32_t* row = idx + ((int64_t)h * Lq + r) * topk;
-      for (int s = 0; s < topk; ++s) {
-        const int j = row[s];
-        if (j >= 0 && j < c) atomicAdd(&s_hist[j], 1);
+  auto for_items = [&](auto f) {
+    for (int i = 0; i < kBucketRows / 256; ++i) {
+      const int64_t r = r0 + 64 * i + lane;
+      if (r < Lq) {
+        const int64_t c = (q_pos0 + r) / S;
+        const int32_t* row = idx + ((int64_t)h * Lq + r) * topk;
+        for (int s = 0; s < topk; ++s) {
+          const int j = row[s];
+          if (j >= 0 && j < c) f(j, r, s);
+        }
       }
     }
-  }
+  };
+  for_items([&](int j, int64_t, int) { atomicAdd(&hist[j], 1); });
   __syncthreads();
   if (!FILL) {
-    for (int b = tid; b < n; b += 256)
-      if (s_hist[b]) atomicAdd(&g_count[kv * n + b], s_hist[b]);
+    for (int b = tid; b < n; b += 256) blk[b] = s_hist[b];
     return;
   }
   for (int b = tid; b < n; b += 256) {
-    const int cnt = s_hist[b];
-    s_base[b] = cnt ? atomicAdd(&g_cursor[kv * n + b], cnt) : 0;
-    s_hist[b] = 0;
-  }
-  __syncthreads();
-  for (int i = 0; i < kBucketRows / 256; ++i) {
-    const int64_t r = r0 + tid + 256 * i;
-    if (r < Lq) {
-      const int64_t c = (q_pos0 + r) / S;
-      const int32_t* row = idx + ((int64_t)h * Lq + r) * topk;
-      for (int s = 0; s < topk; ++s) {
-        const int j = row[s];
-        if (j >= 0 && j < c)
-          items[s_base[j] + atomicAdd(&s_hist[j], 1)] = (int)(((hl * Lq + r) << 5) | s);
-      }
+    int base = g_cursor[kv * n + b] + blk[b];
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      const int cnt = s_hist[w * n + b];
+      s_hist[w * n + b] = base;
+      base += cnt;
     }
   }
+  __syncthreads();
+  for_items([&](int j, int64_t r, int s) { items[atomicAdd(&hist[j], 1)] = (int)(((hl * Lq + r) << 5) | s); });
+}
+
+// grid (ceil(n / 32), Hkv), 256 threads = 32 spans x 8 segments of the E = G * chunks block counts
+// of a (kv head, span): exclusive scan in place, total to g_count.
+__global__ __launch_bounds__(256) void bucket_block_scan_kernel(int* __restrict__ blk_cnt,
+                                                                int* __restrict__ g_count, int E, int n) {
+  __shared__ int s_tot[8][32];
+  const int bl = threadIdx.x & 31, seg = threadIdx.x >> 5;
+  const int b = blockIdx.x * 32 + bl, kv = blockIdx.y;
+  const int per = (E + 7) / 8, e0 = seg * per, e1 = min(E, e0 + per);
+  int* const col = blk_cnt + (int64_t)kv * E * n + b;
+  int sum = 0;
+  if (b < n) {
+    for (int e = e0; e < e1; e += 8) {
+      int v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) v[u] = e + u < e1 ? col[(int64_t)(e + u) * n] : 0;
+#pragma unroll
+      for (int u = 0; u < 8; ++u) sum += v[u];
+    }
+  }
+  s_tot[seg][bl] = sum;
+  __syncthreads();
+  if (b >= n) return;
+  int run = 0;
+  for (int s2 = 0; s2 < seg; ++s2) run += s_tot[s2][bl];
+  for (int e = e0; e < e1; e += 8) {
+    int v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = e + u < e1 ? col[(int64_t)(e + u) * n] : 0;
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      if (e + u < e1) col[(int64_t)(e + u) * n] = run;
+      run += v[u];
+    }
+  }
+  if (seg == 7) g_count[kv * n + b] = run;
 }
 
 // One workgroup: exclusive scans of the item counts and of the tile counts over the B buckets.
@@ -454,13 +492,14 @@ __device__ __forceinline__ void flash_tile(const FlashArgs& a, char* lds, const 
         mx = fmaxf(mx, s[sub][r]);
       }
     mx = pair_max(mx) * sc;
-    // Lazy rescale: the running maximum only moves when some column of the wavefront grew by
-    // more than 2^8; until then exponentials are taken against the old maximum (p <= 256).
+    // Lazy rescale, decided per column: a column's running maximum only moves when that column
+    // grew by more than 2^8; until then its exponentials are taken against the old maximum
+    // (p <= 256).  The branch is per wavefront, the arithmetic of a column does not depend on the
+    // columns it shares the wavefront with (so a row's result does not depend on its tile-mates).
     const bool grow = mx > m + 8.f || (m == -INFINITY && mx > -INFINITY);
     if (__builtin_amdgcn_ballot_w64(grow) != 0ull) {
-      const float m_new = fmaxf(m, mx);
-      const float alpha = m_new > -INFINITY ? fast_exp2(m - m_new) : 1.f;
-      m = m_new;
+      const float alpha = grow ? fast_exp2(m - mx) : 1.f;  // m = -inf: 0, and l and o are still 0
+      m = grow ? mx : m;
       l *= alpha;
 #pragma unroll
       for (int dt = 0; dt < 4; ++dt)
@@ -948,7 +987,8 @@ __global__ __launch_bounds__(256) void merge_combined_kernel(
 
 // ------------------------------------------------------------------ workspace carving
 struct MfmaWs {
-  size_t vt, counts, item_off, tile_off, cursor, tile_info, items, part_lse, part_o, total;
+  size_t vt, counts, blk_cnt, item_off, tile_off, cursor, tile_info, items, part_lse, part_o, total;
+  int chunks;
   int64_t Lp;
   int B, max_tiles;
   int64_t max_items;
@@ -997,6 +1037,8 @@ MfmaWs carve(const Problem& pb) {
   };
   w.vt = take((size_t)pb.Hkv * HD * w.Lp * sizeof(bf16_t));
   w.counts = take((size_t)w.B * sizeof(int));
+  w.chunks = (int)((pb.Lq + kBucketRows - 1) / kBucketRows);
+  w.blk_cnt = take((size_t)pb.Hq * w.chunks * pb.n * sizeof(int));
   w.item_off = take((size_t)(w.B + 1) * sizeof(int));
   w.tile_off = take((size_t)(w.B + 1) * sizeof(int));
   w.cursor = take((size_t)w.B * sizeof(int));
@@ -1034,6 +1076,7 @@ sl_status prefill_attention_mfma(const Problem& pb, const void* Q, const void* K
   char* base = static_cast<char*>(ws);
   bf16_t* Vt = reinterpret_cast<bf16_t*>(base + w.vt);
   int* counts = reinterpret_cast<int*>(base + w.counts);
+  int* blk_cnt = reinterpret_cast<int*>(base + w.blk_cnt);
   int* item_off = reinterpret_cast<int*>(base + w.item_off);
   int* tile_off = reinterpret_cast<int*>(base + w.tile_off);
   int* cursor = reinterpret_cast<int*>(base + w.cursor);
@@ -1075,16 +1118,17 @@ sl_status prefill_attention_mfma(const Problem& pb, const void* Q, const void* K
   a.kvst = pb.kvst;
 
   if (pb.topk > 0) {
-    const dim3 bgrid((unsigned)((pb.Lq + kBucketRows - 1) / kBucketRows), pb.Hq);
-    hipLaunchKernelGGL(zero_i32_kernel, dim3((w.B + 255) / 256), dim3(256), 0, st, counts, w.B);
+    const dim3 bgrid((unsigned)w.chunks, pb.Hq);
     hipLaunchKernelGGL(bucket_kernel<false>, bgrid, dim3(256), (size_t)n * sizeof(int), st, idx,
-                       counts, cursor, items, pb.Lq, pb.q_pos0, pb.G, pb.S, pb.topk, n);
+                       blk_cnt, cursor, items, pb.Lq, pb.q_pos0, pb.G, pb.S, pb.topk, n);
+    hipLaunchKernelGGL(bucket_block_scan_kernel, dim3((n + 31) / 32, pb.Hkv), dim3(256), 0, st, blk_cnt,
+                       counts, pb.G * w.chunks, n);
     hipLaunchKernelGGL(bucket_scan_kernel, dim3(1), dim3(1024), 0, st, counts, item_off, tile_off,
                        cursor, w.B);
     hipLaunchKernelGGL(bucket_tiles_kernel, dim3(w.B), dim3(256), 0, st, tile_off, item_off, tile_info,
                        items);
-    hipLaunchKernelGGL(bucket_kernel<true>, bgrid, dim3(256), (size_t)2 * n * sizeof(int), st, idx,
-                       counts, cursor, items, pb.Lq, pb.q_pos0, pb.G, pb.S, pb.topk, n);
+    hipLaunchKernelGGL(bucket_kernel<true>, bgrid, dim3(256), (size_t)4 * n * sizeof(int), st, idx,
+                       blk_cnt, cursor, items, pb.Lq, pb.q_pos0, pb.G, pb.S, pb.topk, n);
     if (hipGetLastError() != hipSuccess) return SL_ERR_LAUNCH;
     if (pb.prof_start) (void)hipEventRecord(pb.prof_start, st);
     hipLaunchKernelGGL(span_flash_routed_kernel, dim3(persistent_grid()),

@@ -75,3 +75,71 @@ def gated_combination(Q, K, V, idx, scores, S, scale, q_pos0=0):
     Aw, _, _ = dense_masked_attention(Q, K, V, window, scale)
     O[~any_valid] = Aw[~any_valid]
     return O, alpha
+
+
+def check_selection_all_rows(idx, Qs, Ks, S, topk, q_pos0=0, margin=1e-3, chunk=16384):
+    """Every row of a prefill span-search output against library routines, on the tensors' own device.
+
+    idx [Hq, Lq, k] int32, Qs [Hq, Lq, D], Ks [Hkv, n, D] (torch tensors).  Per head and chunk of rows:
+    the full score matrix by one fp64 matmul, the expected rows by a stable descending library sort
+    (ties to the lower span index).  A row that differs from the expected one must (1) have its k-th
+    and (k+1)-th scores within `margin`, (2) list min(k, c) distinct spans below c in ascending order,
+    -1 padding last, (3) pick no span scoring more than `margin` below the k-th score and drop none
+    scoring more than `margin` above it.  Returns (rows checked, rows that differ inside the margin);
+    raises AssertionError on the first violation."""
+    import torch
+
+    Hq, Lq, k = idx.shape
+    Hkv, n, _ = Ks.shape
+    G = Hq // Hkv
+    dev = idx.device
+    ninf = float("-inf")
+    span = torch.arange(n, device=dev)
+    differ = 0
+    for h in range(Hq):
+        Kh = Ks[h // G].double()
+        for r0 in range(0, Lq, chunk):
+            r1 = min(Lq, r0 + chunk)
+            c = (q_pos0 + torch.arange(r0, r1, device=dev)) // S                      # [R]
+            sc = Qs[h, r0:r1].double() @ Kh.T                                          # [R, n]
+            sc = torch.where(span[None, :] < c[:, None], sc, torch.full_like(sc, ninf))
+            kk = torch.clamp(c, max=k)                                                 # spans to select
+            order = torch.sort(sc, dim=1, descending=True, stable=True)
+            kcols = min(k + 1, n)
+            top_v, top_j = order.values[:, :kcols], order.indices[:, :kcols]
+            if kcols < k + 1:
+                pad = k + 1 - kcols
+                top_v = torch.cat([top_v, torch.full((r1 - r0, pad), ninf, device=dev, dtype=top_v.dtype)], 1)
+                top_j = torch.cat([top_j, torch.zeros((r1 - r0, pad), device=dev, dtype=top_j.dtype)], 1)
+            slot = torch.arange(k, device=dev)[None, :]
+            want = torch.where(slot < kk[:, None], top_j[:, :k], torch.full_like(top_j[:, :k], n + 1))
+            want = torch.sort(want, dim=1).values
+            want = torch.where(want > n, torch.full_like(want, -1), want)
+            got = idx[h, r0:r1].long()
+            valid = got >= 0
+            # shape of every row
+            assert torch.equal(valid.sum(1), kk), (h, r0, "number of listed spans")
+            assert bool((valid[:, :-1] >= valid[:, 1:]).all()), (h, r0, "padding must come last")
+            assert bool((got < c[:, None]).all()), (h, r0, "span at or beyond the query's own")
+            both = valid[:, 1:] & valid[:, :-1]
+            assert bool(((got[:, 1:] > got[:, :-1]) | ~both).all()), (h, r0, "ascending, distinct")
+            bad = (got != want).any(1)
+            nbad = int(bad.sum())
+            if nbad == 0:
+                continue
+            differ += nbad
+            rows = bad.nonzero()[:, 0]
+            kb = kk[rows]
+            assert bool((kb > 0).all())
+            s_k = top_v[rows, kb - 1]
+            s_k1 = top_v[rows, kb]                    # -inf when there is no (k+1)-th candidate
+            assert bool((s_k - s_k1 < margin).all()), (h, r0, "a row outside the tie margin differs")
+            scb, gotb, validb = sc[rows], got[rows], valid[rows]
+            picked = torch.gather(scb, 1, gotb.clamp(min=0))
+            picked = torch.where(validb, picked, torch.full_like(picked, float("inf")))
+            assert bool((picked.min(1).values >= s_k - margin).all()), (h, r0, "picked a span below the margin")
+            # scores of the spans that were not picked (empty slots point at a spare column)
+            rest = torch.cat([scb, torch.full_like(scb[:, :1], ninf)], 1)
+            rest.scatter_(1, torch.where(validb, gotb, torch.full_like(gotb, n)), ninf)
+            assert bool((rest.max(1).values <= s_k + margin).all()), (h, r0, "dropped a span above the margin")
+    return Hq * Lq, differ
