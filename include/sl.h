@@ -147,6 +147,24 @@ sl_status sl_span_attention_decode(const sl_params* p, const void* Q, const void
                                    const int32_t* idx, void* O, float* LSE, void* ws,
                                    size_t ws_bytes, void* hip_stream);
 
+/* sl_span_attention_decode for callers that cannot allocate device memory or carry a workspace:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * operation, arguments, outputs and kernels as sl_span_attention_decode, but the split-KV partial
+ * records live in a device array inside the library (sl_noalloc_scratch_bytes() bytes, 8 MiB, held
+ * by every GPU the library runs on until the process ends) instead of (ws, ws_bytes).  The call
+ * allocates and frees nothing.
+ *   - The device that owns hip_stream must be the current device.  The array's address on a
+ *     device is looked up on the first call there (not a stream operation).
+ *   - A request whose records need more than the array (sl_workspace_bytes(p, SL_OP_ATTENTION_DECODE)
+ *     > sl_noalloc_scratch_bytes()) returns SL_ERR_UNSUPPORTED and enqueues nothing.
+ *   - All calls on one GPU share that GPU's array: calls that may overlap on a GPU (different
+ *     streams without an ordering between them) race; order them on one stream or with events.
+ *     Nothing has to be cleared between calls: every record a call reads it has written first. */
+size_t sl_noalloc_scratch_bytes(void);
+sl_status sl_span_attention_decode_noalloc(const sl_params* p, const void* Q, const void* K,
+                                           const void* V, const int32_t* idx, void* O, float* LSE,
+                                           void* hip_stream);
+
 /* Span-attention with the paper's combination step (Section 3.4, eq. (5) and (6); Algorithm 1:
  * DedupConcat + Attention per selected span, Softmax over the selected scores, weighted sum).
  * For each (h, r) and each non-empty slot t of idx: A_t = softmax attention of the query over

@@ -21,7 +21,8 @@ OP_SEARCH_PREFILL, OP_SEARCH_DECODE, OP_ATTENTION_PREFILL, OP_ATTENTION_DECODE =
 SL_MAX_TOPK = 32
 
 EXPORTS = ("sl_workspace_bytes", "sl_span_keys", "sl_span_search_prefill", "sl_span_search_decode",
-           "sl_span_attention_prefill", "sl_span_attention_decode", "sl_span_attention_combined_prefill",
+           "sl_span_attention_prefill", "sl_span_attention_decode", "sl_noalloc_scratch_bytes",
+           "sl_span_attention_decode_noalloc", "sl_span_attention_combined_prefill",
            "sl_span_attention_combined_decode", "sl_anchor_workspace_bytes", "sl_anchor_search_decode",
            "sl_anchor_attention_decode", "sl_anchor_search_prefill", "sl_anchor_attention_prefill",
            "sl_decode_batched_workspace_bytes", "sl_span_search_decode_batched",
@@ -88,6 +89,10 @@ def load():
         fn = getattr(lib, name)
         fn.restype = ctypes.c_int
         fn.argtypes = [pp, vp, vp, vp, i32p, vp, f32p, vp, ctypes.c_size_t, vp]
+    lib.sl_noalloc_scratch_bytes.restype = ctypes.c_size_t
+    lib.sl_noalloc_scratch_bytes.argtypes = []
+    lib.sl_span_attention_decode_noalloc.restype = ctypes.c_int
+    lib.sl_span_attention_decode_noalloc.argtypes = [pp, vp, vp, vp, i32p, vp, f32p, vp]
     for name in ("sl_span_attention_combined_prefill", "sl_span_attention_combined_decode"):
         fn = getattr(lib, name)
         fn.restype = ctypes.c_int
@@ -250,6 +255,25 @@ def _attention(fn_name, op, Q, K, V, idx, S, q_pos0, scale, ws, prof, out):
     st = getattr(lib, fn_name)(ctypes.byref(p), _ptr(Q), _ptr(K), _ptr(V), _ptr(idx), _ptr(O), _ptr(LSE),
                                wptr, wbytes, _stream())
     _check(st, fn_name)
+    return O, LSE
+
+
+def sl_noalloc_scratch_bytes() -> int:
+    return int(load().sl_noalloc_scratch_bytes())
+
+
+def sl_span_attention_decode_noalloc(Q, K, V, idx, S, out, q_pos0=None, scale=0.0):
+    """sl_span_attention_decode without a workspace: the library's own device array holds the partial
+    records.  `out` = (O, LSE) must be given: this wrapper allocates nothing either."""
+    topk = 0 if idx is None else idx.shape[2]
+    q_pos0 = K.shape[1] - 1 if q_pos0 is None else q_pos0
+    p = make_params(Q, K, S, topk, q_pos0, scale)
+    if V.shape != K.shape or V.stride() != K.stride():
+        raise ValueError("V must have the shape and strides of K")
+    O, LSE = out
+    st = load().sl_span_attention_decode_noalloc(ctypes.byref(p), _ptr(Q), _ptr(K), _ptr(V), _ptr(idx),
+                                                 _ptr(O), _ptr(LSE), _stream())
+    _check(st, "sl_span_attention_decode_noalloc")
     return O, LSE
 
 

@@ -172,6 +172,21 @@ sl_status sl_span_attention_decode(const sl_params* p, const void* Q, const void
                              ws_bytes, hip_stream);
 }
 
+size_t sl_noalloc_scratch_bytes(void) { return sl::decode_attention_static_scratch_bytes(); }
+
+sl_status sl_span_attention_decode_noalloc(const sl_params* p, const void* Q, const void* K,
+                                           const void* V, const int32_t* idx, void* O, float* LSE,
+                                           void* hip_stream) {
+  sl::Problem pb;
+  sl_status s = sl::make_problem(p, SL_OP_ATTENTION_DECODE, &pb);
+  if (s != SL_OK) return s;
+  if (!Q || !K || !V || !O || !LSE || (pb.topk > 0 && !idx)) return SL_ERR_INVALID_ARG;
+  if (!sl::aligned16(Q) || !sl::aligned16(K) || !sl::aligned16(V) || !sl::aligned16(O) ||
+      !sl::aligned16(idx) || !sl::aligned16(LSE))
+    return SL_ERR_INVALID_ARG;
+  return sl::decode_attention_static(pb, Q, K, V, idx, O, LSE, static_cast<hipStream_t>(hip_stream));
+}
+
 sl_status sl_span_attention_combined_prefill(const sl_params* p, const void* Q, const void* K,
                                              const void* V, const int32_t* idx, const float* scores,
                                              void* O, void* ws, size_t ws_bytes, void* hip_stream) {

@@ -18,6 +18,11 @@ size_t decode_attention_ws_bytes(const Problem& pb);
 sl_status decode_attention(const Problem& pb, const void* Q, const void* K, const void* V,
                            const int32_t* idx, void* O, float* LSE, void* ws, hipStream_t st);
 
+// a8 + a9 with the partial records in a device array of the library (no workspace argument)
+size_t decode_attention_static_scratch_bytes();
+sl_status decode_attention_static(const Problem& pb, const void* Q, const void* K, const void* V,
+                                  const int32_t* idx, void* O, float* LSE, hipStream_t st);
+
 // a7 .. a9 for a batch of sequences (one more grid dimension; tensors and lengths per sequence
 // come from a device array)
 sl_status decode_search_batched(const Problem& pb, const sl_decode_seq* seqs, int B, hipStream_t st);
