@@ -65,9 +65,21 @@ def prefill_flops(cfg):
     return Hq * search, Hq * routed, Hq * local
 
 
-# HBM bytes per launch of each configuration's dominant kernel, from the FETCH_SIZE and WRITE_SIZE
-# counter runs whose summaries are under profiles/ (scaled by the 1 GiB copy calibration).
-MEASURED_TRAFFIC = {"C3": 258.5e6, "C5": 1053.5e6, "C4": 37.0e9}
+TRAFFIC_TABLE = os.path.join(ROOT, "profiles", "hbm_traffic_per_launch.txt")
+
+
+def recorded_traffic(name):
+    """HBM bytes per launch of a configuration's dominant kernel as recorded by rocprofv3 counter runs
+    (FETCH_SIZE + WRITE_SIZE, scaled by the 1 GiB copy calibration): read from the committed table
+    under profiles/, which names the kernel and the command of each figure.  None if not recorded."""
+    try:
+        for line in open(TRAFFIC_TABLE):
+            f = line.split()
+            if len(f) >= 3 and f[0] == name and not line.startswith("#"):
+                return float(f[2])
+    except OSError:
+        pass
+    return None
 
 
 def decode_bytes(cfg, idx, q_pos):
@@ -108,18 +120,40 @@ def bench_decode(cfg, steps, warmup, torch, B, W):
     torch.cuda.synchronize()
     # The decode step is launch-bound on the host (three short kernels), so the timed loop replays
     # a HIP graph that holds N_DECODE_QUERIES consecutive steps (one per rotating query).
-    steps = max(N_DECODE_QUERIES, steps // N_DECODE_QUERIES * N_DECODE_QUERIES)
+    # Exactly `steps` steps are timed: steps // 8 replays of the 8-step graph plus one replay of a graph
+    # with the remaining steps.
+    steps = max(1, steps)
     graph = torch.cuda.CUDAGraph()
     with torch.cuda.graph(graph):
         for i in range(N_DECODE_QUERIES):
             step(i)
+    rest = steps % N_DECODE_QUERIES
+    rgraph = None
+    if rest:
+        rgraph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(rgraph):
+            for i in range(rest):
+                step(i)
+        rgraph.replay()
     graph.replay()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(steps // N_DECODE_QUERIES):
         graph.replay()
+    if rgraph is not None:
+        rgraph.replay()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
+    # per-replay times (HIP events on the launch stream) for the median
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    rep_ms = []
+    for _ in range(max(3, min(steps // N_DECODE_QUERIES, 25))):
+        e0.record()
+        graph.replay()
+        e1.record()
+        e1.synchronize()
+        rep_ms.append(e0.elapsed_time(e1) / N_DECODE_QUERIES)
+    rep_ms.sort()
     # The combination form of the same steps (search with scores, gated reduction), same replay.
     outs_c = [torch.empty((cfg.Hq, 1, cfg.D), dtype=K.dtype, device=dev) for _ in range(N_DECODE_QUERIES)]
 
@@ -138,7 +172,7 @@ def bench_decode(cfg, steps, warmup, torch, B, W):
     cgraph.replay()
     torch.cuda.synchronize()
     tc = time.perf_counter()
-    nrep = max(1, steps // N_DECODE_QUERIES // 2)
+    nrep = max(2, steps // N_DECODE_QUERIES // 2)
     for _ in range(nrep):
         cgraph.replay()
     torch.cuda.synchronize()
@@ -273,7 +307,6 @@ def bench_decode(cfg, steps, warmup, torch, B, W):
             B.sl_span_attention_decode(Qs[i], K, V, idx_dev[i], cfg.S, ws=ws, out=outs[i])
     agraph.replay()
     torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     entry_ms = []
     for _ in range(max(4, min(steps // N_DECODE_QUERIES, 16))):
         e0.record()
@@ -300,12 +333,13 @@ def bench_decode(cfg, steps, warmup, torch, B, W):
     res = {
         "workload": f"{cfg.name} decode L={cfg.L} Hq={cfg.Hq} Hkv={cfg.Hkv} D={cfg.D} S={cfg.S} topk={cfg.topk}+local",
         "metric": "decode steps/s (span-search + span-attention)", "value": steps / dt, "unit": "steps/s",
-        "ms_per_step": dt / steps * 1e3, "steps": steps, "dtype": cfg.dtype, "launch": "hip-graph replay",
+        "ms_per_step": dt / steps * 1e3, "ms_per_step_median": rep_ms[len(rep_ms) // 2], "steps": steps,
+        "dtype": cfg.dtype, "launch": "hip-graph replay",
         "combined_form": {"ms_per_step": dt_combined * 1e3, "value": 1.0 / dt_combined, "unit": "steps/s"},
         "paper_geometry": paper_geometry,
         "batched_decode": batched,
         "roofline": {"bound": "hbm", "kernel": "decode_split_kernel", "achieved": achieved / 1e9, "peak": PEAK_HBM / 1e9,
-                     "unit": "GB/s", "frac": achieved / PEAK_HBM, "traffic": MEASURED_TRAFFIC.get(cfg.name),
+                     "unit": "GB/s", "frac": achieved / PEAK_HBM, "traffic": recorded_traffic(cfg.name),
                      "kernel_ms": kms_avg, "kernel_ms_min": min(kms), "algorithmic_bytes": sum(kbytes) / len(kbytes),
                      "attention_entry_ms_graph": sum(entry_ms) / len(entry_ms)},
     }
@@ -336,11 +370,17 @@ def bench_prefill(cfg, steps, warmup, torch, B, W):
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     ev_s, ev_a = ProfEvents(torch), ProfEvents(torch)
-    ms_s, ms_a = [], []
-    for _ in range(max(2, min(steps, 10))):
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ms_s, ms_a, step_ms = [], [], []
+    for _ in range(max(3, min(steps, 10))):
+        e0.record()
         step(ev_s.handles(), ev_a.handles())
+        e1.record()
         ms_s.append(ev_s.ms())
         ms_a.append(ev_a.ms())
+        e1.synchronize()
+        step_ms.append(e0.elapsed_time(e1))
+    step_ms.sort()
     # the combination form (per-span softmaxes gated by the search scores) of the same step
     def step_combined():
         B.sl_span_keys(K, cfg.S, out=Ks)
@@ -414,21 +454,27 @@ def bench_prefill(cfg, steps, warmup, torch, B, W):
     res = {
         "workload": f"{cfg.name} prefill L={cfg.L} Hq={cfg.Hq} Hkv={cfg.Hkv} D={cfg.D} S={cfg.S} topk={cfg.topk}+local",
         "metric": "prefill tokens/s (span-search + span-attention)", "value": cfg.L * steps / dt, "unit": "tokens/s",
-        "ms_per_step": dt / steps * 1e3, "steps": steps, "dtype": cfg.dtype,
+        "ms_per_step": dt / steps * 1e3, "ms_per_step_median": step_ms[len(step_ms) // 2], "steps": steps,
+        "dtype": cfg.dtype,
         "step_frac_of_peak": (f_search + f_attn) / (dt / steps) / peak,
         "combined_form": {"ms_per_step": dt_combined * 1e3, "value": cfg.L / dt_combined, "unit": "tokens/s"},
         "chunked_prefill": chunked,
         "paper_geometry_prefill": paper,
         "roofline": {"bound": bound, "kernel": kernel, "achieved": tflops_attn / 1e12,
                      "peak": peak / 1e12, "unit": "TFLOP/s", "frac": tflops_attn / peak,
-                     "traffic": MEASURED_TRAFFIC.get(cfg.name),
+                     "traffic": recorded_traffic(cfg.name),
                      "kernel_ms": ka, "algorithmic_flops": f_kernel, "step_algorithmic_flops": f_search + f_attn,
                      "search_kernel_ms": ks, "search_algorithmic_flops": f_search},
     }
     return res, dict(data=data)
 
 
-def cpu_baseline_decode(cfg, ctx, torch, budget_s=12.0):
+def _oracle_threads():
+    """Threads the oracle's numpy calls may use; the oracle is plain numpy and is timed on ONE thread."""
+    return 1
+
+
+def cpu_baseline_decode(cfg, ctx, torch, budget_s=6.0):
     """The fp64 oracle, as it stands, on whole decode steps (all heads) of the same workload."""
     import numpy as np
     from threadpoolctl import threadpool_limits
@@ -448,7 +494,7 @@ def cpu_baseline_decode(cfg, ctx, torch, budget_s=12.0):
     Ksn = Ks.float().cpu().numpy().astype(np.float64)
     q_pos = cfg.L - 1
     done, t0 = 0, time.perf_counter()
-    with threadpool_limits(limits=1):
+    with threadpool_limits(limits=_oracle_threads()):
         # about budget_s of CPU work: the 8 rotating queries, several times over if they are quick
         while done < 5 * N_DECODE_QUERIES and (time.perf_counter() - t0) < budget_s:
             Qn = data["Q"][done % N_DECODE_QUERIES].float().cpu().numpy().astype(np.float64)
@@ -456,36 +502,47 @@ def cpu_baseline_decode(cfg, ctx, torch, budget_s=12.0):
             orc.span_attention(Qn, Kh, Vh, idx, cfg.S, q_pos0=q_pos)
             done += 1
     dt = time.perf_counter() - t0
-    return {"value": done / dt, "unit": "steps/s", "cores": 1, "kind": "oracle",
+    return {"value": done / dt, "unit": "steps/s", "cores": _oracle_threads(), "kind": "oracle",
             "sample": f"{done} whole decode steps (all {cfg.Hq} heads, search + attention) of {cfg.name}; "
                       "numpy fp64, BLAS limited to 1 thread, K/V resident in host RAM as bf16"}
 
 
-def cpu_baseline_prefill(cfg, ctx, torch, budget_s=12.0):
+def cpu_baseline_prefill(cfg, ctx, torch, budget_s=6.0):
+    """The oracle on query positions of the same workload, all heads per position: every position
+    when that fits the budget (C1), otherwise a seeded sample that includes the first rows, span
+    boundaries and the last row; tokens/s is positions per second (extrapolated when sampled)."""
     import numpy as np
     from threadpoolctl import threadpool_limits
     from oracle import superlinear as orc
     data = ctx["data"]
-    Qn = data["Q"].float().cpu().numpy()
-    Kn = data["K"].float().cpu().numpy()
-    Vn = data["V"].float().cpu().numpy()
-    Ksn = orc.span_keys(Kn, cfg.S)
+    Qh, Kh, Vh = data["Q"].cpu(), data["K"].float().cpu().numpy(), data["V"].float().cpu().numpy()
+    Ksn = orc.span_keys(Kh, cfg.S)
     G = cfg.Hq // cfg.Hkv
+    S, L = cfg.S, cfg.L
     rng = np.random.default_rng(0)
+    special = [0, 1, S - 1, S, S + 1, 2 * S - 1, 2 * S, L - S - 1, L - S, L - 1]
+    order = special + rng.choice(L, size=min(L, 2048), replace=False).tolist()
+    whole = cfg.L * cfg.Hq <= 20000                 # small enough to do every row
+    if whole:
+        order = list(range(L))
     rows, t0 = 0, time.perf_counter()
     sc = 1.0 / math.sqrt(cfg.D)
-    with threadpool_limits(limits=1):
-        while (time.perf_counter() - t0) < budget_s:
-            r = int(rng.integers(0, cfg.L))
+    with threadpool_limits(limits=_oracle_threads()):
+        for r in order:
+            if not whole and (time.perf_counter() - t0) > budget_s:
+                break
+            qrow = Qh[:, r].float().numpy().astype(np.float64)
             for h in range(cfg.Hq):
-                s = orc.search_scores_row(Qn[h, r], Ksn[h // G], r // cfg.S)
-                sel = orc.select_topk(s, cfg.topk)
-                orc.attention_row(Qn[h, r], Kn, Vn, h // G, r, cfg.S, sel, sc)
+                s_ = orc.search_scores_row(qrow[h], Ksn[h // G], r // S)
+                sel = orc.select_topk(s_, cfg.topk)
+                orc.attention_row(qrow[h], Kh, Vh, h // G, r, S, sel, sc)
             rows += 1
     dt = time.perf_counter() - t0
-    return {"value": rows / dt, "unit": "tokens/s", "cores": 1, "kind": "oracle",
-            "sample": f"{rows} seeded random query positions x all {cfg.Hq} heads of {cfg.name} "
-                      "(search + attention per row); numpy fp64, 1 BLAS thread; tokens/s extrapolates rows/s"}
+    what = f"all {rows} query positions" if whole else \
+        f"{rows} positions of the seeded sample (first rows, span boundaries, last rows, random), extrapolated"
+    return {"value": rows / dt, "unit": "tokens/s", "cores": _oracle_threads(), "kind": "oracle",
+            "sample": f"{what} x all {cfg.Hq} heads of {cfg.name} (search + attention per row); "
+                      "numpy fp64, BLAS limited to 1 thread"}
 
 
 def main():
@@ -534,15 +591,25 @@ def main():
         log(f"[bench] {name}: {res['value']:.4g} {res['unit']}, {res['ms_per_step']:.4f} ms/step, "
             f"roofline {res['roofline']['frac'] * 100:.1f}% of {res['roofline']['bound']} "
             f"(kernel {res['roofline']['kernel_ms']:.4f} ms) [{time.perf_counter() - t_cfg:.1f}s]")
+        if not args.no_cpu_baseline:
+            # the oracle beside every configuration, a bounded sample each (rank 0, one GPU)
+            base = (cpu_baseline_decode if cfg.kind == "decode" else cpu_baseline_prefill)(cfg, ctx, torch)
+            res["cpu_baseline"] = base
+            log(f"[bench] {name} cpu oracle baseline: {base['value']:.4g} {base['unit']} ({base['sample']})")
         if name == names[0]:
             primary = (cfg, res)
-            if not args.no_cpu_baseline:
-                cpu = (cpu_baseline_decode if cfg.kind == "decode" else cpu_baseline_prefill)(cfg, ctx, torch)
-                log(f"[bench] cpu oracle baseline: {cpu['value']:.4g} {cpu['unit']} ({cpu['sample']})")
+            cpu = res.get("cpu_baseline")
         del ctx
         torch.cuda.empty_cache()
 
     cfg, res = primary
+    prop = torch.cuda.get_device_properties(0)
+    cus, mhz = prop.multi_processor_count, getattr(prop, "clock_rate", 0) / 1e3
+    device = {"name": prop.name, "compute_units": cus, "max_clock_mhz": mhz,
+              # 4 SIMDs x 1024 flop/clk (a 32x32x16 bf16 MFMA = 32768 flop in 32 cycles) per compute unit
+              "derived_bf16_mfma_peak_tflops": cus * 4096 * mhz * 1e6 / 1e12,
+              "peaks_used": {"hbm_GBps": PEAK_HBM / 1e9, "bf16_mfma_tflops": PEAK_BF16 / 1e12,
+                             "fp32_valu_tflops": PEAK_FP32_VALU / 1e12}}
     line = {
         "metric": "span-attn decode steps/s at L=1M" if cfg.name == "C3" else res["metric"],
         "value": res["value"], "unit": res["unit"], "n_gpus": 1, "steps": res["steps"], "warmup": args.warmup,
@@ -550,6 +617,7 @@ def main():
         "dtype": res["dtype"], "data": "synthetic",
         "config": {"workload": res["workload"], "decode_queries_rotated": N_DECODE_QUERIES},
         "roofline": res["roofline"], "cpu_baseline": cpu,
+        "device": device,
         "all_configs": results,
         "context_only": {"paper_whole_model_decode_tokens_per_s_B200": {"1M": 109, "10M": 76}},
     }

@@ -87,18 +87,24 @@ typedef struct sl_params {
   int32_t reserved0;
   int64_t q_stride_h, q_stride_t;   /* element strides of Q / Qs; 0 = packed                       */
   int64_t kv_stride_h, kv_stride_t; /* element strides of K and V; 0 = packed                      */
-  /* Optional profiling hooks: two caller-owned hipEvent_t handles.  When both are non-NULL the
-   * call records prof_start immediately before, and prof_stop immediately after, its dominant
-   * kernel (the K/V-streaming kernel of span-attention, the scoring kernel of span-search); the
-   * decode span-attention entry point attaches them to that kernel's dispatch, so that they hold
-   * the kernel's own begin and end timestamps.  Do not pass them while the stream is capturing. */
-  void* prof_start;
-  void* prof_stop;
 } sl_params;
 
-/* Bytes of scratch the given operation needs for these parameters (0 if none, or if the
- * parameters are invalid -- the entry point itself reports why). Host-only, no HIP call. */
+/* Returned by the *_workspace_bytes functions for parameters the entry point would reject. */
+#define SL_WORKSPACE_INVALID ((size_t)-1)
+
+/* Bytes of scratch the given operation needs for these parameters: 0 if it needs none,
+ * SL_WORKSPACE_INVALID if the parameters are invalid or unsupported (the entry point itself
+ * reports why). Host-only, no HIP call. */
 size_t sl_workspace_bytes(const sl_params* p, int op /* sl_op */);
+
+/* Optional profiling hook (benchmarks; no part of the operations).  Arms two caller-owned
+ * hipEvent_t handles for the NEXT span-search or span-attention call made by the calling thread
+ * (single-sequence entry points): that call records `start` immediately before, and `stop`
+ * immediately after, its dominant kernel (the K/V-streaming kernel of span-attention, the scoring
+ * kernel of span-search; the decode span-attention entry point attaches them to that kernel's
+ * dispatch, so that they hold the kernel's own begin and end timestamps), and disarms them.
+ * Passing NULL for either disarms.  Do not arm while the stream is capturing. */
+void sl_set_profile_events(void* start, void* stop);
 
 /* Span-key formation.  Section 3.5 / 4.2: the representative stream reuses the key tensor,
  * K_a = K, so the search key of span j is K at the span's anchor.  Gathers
@@ -204,7 +210,7 @@ typedef struct sl_anchor_geometry {
   int32_t reserved;        /* 0 */
 } sl_anchor_geometry;
 
-/* Bytes of scratch sl_anchor_attention_decode needs (0 if the arguments are invalid). */
+/* Bytes of scratch sl_anchor_attention_decode needs (SL_WORKSPACE_INVALID if the arguments are invalid). */
 size_t sl_anchor_workspace_bytes(const sl_params* p, const sl_anchor_geometry* g);
 
 /* Span-search over the candidate anchors (eq. (2)-(3) with K_a = K: the key of anchor t is
@@ -248,7 +254,7 @@ sl_status sl_anchor_attention_prefill(const sl_params* p, const sl_anchor_geomet
  * as 0 means "packed for this sequence's own L").  `seqs` is an array of B records in DEVICE
  * memory, read by the kernels: its contents cannot be validated by the host, so every pointer in
  * it must be valid and 16-byte aligned and 1 <= L <= p->L must hold -- that is the caller's
- * responsibility.  Joint softmax form only; p->prof_start / prof_stop are not recorded. */
+ * responsibility.  Profile events are not recorded by the batched entry points. */
 typedef struct sl_decode_seq {
   const void* Qs;  /* search query   [Hq][1][D]                                   */
   const void* Q;   /* attention query [Hq][1][D]                                  */
@@ -262,7 +268,7 @@ typedef struct sl_decode_seq {
   int64_t L;       /* tokens in this sequence's cache, current token included     */
 } sl_decode_seq;
 
-/* Scratch bytes of sl_span_attention_decode_batched for B sequences (0 if invalid). */
+/* Scratch bytes of sl_span_attention_decode_batched for B sequences (SL_WORKSPACE_INVALID if invalid). */
 size_t sl_decode_batched_workspace_bytes(const sl_params* p, int32_t B);
 
 /* sl_span_search_decode for every sequence of the batch: fills seq[b].idx (and scores).
@@ -294,7 +300,7 @@ sl_status sl_anchor_attention_decode_batched(const sl_params* p, const sl_anchor
                                              size_t ws_bytes, void* hip_stream);
 
 /* Static, human-readable name of a status code. */
-const char* sl_status_string(int status);
+const char* sl_status_string(sl_status status);
 
 /* Library version as major * 10000 + minor * 100 + patch. */
 int sl_version(void);

@@ -28,7 +28,7 @@ EXPORTS = ("sl_workspace_bytes", "sl_span_keys", "sl_span_search_prefill", "sl_s
            "sl_decode_batched_workspace_bytes", "sl_span_search_decode_batched",
            "sl_span_attention_decode_batched", "sl_span_attention_combined_decode_batched",
            "sl_anchor_batched_workspace_bytes", "sl_anchor_search_decode_batched",
-           "sl_anchor_attention_decode_batched", "sl_status_string", "sl_version")
+           "sl_anchor_attention_decode_batched", "sl_set_profile_events", "sl_status_string", "sl_version")
 
 
 class SlAnchorGeometry(ctypes.Structure):
@@ -52,8 +52,9 @@ class SlParams(ctypes.Structure):
         ("scale", ctypes.c_float), ("reserved0", ctypes.c_int32),
         ("q_stride_h", ctypes.c_int64), ("q_stride_t", ctypes.c_int64),
         ("kv_stride_h", ctypes.c_int64), ("kv_stride_t", ctypes.c_int64),
-        ("prof_start", ctypes.c_void_p), ("prof_stop", ctypes.c_void_p),
     ]
+
+WORKSPACE_INVALID = ctypes.c_size_t(-1).value
 
 
 class SlError(RuntimeError):
@@ -122,6 +123,8 @@ def load():
     lib.sl_anchor_search_decode_batched.argtypes = [pp, gp, vp, ctypes.c_int32, vp]
     lib.sl_anchor_attention_decode_batched.restype = ctypes.c_int
     lib.sl_anchor_attention_decode_batched.argtypes = [pp, gp, vp, ctypes.c_int32, vp, ctypes.c_size_t, vp]
+    lib.sl_set_profile_events.restype = None
+    lib.sl_set_profile_events.argtypes = [vp, vp]
     lib.sl_status_string.restype = ctypes.c_char_p
     lib.sl_status_string.argtypes = [ctypes.c_int]
     lib.sl_version.restype = ctypes.c_int
@@ -150,7 +153,13 @@ def _stream():
     return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
 
 
-def make_params(Q, K, S, topk, q_pos0=0, scale=0.0, prof=None) -> SlParams:
+def _arm(prof):
+    """prof = (start, stop) hipEvent_t handles for the next call's dominant kernel, or None."""
+    if prof is not None:
+        load().sl_set_profile_events(ctypes.c_void_p(prof[0]), ctypes.c_void_p(prof[1]))
+
+
+def make_params(Q, K, S, topk, q_pos0=0, scale=0.0) -> SlParams:
     """Q: [Hq, Lq, D] (innermost contiguous), K: [Hkv, L, D]."""
     if Q.dim() != 3 or K.dim() != 3 or Q.stride(2) != 1 or K.stride(2) != 1:
         raise ValueError("expect Q [Hq, Lq, D] and K [Hkv, L, D] with contiguous innermost dimension")
@@ -161,13 +170,13 @@ def make_params(Q, K, S, topk, q_pos0=0, scale=0.0, prof=None) -> SlParams:
     p.scale = float(scale)
     p.q_stride_h, p.q_stride_t = Q.stride(0), Q.stride(1)
     p.kv_stride_h, p.kv_stride_t = K.stride(0), K.stride(1)
-    if prof is not None:
-        p.prof_start, p.prof_stop = prof
     return p
 
 
 def workspace_bytes(p: SlParams, op: int) -> int:
-    return int(load().sl_workspace_bytes(ctypes.byref(p), op))
+    """Scratch bytes of the operation; 0 for parameters the entry point will reject (it reports why)."""
+    need = int(load().sl_workspace_bytes(ctypes.byref(p), op))
+    return 0 if need == WORKSPACE_INVALID else need
 
 
 class Workspace:
@@ -198,6 +207,13 @@ def _ws(ws):
     return _default_ws
 
 
+def _need(nbytes) -> int:
+    """A *_workspace_bytes result as a size to allocate: invalid parameters need nothing (the entry
+    point rejects them and says why)."""
+    nbytes = int(nbytes)
+    return 0 if nbytes == WORKSPACE_INVALID else nbytes
+
+
 def _check(status, where):
     if status != SL_OK:
         raise SlError(status, where)
@@ -217,11 +233,12 @@ def sl_span_keys(K, S, out=None):
 
 def _search(fn_name, op, Qs, K, Ks, S, topk, q_pos0, want_scores, ws, prof):
     lib = load()
-    p = make_params(Qs, K, S, topk, q_pos0, prof=prof)
+    p = make_params(Qs, K, S, topk, q_pos0)
     Hq, Lq, _ = Qs.shape
     idx = torch.empty((Hq, Lq, topk), dtype=torch.int32, device=Qs.device)
     scores = torch.empty((Hq, Lq, topk), dtype=torch.float32, device=Qs.device) if want_scores else None
     wptr, wbytes = _ws(ws).get(workspace_bytes(p, op))
+    _arm(prof)
     st = getattr(lib, fn_name)(ctypes.byref(p), _ptr(Qs), _ptr(K), _ptr(Ks), _ptr(idx), _ptr(scores),
                                wptr, wbytes, _stream())
     _check(st, fn_name)
@@ -242,7 +259,7 @@ def sl_span_search_decode(Qs, K, Ks, S, topk, q_pos0=None, want_scores=False, ws
 def _attention(fn_name, op, Q, K, V, idx, S, q_pos0, scale, ws, prof, out):
     lib = load()
     topk = 0 if idx is None else idx.shape[2]
-    p = make_params(Q, K, S, topk, q_pos0, scale, prof=prof)
+    p = make_params(Q, K, S, topk, q_pos0, scale)
     if V.shape != K.shape or V.stride() != K.stride():
         raise ValueError("V must have the shape and strides of K")
     Hq, Lq, D = Q.shape
@@ -252,6 +269,7 @@ def _attention(fn_name, op, Q, K, V, idx, S, q_pos0, scale, ws, prof, out):
     else:
         O, LSE = out
     wptr, wbytes = _ws(ws).get(workspace_bytes(p, op))
+    _arm(prof)
     st = getattr(lib, fn_name)(ctypes.byref(p), _ptr(Q), _ptr(K), _ptr(V), _ptr(idx), _ptr(O), _ptr(LSE),
                                wptr, wbytes, _stream())
     _check(st, fn_name)
@@ -309,11 +327,12 @@ def sl_span_attention_combined_decode(Q, K, V, idx, scores, S, q_pos0=None, scal
 def sl_anchor_search_decode(Qs, K, topk, window, want_scores=False, prof=None, search_root=2):
     """Top-k anchors of the query at the end of the cache on the paper's stride pattern."""
     lib = load()
-    p = make_params(Qs, K, 1, topk, K.shape[1] - 1, prof=prof)
+    p = make_params(Qs, K, 1, topk, K.shape[1] - 1)
     g = SlAnchorGeometry(window, 0, 0, search_root, 0)
     Hq = Qs.shape[0]
     anchors = torch.empty((Hq, 1, topk), dtype=torch.int32, device=Qs.device)
     scores = torch.empty((Hq, 1, topk), dtype=torch.float32, device=Qs.device) if want_scores else None
+    _arm(prof)
     st = lib.sl_anchor_search_decode(ctypes.byref(p), ctypes.byref(g), _ptr(Qs), _ptr(K), _ptr(anchors),
                                      _ptr(scores), _stream())
     _check(st, "sl_anchor_search_decode")
@@ -325,14 +344,15 @@ def sl_anchor_attention_decode(Q, K, V, anchors, scores, window, backward_factor
     """Algorithm 1's span-attention + combination for the query at the end of the cache."""
     lib = load()
     topk = 0 if anchors is None else anchors.shape[2]
-    p = make_params(Q, K, 1, topk, K.shape[1] - 1, scale, prof=prof)
+    p = make_params(Q, K, 1, topk, K.shape[1] - 1, scale)
     g = SlAnchorGeometry(window, backward_factor, forward_factor, search_root, 0)
     if V.shape != K.shape or V.stride() != K.stride():
         raise ValueError("V must have the shape and strides of K")
     Hq, Lq, D = Q.shape
     O = torch.empty((Hq, Lq, D), dtype=Q.dtype, device=Q.device) if out is None else out
-    need = lib.sl_anchor_workspace_bytes(ctypes.byref(p), ctypes.byref(g))
+    need = _need(lib.sl_anchor_workspace_bytes(ctypes.byref(p), ctypes.byref(g)))
     wptr, wbytes = _ws(ws).get(need)
+    _arm(prof)
     st = lib.sl_anchor_attention_decode(ctypes.byref(p), ctypes.byref(g), _ptr(Q), _ptr(K), _ptr(V),
                                         _ptr(anchors), _ptr(scores), _ptr(O), wptr, wbytes, _stream())
     _check(st, "sl_anchor_attention_decode")
@@ -342,11 +362,12 @@ def sl_anchor_attention_decode(Q, K, V, anchors, scores, window, backward_factor
 def sl_anchor_search_prefill(Qs, K, topk, window, q_pos0=0, want_scores=False, prof=None, search_root=2):
     """Top-k anchors of every query row on the paper's stride pattern (row r sits at q_pos0 + r)."""
     lib = load()
-    p = make_params(Qs, K, 1, topk, q_pos0, prof=prof)
+    p = make_params(Qs, K, 1, topk, q_pos0)
     g = SlAnchorGeometry(window, 0, 0, search_root, 0)
     Hq, Lq, _ = Qs.shape
     anchors = torch.empty((Hq, Lq, topk), dtype=torch.int32, device=Qs.device)
     scores = torch.empty((Hq, Lq, topk), dtype=torch.float32, device=Qs.device) if want_scores else None
+    _arm(prof)
     st = lib.sl_anchor_search_prefill(ctypes.byref(p), ctypes.byref(g), _ptr(Qs), _ptr(K), _ptr(anchors),
                                       _ptr(scores), _stream())
     _check(st, "sl_anchor_search_prefill")
@@ -358,12 +379,13 @@ def sl_anchor_attention_prefill(Q, K, V, anchors, scores, window, backward_facto
     """Algorithm 1's span-attention + combination for every query row."""
     lib = load()
     topk = 0 if anchors is None else anchors.shape[2]
-    p = make_params(Q, K, 1, topk, q_pos0, scale, prof=prof)
+    p = make_params(Q, K, 1, topk, q_pos0, scale)
     g = SlAnchorGeometry(window, backward_factor, forward_factor, search_root, 0)
     if V.shape != K.shape or V.stride() != K.stride():
         raise ValueError("V must have the shape and strides of K")
     Hq, Lq, D = Q.shape
     O = torch.empty((Hq, Lq, D), dtype=Q.dtype, device=Q.device) if out is None else out
+    _arm(prof)
     st = lib.sl_anchor_attention_prefill(ctypes.byref(p), ctypes.byref(g), _ptr(Q), _ptr(K), _ptr(V),
                                          _ptr(anchors), _ptr(scores), _ptr(O), _stream())
     _check(st, "sl_anchor_attention_prefill")
@@ -443,7 +465,7 @@ def sl_span_attention_decode_batched(batch: DecodeBatch, scale=0.0, ws=None):
     """Joint span-attention of every sequence on batch.idx; returns (batch.O, batch.LSE)."""
     lib = load()
     batch.params.scale = float(scale)
-    need = lib.sl_decode_batched_workspace_bytes(ctypes.byref(batch.params), batch.B)
+    need = _need(lib.sl_decode_batched_workspace_bytes(ctypes.byref(batch.params), batch.B))
     wptr, wbytes = _ws(ws).get(need)
     st = lib.sl_span_attention_decode_batched(ctypes.byref(batch.params), _ptr(batch.records), batch.B,
                                               wptr, wbytes, _stream())
@@ -457,7 +479,7 @@ def sl_span_attention_combined_decode_batched(batch: DecodeBatch, scale=0.0, ws=
     if batch.scores is None:
         raise ValueError("the combination form needs the search scores: DecodeBatch(..., want_scores=True)")
     batch.params.scale = float(scale)
-    need = lib.sl_decode_batched_workspace_bytes(ctypes.byref(batch.params), batch.B)
+    need = _need(lib.sl_decode_batched_workspace_bytes(ctypes.byref(batch.params), batch.B))
     wptr, wbytes = _ws(ws).get(need)
     st = lib.sl_span_attention_combined_decode_batched(ctypes.byref(batch.params), _ptr(batch.records),
                                                        batch.B, wptr, wbytes, _stream())
@@ -482,7 +504,7 @@ def sl_anchor_attention_decode_batched(batch: DecodeBatch, window, backward_fact
         raise ValueError("the combination needs the search scores: DecodeBatch(..., want_scores=True)")
     batch.params.scale = float(scale)
     g = SlAnchorGeometry(window, backward_factor, forward_factor, search_root, 0)
-    need = lib.sl_anchor_batched_workspace_bytes(ctypes.byref(batch.params), ctypes.byref(g), batch.B)
+    need = _need(lib.sl_anchor_batched_workspace_bytes(ctypes.byref(batch.params), ctypes.byref(g), batch.B))
     wptr, wbytes = _ws(ws).get(need)
     st = lib.sl_anchor_attention_decode_batched(ctypes.byref(batch.params), ctypes.byref(g),
                                                 _ptr(batch.records), batch.B, wptr, wbytes, _stream())

@@ -31,10 +31,21 @@ def sources() -> list[str]:
     return sorted(glob.glob(os.path.join(CSRC, "*.hip")))
 
 
-def build(verbose: bool = False, extra_flags: list[str] | None = None) -> str:
-    """Compile every kernel translation unit and link libsl.so. Always recompiles."""
+# Host-side sanitizer build: AddressSanitizer + UndefinedBehaviorSanitizer on the host pass only
+# (the validation layer, workspace carving, launch logic); device code is compiled as usual.  The
+# result goes to libsl_san.so and is meant for CPU runs of programs that are themselves built with
+# the sanitizers (tests/cabi/validate_from_c.c).
+SAN_FLAGS = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined",
+             "-Xarch_host", "-fno-omit-frame-pointer", "-g"]
+SAN_LIB = os.path.join(PKG, "libsl_san.so")
+
+
+def build(verbose: bool = False, extra_flags: list[str] | None = None, sanitize: bool = False) -> str:
+    """Compile every kernel translation unit and link libsl.so (sanitize: libsl_san.so). Always recompiles."""
     objs = []
-    bdir = os.path.join(PKG, "_build")
+    if sanitize:
+        extra_flags = (extra_flags or []) + SAN_FLAGS
+    bdir = os.path.join(PKG, "_build_san" if sanitize else "_build")
     os.makedirs(bdir, exist_ok=True)
     procs = []
     for src in sources():
@@ -56,12 +67,15 @@ def build(verbose: bool = False, extra_flags: list[str] | None = None) -> str:
             print(out)
     if failed:
         raise RuntimeError("hipcc failed")
-    tmp = LIB + ".tmp"
+    lib = SAN_LIB if sanitize else LIB
+    tmp = lib + ".tmp"
     cmd = [hipcc_path(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp] + objs
+    if sanitize:
+        cmd += ["-fsanitize=address", "-fsanitize=undefined", "-shared-libsan"]
     subprocess.run(cmd, check=True)
-    os.replace(tmp, LIB)
-    return LIB
+    os.replace(tmp, lib)
+    return lib
 
 
 if __name__ == "__main__":
-    print(build(verbose="-v" in sys.argv))
+    print(build(verbose="-v" in sys.argv, sanitize="--sanitize" in sys.argv))

@@ -11,6 +11,17 @@ namespace {
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
+// Events armed by sl_set_profile_events for the calling thread's next operation.
+thread_local hipEvent_t tl_prof_start = nullptr;
+thread_local hipEvent_t tl_prof_stop = nullptr;
+
+// Hands the armed events to a validated problem and disarms them.
+void take_profile_events(Problem* pb) {
+  pb->prof_start = tl_prof_start;
+  pb->prof_stop = tl_prof_stop;
+  tl_prof_start = tl_prof_stop = nullptr;
+}
+
 // Validates p for the given operation and fills pb.  Pure host code (no HIP call), so every
 // error path can be exercised without a GPU.
 sl_status make_problem(const sl_params* p, int op, Problem* pb) {
@@ -29,14 +40,24 @@ sl_status make_problem(const sl_params* p, int op, Problem* pb) {
   if (p->D != 64 && p->D != 128) return SL_ERR_UNSUPPORTED;
   if (p->topk > SL_MAX_TOPK) return SL_ERR_UNSUPPORTED;
   if (p->Hq / p->Hkv > 64) return SL_ERR_UNSUPPORTED;
-  if ((int64_t)p->Hq * p->Lq > ((int64_t)1 << 31) - 1) return SL_ERR_UNSUPPORTED;
+  // Extents that keep every size and offset computed from them inside 64 bits: at most 2^40
+  // tokens, token strides below 2^20 elements, head strides below 2^60.
+  constexpr int64_t kMaxTokens = (int64_t)1 << 40, kMaxTokenStride = (int64_t)1 << 20,
+                    kMaxHeadStride = (int64_t)1 << 60;
+  if (p->L > kMaxTokens) return SL_ERR_UNSUPPORTED;
+  if (p->Lq > (((int64_t)1 << 31) - 1) / p->Hq) return SL_ERR_UNSUPPORTED;  // row ids are 32-bit
+  if (p->q_stride_t < 0 || p->kv_stride_t < 0 || p->q_stride_h < 0 || p->kv_stride_h < 0)
+    return SL_ERR_INVALID_ARG;
+  if (p->q_stride_t > kMaxTokenStride || p->kv_stride_t > kMaxTokenStride ||
+      p->q_stride_h > kMaxHeadStride || p->kv_stride_h > kMaxHeadStride)
+    return SL_ERR_UNSUPPORTED;
 
   const int64_t epl = p->dtype == SL_BF16 ? 8 : 4;  // elements per 16 bytes
   const int64_t qst = p->q_stride_t ? p->q_stride_t : p->D;
   const int64_t qsh = p->q_stride_h ? p->q_stride_h : p->Lq * qst;
   const int64_t kvst = p->kv_stride_t ? p->kv_stride_t : p->D;
   const int64_t kvsh = p->kv_stride_h ? p->kv_stride_h : p->L * kvst;
-  if (qst < p->D || kvst < p->D || qsh < 0 || kvsh < 0) return SL_ERR_INVALID_ARG;
+  if (qst < p->D || kvst < p->D) return SL_ERR_INVALID_ARG;
   if (qst % epl || qsh % epl || kvst % epl || kvsh % epl) return SL_ERR_INVALID_ARG;
 
   pb->L = p->L;
@@ -56,9 +77,8 @@ sl_status make_problem(const sl_params* p, int op, Problem* pb) {
   pb->kvsh_given = p->kv_stride_h != 0;
   pb->kvst = kvst;
   pb->n = (p->L + p->S - 1) / p->S;
-  const bool prof = p->prof_start && p->prof_stop;
-  pb->prof_start = prof ? static_cast<hipEvent_t>(p->prof_start) : nullptr;
-  pb->prof_stop = prof ? static_cast<hipEvent_t>(p->prof_stop) : nullptr;
+  pb->prof_start = nullptr;
+  pb->prof_stop = nullptr;
   pb->combined = false;
   pb->gate = nullptr;
   return SL_OK;
@@ -92,6 +112,7 @@ sl_status search_entry(const sl_params* p, int op, const void* Qs, const void* K
     return SL_ERR_INVALID_ARG;
   s = check_ws(pb, op, ws, ws_bytes);
   if (s != SL_OK) return s;
+  take_profile_events(&pb);
   hipStream_t st = static_cast<hipStream_t>(stream);
   if (op == SL_OP_SEARCH_DECODE) return decode_search(pb, Qs, K, Ks, idx, scores, ws, st);
   return prefill_search(pb, Qs, K, Ks, idx, scores, ws, st);
@@ -113,6 +134,7 @@ sl_status attention_entry(const sl_params* p, int op, const void* Q, const void*
   pb.gate = scores;
   s = check_ws(pb, op, ws, ws_bytes);
   if (s != SL_OK) return s;
+  take_profile_events(&pb);
   hipStream_t st = static_cast<hipStream_t>(stream);
   if (op == SL_OP_ATTENTION_DECODE) return decode_attention(pb, Q, K, V, idx, O, LSE, ws, st);
   return prefill_attention(pb, Q, K, V, idx, O, LSE, ws, st);
@@ -126,8 +148,14 @@ extern "C" {
 
 size_t sl_workspace_bytes(const sl_params* p, int op) {
   sl::Problem pb;
-  if (sl::make_problem(p, op, &pb) != SL_OK) return 0;
+  if (sl::make_problem(p, op, &pb) != SL_OK) return SL_WORKSPACE_INVALID;
   return sl::ws_bytes_for(pb, op);
+}
+
+void sl_set_profile_events(void* start, void* stop) {
+  const bool both = start && stop;
+  sl::tl_prof_start = both ? static_cast<hipEvent_t>(start) : nullptr;
+  sl::tl_prof_stop = both ? static_cast<hipEvent_t>(stop) : nullptr;
 }
 
 sl_status sl_span_keys(const sl_params* p, const void* K, void* Ks, void* hip_stream) {
@@ -211,8 +239,8 @@ static int anchor_root(const sl_anchor_geometry* g) {
 size_t sl_anchor_workspace_bytes(const sl_params* p, const sl_anchor_geometry* g) {
   sl::Problem pb;
   const int root = anchor_root(g);
-  if (!root) return 0;
-  if (sl::make_problem(p, SL_OP_ATTENTION_DECODE, &pb) != SL_OK) return 0;
+  if (!root) return SL_WORKSPACE_INVALID;
+  if (sl::make_problem(p, SL_OP_ATTENTION_DECODE, &pb) != SL_OK) return SL_WORKSPACE_INVALID;
   return sl::anchor_attention_ws_bytes(pb, g->window, g->backward_factor, g->forward_factor, root);
 }
 
@@ -226,6 +254,7 @@ sl_status sl_anchor_search_decode(const sl_params* p, const sl_anchor_geometry* 
   if (!sl::aligned16(Qs) || !sl::aligned16(K) || !sl::aligned16(anchors) || !sl::aligned16(scores))
     return SL_ERR_INVALID_ARG;
   if (pb.L > ((int64_t)1 << 31) - 1) return SL_ERR_UNSUPPORTED;  // anchors are int32 token positions
+  sl::take_profile_events(&pb);
   return sl::anchor_search_decode(pb, g->window, root, Qs, K, anchors, scores,
                                   static_cast<hipStream_t>(hip_stream));
 }
@@ -248,6 +277,7 @@ sl_status sl_anchor_attention_decode(const sl_params* p, const sl_anchor_geometr
   if (!ws || ws_bytes < need || (reinterpret_cast<uintptr_t>(ws) & 255u)) return SL_ERR_WORKSPACE;
   pb.combined = true;
   pb.gate = scores;
+  sl::take_profile_events(&pb);
   return sl::anchor_attention_decode(pb, g->window, g->backward_factor, g->forward_factor, root, Q, K,
                                      V, anchors, O, ws, static_cast<hipStream_t>(hip_stream));
 }
@@ -262,6 +292,7 @@ sl_status sl_anchor_search_prefill(const sl_params* p, const sl_anchor_geometry*
   if (!sl::aligned16(Qs) || !sl::aligned16(K) || !sl::aligned16(anchors) || !sl::aligned16(scores))
     return SL_ERR_INVALID_ARG;
   if (pb.L > ((int64_t)1 << 31) - 1) return SL_ERR_UNSUPPORTED;  // anchors are int32 token positions
+  sl::take_profile_events(&pb);
   return sl::anchor_search_prefill(pb, g->window, root, Qs, K, anchors, scores,
                                    static_cast<hipStream_t>(hip_stream));
 }
@@ -281,13 +312,14 @@ sl_status sl_anchor_attention_prefill(const sl_params* p, const sl_anchor_geomet
   if (pb.L > ((int64_t)1 << 31) - 1) return SL_ERR_UNSUPPORTED;
   pb.combined = true;
   pb.gate = scores;
+  sl::take_profile_events(&pb);
   return sl::anchor_attention_prefill(pb, g->window, g->backward_factor, g->forward_factor, root, Q, K,
                                       V, anchors, O, static_cast<hipStream_t>(hip_stream));
 }
 
 size_t sl_decode_batched_workspace_bytes(const sl_params* p, int32_t B) {
   sl::Problem pb;
-  if (B < 1 || sl::make_problem(p, SL_OP_ATTENTION_DECODE, &pb) != SL_OK) return 0;
+  if (B < 1 || sl::make_problem(p, SL_OP_ATTENTION_DECODE, &pb) != SL_OK) return SL_WORKSPACE_INVALID;
   return sl::decode_attention_batched_ws_bytes(pb, B);
 }
 
@@ -331,8 +363,8 @@ sl_status sl_span_attention_combined_decode_batched(const sl_params* p, const sl
 size_t sl_anchor_batched_workspace_bytes(const sl_params* p, const sl_anchor_geometry* g, int32_t B) {
   sl::Problem pb;
   const int root = anchor_root(g);
-  if (!root || B < 1) return 0;
-  if (sl::make_problem(p, SL_OP_ATTENTION_DECODE, &pb) != SL_OK) return 0;
+  if (!root || B < 1) return SL_WORKSPACE_INVALID;
+  if (sl::make_problem(p, SL_OP_ATTENTION_DECODE, &pb) != SL_OK) return SL_WORKSPACE_INVALID;
   return sl::anchor_attention_batched_ws_bytes(pb, g->window, g->backward_factor, g->forward_factor, root, B);
 }
 
@@ -364,7 +396,7 @@ sl_status sl_anchor_attention_decode_batched(const sl_params* p, const sl_anchor
                                              seqs, B, ws, static_cast<hipStream_t>(hip_stream));
 }
 
-const char* sl_status_string(int status) {
+const char* sl_status_string(sl_status status) {
   switch (status) {
     case SL_OK: return "SL_OK";
     case SL_ERR_INVALID_ARG: return "SL_ERR_INVALID_ARG: bad pointer, size, stride or alignment";
@@ -375,6 +407,6 @@ const char* sl_status_string(int status) {
   return "unknown sl_status";
 }
 
-int sl_version(void) { return 200; }  // 0.2.0: batched decode entry points
+int sl_version(void) { return 300; }  // 0.3.0: sl_params without the profiling events; sl_set_profile_events
 
 }  // extern "C"

@@ -26,6 +26,8 @@
 //                                         accumulators 8 consecutive kv positions)
 // With v_mfma_f32_32x32x16_bf16, lane l of the 32x32 result holds column l%32 and rows
 // 8*(r/4) + 4*(l/32) + r%4 for accumulator r = 0..15.
+#include <mutex>
+
 #include "kernels.h"
 
 namespace sl {
@@ -994,33 +996,37 @@ struct MfmaWs {
   int64_t max_items;
 };
 
-// One resident workgroup of eight wavefronts per compute unit.
-int persistent_grid() {
-  static int grid = 0;
-  if (grid == 0) {
-    int dev = 0, cus = 0;
-    if (hipGetDevice(&dev) != hipSuccess ||
-        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
-      cus = 256;
-    grid = (cus + 7) / 8 * 8;
-  }
-  return grid;
-}
+// Per-device facts, looked up on the first call with that device current: the grid of the
+// persistent kernel (one resident workgroup of eight wavefronts per compute unit) and whether the
+// flash kernels were granted more dynamic LDS than the 64 KB a kernel gets by default.
+struct DeviceSetup {
+  int grid = 0;     // 0 = not looked up yet
+  bool lds_ok = false;
+};
+constexpr int kMaxDevices = 64;
+std::mutex g_setup_mu;
+DeviceSetup g_setup[kMaxDevices];
 
-// The flash kernels use more dynamic LDS than the 64 KB a kernel gets by default.
-bool allow_large_lds() {
-  static int done = 0;  // 0 = not yet, 1 = ok, -1 = failed
-  if (done == 0) {
-    const bool ok =
+bool device_setup(DeviceSetup* out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return false;
+  std::lock_guard<std::mutex> lock(g_setup_mu);
+  DeviceSetup& d = g_setup[dev];
+  if (d.grid == 0) {
+    int cus = 0;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+      cus = 256;
+    d.lds_ok =
         hipFuncSetAttribute(reinterpret_cast<const void*>(span_flash_routed_kernel),
                             hipFuncAttributeMaxDynamicSharedMemorySize, FlashLds<2>::kBytes) == hipSuccess &&
         hipFuncSetAttribute(reinterpret_cast<const void*>(span_flash_local_kernel<false>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, FlashLds<1>::kBytes) == hipSuccess &&
         hipFuncSetAttribute(reinterpret_cast<const void*>(span_flash_local_kernel<true>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, FlashLds<1>::kBytes) == hipSuccess;
-    done = ok ? 1 : -1;
+    d.grid = (cus + 7) / 8 * 8;
   }
-  return done == 1;
+  *out = d;
+  return true;
 }
 
 MfmaWs carve(const Problem& pb) {
@@ -1072,7 +1078,8 @@ sl_status prefill_attention_mfma(const Problem& pb, const void* Q, const void* K
                                  const int32_t* idx, void* O, float* LSE, void* ws,
                                  hipStream_t st) {
   const MfmaWs w = carve(pb);
-  if (!allow_large_lds()) return SL_ERR_LAUNCH;
+  DeviceSetup dev;
+  if (!device_setup(&dev) || !dev.lds_ok) return SL_ERR_LAUNCH;
   char* base = static_cast<char*>(ws);
   bf16_t* Vt = reinterpret_cast<bf16_t*>(base + w.vt);
   int* counts = reinterpret_cast<int*>(base + w.counts);
@@ -1131,7 +1138,7 @@ sl_status prefill_attention_mfma(const Problem& pb, const void* Q, const void* K
                        blk_cnt, cursor, items, pb.Lq, pb.q_pos0, pb.G, pb.S, pb.topk, n);
     if (hipGetLastError() != hipSuccess) return SL_ERR_LAUNCH;
     if (pb.prof_start) (void)hipEventRecord(pb.prof_start, st);
-    hipLaunchKernelGGL(span_flash_routed_kernel, dim3(persistent_grid()),
+    hipLaunchKernelGGL(span_flash_routed_kernel, dim3(dev.grid),
                        dim3(FlashLds<2>::kThreads), FlashLds<2>::kBytes, st, a);
     if (pb.prof_stop) (void)hipEventRecord(pb.prof_stop, st);
   }

@@ -63,6 +63,29 @@ def test_library_is_callable_from_plain_c(tmp_path):
     assert "ok=SL_OK" in out and "bad=SL_ERR_INVALID_ARG" in out, out
 
 
+def test_validation_layer_under_address_and_undefined_sanitizers(tmp_path):
+    """The host side of the library (validation, size arithmetic) built with ASan + UBSan, driven by
+    a C program built the same way through every rejection path; nothing is launched."""
+    import glob
+    import shutil
+    import subprocess
+    from paper_2601_18401_amd import build as _build
+    clang = "/opt/rocm/lib/llvm/bin/clang"
+    if not os.path.exists(clang) or not shutil.which("hipcc"):
+        pytest.skip("no ROCm clang")
+    lib = _build.build(sanitize=True)
+    exe = str(tmp_path / "validate_from_c")
+    subprocess.run([clang, "-std=c99", "-Wall", "-Wextra", "-Werror", "-g", "-fsanitize=address,undefined",
+                    "-fno-sanitize-recover=undefined", "-shared-libsan", "-I", os.path.join(ROOT, "include"),
+                    os.path.join(ROOT, "tests", "cabi", "validate_from_c.c"), "-o", exe, "-ldl"], check=True)
+    rt = glob.glob("/opt/rocm/lib/llvm/lib/clang/*/lib/linux")[0]
+    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=0:abort_on_error=0", UBSAN_OPTIONS="halt_on_error=1:print_stacktrace=1",
+               LD_LIBRARY_PATH=rt + ":" + os.environ.get("LD_LIBRARY_PATH", ""))
+    run = subprocess.run([exe, lib], capture_output=True, text=True, env=env)
+    assert run.returncode == 0 and "failures=0" in run.stdout, (run.stdout, run.stderr[-3000:])
+    assert "runtime error" not in run.stderr and "AddressSanitizer" not in run.stderr, run.stderr[-3000:]
+
+
 def test_struct_layouts_match_the_header():
     # sl_anchor_geometry: int64 + 4 x int32; sl_decode_seq: 9 pointers + int64
     assert ctypes.sizeof(B.SlAnchorGeometry) == 24
@@ -71,8 +94,8 @@ def test_struct_layouts_match_the_header():
 
 
 def test_params_struct_matches_header_size():
-    # 3 x int64, 6 x int32, float, int32, 4 x int64, 2 pointers
-    assert ctypes.sizeof(B.SlParams) == 24 + 24 + 8 + 32 + 16
+    # 3 x int64, 6 x int32, float, int32, 4 x int64
+    assert ctypes.sizeof(B.SlParams) == 24 + 24 + 8 + 32
 
 
 BAD = [
@@ -92,7 +115,7 @@ def test_invalid_params_rejected_before_launch(kw, status):
         assert fn(ctypes.byref(p), FAKE, FAKE, FAKE, FAKE, None, FAKE_WS, 1 << 40, None) == status
     assert lib.sl_span_attention_prefill(ctypes.byref(p), FAKE, FAKE, FAKE, FAKE, FAKE, FAKE,
                                          FAKE_WS, 1 << 40, None) == status
-    assert lib.sl_workspace_bytes(ctypes.byref(p), B.OP_ATTENTION_DECODE) == 0
+    assert lib.sl_workspace_bytes(ctypes.byref(p), B.OP_ATTENTION_DECODE) == B.WORKSPACE_INVALID
 
 
 def test_null_and_misaligned_pointers():
@@ -141,8 +164,8 @@ def test_batched_decode_argument_checks():
     p = good(Lq=1, q_pos0=4095)
     need = lib.sl_decode_batched_workspace_bytes(ctypes.byref(p), 3)
     assert need > 0 and need % 3 == 0
-    assert lib.sl_decode_batched_workspace_bytes(ctypes.byref(p), 0) == 0
-    assert lib.sl_decode_batched_workspace_bytes(ctypes.byref(good()), 3) == 0     # Lq != 1
+    assert lib.sl_decode_batched_workspace_bytes(ctypes.byref(p), 0) == B.WORKSPACE_INVALID
+    assert lib.sl_decode_batched_workspace_bytes(ctypes.byref(good()), 3) == B.WORKSPACE_INVALID     # Lq != 1
     assert lib.sl_span_search_decode_batched(ctypes.byref(p), None, 3, None) == 1
     assert lib.sl_span_search_decode_batched(ctypes.byref(p), FAKE, 0, None) == 1
     assert lib.sl_span_search_decode_batched(ctypes.byref(p), ctypes.c_void_p(0x1004), 3, None) == 1
@@ -161,8 +184,8 @@ def test_batched_combination_and_anchor_argument_checks():
     bad_g = B.SlAnchorGeometry(1088, 4, 2, 5, 0)          # exponent 1/5 is not offered
     need = lib.sl_anchor_batched_workspace_bytes(ctypes.byref(p), ctypes.byref(g), 2)
     assert need > 0
-    assert lib.sl_anchor_batched_workspace_bytes(ctypes.byref(p), ctypes.byref(bad_g), 2) == 0
-    assert lib.sl_anchor_batched_workspace_bytes(ctypes.byref(p), ctypes.byref(g), 0) == 0
+    assert lib.sl_anchor_batched_workspace_bytes(ctypes.byref(p), ctypes.byref(bad_g), 2) == B.WORKSPACE_INVALID
+    assert lib.sl_anchor_batched_workspace_bytes(ctypes.byref(p), ctypes.byref(g), 0) == B.WORKSPACE_INVALID
     assert lib.sl_anchor_search_decode_batched(ctypes.byref(p), ctypes.byref(g), None, 2, None) == 1
     assert lib.sl_anchor_search_decode_batched(ctypes.byref(p), ctypes.byref(bad_g), FAKE, 2, None) == 1
     assert lib.sl_anchor_search_decode_batched(ctypes.byref(good()), ctypes.byref(g), FAKE, 2, None) == 1
