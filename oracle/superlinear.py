@@ -21,6 +21,11 @@ window W is [c*S, i]; its candidate anchors are the spans j < c (window indices 
 from the candidates, Algorithm 1).  K_a = K (Section 3.5 / 4.2), so the default search key of
 span j is K[t_j].
 
+Redundant grid (Section 2.4: p_sh + p_sp > 1; Section 4.4's redundancy factors): anchors every
+`stride` tokens with spans S > stride tokens long, so that neighbouring spans overlap; the
+attended set is then the set UNION of the selected spans and the window (DedupConcat), and the
+search runs on the anchor grid (S = stride in the search functions).
+
 Readings of points the paper leaves open (all listed in the design notes of the repository):
 ties in TopK go to the lower span index; selected spans are reported in ascending index order
 and padded with -1; selection is per query head; the search score is the raw dot product (no
@@ -135,27 +140,44 @@ def selection_margin(scores, k: int) -> float:
     return float(s[k - 1] - s[k])
 
 
-def attended_ranges(i: int, S: int, sel):
-    """Token ranges [t0, t1) attended by the query at position i: the selected spans (entries
-    < 0 or >= c are empty slots) followed by the local window [c*S, i]."""
-    c = i // S
+def span_extent(j: int, S: int, stride: int | None = None):
+    """Token range [t0, t1) of span j.  Anchors sit every `stride` tokens (anchor of span j:
+    (j+1)*stride - 1) and a span reaches S tokens back from its anchor, clipped at token 0:
+    Algorithm 1's S_t = [t - b*l, t] with b*l = S.  stride = S (the default) is the disjoint grid;
+    S > stride is the redundant setting of Section 2.4 / 4.4 (spans overlap their predecessors)."""
+    A = S if stride is None else int(stride)
+    t1 = (int(j) + 1) * A
+    return max(0, t1 - S), t1
+
+
+def attended_ranges(i: int, S: int, sel, stride: int | None = None):
+    """The attended token set of the query at position i as disjoint ranges [t0, t1), ascending:
+    the UNION of the selected spans (entries < 0 or >= c are empty slots; c = i // stride) and the
+    local window [c*stride, i] -- Algorithm 1's DedupConcat: every token once, however many of the
+    selected spans contain it."""
+    A = S if stride is None else int(stride)
+    c = i // A
+    pieces = [span_extent(int(j), S, A) for j in sel if 0 <= int(j) < c]
+    pieces.append((c * A, i + 1))
+    pieces.sort()
     out = []
-    for j in sel:
-        j = int(j)
-        if 0 <= j < c:
-            out.append((j * S, (j + 1) * S))
-    out.append((c * S, i + 1))
+    for (t0, t1) in pieces:
+        if out and t0 <= out[-1][1]:          # overlaps or touches the previous range: extend it
+            out[-1] = (out[-1][0], max(out[-1][1], t1))
+        else:
+            out.append((t0, t1))
     return out
 
 
-def attention_row(q, K, V, kv: int, i: int, S: int, sel, scale: float, return_weights=False):
+def attention_row(q, K, V, kv: int, i: int, S: int, sel, scale: float, return_weights=False,
+                  stride: int | None = None):
     """Eq. (4) over J = union of selected spans and the local window, one joint softmax.
 
     K, V: anything indexable as X[kv, t0:t1] -> [t1-t0, D].  Returns (o [D], lse), fp64.
     """
     q = _f64(q)
     ks, vs = [], []
-    for (t0, t1) in attended_ranges(i, S, sel):
+    for (t0, t1) in attended_ranges(i, S, sel, stride):
         ks.append(_f64(K[kv, t0:t1]))
         vs.append(_f64(V[kv, t0:t1]))
     Kj = np.concatenate(ks, axis=0)
@@ -171,10 +193,12 @@ def attention_row(q, K, V, kv: int, i: int, S: int, sel, scale: float, return_we
     return o, lse
 
 
-def span_attention(Q, K, V, idx, S: int, scale: float | None = None, q_pos0: int = 0):
+def span_attention(Q, K, V, idx, S: int, scale: float | None = None, q_pos0: int = 0,
+                   stride: int | None = None):
     """Span-attention for every (head, query row): O [Hq, Lq, D] and LSE [Hq, Lq], fp64.
 
-    Q: [Hq, Lq, D]; K, V: [Hkv, L, D]; idx: [Hq, Lq, k] from span_search.
+    Q: [Hq, Lq, D]; K, V: [Hkv, L, D]; idx: [Hq, Lq, k] from span_search (run with S = stride when
+    the spans are longer than the anchor spacing).
     """
     Q = np.asarray(Q)
     Hq, Lq, D = Q.shape
@@ -187,7 +211,7 @@ def span_attention(Q, K, V, idx, S: int, scale: float | None = None, q_pos0: int
     for h in range(Hq):
         kv = h // G
         for r in range(Lq):
-            o, lse = attention_row(Q[h, r], K, V, kv, q_pos0 + r, S, idx[h, r], scale)
+            o, lse = attention_row(Q[h, r], K, V, kv, q_pos0 + r, S, idx[h, r], scale, stride=stride)
             O[h, r] = o
             LSE[h, r] = lse
     return O, LSE
@@ -212,7 +236,8 @@ def gate_weights(scores_sel):
     return e / np.sum(e)
 
 
-def combined_row(q, K, V, kv: int, i: int, S: int, sel, sel_scores, scale: float, return_parts=False):
+def combined_row(q, K, V, kv: int, i: int, S: int, sel, sel_scores, scale: float, return_parts=False,
+                 stride: int | None = None):
     """Algorithm 1, the per-span attention and the gate, for one query row.
 
     sel: selected span indices (entries < 0 or >= c are empty slots); sel_scores: the search
@@ -220,11 +245,14 @@ def combined_row(q, K, V, kv: int, i: int, S: int, sel, sel_scores, scale: float
     local window [c*S, i] (disjoint on the grid, so DedupConcat is a concatenation) and
     A_t = softmax-attention of q over J_t (eq. (4)).  O = sum_t alpha_t A_t (eq. (5)) with
     alpha from eq. (6).  No valid slot: attention over the window only.  Returns o [D] (fp64);
-    with return_parts also (alpha, [A_t], valid slot numbers).
+    with return_parts also (alpha, [A_t], valid slot numbers).  With stride < S the spans are S
+    tokens long at an anchor spacing of `stride` (span_extent); a span never reaches into the
+    window, and every A_t has its own softmax, so overlapping spans need no de-duplication here.
     """
     q = _f64(q)
-    c = i // S
-    Kw, Vw = _f64(K[kv, c * S:i + 1]), _f64(V[kv, c * S:i + 1])
+    A_ = S if stride is None else int(stride)
+    c = i // A_
+    Kw, Vw = _f64(K[kv, c * A_:i + 1]), _f64(V[kv, c * A_:i + 1])
     slots = [n for n, j in enumerate(sel) if 0 <= int(j) < c]
 
     def attend(Kj, Vj):
@@ -237,9 +265,9 @@ def combined_row(q, K, V, kv: int, i: int, S: int, sel, sel_scores, scale: float
         return (o, np.zeros(0), [], []) if return_parts else o
     A = []
     for n in slots:
-        j = int(sel[n])
-        Kj = np.concatenate([_f64(K[kv, j * S:(j + 1) * S]), Kw], axis=0)
-        Vj = np.concatenate([_f64(V[kv, j * S:(j + 1) * S]), Vw], axis=0)
+        t0, t1 = span_extent(int(sel[n]), S, A_)
+        Kj = np.concatenate([_f64(K[kv, t0:t1]), Kw], axis=0)
+        Vj = np.concatenate([_f64(V[kv, t0:t1]), Vw], axis=0)
         A.append(attend(Kj, Vj))
     alpha = gate_weights([sel_scores[n] for n in slots])
     o = np.zeros_like(A[0])
@@ -248,7 +276,8 @@ def combined_row(q, K, V, kv: int, i: int, S: int, sel, sel_scores, scale: float
     return (o, alpha, A, slots) if return_parts else o
 
 
-def span_attention_combined(Q, K, V, idx, scores, S: int, scale: float | None = None, q_pos0: int = 0):
+def span_attention_combined(Q, K, V, idx, scores, S: int, scale: float | None = None, q_pos0: int = 0,
+                            stride: int | None = None):
     """combined_row for every (head, query row): O [Hq, Lq, D], fp64.  idx, scores: [Hq, Lq, k]."""
     Q = np.asarray(Q)
     Hq, Lq, D = Q.shape
@@ -258,7 +287,8 @@ def span_attention_combined(Q, K, V, idx, scores, S: int, scale: float | None = 
     O = np.zeros((Hq, Lq, D), dtype=F64)
     for h in range(Hq):
         for r in range(Lq):
-            O[h, r] = combined_row(Q[h, r], K, V, h // G, q_pos0 + r, S, idx[h, r], scores[h, r], scale)
+            O[h, r] = combined_row(Q[h, r], K, V, h // G, q_pos0 + r, S, idx[h, r], scores[h, r], scale,
+                                   stride=stride)
     return O
 
 

@@ -26,18 +26,21 @@ def causal_mask(Hq, Lq, L, q_pos0=0):
     return np.broadcast_to(t <= i, (Hq, Lq, L)).copy()
 
 
-def span_mask(idx, S, L, q_pos0=0):
-    """Mask of the attended set: selected spans below the query's own span + [c*S, i]."""
+def span_mask(idx, S, L, q_pos0=0, stride=None):
+    """Mask of the attended set: selected spans below the query's own cell + the window [c*A, i].
+    Anchors sit every A = stride tokens (default S); span j is the S tokens that end at its
+    anchor (j+1)*A - 1, so with S > A the spans overlap and the mask is their union."""
+    A = S if stride is None else stride
     Hq, Lq, k = idx.shape
     m = np.zeros((Hq, Lq, L), dtype=bool)
     for h in range(Hq):
         for r in range(Lq):
             i = q_pos0 + r
-            c = i // S
-            m[h, r, c * S:i + 1] = True
+            c = i // A
+            m[h, r, c * A:i + 1] = True
             for j in idx[h, r]:
                 if 0 <= j < c:
-                    m[h, r, j * S:(j + 1) * S] = True
+                    m[h, r, max(0, (j + 1) * A - S):(j + 1) * A] = True
     return m
 
 
@@ -48,7 +51,7 @@ def argsort_topk(scores, k):
     return np.sort(order[:k])
 
 
-def gated_combination(Q, K, V, idx, scores, S, scale, q_pos0=0):
+def gated_combination(Q, K, V, idx, scores, S, scale, q_pos0=0, stride=None):
     """Algorithm 1's output rule by full masked matrices: one dense masked softmax per slot over
     (span of the slot) | (local window), library softmax over the slot scores, weighted sum.
     Rows without a valid slot get the window-only attention.  Q [Hq,Lq,D]; idx, scores [Hq,Lq,k]."""
@@ -56,10 +59,11 @@ def gated_combination(Q, K, V, idx, scores, S, scale, q_pos0=0):
     Hq, Lq, _ = Q.shape
     L = K.shape[1]
     k = idx.shape[2]
+    A_ = S if stride is None else stride
     pos = q_pos0 + np.arange(Lq)
-    c = pos // S
+    c = pos // A_
     t = np.arange(L)[None, None, :]
-    window = (t >= (c * S)[None, :, None]) & (t <= pos[None, :, None])
+    window = (t >= (c * A_)[None, :, None]) & (t <= pos[None, :, None])
     window = np.broadcast_to(window, (Hq, Lq, L))
     valid = (idx >= 0) & (idx < c[None, :, None])                       # [Hq,Lq,k]
     gate_logits = np.where(valid, np.asarray(scores, dtype=np.float64), -np.inf)
@@ -69,7 +73,7 @@ def gated_combination(Q, K, V, idx, scores, S, scale, q_pos0=0):
     O = np.zeros(Q.shape)
     for n in range(k):
         j = idx[:, :, n]
-        in_span = (t >= (j * S)[:, :, None]) & (t < ((j + 1) * S)[:, :, None]) & valid[:, :, n, None]
+        in_span = (t >= ((j + 1) * A_ - S)[:, :, None]) & (t < ((j + 1) * A_)[:, :, None]) & valid[:, :, n, None]
         A, _, _ = dense_masked_attention(Q, K, V, in_span | window, scale)
         O += alpha[:, :, n, None] * A
     Aw, _, _ = dense_masked_attention(Q, K, V, window, scale)

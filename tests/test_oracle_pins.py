@@ -499,3 +499,66 @@ def test_anchor_combined_equals_dense_masked_bruteforce():
     mask[0, 0, i - w + 1:i + 1] = True
     Aw, _, _ = brute.dense_masked_attention(Q, K, V, mask, 0.5)
     assert np.allclose(o0, Aw[0, 0], rtol=1e-12, atol=1e-13)
+
+
+# ---------------------------------------------------------------- redundant grid: spans longer than the anchor
+# spacing (Section 2.4: p_sh + p_sp > 1; Section 4.4's redundancy factors), de-duplicated union
+
+def test_redundant_spans_extent_and_union_closed_forms():
+    # anchors every A = 4 tokens, spans S = 12 tokens long: span j = [max(0, 4(j+1) - 12), 4(j+1))
+    A, S = 4, 12
+    assert orc.span_extent(0, S, A) == (0, 4) and orc.span_extent(1, S, A) == (0, 8)
+    assert orc.span_extent(2, S, A) == (0, 12) and orc.span_extent(5, S, A) == (12, 24)
+    assert orc.span_extent(3, S) == (36, 48)                        # stride = S: the disjoint grid
+    i = 41                                                          # cell c = 10, window [40, 41]
+    # spans 4 = [8, 20) and 5 = [12, 24) overlap in [12, 20): union [8, 24); span 8 = [24, 36) touches it
+    assert orc.attended_ranges(i, S, [4, 5, -1], A) == [(8, 24), (40, 42)]
+    assert orc.attended_ranges(i, S, [5, 4, 8], A) == [(8, 36), (40, 42)]
+    assert orc.attended_ranges(i, S, [9, 10, 11], A) == [(28, 42)]   # span 9 = [28, 40) meets the window; 10, 11 are not candidates
+    # attended keys of consecutive selections j .. j+m-1 (start >= 0): S + (m-1)*A, plus the window
+    Q, K, V = _rand(7, 1, 1, 64, 4)
+    for m in (1, 2, 3, 5):
+        sel = list(range(3, 3 + m))
+        o, lse, w = orc.attention_row(Q[0, 63], K, V, 0, 63, S, sel, 0.5, return_weights=True, stride=A)
+        assert w.shape[0] == S + (m - 1) * A + 4 and w.sum() == pytest.approx(1.0, abs=1e-14)
+
+
+@pytest.mark.parametrize("seed,A,S", [(0, 5, 10), (1, 4, 12), (2, 3, 7), (3, 6, 6)])
+def test_redundant_spans_equal_masked_dense(seed, A, S):
+    # random selections on the anchor grid, incl. neighbours (overlapping spans), empty and garbage slots
+    Hq, Hkv, L, D, k = 4, 2, 61, 8, 4
+    Q, K, V = _rand(50 + seed, Hq, Hkv, L, D)
+    rng = np.random.default_rng(seed)
+    idx = np.full((Hq, L, k), -1, dtype=np.int32)
+    for h in range(Hq):
+        for i in range(L):
+            c = i // A
+            pool = list(rng.permutation(c))[:k]
+            row = pool + [-1] * (k - len(pool))
+            if rng.random() < 0.3:
+                row[-1] = c + int(rng.integers(0, 2))               # own cell or beyond: ignored
+            idx[h, i] = row
+    O, LSE = orc.span_attention(Q, K, V, idx, S, scale=0.5, stride=A)
+    Od, LSEd, _ = brute.dense_masked_attention(Q, K, V, brute.span_mask(idx, S, L, stride=A), 0.5)
+    assert np.allclose(O, Od, rtol=1e-12, atol=1e-13)
+    assert np.allclose(LSE, LSEd, rtol=1e-12, atol=1e-13)
+
+
+def test_redundant_spans_all_selected_is_dense_causal():
+    # every anchor selected: the overlapping spans and the window cover [0, i] exactly once each
+    Hq, Hkv, L, D, A, S = 2, 1, 50, 8, 4, 12
+    Q, K, V = _rand(8, Hq, Hkv, L, D)
+    n = -(-L // A)
+    idx = orc.span_search(Q, orc.span_keys(K, A), A, n)             # the search runs on the anchor grid
+    O, LSE = orc.span_attention(Q, K, V, idx, S, stride=A)
+    Od, LSEd, _ = brute.dense_masked_attention(Q, K, V, brute.causal_mask(Hq, L, L), 1.0 / math.sqrt(D))
+    assert np.allclose(O, Od, rtol=1e-12, atol=1e-13) and np.allclose(LSE, LSEd, rtol=1e-12, atol=1e-13)
+
+
+def test_redundant_spans_combination_equals_dense_per_slot_bruteforce():
+    Hq, Hkv, L, D, A, S, k = 4, 2, 47, 8, 4, 10, 3
+    Q, K, V = _rand(9, Hq, Hkv, L, D)
+    idx, sc = orc.span_search(Q, orc.span_keys(K, A), A, k, return_scores=True)
+    O = orc.span_attention_combined(Q, K, V, idx, sc, S, scale=0.4, stride=A)
+    Ob, _ = brute.gated_combination(Q, K, V, idx, sc, S, 0.4, stride=A)
+    assert np.allclose(O, Ob, rtol=1e-12, atol=1e-13)
