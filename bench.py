@@ -420,6 +420,29 @@ def bench_prefill(cfg, steps, warmup, torch, B, W):
         torch.cuda.synchronize()
         dt_ch = (time.perf_counter() - tch) / nch
         chunked = {"chunk_rows": CH, "ms_per_step": dt_ch * 1e3, "value": cfg.L / dt_ch, "unit": "tokens/s"}
+    # the redundant grid (anchors every S/2 tokens, spans S tokens long: twice the candidates, overlapping
+    # spans de-duplicated in the joint softmax) through the same kernels
+    redundant = None
+    if cfg.dtype == "bf16" and cfg.S % 128 == 0:
+        A = cfg.S // 2
+        Ks2 = torch.zeros((cfg.Hkv, -(-cfg.L // A), cfg.D), dtype=K.dtype, device=dev)
+
+        def step_redundant():
+            B.sl_span_keys(K, A, out=Ks2)
+            idx = B.sl_span_search_prefill(Qs, K, Ks2, A, cfg.topk, ws=ws)
+            B.sl_span_attention_prefill(Q, K, V, idx, cfg.S, ws=ws, out=out, span_stride=A)
+
+        step_redundant()
+        torch.cuda.synchronize()
+        tr = time.perf_counter()
+        nr = max(1, min(steps, 3))
+        for _ in range(nr):
+            step_redundant()
+        torch.cuda.synchronize()
+        dt_r = (time.perf_counter() - tr) / nr
+        redundant = {"anchor_spacing": A, "span_length": cfg.S, "topk": cfg.topk, "ms_per_step": dt_r * 1e3,
+                     "value": cfg.L / dt_r, "unit": "tokens/s"}
+        del Ks2
     # the paper's own geometry in prefill form (row-stationary kernels: every row has its own
     # anchors and span length): the last 4K rows of the cache at the paper's kernel configuration
     paper = None
@@ -459,6 +482,7 @@ def bench_prefill(cfg, steps, warmup, torch, B, W):
         "step_frac_of_peak": (f_search + f_attn) / (dt / steps) / peak,
         "combined_form": {"ms_per_step": dt_combined * 1e3, "value": cfg.L / dt_combined, "unit": "tokens/s"},
         "chunked_prefill": chunked,
+        "redundant_spans": redundant,
         "paper_geometry_prefill": paper,
         "roofline": {"bound": bound, "kernel": kernel, "achieved": tflops_attn / 1e12,
                      "peak": peak / 1e12, "unit": "TFLOP/s", "frac": tflops_attn / peak,

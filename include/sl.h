@@ -19,7 +19,8 @@
  * (search position) is its last token (j+1)*S - 1 (Algorithm 1's span [t - b*l, t + f*l] with
  * f = 0, b*l = S).  Query row r has absolute position i = q_pos0 + r and lies in span
  * c = i / S.  Its candidates are the complete spans j < c (Algorithm 1 removes the window's
- * indices from the anchor candidates); its local window is [c*S, i].
+ * indices from the anchor candidates); its local window is [c*S, i].  (sl_params.span_stride
+ * turns this into a grid of overlapping spans.)
  *
  * Conventions shared by every entry point
  *   - All tensor pointers are DEVICE pointers owned by the caller; the library never allocates,
@@ -84,7 +85,14 @@ typedef struct sl_params {
   int32_t topk;    /* routed spans per (head, query): 1..SL_MAX_TOPK for search, 0..SL_MAX_TOPK for attention */
   int32_t dtype;   /* sl_dtype                                                                     */
   float scale;     /* softmax scale of span-attention; 0 means 1/sqrt(D). Search scores are unscaled (eq. (2)) */
-  int32_t reserved0;
+  int32_t span_stride; /* anchor spacing A in tokens: 0 (or S) = the disjoint grid described above.
+                          0 < A < S is the redundant grid (Section 2.4, p_sh + p_sp > 1; Section 4.4's
+                          redundancy factors): anchors at (j+1)*A - 1, span j = the S tokens ending at its
+                          anchor, [max(0, (j+1)*A - S), (j+1)*A - 1], so neighbouring spans overlap;
+                          c = i / A, candidates j < c, window [c*A, i]; span-attention's joint softmax
+                          runs over the UNION of the selected spans and the window (every token once).
+                          Span-search and sl_span_keys only see the anchor grid: they use A where the
+                          text says S. */
   int64_t q_stride_h, q_stride_t;   /* element strides of Q / Qs; 0 = packed                       */
   int64_t kv_stride_h, kv_stride_t; /* element strides of K and V; 0 = packed                      */
 } sl_params;
@@ -139,7 +147,8 @@ sl_status sl_span_search_decode(const sl_params* p, const void* Qs, const void* 
  * J = union of spans idx[h][r][*] and the local window [c*S, i], logits scale * <Q, K_t>.
  *   idx    in: span indices as produced by span-search.  Entries < 0 or >= c are empty slots
  *          (so arbitrary garbage cannot cause an out-of-range read).  A row must not list a
- *          span twice: the result for such a row is unspecified (still memory-safe).
+ *          span twice: the result for such a row is unspecified (still memory-safe).  Distinct
+ *          spans that overlap (span_stride < S) are de-duplicated: a token counts once.
  *   O      out: [Hq][Lq][D] in the input dtype.
  *   LSE    out: natural-log sum over J of exp(logit), fp32. */
 sl_status sl_span_attention_prefill(const sl_params* p, const void* Q, const void* K, const void* V,

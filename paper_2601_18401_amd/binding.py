@@ -49,7 +49,7 @@ class SlParams(ctypes.Structure):
         ("L", ctypes.c_int64), ("Lq", ctypes.c_int64), ("q_pos0", ctypes.c_int64),
         ("Hq", ctypes.c_int32), ("Hkv", ctypes.c_int32), ("D", ctypes.c_int32),
         ("S", ctypes.c_int32), ("topk", ctypes.c_int32), ("dtype", ctypes.c_int32),
-        ("scale", ctypes.c_float), ("reserved0", ctypes.c_int32),
+        ("scale", ctypes.c_float), ("span_stride", ctypes.c_int32),
         ("q_stride_h", ctypes.c_int64), ("q_stride_t", ctypes.c_int64),
         ("kv_stride_h", ctypes.c_int64), ("kv_stride_t", ctypes.c_int64),
     ]
@@ -159,7 +159,7 @@ def _arm(prof):
         load().sl_set_profile_events(ctypes.c_void_p(prof[0]), ctypes.c_void_p(prof[1]))
 
 
-def make_params(Q, K, S, topk, q_pos0=0, scale=0.0) -> SlParams:
+def make_params(Q, K, S, topk, q_pos0=0, scale=0.0, span_stride=0) -> SlParams:
     """Q: [Hq, Lq, D] (innermost contiguous), K: [Hkv, L, D]."""
     if Q.dim() != 3 or K.dim() != 3 or Q.stride(2) != 1 or K.stride(2) != 1:
         raise ValueError("expect Q [Hq, Lq, D] and K [Hkv, L, D] with contiguous innermost dimension")
@@ -168,6 +168,7 @@ def make_params(Q, K, S, topk, q_pos0=0, scale=0.0) -> SlParams:
     p.Hq, p.Hkv, p.D = Q.shape[0], K.shape[0], Q.shape[2]
     p.S, p.topk, p.dtype = int(S), int(topk), _dtype_code(Q)
     p.scale = float(scale)
+    p.span_stride = int(span_stride)
     p.q_stride_h, p.q_stride_t = Q.stride(0), Q.stride(1)
     p.kv_stride_h, p.kv_stride_t = K.stride(0), K.stride(1)
     return p
@@ -256,10 +257,10 @@ def sl_span_search_decode(Qs, K, Ks, S, topk, q_pos0=None, want_scores=False, ws
                    want_scores, ws, prof)
 
 
-def _attention(fn_name, op, Q, K, V, idx, S, q_pos0, scale, ws, prof, out):
+def _attention(fn_name, op, Q, K, V, idx, S, q_pos0, scale, ws, prof, out, span_stride=0):
     lib = load()
     topk = 0 if idx is None else idx.shape[2]
-    p = make_params(Q, K, S, topk, q_pos0, scale)
+    p = make_params(Q, K, S, topk, q_pos0, scale, span_stride)
     if V.shape != K.shape or V.stride() != K.stride():
         raise ValueError("V must have the shape and strides of K")
     Hq, Lq, D = Q.shape
@@ -295,10 +296,10 @@ def sl_span_attention_decode_noalloc(Q, K, V, idx, S, out, q_pos0=None, scale=0.
     return O, LSE
 
 
-def _combined(fn_name, op, Q, K, V, idx, scores, S, q_pos0, scale, ws, out):
+def _combined(fn_name, op, Q, K, V, idx, scores, S, q_pos0, scale, ws, out, span_stride=0):
     lib = load()
     topk = 0 if idx is None else idx.shape[2]
-    p = make_params(Q, K, S, topk, q_pos0, scale)
+    p = make_params(Q, K, S, topk, q_pos0, scale, span_stride)
     if V.shape != K.shape or V.stride() != K.stride():
         raise ValueError("V must have the shape and strides of K")
     if topk > 0 and (scores is None or scores.shape != idx.shape or scores.dtype != torch.float32
@@ -313,15 +314,17 @@ def _combined(fn_name, op, Q, K, V, idx, scores, S, q_pos0, scale, ws, out):
     return O
 
 
-def sl_span_attention_combined_prefill(Q, K, V, idx, scores, S, q_pos0=0, scale=0.0, ws=None, out=None):
+def sl_span_attention_combined_prefill(Q, K, V, idx, scores, S, q_pos0=0, scale=0.0, ws=None, out=None,
+                                       span_stride=0):
     return _combined("sl_span_attention_combined_prefill", OP_ATTENTION_PREFILL, Q, K, V, idx, scores, S,
-                     q_pos0, scale, ws, out)
+                     q_pos0, scale, ws, out, span_stride)
 
 
-def sl_span_attention_combined_decode(Q, K, V, idx, scores, S, q_pos0=None, scale=0.0, ws=None, out=None):
+def sl_span_attention_combined_decode(Q, K, V, idx, scores, S, q_pos0=None, scale=0.0, ws=None, out=None,
+                                      span_stride=0):
     q_pos0 = K.shape[1] - 1 if q_pos0 is None else q_pos0
     return _combined("sl_span_attention_combined_decode", OP_ATTENTION_DECODE, Q, K, V, idx, scores, S,
-                     q_pos0, scale, ws, out)
+                     q_pos0, scale, ws, out, span_stride)
 
 
 def sl_anchor_search_decode(Qs, K, topk, window, want_scores=False, prof=None, search_root=2):
@@ -392,15 +395,15 @@ def sl_anchor_attention_prefill(Q, K, V, anchors, scores, window, backward_facto
     return O
 
 
-def sl_span_attention_prefill(Q, K, V, idx, S, q_pos0=0, scale=0.0, ws=None, prof=None, out=None):
+def sl_span_attention_prefill(Q, K, V, idx, S, q_pos0=0, scale=0.0, ws=None, prof=None, out=None, span_stride=0):
     return _attention("sl_span_attention_prefill", OP_ATTENTION_PREFILL, Q, K, V, idx, S, q_pos0,
-                      scale, ws, prof, out)
+                      scale, ws, prof, out, span_stride)
 
 
-def sl_span_attention_decode(Q, K, V, idx, S, q_pos0=None, scale=0.0, ws=None, prof=None, out=None):
+def sl_span_attention_decode(Q, K, V, idx, S, q_pos0=None, scale=0.0, ws=None, prof=None, out=None, span_stride=0):
     q_pos0 = K.shape[1] - 1 if q_pos0 is None else q_pos0
     return _attention("sl_span_attention_decode", OP_ATTENTION_DECODE, Q, K, V, idx, S, q_pos0,
-                      scale, ws, prof, out)
+                      scale, ws, prof, out, span_stride)
 
 
 class DecodeBatch:
@@ -412,7 +415,7 @@ class DecodeBatch:
     the same one (caches cut from one [B, Hkv, Lmax, D] buffer); otherwise every cache must be
     contiguous and the library takes L_b * D."""
 
-    def __init__(self, Qs, Q, K, V, Ks, S, topk, want_scores=False):
+    def __init__(self, Qs, Q, K, V, Ks, S, topk, want_scores=False, span_stride=0):
         B = len(Q)
         if not (len(Qs) == len(K) == len(V) == B) or (Ks is not None and len(Ks) != B) or B < 1:
             raise ValueError("one Qs, Q, K, V (and Ks) per sequence")
@@ -448,7 +451,7 @@ class DecodeBatch:
         host = torch.frombuffer(bytearray(bytes(recs)), dtype=torch.int64).clone()
         self.records = host.to(dev)
         m = self.longest
-        self.params = make_params(Q[m], K[m], S, topk, K[m].shape[1] - 1)
+        self.params = make_params(Q[m], K[m], S, topk, K[m].shape[1] - 1, span_stride=span_stride)
         if not same:
             self.params.kv_stride_h = 0
 

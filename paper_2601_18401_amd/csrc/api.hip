@@ -30,6 +30,7 @@ sl_status make_problem(const sl_params* p, int op, Problem* pb) {
   if (p->q_pos0 > p->L - p->Lq) return SL_ERR_INVALID_ARG;  // last query must be a visible key
   if (p->Hq < 1 || p->Hkv < 1 || p->Hq % p->Hkv != 0) return SL_ERR_INVALID_ARG;
   if (p->S < 1 || p->topk < 0) return SL_ERR_INVALID_ARG;
+  if (p->span_stride < 0 || p->span_stride > p->S) return SL_ERR_INVALID_ARG;
   if (p->dtype != SL_F32 && p->dtype != SL_BF16) return SL_ERR_INVALID_ARG;
   if (!(p->scale >= 0.f) || std::isinf(p->scale)) return SL_ERR_INVALID_ARG;
   const bool is_search = (op == SL_OP_SEARCH_PREFILL || op == SL_OP_SEARCH_DECODE);
@@ -68,6 +69,7 @@ sl_status make_problem(const sl_params* p, int op, Problem* pb) {
   pb->G = p->Hq / p->Hkv;
   pb->D = p->D;
   pb->S = p->S;
+  pb->A = p->span_stride ? p->span_stride : p->S;
   pb->topk = p->topk;
   pb->dtype = p->dtype;
   pb->scale = p->scale > 0.f ? p->scale : 1.0f / std::sqrt((float)p->D);
@@ -76,7 +78,7 @@ sl_status make_problem(const sl_params* p, int op, Problem* pb) {
   pb->kvsh = kvsh;
   pb->kvsh_given = p->kv_stride_h != 0;
   pb->kvst = kvst;
-  pb->n = (p->L + p->S - 1) / p->S;
+  pb->n = (p->L + pb->A - 1) / pb->A;
   pb->prof_start = nullptr;
   pb->prof_stop = nullptr;
   pb->combined = false;
@@ -113,6 +115,7 @@ sl_status search_entry(const sl_params* p, int op, const void* Qs, const void* K
   s = check_ws(pb, op, ws, ws_bytes);
   if (s != SL_OK) return s;
   take_profile_events(&pb);
+  pb.S = pb.A;  // span-search only sees the anchor grid
   hipStream_t st = static_cast<hipStream_t>(stream);
   if (op == SL_OP_SEARCH_DECODE) return decode_search(pb, Qs, K, Ks, idx, scores, ws, st);
   return prefill_search(pb, Qs, K, Ks, idx, scores, ws, st);
@@ -171,6 +174,7 @@ sl_status sl_span_keys(const sl_params* p, const void* K, void* Ks, void* hip_st
   sl_status s = sl::make_problem(&q, SL_OP_ATTENTION_PREFILL, &pb);
   if (s != SL_OK) return s;
   if (!K || !Ks || !sl::aligned16(K) || !sl::aligned16(Ks)) return SL_ERR_INVALID_ARG;
+  pb.S = pb.A;  // keys sit on the anchor grid
   return sl::span_keys(pb, K, Ks, static_cast<hipStream_t>(hip_stream));
 }
 
@@ -329,6 +333,7 @@ sl_status sl_span_search_decode_batched(const sl_params* p, const sl_decode_seq*
   sl_status s = sl::make_problem(p, SL_OP_SEARCH_DECODE, &pb);
   if (s != SL_OK) return s;
   if (!seqs || B < 1 || B > 65535 || (reinterpret_cast<uintptr_t>(seqs) & 7u)) return SL_ERR_INVALID_ARG;
+  pb.S = pb.A;  // span-search only sees the anchor grid
   return sl::decode_search_batched(pb, seqs, B, static_cast<hipStream_t>(hip_stream));
 }
 

@@ -35,8 +35,11 @@ template <typename T, int D>
 __global__ __launch_bounds__(256) void prefill_attention_rows_kernel(
     const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
     const int32_t* __restrict__ idx, T* __restrict__ O, float* __restrict__ LSE, int64_t Lq,
-    int64_t q_pos0, int Hq, int G, int S, int topk, float scale_log2e, int64_t qsh, int64_t qst,
+    int64_t q_pos0, int Hq, int G, int S, int A, int topk, float scale_log2e, int64_t qsh, int64_t qst,
     int64_t kvsh, int64_t kvst) {
+  // Anchors every A tokens, span j = the S tokens ending at (j+1)*A - 1 (A = S: the disjoint grid).
+  // With A < S the spans of a row overlap: a span's range then starts behind the end of the
+  // nearest lower span the row lists, so that every token of the union is attended once.
   using RL = RowLayout<T, D>;
   constexpr int EPL = RL::EPL, LPR = RL::LPR;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -45,7 +48,7 @@ __global__ __launch_bounds__(256) void prefill_attention_rows_kernel(
   const int h = (int)(row / Lq);
   const int64_t r = row % Lq, i = q_pos0 + r;
   const int kv = h / G;
-  const int64_t c = i / S;
+  const int64_t c = i / A;
   const int lr = lane % LPR;
   float q2[EPL];
   {
@@ -60,9 +63,19 @@ __global__ __launch_bounds__(256) void prefill_attention_rows_kernel(
   st.init();
   for (int slot = 0; slot < topk; ++slot) {
     const int64_t j = idx[row * topk + slot];
-    if (j >= 0 && j < c) attend_range<T, D, 4>(q2, Kb, Vb, kvst, j * S, (j + 1) * S, lane, st);
+    if (j >= 0 && j < c) {
+      const int64_t end = (j + 1) * A;
+      int64_t begin = end - S > 0 ? end - S : 0;
+      if (A < S) {
+        for (int s2 = 0; s2 < topk; ++s2) {
+          const int64_t jj = idx[row * topk + s2];
+          if (jj >= 0 && jj < j && (jj + 1) * A > begin) begin = (jj + 1) * A;
+        }
+      }
+      attend_range<T, D, 4>(q2, Kb, Vb, kvst, begin, end, lane, st);
+    }
   }
-  attend_range<T, D, 4>(q2, Kb, Vb, kvst, c * S, i + 1, lane, st);
+  attend_range<T, D, 4>(q2, Kb, Vb, kvst, c * A, i + 1, lane, st);
 
   merge_row_groups<T, D>(st);
   if (lane < LPR) {
@@ -83,7 +96,7 @@ template <typename T, int D>
 __global__ __launch_bounds__(256) void prefill_combined_rows_kernel(
     const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
     const int32_t* __restrict__ idx, const float* __restrict__ gate, T* __restrict__ O, int64_t Lq,
-    int64_t q_pos0, int Hq, int G, int S, int topk, float scale_log2e, int64_t qsh, int64_t qst,
+    int64_t q_pos0, int Hq, int G, int S, int A, int topk, float scale_log2e, int64_t qsh, int64_t qst,
     int64_t kvsh, int64_t kvst) {
   using RL = RowLayout<T, D>;
   constexpr int EPL = RL::EPL, LPR = RL::LPR;
@@ -93,7 +106,7 @@ __global__ __launch_bounds__(256) void prefill_combined_rows_kernel(
   const int h = (int)(row / Lq);
   const int64_t r = row % Lq, i = q_pos0 + r;
   const int kv = h / G;
-  const int64_t c = i / S;
+  const int64_t c = i / A;  // anchors every A tokens; every span has its own softmax: no clipping here
   const int lr = lane % LPR;
   float q2[EPL];
   {
@@ -106,7 +119,7 @@ __global__ __launch_bounds__(256) void prefill_combined_rows_kernel(
   const T* Vb = V + kv * kvsh;
   AttendState<T, D> win;
   win.init();
-  attend_range<T, D, 4>(q2, Kb, Vb, kvst, c * S, i + 1, lane, win);
+  attend_range<T, D, 4>(q2, Kb, Vb, kvst, c * A, i + 1, lane, win);
   merge_row_groups<T, D>(win);  // the window always holds the query's own token: win.l > 0
 
   // gate: softmax of the scores of the valid slots
@@ -124,7 +137,7 @@ __global__ __launch_bounds__(256) void prefill_combined_rows_kernel(
     if (!(j >= 0 && j < c)) continue;
     AttendState<T, D> st;
     st.init();
-    attend_range<T, D, 4>(q2, Kb, Vb, kvst, j * S, (j + 1) * S, lane, st);
+    attend_range<T, D, 4>(q2, Kb, Vb, kvst, (j + 1) * A - S > 0 ? (j + 1) * A - S : 0, (j + 1) * A, lane, st);
     merge_row_groups<T, D>(st);
     const float M = fmaxf(st.m, win.m);
     const float wa = fast_exp2(st.m - M), wb = fast_exp2(win.m - M);
@@ -244,7 +257,7 @@ sl_status launch_rows(const Problem& pb, const void* Q, const void* K, const voi
     hipLaunchKernelGGL((prefill_combined_rows_kernel<T, D>), dim3((unsigned)((rows + 3) / 4)),
                        dim3(256), 0, st, static_cast<const T*>(Q), static_cast<const T*>(K),
                        static_cast<const T*>(V), idx, pb.gate, static_cast<T*>(O), pb.Lq, pb.q_pos0,
-                       pb.Hq, pb.G, pb.S, pb.topk, pb.scale * kLog2e, pb.qsh, pb.qst, pb.kvsh,
+                       pb.Hq, pb.G, pb.S, pb.A, pb.topk, pb.scale * kLog2e, pb.qsh, pb.qst, pb.kvsh,
                        pb.kvst);
     if (pb.prof_stop) (void)hipEventRecord(pb.prof_stop, st);
     return hipGetLastError() == hipSuccess ? SL_OK : SL_ERR_LAUNCH;
@@ -252,7 +265,7 @@ sl_status launch_rows(const Problem& pb, const void* Q, const void* K, const voi
   hipLaunchKernelGGL((prefill_attention_rows_kernel<T, D>), dim3((unsigned)((rows + 3) / 4)),
                      dim3(256), 0, st, static_cast<const T*>(Q), static_cast<const T*>(K),
                      static_cast<const T*>(V), idx, static_cast<T*>(O), LSE, pb.Lq, pb.q_pos0,
-                     pb.Hq, pb.G, pb.S, pb.topk, pb.scale * kLog2e, pb.qsh, pb.qst, pb.kvsh,
+                     pb.Hq, pb.G, pb.S, pb.A, pb.topk, pb.scale * kLog2e, pb.qsh, pb.qst, pb.kvsh,
                      pb.kvst);
   if (pb.prof_stop) (void)hipEventRecord(pb.prof_stop, st);
   return hipGetLastError() == hipSuccess ? SL_OK : SL_ERR_LAUNCH;

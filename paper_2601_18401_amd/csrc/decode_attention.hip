@@ -29,8 +29,11 @@ template <typename T, int D, int U>
 __device__ __forceinline__ void decode_split_body(
     const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
     const int32_t* __restrict__ idx, float* __restrict__ part, int64_t q_pos, int Hq, int Hkv,
-    int S, int topk, int nchunks, int CT, float scale_log2e, int64_t qsh, int64_t kvsh,
+    int S, int A, bool clip, int topk, int nchunks, int CT, float scale_log2e, int64_t qsh, int64_t kvsh,
     int64_t kvst, int n_routed_blocks, int local_stride, const AnchorRanges ar) {
+  // Grid: anchors every A tokens, span j = the S tokens ending at (j+1)*A - 1 (A = S: disjoint spans).
+  // clip (joint softmax with A < S): spans of one head overlap, and a token must count once, so an
+  // entry's range starts behind the end of the nearest lower span that the same head lists.
   // ar.on: the paper's geometry (Section 3.3, Algorithm 1) instead of the grid: idx holds anchor
   // tokens, slot s of head h attends S_t minus W for t = idx[h][s] (W is a suffix of [0, q_pos], so
   // the set difference is a clip; DedupConcat(S_t, W) is then the slot's range plus the window's),
@@ -42,7 +45,7 @@ __device__ __forceinline__ void decode_split_body(
   __shared__ float s_o[NG][D];
 
   const int G = Hq / Hkv;
-  const int64_t c = q_pos / S;
+  const int64_t c = q_pos / A;
   int h, slot, ck;
   // The local-window items come first in the grid: they are served by the L2 after their first
   // reader, and at the end of the grid they would leave the HBM idle while the last of them run.
@@ -67,6 +70,22 @@ __device__ __forceinline__ void decode_split_body(
   }
   const int kv = h / G;
 
+  // chunk ck of span j as head hh attends it: [t0, t1), empty for an empty slot or past the range
+  auto grid_chunk = [&](int hh, int64_t j, int64_t& t0, int64_t& t1) {
+    t0 = t1 = 0;
+    if (j < 0 || j >= c) return;
+    const int64_t end = (j + 1) * A;
+    int64_t begin = end - S > 0 ? end - S : 0;
+    if (clip) {
+      for (int s2 = 0; s2 < topk; ++s2) {
+        const int64_t jj = idx[(int64_t)hh * topk + s2];
+        if (jj >= 0 && jj < j && (jj + 1) * A > begin) begin = (jj + 1) * A;
+      }
+    }
+    t0 = begin + (int64_t)ck * CT;
+    t1 = t0 + CT < end ? t0 + CT : end;
+    if (t1 < t0) t1 = t0;
+  };
   int64_t t0, t1;
   if (ar.on) {
     int64_t r0 = 0, r1 = 0;
@@ -85,15 +104,9 @@ __device__ __forceinline__ void decode_split_body(
     t0 = r0 + (int64_t)ck * CT;
     t1 = t0 + CT < r1 ? t0 + CT : r1;
   } else if (slot < topk) {
-    const int64_t j = idx[(int64_t)h * topk + slot];
-    if (j >= 0 && j < c) {
-      t0 = j * S + (int64_t)ck * CT;
-      t1 = t0 + CT < (j + 1) * S ? t0 + CT : (j + 1) * S;
-    } else {
-      t0 = t1 = 0;
-    }
+    grid_chunk(h, idx[(int64_t)h * topk + slot], t0, t1);
   } else {
-    t0 = c * S + (int64_t)ck * CT;
+    t0 = c * A + (int64_t)ck * CT;
     t1 = t0 + CT < q_pos + 1 ? t0 + CT : q_pos + 1;
   }
 
@@ -136,6 +149,7 @@ __device__ __forceinline__ void decode_split_body(
   while (true) {
     const int he = shared_span ? kv * G + entry / topk : h;
     const int se = shared_span ? entry % topk : slot;
+    if (shared_span && clip && !ar.on) grid_chunk(he, idx[(int64_t)he * topk + se], t0, t1);  // the entry's own clip
     float* prec = part + (((int64_t)he * (topk + 1) + se) * nchunks + ck) * (D + 2);
     if (t0 >= t1) {  // empty slot or chunk past the end of the range (uniform over the workgroup)
       if (tid < D) prec[tid] = 0.f;
@@ -215,10 +229,10 @@ template <typename T, int D, int U>
 __global__ __launch_bounds__(kDecodeThreads) void decode_split_kernel(
     const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
     const int32_t* __restrict__ idx, float* __restrict__ part, int64_t q_pos, int Hq, int Hkv,
-    int S, int topk, int nchunks, int CT, float scale_log2e, int64_t qsh, int64_t kvsh,
+    int S, int A, bool clip, int topk, int nchunks, int CT, float scale_log2e, int64_t qsh, int64_t kvsh,
     int64_t kvst, int n_routed_blocks, int local_stride, const AnchorRanges ar) {
-  decode_split_body<T, D, U>(Q, K, V, idx, part, q_pos, Hq, Hkv, S, topk, nchunks, CT, scale_log2e, qsh,
-                          kvsh, kvst, n_routed_blocks, local_stride, ar);
+  decode_split_body<T, D, U>(Q, K, V, idx, part, q_pos, Hq, Hkv, S, A, clip, topk, nchunks, CT, scale_log2e,
+                          qsh, kvsh, kvst, n_routed_blocks, local_stride, ar);
 }
 
 // Batched decode: blockIdx.y is the sequence; its tensors and length come from the device array.
@@ -234,8 +248,8 @@ struct AnchorBatch {
 template <typename T, int D, int U>
 __global__ __launch_bounds__(kDecodeThreads) void decode_split_batched_kernel(
     const sl_decode_seq* __restrict__ seqs, float* __restrict__ part, int64_t part_stride, int Hq,
-    int Hkv, int S, int topk, int nchunks, int CT, float scale_log2e, int64_t qsh, int64_t kvsh,
-    int64_t kvst, int n_routed_blocks, int local_stride, const AnchorBatch ab) {
+    int Hkv, int S, int A, bool clip, int topk, int nchunks, int CT, float scale_log2e, int64_t qsh,
+    int64_t kvsh, int64_t kvst, int n_routed_blocks, int local_stride, const AnchorBatch ab) {
   const sl_decode_seq sq = seqs[blockIdx.y];
   const int64_t i = sq.L - 1;
   AnchorRanges ar{false, 0, 0, 0};
@@ -248,8 +262,8 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_split_batched_kernel(
   }
   decode_split_body<T, D, U>(static_cast<const T*>(sq.Q), static_cast<const T*>(sq.K),
                           static_cast<const T*>(sq.V), sq.idx, part + blockIdx.y * part_stride, i, Hq,
-                          Hkv, S, topk, nchunks, CT, scale_log2e, qsh, kvsh ? kvsh : sq.L * kvst, kvst,
-                          n_routed_blocks, local_stride, ar);
+                          Hkv, S, A, clip, topk, nchunks, CT, scale_log2e, qsh, kvsh ? kvsh : sq.L * kvst,
+                          kvst, n_routed_blocks, local_stride, ar);
 }
 
 // Merges the (topk + 1) * nchunks partial records of a head.  grid (Hq, D / 32): each workgroup
@@ -506,19 +520,21 @@ void launch_split_u(int grid, hipStream_t st, hipEvent_t e0, hipEvent_t e1, cons
                     const void* V, const int32_t* idx, float* part, const Problem& pb, int S, int nchunks,
                     int CT, int n_routed, int local_stride, const AnchorRanges& ar) {
   const float scale_log2e = pb.scale * kLog2e;
+  const bool clip = !ar.on && pb.A < pb.S && !pb.combined;  // overlapping spans in one joint softmax
   if (e0) {
     // With profiling events the launch itself carries them: they then hold the kernel's own
     // begin and end timestamps (events recorded on the stream before / after a 45 us kernel would
     // add the dispatch gaps, several microseconds).
     hipExtLaunchKernelGGL((decode_split_kernel<T, D, U>), dim3(grid), dim3(kDecodeThreads), 0, st, e0, e1,
                           0, static_cast<const T*>(Q), static_cast<const T*>(K),
-                          static_cast<const T*>(V), idx, part, pb.q_pos0, pb.Hq, pb.Hkv, S, pb.topk,
-                          nchunks, CT, scale_log2e, pb.qsh, pb.kvsh, pb.kvst, n_routed, local_stride, ar);
+                          static_cast<const T*>(V), idx, part, pb.q_pos0, pb.Hq, pb.Hkv, S, ar.on ? S : pb.A,
+                          clip, pb.topk, nchunks, CT, scale_log2e, pb.qsh, pb.kvsh, pb.kvst, n_routed,
+                          local_stride, ar);
   } else {
     hipLaunchKernelGGL((decode_split_kernel<T, D, U>), dim3(grid), dim3(kDecodeThreads), 0, st,
                        static_cast<const T*>(Q), static_cast<const T*>(K), static_cast<const T*>(V), idx,
-                       part, pb.q_pos0, pb.Hq, pb.Hkv, S, pb.topk, nchunks, CT, scale_log2e, pb.qsh,
-                       pb.kvsh, pb.kvst, n_routed, local_stride, ar);
+                       part, pb.q_pos0, pb.Hq, pb.Hkv, S, ar.on ? S : pb.A, clip, pb.topk, nchunks, CT,
+                       scale_log2e, pb.qsh, pb.kvsh, pb.kvst, n_routed, local_stride, ar);
   }
 }
 
@@ -540,14 +556,16 @@ void launch_split_batched(int grid, int B, hipStream_t st, const sl_decode_seq* 
                           int local_stride, const AnchorBatch& ab) {
   const float scale_log2e = pb.scale * kLog2e;
   const int64_t kvsh = pb.kvsh_given ? pb.kvsh : (int64_t)0;
+  const int A = ab.on ? S : pb.A;
+  const bool clip = !ab.on && pb.A < pb.S && !pb.combined;
   if (wide_batches(CT))
     hipLaunchKernelGGL((decode_split_batched_kernel<T, D, 16>), dim3(grid, B), dim3(kDecodeThreads), 0, st,
-                       seqs, part, part_stride, pb.Hq, pb.Hkv, S, pb.topk, nchunks, CT, scale_log2e, pb.qsh,
-                       kvsh, pb.kvst, n_routed, local_stride, ab);
+                       seqs, part, part_stride, pb.Hq, pb.Hkv, S, A, clip, pb.topk, nchunks, CT, scale_log2e,
+                       pb.qsh, kvsh, pb.kvst, n_routed, local_stride, ab);
   else
     hipLaunchKernelGGL((decode_split_batched_kernel<T, D, 8>), dim3(grid, B), dim3(kDecodeThreads), 0, st,
-                       seqs, part, part_stride, pb.Hq, pb.Hkv, S, pb.topk, nchunks, CT, scale_log2e, pb.qsh,
-                       kvsh, pb.kvst, n_routed, local_stride, ab);
+                       seqs, part, part_stride, pb.Hq, pb.Hkv, S, A, clip, pb.topk, nchunks, CT, scale_log2e,
+                       pb.qsh, kvsh, pb.kvst, n_routed, local_stride, ab);
 }
 
 // The reductions keep one weight (joint form) or two statistics (gated form) per partial record of

@@ -297,7 +297,7 @@ struct FlashArgs {
   bf16_t* O;
   float* LSE;
   int64_t L, Lp, Lq, q_pos0;
-  int Hq, G, S, topk, n;
+  int Hq, G, S, A, topk, n;  // A: anchor spacing (= S on the disjoint grid); n = ceil(L / A)
   float scale_log2e;
   int64_t qsh, qst, kvsh, kvst;
 };
@@ -382,7 +382,7 @@ __device__ __forceinline__ void flush_routed_output(const FlashArgs& a, char* ld
 // When the kv loop is over, the first K/V stage and the Q fragments of the next tile are
 // requested before the output tile is normalised and staged in LDS; a routed tile's staged
 // output goes to HBM during the next tile's first kv step (c.pending), a window tile's at once.
-template <int NG, bool LOCAL, bool FUSED, typename RequestNext, typename DescribeNext>
+template <int NG, bool LOCAL, bool FUSED, bool CLIP, typename RequestNext, typename DescribeNext>
 __device__ __forceinline__ void flash_tile(const FlashArgs& a, char* lds, const TileDesc& cur,
                                            TileDesc& next, bool has_next, RequestNext&& request_next,
                                            DescribeNext&& describe_next, FlashCarry& c) {
@@ -487,7 +487,7 @@ __device__ __forceinline__ void flash_tile(const FlashArgs& a, char* lds, const 
     for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        if (LOCAL) {
+        if (LOCAL || CLIP) {  // per-row range: the causal window, or a span clipped behind a lower one
           const int64_t t = t0 + 32 * sub + 16 * (r >> 3) + 8 * hf + (r & 7);
           s[sub][r] = (t <= cur.i_q && t >= cur.lo_q) ? s[sub][r] : -INFINITY;
         }
@@ -643,7 +643,7 @@ __device__ __forceinline__ void flash_tile(const FlashArgs& a, char* lds, const 
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
         const int row = w4 * 32 + (half * 4 + u) * 4 + (lane >> 4), piece = lane & 15;
-        const int cq = (int)((a.q_pos0 + (outs[u] - cur.row_base)) / a.S);
+        const int cq = (int)((a.q_pos0 + (outs[u] - cur.row_base)) / a.A);
         const float lw = row_lse[row];
         float M = lw;
 #pragma unroll
@@ -722,6 +722,9 @@ __device__ __forceinline__ void flash_tile(const FlashArgs& a, char* lds, const 
 // workgroups walk the chunk interleaved, so at any moment they sit on neighbouring tiles -- the
 // same one or two buckets -- and share the span through that XCD's L2.  The record and the item
 // of a workgroup's next tile are fetched while its current tile is computed.
+// CLIP (overlapping spans, anchor spacing A < S, joint softmax): a row's range in span j starts behind
+// the end of the nearest lower span that the row lists, so that every token of the union counts once.
+template <bool CLIP>
 __global__ __launch_bounds__(FlashLds<2>::kThreads, 1) void span_flash_routed_kernel(const FlashArgs a) {
   extern __shared__ __align__(16) char lds[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -737,15 +740,24 @@ __global__ __launch_bounds__(FlashLds<2>::kThreads, 1) void span_flash_routed_ke
     TileDesc d;
     d.kv = info.x / a.n;
     const int j = info.x % a.n;
-    d.kv_begin = (int64_t)j * a.S;
-    d.kv_end = d.kv_begin + a.S;
+    d.kv_end = (int64_t)(j + 1) * a.A;
+    d.kv_begin = d.kv_end - a.S > 0 ? d.kv_end - a.S : 0;
     const int rowid = item >> 5, slot = item & 31;
     const int hl = rowid / (int)a.Lq;
     const int64_t r = rowid - (int64_t)hl * a.Lq;
     const int h = d.kv * a.G + hl;
     d.q_off = h * a.qsh + r * a.qst;
     d.row_out = qrow < info.z ? ((int64_t)h * a.Lq + r) * (a.topk + 1) + slot : -1;
-    d.i_q = d.lo_q = 0;
+    d.i_q = d.kv_end;
+    d.lo_q = 0;
+    if (CLIP) {
+      const int64_t c = (a.q_pos0 + r) / a.A;
+      const int32_t* irow = a.idx + ((int64_t)h * a.Lq + r) * a.topk;
+      for (int s2 = 0; s2 < a.topk; ++s2) {
+        const int64_t jj = irow[s2];
+        if (jj >= 0 && jj < c && jj < j && (jj + 1) * a.A > d.lo_q) d.lo_q = (jj + 1) * a.A;
+      }
+    }
     d.row_base = 0;
     return d;
   };
@@ -762,7 +774,7 @@ __global__ __launch_bounds__(FlashLds<2>::kThreads, 1) void span_flash_routed_ke
   for (int64_t t = t_begin; t < t_end; t += NWL) {
     const bool has_next = t + NWL < t_end;
     TileDesc nxt = cur;
-    flash_tile<2, false, false>(
+    flash_tile<2, false, false, CLIP>(
         a, lds, cur, nxt, has_next,
         [&] {
           const int* rec = reinterpret_cast<const int*>(a.tile_info + (t + NWL)) + (lane & 3);
@@ -821,7 +833,7 @@ __global__ __launch_bounds__(FlashLds<1>::kThreads, 2) void span_flash_local_ker
   // with its own L2.  A run of `tps` consecutive row tiles (one span's worth) goes to one XCD,
   // and inside an XCD the G query heads of a kv head take the same row tile back to back, so the
   // window's K/V tiles are fetched from HBM about once instead of once per head and row tile.
-  const LocalMap lm = local_map(a.Lq, a.S);
+  const LocalMap lm = local_map(a.Lq, a.A);
   const int xcd = blockIdx.x % 8, slot = blockIdx.x / 8;
   const int chunks_x = (lm.chunks - xcd + 7) / 8;                 // chunks xcd, xcd+8, ... of a kv head
   const bool has_last = lm.chunks > 0 && (lm.chunks - 1) % 8 == xcd;  // the only chunk that may be short
@@ -841,17 +853,17 @@ __global__ __launch_bounds__(FlashLds<1>::kThreads, 2) void span_flash_local_ker
   if (FUSED) d.row_out = r < a.Lq ? d.row_base + r : -1;
   else d.row_out = r < a.Lq ? (d.row_base + r) * (a.topk + 1) + a.topk : -1;
   d.i_q = a.q_pos0 + rc;
-  d.lo_q = (d.i_q / a.S) * a.S;
+  d.lo_q = (d.i_q / a.A) * a.A;
   const int64_t i_first = a.q_pos0 + r0;
   const int64_t i_last = min(a.q_pos0 + r0 + TML - 1, a.q_pos0 + a.Lq - 1);
-  d.kv_begin = (i_first / a.S) * a.S;
+  d.kv_begin = (i_first / a.A) * a.A;
   d.kv_end = d.kv_begin + ((i_last - d.kv_begin) / TN + 1) * TN;
   FlashCarry carry;
   carry.kb = carry.vb = 0;
   carry.primed = false;
   carry.pending = false;
   TileDesc unused = d;
-  flash_tile<1, true, FUSED>(a, lds, d, unused, false, [] {}, [&] { return d; }, carry);
+  flash_tile<1, true, FUSED, false>(a, lds, d, unused, false, [] {}, [&] { return d; }, carry);
 }
 
 // ------------------------------------------------------------------ merge
@@ -1017,7 +1029,9 @@ bool device_setup(DeviceSetup* out) {
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
       cus = 256;
     d.lds_ok =
-        hipFuncSetAttribute(reinterpret_cast<const void*>(span_flash_routed_kernel),
+        hipFuncSetAttribute(reinterpret_cast<const void*>(span_flash_routed_kernel<false>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, FlashLds<2>::kBytes) == hipSuccess &&
+        hipFuncSetAttribute(reinterpret_cast<const void*>(span_flash_routed_kernel<true>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, FlashLds<2>::kBytes) == hipSuccess &&
         hipFuncSetAttribute(reinterpret_cast<const void*>(span_flash_local_kernel<false>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, FlashLds<1>::kBytes) == hipSuccess &&
@@ -1060,7 +1074,7 @@ MfmaWs carve(const Problem& pb) {
 }  // namespace
 
 bool prefill_attention_mfma_supported(const Problem& pb) {
-  return pb.dtype == SL_BF16 && pb.D == HD && pb.S % TN == 0 && pb.n <= 4096 &&
+  return pb.dtype == SL_BF16 && pb.D == HD && pb.S % TN == 0 && pb.A % TN == 0 && pb.n <= 4096 &&
          (int64_t)pb.G * pb.Lq < ((int64_t)1 << 26) &&  // item = (row id << 5) | slot
          // staging uses 32-bit byte offsets inside one kv head's V^T and inside a 64-row K tile
          (int64_t)HD * (int64_t)align_up((size_t)pb.L, 64) * 2 < ((int64_t)1 << 32) &&
@@ -1116,6 +1130,7 @@ sl_status prefill_attention_mfma(const Problem& pb, const void* Q, const void* K
   a.Hq = pb.Hq;
   a.G = pb.G;
   a.S = pb.S;
+  a.A = pb.A;
   a.topk = pb.topk;
   a.n = n;
   a.scale_log2e = pb.scale * kLog2e;
@@ -1127,7 +1142,7 @@ sl_status prefill_attention_mfma(const Problem& pb, const void* Q, const void* K
   if (pb.topk > 0) {
     const dim3 bgrid((unsigned)w.chunks, pb.Hq);
     hipLaunchKernelGGL(bucket_kernel<false>, bgrid, dim3(256), (size_t)n * sizeof(int), st, idx,
-                       blk_cnt, cursor, items, pb.Lq, pb.q_pos0, pb.G, pb.S, pb.topk, n);
+                       blk_cnt, cursor, items, pb.Lq, pb.q_pos0, pb.G, pb.A, pb.topk, n);
     hipLaunchKernelGGL(bucket_block_scan_kernel, dim3((n + 31) / 32, pb.Hkv), dim3(256), 0, st, blk_cnt,
                        counts, pb.G * w.chunks, n);
     hipLaunchKernelGGL(bucket_scan_kernel, dim3(1), dim3(1024), 0, st, counts, item_off, tile_off,
@@ -1135,14 +1150,18 @@ sl_status prefill_attention_mfma(const Problem& pb, const void* Q, const void* K
     hipLaunchKernelGGL(bucket_tiles_kernel, dim3(w.B), dim3(256), 0, st, tile_off, item_off, tile_info,
                        items);
     hipLaunchKernelGGL(bucket_kernel<true>, bgrid, dim3(256), (size_t)4 * n * sizeof(int), st, idx,
-                       blk_cnt, cursor, items, pb.Lq, pb.q_pos0, pb.G, pb.S, pb.topk, n);
+                       blk_cnt, cursor, items, pb.Lq, pb.q_pos0, pb.G, pb.A, pb.topk, n);
     if (hipGetLastError() != hipSuccess) return SL_ERR_LAUNCH;
     if (pb.prof_start) (void)hipEventRecord(pb.prof_start, st);
-    hipLaunchKernelGGL(span_flash_routed_kernel, dim3(dev.grid),
-                       dim3(FlashLds<2>::kThreads), FlashLds<2>::kBytes, st, a);
+    if (pb.A < pb.S && !pb.combined)  // overlapping spans in one joint softmax: per-row clipping
+      hipLaunchKernelGGL(span_flash_routed_kernel<true>, dim3(dev.grid), dim3(FlashLds<2>::kThreads),
+                         FlashLds<2>::kBytes, st, a);
+    else
+      hipLaunchKernelGGL(span_flash_routed_kernel<false>, dim3(dev.grid), dim3(FlashLds<2>::kThreads),
+                         FlashLds<2>::kBytes, st, a);
     if (pb.prof_stop) (void)hipEventRecord(pb.prof_stop, st);
   }
-  const unsigned lgrid = local_grid(pb.Lq, pb.S, pb.Hkv, pb.G);
+  const unsigned lgrid = local_grid(pb.Lq, pb.A, pb.Hkv, pb.G);
   if (!pb.combined && pb.topk <= 8) {  // the window kernel merges and writes the final output
     hipLaunchKernelGGL(span_flash_local_kernel<true>, dim3(lgrid), dim3(FlashLds<1>::kThreads),
                        FlashLds<1>::kBytes, st, a);
@@ -1156,10 +1175,10 @@ sl_status prefill_attention_mfma(const Problem& pb, const void* Q, const void* K
   do {                                                                                           \
     if (pb.combined)                                                                                 \
       hipLaunchKernelGGL(merge_combined_kernel<KM>, mgrid, dim3(256), 0, st, idx, pb.gate,       \
-                         part_o, part_lse, a.O, rows, pb.Lq, pb.q_pos0, pb.S, pb.topk);          \
+                         part_o, part_lse, a.O, rows, pb.Lq, pb.q_pos0, pb.A, pb.topk);          \
     else                                                                                         \
       hipLaunchKernelGGL(merge_partials_kernel<KM>, mgrid, dim3(256), 0, st, idx, part_o,        \
-                         part_lse, a.O, LSE, rows, pb.Lq, pb.q_pos0, pb.S, pb.topk);             \
+                         part_lse, a.O, LSE, rows, pb.Lq, pb.q_pos0, pb.A, pb.topk);             \
   } while (0)
   if (pb.topk == 0) SL_MERGE(1);
   else if (pb.topk <= 8) SL_MERGE(8);

@@ -14,11 +14,12 @@ namespace sl {
 struct Problem {
   int64_t L, Lq, q_pos0;
   int Hq, Hkv, G, D, S, topk;
+  int A;  // anchor spacing (sl_params.span_stride, S if not given): c = i / A, span j = [max(0, (j+1)A - S), (j+1)A)
   int dtype;
   float scale;  // resolved softmax scale
   int64_t qsh, qst, kvsh, kvst;
   bool kvsh_given;  // the caller gave a kv head stride (else kvsh = L * kvst: packed)
-  int64_t n;  // ceil(L / S)
+  int64_t n;  // ceil(L / A): rows of the span-key tensor, spans of the grid
   hipEvent_t prof_start, prof_stop;
   // Combination (Section 3.4) instead of one joint softmax over the selected spans and the
   // window; gate = search scores [Hq][Lq][topk] of the slots of idx (unread when topk == 0).

@@ -104,6 +104,7 @@ BAD = [
     (dict(scale=-1.0), 1), (dict(scale=float("inf")), 1), (dict(scale=float("nan")), 1),
     (dict(D=96), 2), (dict(topk=B.SL_MAX_TOPK + 1), 2), (dict(Hq=130, Hkv=2), 2),
     (dict(q_stride_t=64), 1), (dict(kv_stride_t=129), 1), (dict(q_stride_h=4), 1),
+    (dict(span_stride=-1), 1), (dict(span_stride=65), 1),      # anchor spacing must be within [0, S]
 ]
 
 

@@ -110,6 +110,26 @@ def test_config2_prefill_combined_65k():
     check_combined(O, Q, K, V, idx, sc, cfg.S, 0, 0.0, sample_rows(cfg, data, n_random=300))
 
 
+def test_config2_prefill_redundant_spans_65k():
+    # config 2 with anchors every 128 tokens and spans 256 tokens long (what bench.py's
+    # redundant_spans line runs): all-row selection check on the anchor grid, sampled rows against
+    # the oracle's de-duplicated union
+    cfg = W.CONFIGS["C2"]
+    A = cfg.S // 2
+    data = W.generate(cfg, device=DEV)
+    Q, K, V = data["Q"], data["K"], data["V"]
+    Ks = B.sl_span_keys(K, A)
+    idx = B.sl_span_search_prefill(data["Qs"], K, Ks, A, cfg.topk)
+    O, LSE = B.sl_span_attention_prefill(Q, K, V, idx, cfg.S, span_stride=A)
+    torch.cuda.synchronize()
+    nrows, differ = brute.check_selection_all_rows(idx, data["Qs"], Ks, A, cfg.topk, margin=1e-3)
+    print(f"[C2, anchors every {A}] all {nrows} rows checked, {differ} differ inside the margin")
+    assert differ <= nrows // 1000
+    rows = sample_rows(cfg, data, n_random=500)
+    worst = check_attention(O.cpu(), LSE.cpu(), Q.cpu(), K.cpu(), V.cpu(), idx.cpu(), cfg.S, 0, 0.0, rows, stride=A)
+    print(f"[C2, anchors every {A}] attention on {len(rows)} rows: max abs error {worst:.3e}")
+
+
 @pytest.mark.parametrize("name", ["C3", "C5"])
 def test_decode_configs_full_cache(name):
     cfg = W.CONFIGS[name]

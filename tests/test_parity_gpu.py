@@ -100,7 +100,7 @@ def check_anchor_row(got, want, cand, cand_scores, k, where):
     return 1
 
 
-def check_attention(O, LSE, Q, K, V, idx, S, q_pos0, scale, rows=None):
+def check_attention(O, LSE, Q, K, V, idx, S, q_pos0, scale, rows=None, stride=None):
     tol = TOL[Q.dtype]
     if rows is None:
         On, Ln, Qn = f64(O), f64(LSE), f64(Q)
@@ -115,7 +115,7 @@ def check_attention(O, LSE, Q, K, V, idx, S, q_pos0, scale, rows=None):
         rows = [(h, r) for h in range(Hq) for r in range(Lq)]
     worst = 0.0
     for (h, r) in rows:
-        o, lse = orc.attention_row(Qn[h, r], Kd, Vd, h // G, q_pos0 + r, S, idxn[h, r], sc)
+        o, lse = orc.attention_row(Qn[h, r], Kd, Vd, h // G, q_pos0 + r, S, idxn[h, r], sc, stride=stride)
         eo = float(np.max(np.abs(On[h, r] - o)))
         el = abs(float(Ln[h, r]) - lse)
         worst = max(worst, eo, el)
@@ -693,7 +693,7 @@ def test_prefill_and_decode_replay_in_a_hip_graph():
 
 # ------------------------------------------------------------------------------ combination (Section 3.4)
 
-def check_combined(O, Q, K, V, idx, scores, S, q_pos0, scale, rows=None):
+def check_combined(O, Q, K, V, idx, scores, S, q_pos0, scale, rows=None, stride=None):
     tol = TOL[Q.dtype]
     On, Qn = f64(O), f64(Q)
     idxn, scn = idx.cpu().numpy(), scores.cpu().numpy().astype(np.float64)
@@ -704,7 +704,7 @@ def check_combined(O, Q, K, V, idx, scores, S, q_pos0, scale, rows=None):
     if rows is None:
         rows = [(h, r) for h in range(Hq) for r in range(Lq)]
     for (h, r) in rows:
-        o = orc.combined_row(Qn[h, r], Kd, Vd, h // G, q_pos0 + r, S, idxn[h, r], scn[h, r], sc)
+        o = orc.combined_row(Qn[h, r], Kd, Vd, h // G, q_pos0 + r, S, idxn[h, r], scn[h, r], sc, stride=stride)
         err = float(np.max(np.abs(On[h, r] - o)))
         assert err <= tol, (h, r, err)
 
@@ -784,6 +784,138 @@ def test_combined_invalid_arguments():
     st = lib.sl_span_attention_combined_prefill(ctypes.byref(p), Q.data_ptr(), K.data_ptr(), V.data_ptr(),
                                                 idx.data_ptr(), None, O.data_ptr(), wptr, wbytes, None)
     assert st == 1   # SL_ERR_INVALID_ARG: scores missing
+
+
+# ------------------------------------------------------------------------------ redundant grid: overlapping spans
+# Anchors every A tokens, spans S > A tokens long (Section 2.4: p_sh + p_sp > 1; Section 4.4's
+# redundancy factors); the joint softmax runs over the de-duplicated union of the selected spans.
+
+def overlapping_idx(rng, Hq, Lq, q_pos0, A, k):
+    """Selections that stress the de-duplication: runs of neighbouring anchors, unsorted slots,
+    empty and out-of-range entries."""
+    idx = np.full((Hq, Lq, k), -1, dtype=np.int32)
+    for h in range(Hq):
+        for r in range(Lq):
+            c = (q_pos0 + r) // A
+            if c == 0:
+                continue
+            kind = rng.integers(0, 4)
+            if kind == 0:                         # a run of neighbours ending just below the window
+                sel = list(range(max(0, c - k), c))
+            elif kind == 1:                       # a run somewhere, then scattered ones
+                j0 = int(rng.integers(0, c))
+                sel = list(range(j0, min(c, j0 + k // 2 + 1)))
+                rest = [j for j in rng.permutation(c).tolist() if j not in sel]
+                sel = (sel + rest)[:k]
+            else:
+                sel = rng.permutation(c).tolist()[:k]
+            if kind == 3:
+                rng.shuffle(sel)                  # unsorted slots
+            row = (sel + [-1] * k)[:k]
+            if rng.random() < 0.2:
+                row[-1] = c + int(rng.integers(0, 3))   # own cell or beyond: ignored
+            idx[h, r] = row
+    return idx
+
+
+REDUNDANT_PREFILL = [
+    # seed Hq Hkv L     D    A    S    k  dtype           q_pos0 Lq
+    (81, 8, 2, 3000, 128, 64, 192, 5, torch.bfloat16, 0, None),      # matrix-core path, spans of 3 cells
+    (82, 4, 1, 4000, 128, 128, 256, 8, torch.bfloat16, 1500, 900),   # matrix-core path, a chunk inside the cache
+    (83, 4, 2, 2500, 128, 64, 512, 3, torch.bfloat16, 0, None),      # spans of 8 cells, clipped at token 0 early on
+    (84, 4, 4, 700, 64, 16, 48, 4, torch.float32, 0, None),          # row-stationary fp32
+    (85, 2, 1, 1100, 128, 48, 100, 6, torch.bfloat16, 0, None),      # row-stationary: S not a multiple of A
+]
+
+
+@pytest.mark.parametrize("seed,Hq,Hkv,L,D,A,S,k,dtype,q_pos0,Lq", REDUNDANT_PREFILL)
+def test_redundant_spans_prefill(seed, Hq, Hkv, L, D, A, S, k, dtype, q_pos0, Lq):
+    Q, K, V = make(seed, Hq, Hkv, L, D, dtype, Lq=Lq)
+    Lq = Q.shape[1]
+    # the search runs on the anchor grid: span keys every A tokens, candidates j < i // A
+    Ks = B.sl_span_keys(K, A)
+    idx, sc = B.sl_span_search_prefill(Q, K, Ks, A, k, q_pos0=q_pos0, want_scores=True)
+    torch.cuda.synchronize()
+    check_idx(idx, Q, Ks, A, k, q_pos0)
+    rows = [(h, r) for h in range(Hq) for r in range(0, Lq, 7)] + [(h, Lq - 1) for h in range(Hq)]
+    # joint softmax over the union: on the searched indices and on selections built to overlap
+    O, LSE = B.sl_span_attention_prefill(Q, K, V, idx, S, q_pos0=q_pos0, span_stride=A)
+    torch.cuda.synchronize()
+    check_attention(O, LSE, Q, K, V, idx, S, q_pos0, 0.0, rows, stride=A)
+    idx2 = torch.from_numpy(overlapping_idx(np.random.default_rng(seed), Hq, Lq, q_pos0, A, k)).to(DEV)
+    O2, LSE2 = B.sl_span_attention_prefill(Q, K, V, idx2, S, q_pos0=q_pos0, span_stride=A)
+    torch.cuda.synchronize()
+    check_attention(O2, LSE2, Q, K, V, idx2, S, q_pos0, 0.0, rows, stride=A)
+    # the gated form: every span has its own softmax over span | window
+    scf = torch.where(torch.isfinite(sc), sc, torch.zeros_like(sc))
+    Oc = B.sl_span_attention_combined_prefill(Q, K, V, idx, scf, S, q_pos0=q_pos0, span_stride=A)
+    torch.cuda.synchronize()
+    check_combined(Oc, Q, K, V, idx, scf, S, q_pos0, 0.0, rows[::3], stride=A)
+
+
+def test_redundant_spans_every_anchor_selected_is_dense_causal():
+    # top-k covers every anchor: the union of the overlapping spans and the window is [0, i]
+    Hq, Hkv, L, D, A, S = 4, 2, 1500, 128, 64, 256
+    Q, K, V = make(86, Hq, Hkv, L, D, torch.bfloat16)
+    k = -(-L // A)
+    idx = B.sl_span_search_prefill(Q, K, None, A, k)
+    O, LSE = B.sl_span_attention_prefill(Q, K, V, idx, S, span_stride=A)
+    torch.cuda.synchronize()
+    ref = torch.nn.functional.scaled_dot_product_attention(
+        Q.float()[None], K.float().repeat_interleave(Hq // Hkv, 0)[None], V.float().repeat_interleave(Hq // Hkv, 0)[None],
+        is_causal=True)[0]
+    assert float((O.float() - ref).abs().max()) <= TOL[torch.bfloat16]
+
+
+REDUNDANT_DECODE = [
+    # seed Hq Hkv L      D    A    S     k   dtype
+    (91, 32, 4, 70000, 128, 256, 1024, 16, torch.bfloat16),   # config-3 head geometry, spans of 4 cells
+    (92, 8, 2, 9000, 128, 96, 200, 6, torch.bfloat16),        # S not a multiple of A, ragged window
+    (93, 4, 4, 3000, 64, 50, 150, 4, torch.float32),
+]
+
+
+@pytest.mark.parametrize("seed,Hq,Hkv,L,D,A,S,k,dtype", REDUNDANT_DECODE)
+def test_redundant_spans_decode(seed, Hq, Hkv, L, D, A, S, k, dtype):
+    Q, K, V = make(seed, Hq, Hkv, L, D, dtype, Lq=1)
+    Ks = B.sl_span_keys(K, A)
+    idx, sc = B.sl_span_search_decode(Q, K, Ks, A, k, want_scores=True)
+    torch.cuda.synchronize()
+    check_idx(idx, Q, Ks, A, k, L - 1)
+    O, LSE = B.sl_span_attention_decode(Q, K, V, idx, S, span_stride=A)
+    torch.cuda.synchronize()
+    check_attention(O, LSE, Q, K, V, idx, S, L - 1, 0.0, stride=A)
+    # heads of a kv head sharing spans (one workgroup serves them all) with different neighbours to clip against
+    idx2 = overlapping_idx(np.random.default_rng(seed), Hq, 1, L - 1, A, k)
+    G = Hq // Hkv
+    for kv in range(Hkv):
+        for g in range(1, G):
+            idx2[kv * G + g, 0, : k // 2] = idx2[kv * G, 0, : k // 2]
+            row = idx2[kv * G + g, 0]
+            seen = set()
+            for s_ in range(k):                     # later duplicates emptied
+                if row[s_] >= 0 and int(row[s_]) in seen:
+                    row[s_] = -1
+                seen.add(int(row[s_]))
+    idx2 = torch.from_numpy(idx2).to(DEV)
+    O2, LSE2 = B.sl_span_attention_decode(Q, K, V, idx2, S, span_stride=A)
+    torch.cuda.synchronize()
+    check_attention(O2, LSE2, Q, K, V, idx2, S, L - 1, 0.0, stride=A)
+    # prefill entry point with one row agrees; gated form; batched form
+    Op, LSEp = B.sl_span_attention_prefill(Q, K, V, idx2, S, q_pos0=L - 1, span_stride=A)
+    torch.cuda.synchronize()
+    check_attention(Op, LSEp, Q, K, V, idx2, S, L - 1, 0.0, stride=A)
+    scf = torch.where(torch.isfinite(sc), sc, torch.zeros_like(sc))
+    Oc = B.sl_span_attention_combined_decode(Q, K, V, idx, scf, S, span_stride=A)
+    torch.cuda.synchronize()
+    check_combined(Oc, Q, K, V, idx, scf, S, L - 1, 0.0, stride=A)
+    batch = B.DecodeBatch([Q, Q], [Q, Q], [K, K[:, : L - 333]], [V, V[:, : L - 333]], None, S, k, span_stride=A)
+    idb = B.sl_span_search_decode_batched(batch)
+    Ob, LSEb = B.sl_span_attention_decode_batched(batch)
+    torch.cuda.synchronize()
+    assert torch.equal(idb[0], idx)
+    check_attention(Ob[0], LSEb[0], Q, K, V, idb[0], S, L - 1, 0.0, stride=A)
+    check_attention(Ob[1], LSEb[1], Q, K[:, : L - 333].contiguous(), V[:, : L - 333].contiguous(), idb[1], S, L - 334, 0.0, stride=A)
 
 
 # ------------------------------------------------------------------------------ the paper's own geometry (decode form)
