@@ -11,6 +11,8 @@
 
 namespace sl {
 
+int64_t decode_score_ld(const Problem& pb);
+
 namespace {
 
 // ------------------------------------------------------------------ a0: span keys
@@ -120,7 +122,9 @@ __device__ __forceinline__ void decode_search_block_body(
     const T* __restrict__ Qs, const T* __restrict__ K, const T* __restrict__ Ks,
     int32_t* __restrict__ idx, float* __restrict__ scores, int64_t c, int64_t n, int G, int S,
     int topk, int64_t qsh, int64_t kvsh, int64_t kvst, int64_t anchor_i, int anchor_s0,
-    int anchor_root) {
+    int anchor_root, const float* __restrict__ pre_scores = nullptr, int64_t pre_ld = 0) {
+  // pre_scores: the head's candidate scores were computed by decode_score_group_kernel
+  // (row h of a [Hq][pre_ld] array); the scoring loop is skipped.
   // anchor_i >= 0: the candidates are the anchors of query position anchor_i on the paper's
   // stride pattern (Section 3.3, p = 1/anchor_root): candidate j is stride index s = anchor_s0 + j
   // at token anchor_i - (s+1)^root + 1, its key is K at that token, and the output lists tokens.
@@ -138,31 +142,33 @@ __device__ __forceinline__ void decode_search_block_body(
   const int g = lane / LPR, lr = lane % LPR;
   const int kk = topk < c ? topk : (int)c;
 
-  float qf[EPL];
-  Elem<T>::unpack(load16(Qs + (int64_t)h * qsh + lr * EPL), qf);
-  for (int64_t jb = (int64_t)wave * RPW * U; jb < c; jb += NW * RPW * U) {
-    uint4 kr[U];
+  if (!pre_scores) {
+    float qf[EPL];
+    Elem<T>::unpack(load16(Qs + (int64_t)h * qsh + lr * EPL), qf);
+    for (int64_t jb = (int64_t)wave * RPW * U; jb < c; jb += NW * RPW * U) {
+      uint4 kr[U];
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      int64_t j = jb + u * RPW + g;
-      j = j < c ? j : c - 1;
-      const T* kp = anchor_i >= 0 ? K + kv * kvsh + anchor_token(j) * kvst
-                                  : span_key_ptr<T, D>(K, Ks, kv, j, n, S, kvsh, kvst);
-      kr[u] = load16(kp + lr * EPL);
-    }
+      for (int u = 0; u < U; ++u) {
+        int64_t j = jb + u * RPW + g;
+        j = j < c ? j : c - 1;
+        const T* kp = anchor_i >= 0 ? K + kv * kvsh + anchor_token(j) * kvst
+                                    : span_key_ptr<T, D>(K, Ks, kv, j, n, S, kvsh, kvst);
+        kr[u] = load16(kp + lr * EPL);
+      }
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      float kf[EPL];
-      Elem<T>::unpack(kr[u], kf);
-      float acc = 0.f;
+      for (int u = 0; u < U; ++u) {
+        float kf[EPL];
+        Elem<T>::unpack(kr[u], kf);
+        float acc = 0.f;
 #pragma unroll
-      for (int e = 0; e < EPL; ++e) acc = fmaf(qf[e], kf[e], acc);
-      acc = group_sum<LPR>(acc);
-      const int64_t j = jb + u * RPW + g;
-      if (lr == 0 && j < c) s_sc[j] = acc;
+        for (int e = 0; e < EPL; ++e) acc = fmaf(qf[e], kf[e], acc);
+        acc = group_sum<LPR>(acc);
+        const int64_t j = jb + u * RPW + g;
+        if (lr == 0 && j < c) s_sc[j] = acc;
+      }
     }
   }
-  __syncthreads();
+  __syncthreads();  // the scores, and the cleared histograms
 
   // 1. thread t owns candidates t*R .. t*R + R-1 (index order = thread order)
   const int R = (int)((c + kDecodeSearchThreads - 1) / kDecodeSearchThreads);
@@ -171,18 +177,23 @@ __device__ __forceinline__ void decode_search_block_body(
 #pragma unroll
   for (int r = 0; r < RMAX; ++r) {
     const int j = tid * R + r;
-    v[r] = (r < R && j < c) ? s_sc[j] : -INFINITY;
-    const unsigned u = __float_as_uint(v[r]);
+    const bool in = r < R && j < c;
+    v[r] = !in ? -INFINITY : pre_scores ? pre_scores[(int64_t)h * pre_ld + j] : s_sc[j];
+    const unsigned u = __float_as_uint(v[r] + 0.0f);  // -0 scores as +0: equal scores, equal keys
     key[r] = (u & 0x80000000u) ? ~u : (u | 0x80000000u);
     if (!(v[r] > -INFINITY)) key[r] = 0u;  // empty slots (and non-finite input) never match
   }
 
-  // 2. radix select of the kk-th largest key
-  float Tval = INFINITY;  // kk == 0: nothing is selected
+  // 2. radix select of the kk-th largest key.  Tkey: every key above it is selected, keys equal to
+  // it are ties (lowest index first).  The passes stop early when the bin that holds the kk-th
+  // largest key is taken whole: every key at or above the bin's lower bound is then selected
+  // (Tkey = that bound - 1; a valid key is never 0, so the bound is at least 1).
+  unsigned Tkey = 0xffffffffu;  // kk == 0: nothing is selected
   if (kk > 0) {
     unsigned prefix = 0u, mask = 0u;
     int krem = kk;
-    for (int pass = 0; pass < 4; ++pass) {
+    bool whole = false;
+    for (int pass = 0; pass < 4 && !whole; ++pass) {
       const int shift = 24 - 8 * pass;
 #pragma unroll
       for (int r = 0; r < RMAX; ++r)
@@ -195,12 +206,13 @@ __device__ __forceinline__ void decode_search_block_body(
       const int total = __builtin_amdgcn_readlane(incl, 63);
       int above = total - incl;  // candidates in bins above this lane's four
       const unsigned cnt[4] = {c4.x, c4.y, c4.z, c4.w};
-      int digit = -1, kleft = 0;
+      int digit = -1, kleft = 0, inbin = 0;
 #pragma unroll
       for (int b4 = 3; b4 >= 0; --b4) {
         if (above < krem && krem <= above + (int)cnt[b4]) {
           digit = 4 * lane + b4;
           kleft = krem - above;
+          inbin = (int)cnt[b4];
         }
         above += (int)cnt[b4];
       }
@@ -210,19 +222,19 @@ __device__ __forceinline__ void decode_search_block_body(
       const int src = found ? __builtin_ctzll(found) : 0;
       digit = found ? __builtin_amdgcn_readlane(digit, src) : 0;
       krem = found ? __builtin_amdgcn_readlane(kleft, src) : krem;
+      whole = found && krem == __builtin_amdgcn_readlane(inbin, src);
       prefix |= (unsigned)digit << shift;
       mask |= 255u << shift;
     }
-    const unsigned tu = (prefix & 0x80000000u) ? (prefix & 0x7fffffffu) : ~prefix;
-    Tval = __uint_as_float(tu);
+    Tkey = whole ? prefix - 1u : prefix;
   }
 
   // 3. select and place
   int gt = 0, eq = 0;
 #pragma unroll
   for (int r = 0; r < RMAX; ++r) {
-    gt += v[r] > Tval ? 1 : 0;
-    eq += (v[r] == Tval && v[r] > -INFINITY) ? 1 : 0;
+    gt += key[r] > Tkey ? 1 : 0;
+    eq += (key[r] == Tkey && key[r] != 0u) ? 1 : 0;
   }
   const int packed = gt | (eq << 16);
   const int incl = wave_inclusive_scan(packed);
@@ -242,8 +254,8 @@ __device__ __forceinline__ void decode_search_block_body(
   float* os = scores ? scores + (int64_t)h * topk : nullptr;
 #pragma unroll
   for (int r = 0; r < RMAX; ++r) {
-    const bool is_gt = v[r] > Tval;
-    const bool is_eq = v[r] == Tval && v[r] > -INFINITY;
+    const bool is_gt = key[r] > Tkey;
+    const bool is_eq = key[r] == Tkey && key[r] != 0u;
     if (is_gt || (is_eq && eq_before < need_eq)) {
       const int pos = gt_before + (eq_before < need_eq ? eq_before : need_eq);
       if ((unsigned)pos < (unsigned)kk) {  // always true unless scores are NaN
@@ -265,9 +277,65 @@ __global__ __launch_bounds__(kDecodeSearchThreads) void decode_search_block_kern
     const T* __restrict__ Qs, const T* __restrict__ K, const T* __restrict__ Ks,
     int32_t* __restrict__ idx, float* __restrict__ scores, int64_t c, int64_t n, int G, int S,
     int topk, int64_t qsh, int64_t kvsh, int64_t kvst, int64_t anchor_i, int anchor_s0,
-    int anchor_root) {
+    int anchor_root, const float* __restrict__ pre_scores, int64_t pre_ld) {
   decode_search_block_body<T, D, RMAX>(Qs, K, Ks, idx, scores, c, n, G, S, topk, qsh, kvsh, kvst,
-                                       anchor_i, anchor_s0, anchor_root);
+                                       anchor_i, anchor_s0, anchor_root, pre_scores, pre_ld);
+}
+
+// First launch of the two-launch decode search: the candidates of a kv head are scored ONCE for
+// all G query heads of its group, by many small workgroups (the key rows are read once instead
+// of once per head, and from every compute unit instead of from Hq of them).  grid
+// (ceil(c / kScoreCand), Hkv), 4 wavefronts; a wavefront takes kScoreCand / 4 consecutive
+// candidates, LPR lanes per key row.  Same arithmetic as the one-launch kernel (fp32 fma chain over
+// the lane's elements, then the lane-group sum), so the scores are bit-identical to it.
+constexpr int kScoreCand = 32;
+
+template <typename T, int D>
+__global__ __launch_bounds__(256) void decode_score_group_kernel(
+    const T* __restrict__ Qs, const T* __restrict__ K, const T* __restrict__ Ks,
+    float* __restrict__ sc_out, int64_t c, int64_t n, int G, int S, int64_t qsh, int64_t kvsh,
+    int64_t kvst, int64_t ld) {
+  using RL = RowLayout<T, D>;
+  constexpr int EPL = RL::EPL, LPR = RL::LPR, RPW = RL::RPW;
+  constexpr int PER_WAVE = kScoreCand / 4, U = PER_WAVE / RPW;
+  static_assert(U >= 1 && U * RPW == PER_WAVE, "candidates per wavefront must be whole load batches");
+  const int kv = blockIdx.y;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int g = lane / LPR, lr = lane % LPR;
+  const int64_t j0 = (int64_t)blockIdx.x * kScoreCand + wave * PER_WAVE;
+  if (j0 >= c) return;
+  uint4 kr[U];
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    int64_t j = j0 + u * RPW + g;
+    j = j < c ? j : c - 1;
+    kr[u] = load16(span_key_ptr<T, D>(K, Ks, kv, j, n, S, kvsh, kvst) + lr * EPL);
+  }
+  constexpr int HB = 8;  // query heads per batch of query loads
+  for (int h0 = 0; h0 < G; h0 += HB) {
+    uint4 qr[HB];
+#pragma unroll
+    for (int b = 0; b < HB; ++b) {
+      const int hh = kv * G + (h0 + b < G ? h0 + b : G - 1);
+      qr[b] = load16(Qs + (int64_t)hh * qsh + lr * EPL);
+    }
+#pragma unroll
+    for (int b = 0; b < HB; ++b) {
+      float qf[EPL];
+      Elem<T>::unpack(qr[b], qf);
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        float kf[EPL];
+        Elem<T>::unpack(kr[u], kf);
+        float acc = 0.f;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) acc = fmaf(qf[e], kf[e], acc);
+        acc = group_sum<LPR>(acc);
+        const int64_t j = j0 + u * RPW + g;
+        if (lr == 0 && j < c && h0 + b < G) sc_out[(int64_t)(kv * G + h0 + b) * ld + j] = acc;
+      }
+    }
+  }
 }
 
 // Batched decode: blockIdx.y is the sequence; candidates c = (L - 1) / S and the span-key row count
@@ -418,21 +486,30 @@ sl_status launch_span_keys(const Problem& pb, const void* K, void* Ks, hipStream
 
 template <typename T, int D>
 sl_status launch_decode_search(const Problem& pb, const void* Qs, const void* K, const void* Ks,
-                               int32_t* idx, float* scores, hipStream_t st) {
+                               int32_t* idx, float* scores, void* ws, hipStream_t st) {
   const int64_t c = pb.q_pos0 / pb.S;
   if (pb.prof_start) (void)hipEventRecord(pb.prof_start, st);
   if (c <= (int64_t)kDecodeSearchThreads * 4) {
-    // block-parallel selection: candidates fit 4 registers per thread
+    // Two launches: the group-wide scoring kernel fills the workspace [Hq][ld], then one workgroup
+    // per head selects (block-parallel selection: candidates fit 4 registers per thread).
+    // (a cache with more spans than that sizes no workspace: its shorter queries score in the
+    // selecting workgroup itself)
+    float* sc_ws = pb.n <= (int64_t)kDecodeSearchThreads * 4 ? static_cast<float*>(ws) : nullptr;
+    const int64_t ld = decode_score_ld(pb);
+    if (c > 0 && sc_ws)
+      hipLaunchKernelGGL((decode_score_group_kernel<T, D>), dim3((unsigned)((c + kScoreCand - 1) / kScoreCand), pb.Hkv),
+                         dim3(256), 0, st, static_cast<const T*>(Qs), static_cast<const T*>(K),
+                         static_cast<const T*>(Ks), sc_ws, c, pb.n, pb.G, pb.S, pb.qsh, pb.kvsh, pb.kvst, ld);
     if (c <= kDecodeSearchThreads)
       hipLaunchKernelGGL((decode_search_block_kernel<T, D, 1>), dim3(pb.Hq),
                          dim3(kDecodeSearchThreads), 0, st, static_cast<const T*>(Qs),
                          static_cast<const T*>(K), static_cast<const T*>(Ks), idx, scores, c, pb.n,
-                         pb.G, pb.S, pb.topk, pb.qsh, pb.kvsh, pb.kvst, (int64_t)-1, 0, 2);
+                         pb.G, pb.S, pb.topk, pb.qsh, pb.kvsh, pb.kvst, (int64_t)-1, 0, 2, sc_ws, ld);
     else
       hipLaunchKernelGGL((decode_search_block_kernel<T, D, 4>), dim3(pb.Hq),
                          dim3(kDecodeSearchThreads), 0, st, static_cast<const T*>(Qs),
                          static_cast<const T*>(K), static_cast<const T*>(Ks), idx, scores, c, pb.n,
-                         pb.G, pb.S, pb.topk, pb.qsh, pb.kvsh, pb.kvst, (int64_t)-1, 0, 2);
+                         pb.G, pb.S, pb.topk, pb.qsh, pb.kvsh, pb.kvst, (int64_t)-1, 0, 2, sc_ws, ld);
     if (pb.prof_stop) (void)hipEventRecord(pb.prof_stop, st);
     return hipGetLastError() == hipSuccess ? SL_OK : SL_ERR_LAUNCH;
   }
@@ -488,12 +565,14 @@ sl_status launch_anchor_search(const Problem& pb, const void* Qs, const void* K,
     hipLaunchKernelGGL((decode_search_block_kernel<T, D, 1>), dim3(pb.Hq), dim3(kDecodeSearchThreads),
                        0, st, static_cast<const T*>(Qs), static_cast<const T*>(K),
                        static_cast<const T*>(nullptr), anchors, scores, c, (int64_t)0, pb.G, 1,
-                       pb.topk, pb.qsh, pb.kvsh, pb.kvst, pb.q_pos0, s0, root);
+                       pb.topk, pb.qsh, pb.kvsh, pb.kvst, pb.q_pos0, s0, root,
+                       static_cast<const float*>(nullptr), (int64_t)0);
   else
     hipLaunchKernelGGL((decode_search_block_kernel<T, D, 4>), dim3(pb.Hq), dim3(kDecodeSearchThreads),
                        0, st, static_cast<const T*>(Qs), static_cast<const T*>(K),
                        static_cast<const T*>(nullptr), anchors, scores, c, (int64_t)0, pb.G, 1,
-                       pb.topk, pb.qsh, pb.kvsh, pb.kvst, pb.q_pos0, s0, root);
+                       pb.topk, pb.qsh, pb.kvsh, pb.kvst, pb.q_pos0, s0, root,
+                       static_cast<const float*>(nullptr), (int64_t)0);
   if (pb.prof_stop) (void)hipEventRecord(pb.prof_stop, st);
   return hipGetLastError() == hipSuccess ? SL_OK : SL_ERR_LAUNCH;
 }
@@ -555,7 +634,15 @@ sl_status span_keys(const Problem& pb, const void* K, void* Ks, hipStream_t st) 
   SL_DISPATCH(launch_span_keys, pb, K, Ks, st);
 }
 
-size_t decode_search_ws_bytes(const Problem&) { return 0; }
+// Row length (floats) of the decode search's score workspace [Hq][ld]: the candidate spans,
+// rounded up to whole 256-byte lines.
+int64_t decode_score_ld(const Problem& pb) { return (int64_t)align_up((size_t)(pb.n > 0 ? pb.n : 1), 64); }
+
+size_t decode_search_ws_bytes(const Problem& pb) {
+  // more candidates than the block-parallel selection takes: the one-launch kernel, no workspace
+  if (pb.n > (int64_t)kDecodeSearchThreads * 4) return 0;
+  return (size_t)pb.Hq * decode_score_ld(pb) * sizeof(float);
+}
 
 // Candidate anchors of query position i = pb.q_pos0 with window w (Section 3.3, Algorithm 1):
 // stride indices s0 .. s_max, where t_s = i - (s+1)^root + 1 >= 0 and t_s < i - w + 1.
@@ -603,9 +690,9 @@ sl_status decode_search_batched(const Problem& pb, const sl_decode_seq* seqs, in
 }
 
 sl_status decode_search(const Problem& pb, const void* Qs, const void* K, const void* Ks,
-                        int32_t* idx, float* scores, void* /*ws*/, hipStream_t st) {
+                        int32_t* idx, float* scores, void* ws, hipStream_t st) {
   if (pb.n > kMaxSpansLds) return SL_ERR_UNSUPPORTED;
-  SL_DISPATCH(launch_decode_search, pb, Qs, K, Ks, idx, scores, st);
+  SL_DISPATCH(launch_decode_search, pb, Qs, K, Ks, idx, scores, ws, st);
 }
 
 sl_status prefill_search_rows(const Problem& pb, const void* Qs, const void* K, const void* Ks,

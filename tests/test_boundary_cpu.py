@@ -156,7 +156,8 @@ def test_workspace_checks():
     assert lib.sl_span_attention_decode(ctypes.byref(p), *args, None, 0, None) == 3
     assert lib.sl_span_attention_decode(ctypes.byref(p), *args, FAKE_WS, need - 1, None) == 3
     assert lib.sl_span_attention_decode(ctypes.byref(p), *args, ctypes.c_void_p(0x10010), need, None) == 3
-    assert lib.sl_workspace_bytes(ctypes.byref(p), B.OP_SEARCH_DECODE) == 0   # scores stay in LDS
+    # decode search: one fp32 score row per head, whole 256-byte lines
+    assert lib.sl_workspace_bytes(ctypes.byref(p), B.OP_SEARCH_DECODE) == p.Hq * 64 * ((-(-p.L // p.S) + 63) // 64) * 4
 
 
 def test_batched_decode_argument_checks():
