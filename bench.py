@@ -443,27 +443,49 @@ def bench_prefill(cfg, steps, warmup, torch, B, W):
         redundant = {"anchor_spacing": A, "span_length": cfg.S, "topk": cfg.topk, "ms_per_step": dt_r * 1e3,
                      "value": cfg.L / dt_r, "unit": "tokens/s"}
         del Ks2
-    # the paper's own geometry in prefill form (row-stationary kernels: every row has its own
-    # anchors and span length): the last 4K rows of the cache at the paper's kernel configuration
+    # the paper's own geometry in prefill form over ALL rows (every row has its own anchors, span
+    # length and window) at the paper's kernel configuration: group-shared anchor search, then the
+    # bucketed matrix-core span-attention + banded window + gated merge
     paper = None
     if cfg.dtype == "bf16" and cfg.L >= 16384:
-        PR, PW, PK, PB, PF = 4096, 1088, 2, 4, 2
-        p0 = cfg.L - PR
-        Qp, Qsp = Q[:, p0:], Qs[:, p0:]
-        op = torch.empty((cfg.Hq, PR, cfg.D), dtype=Q.dtype, device=dev)
+        PW, PK, PB, PF = 1088, 2, 4, 2
+        op = out[0]
+        ev_p = ProfEvents(torch)
 
-        def step_paper():
-            an, sc = B.sl_anchor_search_prefill(Qsp, K, PK, PW, q_pos0=p0, want_scores=True)
-            B.sl_anchor_attention_prefill(Qp, K, V, an, sc, PW, PB, PF, q_pos0=p0, out=op)
+        def step_paper(prof=None):
+            an, sc = B.sl_anchor_search_prefill(Qs, K, PK, PW, want_scores=True)
+            B.sl_anchor_attention_prefill(Q, K, V, an, sc, PW, PB, PF, out=op, ws=ws, prof=prof)
+            return an
 
-        step_paper()
+        an = step_paper()
         torch.cuda.synchronize()
         tp = time.perf_counter()
-        step_paper()
+        npp = max(1, min(steps, 3))
+        for _ in range(npp):
+            step_paper(ev_p.handles())
         torch.cuda.synchronize()
-        dt_p = time.perf_counter() - tp
-        paper = {"rows": PR, "q_pos0": p0, "window": PW, "topk": PK, "backward_factor": PB, "forward_factor": PF,
-                 "ms_per_step": dt_p * 1e3, "value": PR / dt_p, "unit": "tokens/s"}
+        dt_p = (time.perf_counter() - tp) / npp
+        kp = ev_p.ms()
+        # algorithmic flops of the routed kernel: sum over valid (row, slot) of the span length (span minus window) x 4D
+        i_pos = torch.arange(cfg.L, device=dev, dtype=torch.int64)
+        ell = torch.sqrt(i_pos.double()).ceil().long()
+        ell = torch.where((ell - 1) * (ell - 1) >= i_pos, ell - 1, ell)        # exact ceil(sqrt(i))
+        ell = torch.where(ell * ell < i_pos, ell + 1, ell)
+        wlo = (i_pos - PW + 1).clamp(min=0)
+        keys = 0
+        for h0 in range(0, cfg.Hq, 8):
+            t = an[h0:h0 + 8].long()                                           # [8, L, k]
+            valid = (t >= 0) & (t <= i_pos[None, :, None])
+            lo = (t - PB * ell[None, :, None]).clamp(min=0)
+            hi = torch.minimum(torch.minimum(t + PF * ell[None, :, None], i_pos[None, :, None]), wlo[None, :, None] - 1) + 1
+            keys += int(((hi - lo).clamp(min=0) * valid).sum())
+        f_paper = keys * 4 * cfg.D
+        paper = {"rows": cfg.L, "window": PW, "topk": PK, "backward_factor": PB, "forward_factor": PF,
+                 "ms_per_step": dt_p * 1e3, "value": cfg.L / dt_p, "unit": "tokens/s",
+                 "roofline": {"bound": "mfma", "kernel": "span_flash_anchor_kernel", "kernel_ms": kp,
+                              "algorithmic_flops": f_paper, "achieved": f_paper / (kp * 1e-3) / 1e12,
+                              "peak": PEAK_BF16 / 1e12, "unit": "TFLOP/s", "frac": f_paper / (kp * 1e-3) / PEAK_BF16}}
+        del an
     f_search, f_routed, f_local = prefill_flops(cfg)
     f_attn = f_routed + f_local
     ka = sum(ms_a) / len(ms_a)

@@ -245,15 +245,27 @@ sl_status sl_anchor_attention_decode(const sl_params* p, const sl_anchor_geometr
 
 /* ---- The same geometry, prefill form: every query row r (position i = q_pos0 + r) has its own
  * anchors, its own l = ceil(sqrt(i)) and its own window, exactly as in the decode form above
- * (Section 3.3, Algorithm 1).  Row-stationary kernels (one wavefront per query row), fp32 or bf16;
- * no workspace.  S of sl_params is ignored.
+ * (Section 3.3, Algorithm 1).  S of sl_params is ignored.
  *   anchors: [Hq][Lq][topk] int32, scores: [Hq][Lq][topk] float, O: [Hq][Lq][D]; slot meaning and
- *   tie rule as in the decode form.  At most 12288 candidate anchors per row. */
+ *   tie rule as in the decode form.  At most 12288 candidate anchors per row.
+ * Span-search is row-stationary (one wavefront per query row), fp32 or bf16, no workspace.
+ * Span-attention + combination has two forms:
+ *   - with a workspace of sl_anchor_prefill_workspace_bytes (bf16, D = 128, window >= 1, topk >= 1):
+ *     the matrix-core form, which follows Section 4.3's prefilling kernel: (row, slot) pairs are
+ *     bucketed by the key block that holds the last token of their span (blocks of 64 .. 4096
+ *     tokens, chosen from the problem size), the rows of a bucket share one sliding K/V range with
+ *     per-row masks, the window is a banded flash kernel, and a gated merge combines the partials;
+ *   - with ws == NULL, or where sl_anchor_prefill_workspace_bytes returns 0: row-stationary kernels
+ *     (fp32 or bf16, any shape), no workspace. */
 sl_status sl_anchor_search_prefill(const sl_params* p, const sl_anchor_geometry* g, const void* Qs,
                                    const void* K, int32_t* anchors, float* scores, void* hip_stream);
+/* Scratch bytes of the matrix-core form (0: that form does not apply to these parameters;
+ * SL_WORKSPACE_INVALID: invalid parameters). */
+size_t sl_anchor_prefill_workspace_bytes(const sl_params* p, const sl_anchor_geometry* g);
 sl_status sl_anchor_attention_prefill(const sl_params* p, const sl_anchor_geometry* g, const void* Q,
                                       const void* K, const void* V, const int32_t* anchors,
-                                      const float* scores, void* O, void* hip_stream);
+                                      const float* scores, void* O, void* ws, size_t ws_bytes,
+                                      void* hip_stream);
 
 /* ---- Batched decode: one step for B independent sequences in three launches (Section 4.3's
  * decoding path serves a batch of sequences; the grid gains a sequence dimension).  Every

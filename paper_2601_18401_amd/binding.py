@@ -24,7 +24,8 @@ EXPORTS = ("sl_workspace_bytes", "sl_span_keys", "sl_span_search_prefill", "sl_s
            "sl_span_attention_prefill", "sl_span_attention_decode", "sl_noalloc_scratch_bytes",
            "sl_span_attention_decode_noalloc", "sl_span_attention_combined_prefill",
            "sl_span_attention_combined_decode", "sl_anchor_workspace_bytes", "sl_anchor_search_decode",
-           "sl_anchor_attention_decode", "sl_anchor_search_prefill", "sl_anchor_attention_prefill",
+           "sl_anchor_attention_decode", "sl_anchor_search_prefill", "sl_anchor_prefill_workspace_bytes",
+           "sl_anchor_attention_prefill",
            "sl_decode_batched_workspace_bytes", "sl_span_search_decode_batched",
            "sl_span_attention_decode_batched", "sl_span_attention_combined_decode_batched",
            "sl_anchor_batched_workspace_bytes", "sl_anchor_search_decode_batched",
@@ -108,7 +109,9 @@ def load():
     lib.sl_anchor_search_prefill.restype = ctypes.c_int
     lib.sl_anchor_search_prefill.argtypes = [pp, gp, vp, vp, i32p, f32p, vp]
     lib.sl_anchor_attention_prefill.restype = ctypes.c_int
-    lib.sl_anchor_attention_prefill.argtypes = [pp, gp, vp, vp, vp, i32p, f32p, vp, vp]
+    lib.sl_anchor_attention_prefill.argtypes = [pp, gp, vp, vp, vp, i32p, f32p, vp, vp, ctypes.c_size_t, vp]
+    lib.sl_anchor_prefill_workspace_bytes.restype = ctypes.c_size_t
+    lib.sl_anchor_prefill_workspace_bytes.argtypes = [pp, gp]
     lib.sl_decode_batched_workspace_bytes.restype = ctypes.c_size_t
     lib.sl_decode_batched_workspace_bytes.argtypes = [pp, ctypes.c_int32]
     lib.sl_span_search_decode_batched.restype = ctypes.c_int
@@ -378,8 +381,10 @@ def sl_anchor_search_prefill(Qs, K, topk, window, q_pos0=0, want_scores=False, p
 
 
 def sl_anchor_attention_prefill(Q, K, V, anchors, scores, window, backward_factor, forward_factor,
-                                q_pos0=0, scale=0.0, prof=None, out=None, search_root=2):
-    """Algorithm 1's span-attention + combination for every query row."""
+                                q_pos0=0, scale=0.0, prof=None, out=None, search_root=2, ws=None,
+                                row_stationary=False):
+    """Algorithm 1's span-attention + combination for every query row.  The matrix-core form runs
+    where it applies (bf16, D = 128, window >= 1) unless row_stationary is set."""
     lib = load()
     topk = 0 if anchors is None else anchors.shape[2]
     p = make_params(Q, K, 1, topk, q_pos0, scale)
@@ -388,9 +393,11 @@ def sl_anchor_attention_prefill(Q, K, V, anchors, scores, window, backward_facto
         raise ValueError("V must have the shape and strides of K")
     Hq, Lq, D = Q.shape
     O = torch.empty((Hq, Lq, D), dtype=Q.dtype, device=Q.device) if out is None else out
+    need = 0 if row_stationary else _need(lib.sl_anchor_prefill_workspace_bytes(ctypes.byref(p), ctypes.byref(g)))
+    wptr, wbytes = _ws(ws).get(need)
     _arm(prof)
     st = lib.sl_anchor_attention_prefill(ctypes.byref(p), ctypes.byref(g), _ptr(Q), _ptr(K), _ptr(V),
-                                         _ptr(anchors), _ptr(scores), _ptr(O), _stream())
+                                         _ptr(anchors), _ptr(scores), _ptr(O), wptr, wbytes, _stream())
     _check(st, "sl_anchor_attention_prefill")
     return O
 

@@ -301,9 +301,18 @@ sl_status sl_anchor_search_prefill(const sl_params* p, const sl_anchor_geometry*
                                    static_cast<hipStream_t>(hip_stream));
 }
 
+size_t sl_anchor_prefill_workspace_bytes(const sl_params* p, const sl_anchor_geometry* g) {
+  sl::Problem pb;
+  const int root = anchor_root(g);
+  if (!root) return SL_WORKSPACE_INVALID;
+  if (sl::make_problem(p, SL_OP_ATTENTION_PREFILL, &pb) != SL_OK) return SL_WORKSPACE_INVALID;
+  return sl::prefill_anchor_mfma_supported(pb, g->window) ? sl::prefill_anchor_mfma_ws_bytes(pb) : 0;
+}
+
 sl_status sl_anchor_attention_prefill(const sl_params* p, const sl_anchor_geometry* g, const void* Q,
                                       const void* K, const void* V, const int32_t* anchors,
-                                      const float* scores, void* O, void* hip_stream) {
+                                      const float* scores, void* O, void* ws, size_t ws_bytes,
+                                      void* hip_stream) {
   sl::Problem pb;
   sl_status s = sl::make_problem(p, SL_OP_ATTENTION_PREFILL, &pb);
   if (s != SL_OK) return s;
@@ -316,9 +325,18 @@ sl_status sl_anchor_attention_prefill(const sl_params* p, const sl_anchor_geomet
   if (pb.L > ((int64_t)1 << 31) - 1) return SL_ERR_UNSUPPORTED;
   pb.combined = true;
   pb.gate = scores;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  // the matrix-core form needs scratch; without one (ws == NULL) the row-stationary kernels run
+  if (ws && sl::prefill_anchor_mfma_supported(pb, g->window)) {
+    if (ws_bytes < sl::prefill_anchor_mfma_ws_bytes(pb) || (reinterpret_cast<uintptr_t>(ws) & 255u))
+      return SL_ERR_WORKSPACE;
+    sl::take_profile_events(&pb);
+    return sl::prefill_anchor_attention_mfma(pb, g->window, g->backward_factor, g->forward_factor, root, Q, K, V,
+                                             anchors, O, ws, st);
+  }
   sl::take_profile_events(&pb);
   return sl::anchor_attention_prefill(pb, g->window, g->backward_factor, g->forward_factor, root, Q, K,
-                                      V, anchors, O, static_cast<hipStream_t>(hip_stream));
+                                      V, anchors, O, st);
 }
 
 size_t sl_decode_batched_workspace_bytes(const sl_params* p, int32_t B) {
@@ -412,6 +430,6 @@ const char* sl_status_string(sl_status status) {
   return "unknown sl_status";
 }
 
-int sl_version(void) { return 300; }  // 0.3.0: sl_params without the profiling events; sl_set_profile_events
+int sl_version(void) { return 400; }  // 0.4.0: sl_anchor_attention_prefill takes a workspace (matrix-core form)
 
 }  // extern "C"

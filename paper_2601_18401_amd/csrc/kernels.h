@@ -55,6 +55,13 @@ sl_status anchor_attention_prefill(const Problem& pb, int64_t window, int b, int
                                    const void* Q, const void* K, const void* V,
                                    const int32_t* anchors, void* O, hipStream_t st);
 
+// ... and its span-attention + combination on the matrix cores (bf16, D = 128, window >= 1)
+bool prefill_anchor_mfma_supported(const Problem& pb, int64_t window);
+size_t prefill_anchor_mfma_ws_bytes(const Problem& pb);
+sl_status prefill_anchor_attention_mfma(const Problem& pb, int64_t window, int b, int f, int root,
+                                        const void* Q, const void* K, const void* V,
+                                        const int32_t* anchors, void* O, void* ws, hipStream_t st);
+
 // a1 + a2: prefill span-search
 size_t prefill_search_ws_bytes(const Problem& pb);
 sl_status prefill_search(const Problem& pb, const void* Qs, const void* K, const void* Ks,

@@ -91,6 +91,25 @@ __device__ __forceinline__ float pair_sum(float x) {
   return __int_as_float(r[0]) + __int_as_float(r[1]);
 }
 
+// The paper's geometry: token range [lo, hi) that slot anchor t contributes for the query at i
+// (S_t minus the window, Algorithm 1's DedupConcat(S_t, W) being that range followed by W).
+// ell = l(i).  valid: t is an anchor of this query at all; the range may still be empty.
+struct AnchorSpan {
+  int64_t lo, hi;
+  bool valid;
+};
+__device__ __forceinline__ AnchorSpan anchor_span_of(int64_t i, int64_t t, int64_t ell, int64_t window, int ab,
+                                                     int af) {
+  AnchorSpan r;
+  r.valid = t >= 0 && t <= i;
+  const int64_t wlo = window > 0 ? (i - window + 1 > 0 ? i - window + 1 : 0) : i + 1;
+  r.lo = t - ab * ell > 0 ? t - ab * ell : 0;
+  const int64_t e1 = t + af * ell < i ? t + af * ell : i;
+  r.hi = (e1 < wlo - 1 ? e1 : wlo - 1) + 1;
+  if (r.hi < r.lo || !r.valid) r.hi = r.lo;
+  return r;
+}
+
 // ------------------------------------------------------------------ V transpose (workspace)
 // Vt[kv][d][t] = V[kv][t][d], row length Lp (L rounded up to 64, zero padded).
 __global__ __launch_bounds__(256) void transpose_v_kernel(const bf16_t* __restrict__ V,
@@ -217,6 +236,62 @@ __global__ __launch_bounds__(256) void bucket_block_scan_kernel(int* __restrict_
   if (seg == 7) g_count[kv * n + b] = run;
 }
 
+// The same two passes for the paper's geometry: an item is a (row, slot) whose anchor is valid and
+// whose span minus the window is not empty; its bucket is (kv head, block of E tokens that holds the
+// span's last token).  Blocks of one kv head are ordered by (chunk of rows, head of the group), so
+// that a bucket's items come by query position first: the rows of a tile then have nearly the
+// same span length.  The fill pass also marks the partial of a valid anchor with an empty span
+// as empty (lse = -inf) for the merge.
+template <bool FILL>
+__global__ __launch_bounds__(256) void bucket_anchor_kernel(const int32_t* __restrict__ anchors,
+                                                            int* __restrict__ blk_cnt,
+                                                            const int* __restrict__ g_cursor,
+                                                            int* __restrict__ items,
+                                                            float* __restrict__ part_lse, int64_t Lq,
+                                                            int64_t q_pos0, int G, int topk, int n,
+                                                            int64_t window, int ab, int af, int aroot, int E) {
+  extern __shared__ int s_hist[];  // count pass: [n]; fill pass: [4][n], one histogram per wavefront
+  const int h = blockIdx.y, kv = h / G, hl = h % G;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int64_t r0 = (int64_t)blockIdx.x * kBucketRows + wave * (kBucketRows / 4);
+  int* const blk = blk_cnt + (((int64_t)kv * gridDim.x + blockIdx.x) * G + hl) * n;
+  int* const hist = FILL ? s_hist + wave * n : s_hist;
+  for (int b = tid; b < (FILL ? 4 : 1) * n; b += 256) s_hist[b] = 0;
+  __syncthreads();
+  auto for_items = [&](auto f) {
+    for (int it = 0; it < kBucketRows / 256; ++it) {
+      const int64_t r = r0 + 64 * it + lane;
+      if (r < Lq) {
+        const int64_t i = q_pos0 + r;
+        const int64_t ell = span_base_length(i, aroot);
+        const int32_t* row = anchors + ((int64_t)h * Lq + r) * topk;
+        for (int s = 0; s < topk; ++s) {
+          const AnchorSpan sp = anchor_span_of(i, row[s], ell, window, ab, af);
+          if (sp.hi > sp.lo) f((int)((sp.hi - 1) / E), r, s);
+          else if (FILL && sp.valid) part_lse[((int64_t)h * Lq + r) * (topk + 1) + s] = -INFINITY;
+        }
+      }
+    }
+  };
+  for_items([&](int j, int64_t, int) { atomicAdd(&hist[j], 1); });
+  __syncthreads();
+  if (!FILL) {
+    for (int b = tid; b < n; b += 256) blk[b] = s_hist[b];
+    return;
+  }
+  for (int b = tid; b < n; b += 256) {
+    int base = g_cursor[kv * n + b] + blk[b];
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      const int cnt = s_hist[w * n + b];
+      s_hist[w * n + b] = base;
+      base += cnt;
+    }
+  }
+  __syncthreads();
+  for_items([&](int j, int64_t r, int s) { items[atomicAdd(&hist[j], 1)] = (int)(((hl * Lq + r) << 5) | s); });
+}
+
 // One workgroup: exclusive scans of the item counts and of the tile counts over the B buckets.
 // item_off[B] / tile_off[B] receive the totals.  The item list is laid out tile by tile, TM
 // entries per tile (a bucket's last tile is padded), so that the items of tile t start at t*TM
@@ -298,6 +373,13 @@ struct FlashArgs {
   float* LSE;
   int64_t L, Lp, Lq, q_pos0;
   int Hq, G, S, A, topk, n;  // A: anchor spacing (= S on the disjoint grid); n = ceil(L / A)
+  // The paper's own geometry (Section 3.3, Algorithm 1) instead of the grid: idx holds anchor
+  // TOKENS; window > 0 marks this mode.  Span of anchor t for the query at i:
+  // [max(0, t - ab*l(i)), min(i, t + af*l(i))] minus the window [i - window + 1, i], l = ceil(i^(1-1/aroot)).
+  // Buckets are (kv head, end block): block e holds the spans whose last token lies in
+  // [e*E, (e+1)*E), E a multiple of 64 (the key-block bucketing of Section 4.3); n = ceil(L / E).
+  int64_t window;
+  int ab, af, aroot, E;
   float scale_log2e;
   int64_t qsh, qst, kvsh, kvst;
 };
@@ -415,7 +497,7 @@ __device__ __forceinline__ void flash_tile(const FlashArgs& a, char* lds, const 
 #pragma unroll
     for (int i = 0; i < BPW; ++i) {
       uint32_t off = koff[i];
-      if (LOCAL) {  // rows past the end of the sequence re-read the last row (masked later)
+      if (LOCAL || CLIP) {  // rows past the end of the sequence re-read the last row (masked later)
         const int row = (wave * BPW + i) * 4 + (lane >> 4);
         if (t0 + row >= a.L) off -= (uint32_t)((t0 + row - (a.L - 1)) * a.kvst * sizeof(bf16_t));
       }
@@ -793,6 +875,90 @@ __global__ __launch_bounds__(FlashLds<2>::kThreads, 1) void span_flash_routed_ke
   if (carry.pending) flush_routed_output(a, lds, wave >> 2, wave & 3, lane);
 }
 
+// The paper's geometry: routed tiles of a (kv head, end block) bucket.  Every row of a tile has
+// its own token range [lo, hi) (hi inside the bucket's block); the tile walks the kv range from
+// the lowest lo to the highest hi of its rows (rounded to whole 64-token tiles) with per-row masks.
+__global__ __launch_bounds__(FlashLds<2>::kThreads, 1) void span_flash_anchor_kernel(const FlashArgs a) {
+  extern __shared__ __align__(16) char lds[];
+  __shared__ int64_t s_lo[8], s_hi[8];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int qrow = (wave >> 2) * TG + (wave & 3) * 32 + (lane & 31);
+  const int64_t T = a.tile_off[a.Hq / a.G * a.n];
+  const int NWL = gridDim.x / 8;
+  const int xcd = blockIdx.x % 8, wl = blockIdx.x / 8;
+  const int64_t c_begin = T * xcd / 8, c_end = T * (xcd + 1) / 8;
+  const int64_t t_begin = c_begin + wl, t_end = c_end;
+  if (t_begin >= t_end) return;
+
+  // all threads call (two barriers inside)
+  auto describe = [&](const int4& info, int item) {
+    TileDesc d;
+    d.kv = info.x / a.n;
+    const int rowid = item >> 5, slot = item & 31;
+    const int hl = rowid / (int)a.Lq;
+    const int64_t r = rowid - (int64_t)hl * a.Lq;
+    const int h = d.kv * a.G + hl;
+    const int64_t i = a.q_pos0 + r;
+    const bool real = qrow < info.z;
+    const int64_t t = a.idx[((int64_t)h * a.Lq + r) * a.topk + slot];
+    const AnchorSpan sp = anchor_span_of(i, t, span_base_length(i, a.aroot), a.window, a.ab, a.af);
+    d.q_off = h * a.qsh + r * a.qst;
+    d.row_out = real ? ((int64_t)h * a.Lq + r) * (a.topk + 1) + slot : -1;
+    d.lo_q = sp.lo;
+    d.i_q = sp.hi - 1;
+    d.row_base = 0;
+    // the tile's kv range: from the lowest lo to the highest hi of its rows
+    int64_t lo = real && sp.hi > sp.lo ? sp.lo : INT64_MAX, hi = real && sp.hi > sp.lo ? sp.hi : 0;
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+      const int64_t lo2 = __shfl_xor(lo, off, 64), hi2 = __shfl_xor(hi, off, 64);
+      lo = lo2 < lo ? lo2 : lo;
+      hi = hi2 > hi ? hi2 : hi;
+    }
+    __syncthreads();  // earlier readers of s_lo / s_hi are done
+    if (lane == 0) {
+      s_lo[wave] = lo;
+      s_hi[wave] = hi;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int w = 0; w < 8; ++w) {
+      lo = s_lo[w] < lo ? s_lo[w] : lo;
+      hi = s_hi[w] > hi ? s_hi[w] : hi;
+    }
+    if (hi <= lo) lo = hi = 0;  // cannot happen for a tile with items; keeps the range sane
+    d.kv_begin = lo / TN * TN;
+    d.kv_end = (hi + TN - 1) / TN * TN;
+    return d;
+  };
+  FlashCarry carry;
+  carry.kb = carry.vb = 0;
+  carry.primed = false;
+  carry.pending = false;
+  int* const ahead = reinterpret_cast<int*>(lds + FlashLds<2>::kAhead) + wave * 128;
+  const int4 info0 = a.tile_info[t_begin];
+  TileDesc cur = describe(info0, a.items[t_begin * TM + qrow]);
+  for (int64_t t = t_begin; t < t_end; t += NWL) {
+    const bool has_next = t + NWL < t_end;
+    TileDesc nxt = cur;
+    flash_tile<2, false, false, true>(
+        a, lds, cur, nxt, has_next,
+        [&] {
+          const int* rec = reinterpret_cast<const int*>(a.tile_info + (t + NWL)) + (lane & 3);
+          const int* itm = a.items + (t + NWL) * TM + wave * 32 + (lane & 31);
+          __builtin_amdgcn_global_load_lds(SL_GLOBAL_PTR(rec), SL_LDS_PTR(ahead), 4, 0, 0);
+          __builtin_amdgcn_global_load_lds(SL_GLOBAL_PTR(itm), SL_LDS_PTR(ahead + 64), 4, 0, 0);
+        },
+        [&] {
+          const int4 ninfo = make_int4(ahead[0], ahead[1], ahead[2], 0);
+          return describe(ninfo, ahead[64 + lane]);
+        },
+        carry);
+    cur = nxt;
+  }
+  if (carry.pending) flush_routed_output(a, lds, wave >> 2, wave & 3, lane);
+}
+
 // Row tiles of the local-window kernel and their grouping into chunks of `tps` tiles (the tiles
 // of one span when S is a multiple of the tile height).
 struct LocalMap {
@@ -853,10 +1019,16 @@ __global__ __launch_bounds__(FlashLds<1>::kThreads, 2) void span_flash_local_ker
   if (FUSED) d.row_out = r < a.Lq ? d.row_base + r : -1;
   else d.row_out = r < a.Lq ? (d.row_base + r) * (a.topk + 1) + a.topk : -1;
   d.i_q = a.q_pos0 + rc;
-  d.lo_q = (d.i_q / a.A) * a.A;
   const int64_t i_first = a.q_pos0 + r0;
   const int64_t i_last = min(a.q_pos0 + r0 + TML - 1, a.q_pos0 + a.Lq - 1);
-  d.kv_begin = (i_first / a.A) * a.A;
+  if (a.window > 0) {  // the paper's geometry: a sliding window [i - window + 1, i] per row
+    d.lo_q = d.i_q - a.window + 1 > 0 ? d.i_q - a.window + 1 : 0;
+    const int64_t first_lo = i_first - a.window + 1 > 0 ? i_first - a.window + 1 : 0;
+    d.kv_begin = first_lo / TN * TN;
+  } else {
+    d.lo_q = (d.i_q / a.A) * a.A;
+    d.kv_begin = (i_first / a.A) * a.A;
+  }
   d.kv_end = d.kv_begin + ((i_last - d.kv_begin) / TN + 1) * TN;
   FlashCarry carry;
   carry.kb = carry.vb = 0;
@@ -933,7 +1105,10 @@ __global__ __launch_bounds__(256) void merge_partials_kernel(
 // A_t = log-sum-exp merge of the slot's partial with the local window's partial (the attention
 // over span t and the window with its own softmax); O = sum_t alpha_t A_t with alpha = softmax of
 // the slots' search scores; no valid slot: the window's partial.
-template <int KMAX>
+// ANCHOR: the paper's geometry.  idx holds anchor tokens, a slot is valid if its anchor is one of
+// the row's (0 <= t <= i); a valid slot whose span minus the window is empty has lse = -inf and
+// A_t is then the window's attention alone.
+template <int KMAX, bool ANCHOR>
 __global__ __launch_bounds__(256) void merge_combined_kernel(
     const int32_t* __restrict__ idx, const float* __restrict__ gate,
     const bf16_t* __restrict__ part_o, const float* __restrict__ part_lse, bf16_t* __restrict__ O,
@@ -942,7 +1117,7 @@ __global__ __launch_bounds__(256) void merge_combined_kernel(
   const int piece = threadIdx.x & 15;
   if (row >= rows) return;
   const int64_t r = row % Lq;
-  const int c = (int)((q_pos0 + r) / S);
+  const int64_t limit = ANCHOR ? q_pos0 + r + 1 : (q_pos0 + r) / S;  // valid entries lie in [0, limit)
   const int nslot = topk + 1;
   const int32_t* irow = idx + row * topk;
   const float* grow = gate + row * topk;
@@ -955,15 +1130,19 @@ __global__ __launch_bounds__(256) void merge_combined_kernel(
 #pragma unroll
   for (int s = 0; s < KMAX; ++s) js[s] = s < topk ? irow[s] : -1;
   float gmax = -INFINITY;
+  unsigned okmask = 0u;
 #pragma unroll
   for (int s = 0; s < KMAX; ++s) {
-    bool ok = js[s] >= 0 && js[s] < c;
+    bool ok = js[s] >= 0 && js[s] < limit;
+    if (!ANCHOR) {
 #pragma unroll
-    for (int u = 0; u < s; ++u) ok = ok && js[u] != js[s];
+      for (int u = 0; u < s; ++u) ok = ok && js[u] != js[s];
+    }
     ls[s] = ok ? lrow[s] : -INFINITY;
     gs[s] = ok ? grow[s] : -INFINITY;
-    ov[s] = ok ? load16_stream(orow + (int64_t)s * HD) : make_uint4(0, 0, 0, 0);
+    ov[s] = (ok && ls[s] > -INFINITY) ? load16_stream(orow + (int64_t)s * HD) : make_uint4(0, 0, 0, 0);
     gmax = fmaxf(gmax, gs[s]);
+    okmask |= ok ? (1u << s) : 0u;
   }
   const float lw = lrow[topk];
   ov[KMAX] = load16_stream(orow + (int64_t)topk * HD);
@@ -975,9 +1154,9 @@ __global__ __launch_bounds__(256) void merge_combined_kernel(
   float asum = 0.f;
 #pragma unroll
   for (int s = 0; s < KMAX; ++s) {
-    if (ls[s] > -INFINITY) {  // valid slot
+    if (okmask & (1u << s)) {  // valid slot
       const float M = fmaxf(ls[s], lw);
-      const float wa = __expf(ls[s] - M), wb = __expf(lw - M);
+      const float wa = ls[s] > -INFINITY ? __expf(ls[s] - M) : 0.f, wb = __expf(lw - M);
       const float a = __expf(gs[s] - gmax);
       const float fa = a * wa / (wa + wb), fb = a * wb / (wa + wb);
       asum += a;
@@ -1032,6 +1211,8 @@ bool device_setup(DeviceSetup* out) {
         hipFuncSetAttribute(reinterpret_cast<const void*>(span_flash_routed_kernel<false>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, FlashLds<2>::kBytes) == hipSuccess &&
         hipFuncSetAttribute(reinterpret_cast<const void*>(span_flash_routed_kernel<true>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, FlashLds<2>::kBytes) == hipSuccess &&
+        hipFuncSetAttribute(reinterpret_cast<const void*>(span_flash_anchor_kernel),
                             hipFuncAttributeMaxDynamicSharedMemorySize, FlashLds<2>::kBytes) == hipSuccess &&
         hipFuncSetAttribute(reinterpret_cast<const void*>(span_flash_local_kernel<false>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, FlashLds<1>::kBytes) == hipSuccess &&
@@ -1131,6 +1312,10 @@ sl_status prefill_attention_mfma(const Problem& pb, const void* Q, const void* K
   a.G = pb.G;
   a.S = pb.S;
   a.A = pb.A;
+  a.window = 0;
+  a.ab = a.af = 0;
+  a.aroot = 2;
+  a.E = 0;
   a.topk = pb.topk;
   a.n = n;
   a.scale_log2e = pb.scale * kLog2e;
@@ -1174,7 +1359,7 @@ sl_status prefill_attention_mfma(const Problem& pb, const void* Q, const void* K
 #define SL_MERGE(KM)                                                                             \
   do {                                                                                           \
     if (pb.combined)                                                                                 \
-      hipLaunchKernelGGL(merge_combined_kernel<KM>, mgrid, dim3(256), 0, st, idx, pb.gate,       \
+      hipLaunchKernelGGL((merge_combined_kernel<KM, false>), mgrid, dim3(256), 0, st, idx, pb.gate, \
                          part_o, part_lse, a.O, rows, pb.Lq, pb.q_pos0, pb.A, pb.topk);          \
     else                                                                                         \
       hipLaunchKernelGGL(merge_partials_kernel<KM>, mgrid, dim3(256), 0, st, idx, part_o,        \
@@ -1185,6 +1370,133 @@ sl_status prefill_attention_mfma(const Problem& pb, const void* Q, const void* K
   else if (pb.topk <= 16) SL_MERGE(16);
   else SL_MERGE(32);
 #undef SL_MERGE
+  return hipGetLastError() == hipSuccess ? SL_OK : SL_ERR_LAUNCH;
+}
+
+// ------------------------------------------------------------------ the paper's geometry on the matrix cores
+namespace {
+
+// End-block size E of the buckets: the smallest power-of-two multiple of 64 tokens that gives a
+// bucket about two 256-row tiles of items on average, and at most 4096 blocks per kv head.
+int anchor_block_tokens(const Problem& pb) {
+  const int64_t items = (int64_t)pb.G * pb.Lq * (pb.topk > 0 ? pb.topk : 1);
+  int64_t E = 64;
+  while (E < 4096 && (items * E < 512 * pb.L || (pb.L + E - 1) / E > 4096)) E <<= 1;
+  return (int)E;
+}
+
+Problem anchor_view(const Problem& pb) {
+  Problem q = pb;
+  q.A = anchor_block_tokens(pb);
+  q.n = (pb.L + q.A - 1) / q.A;
+  return q;
+}
+
+}  // namespace
+
+bool prefill_anchor_mfma_supported(const Problem& pb, int64_t window) {
+  const Problem q = anchor_view(pb);
+  return window >= 1 && pb.topk >= 1 && pb.dtype == SL_BF16 && pb.D == HD && q.n <= 4096 &&
+         (int64_t)pb.G * pb.Lq < ((int64_t)1 << 26) &&
+         (int64_t)HD * (int64_t)align_up((size_t)pb.L, 64) * 2 < ((int64_t)1 << 32) &&
+         64 * pb.kvst * 2 < ((int64_t)1 << 31) &&
+         (int64_t)pb.Hq * pb.Lq * (pb.topk + 1) < ((int64_t)1 << 31) &&
+         (int64_t)pb.Hq * pb.Lq * pb.topk + ((int64_t)pb.Hkv * q.n + 1) * TM < ((int64_t)1 << 31) &&
+         (int64_t)pb.Hq * pb.qsh + pb.Lq * pb.qst < ((int64_t)1 << 31);
+}
+
+size_t prefill_anchor_mfma_ws_bytes(const Problem& pb) { return carve(anchor_view(pb)).total; }
+
+// Span-attention and combination on the paper's geometry (Section 3.3-3.4, Algorithm 1), matrix-core
+// form following Section 4.3's bucketing by key-block footprint: (row, slot) pairs are bucketed by
+// the block that holds their span's last token, a bucket's rows share one sliding K/V range with
+// per-row masks, the sliding window is a banded flash kernel, and the gated merge combines them.
+sl_status prefill_anchor_attention_mfma(const Problem& pb, int64_t window, int b, int f, int root,
+                                        const void* Q, const void* K, const void* V,
+                                        const int32_t* anchors, void* O, void* ws, hipStream_t st) {
+  const Problem q = anchor_view(pb);
+  const MfmaWs w = carve(q);
+  DeviceSetup dev;
+  if (!device_setup(&dev) || !dev.lds_ok) return SL_ERR_LAUNCH;
+  char* base = static_cast<char*>(ws);
+  bf16_t* Vt = reinterpret_cast<bf16_t*>(base + w.vt);
+  int* counts = reinterpret_cast<int*>(base + w.counts);
+  int* blk_cnt = reinterpret_cast<int*>(base + w.blk_cnt);
+  int* item_off = reinterpret_cast<int*>(base + w.item_off);
+  int* tile_off = reinterpret_cast<int*>(base + w.tile_off);
+  int* cursor = reinterpret_cast<int*>(base + w.cursor);
+  int4* tile_info = reinterpret_cast<int4*>(base + w.tile_info);
+  int* items = reinterpret_cast<int*>(base + w.items);
+  float* part_lse = reinterpret_cast<float*>(base + w.part_lse);
+  bf16_t* part_o = reinterpret_cast<bf16_t*>(base + w.part_o);
+  const int n = (int)q.n;
+
+  hipLaunchKernelGGL(transpose_v_kernel, dim3((unsigned)(w.Lp / 64), pb.Hkv), dim3(256), 0, st,
+                     static_cast<const bf16_t*>(V), Vt, pb.L, w.Lp, pb.kvsh, pb.kvst);
+  FlashArgs a;
+  a.Q = static_cast<const bf16_t*>(Q);
+  a.K = static_cast<const bf16_t*>(K);
+  a.Vt = Vt;
+  a.idx = anchors;
+  a.item_off = item_off;
+  a.tile_off = tile_off;
+  a.tile_info = tile_info;
+  a.items = items;
+  a.part_o = part_o;
+  a.part_lse = part_lse;
+  a.O = static_cast<bf16_t*>(O);
+  a.LSE = nullptr;
+  a.L = pb.L;
+  a.Lp = w.Lp;
+  a.Lq = pb.Lq;
+  a.q_pos0 = pb.q_pos0;
+  a.Hq = pb.Hq;
+  a.G = pb.G;
+  a.S = 1024;  // only groups the window kernel's row tiles per XCD
+  a.A = 1024;
+  a.topk = pb.topk;
+  a.n = n;
+  a.window = window;
+  a.ab = b;
+  a.af = f;
+  a.aroot = root;
+  a.E = q.A;
+  a.scale_log2e = pb.scale * kLog2e;
+  a.qsh = pb.qsh;
+  a.qst = pb.qst;
+  a.kvsh = pb.kvsh;
+  a.kvst = pb.kvst;
+
+  const dim3 bgrid((unsigned)w.chunks, pb.Hq);
+  hipLaunchKernelGGL(bucket_anchor_kernel<false>, bgrid, dim3(256), (size_t)n * sizeof(int), st, anchors,
+                     blk_cnt, cursor, items, part_lse, pb.Lq, pb.q_pos0, pb.G, pb.topk, n, window, b, f, root,
+                     a.E);
+  hipLaunchKernelGGL(bucket_block_scan_kernel, dim3((n + 31) / 32, pb.Hkv), dim3(256), 0, st, blk_cnt, counts,
+                     pb.G * w.chunks, n);
+  hipLaunchKernelGGL(bucket_scan_kernel, dim3(1), dim3(1024), 0, st, counts, item_off, tile_off, cursor, w.B);
+  hipLaunchKernelGGL(bucket_tiles_kernel, dim3(w.B), dim3(256), 0, st, tile_off, item_off, tile_info, items);
+  hipLaunchKernelGGL(bucket_anchor_kernel<true>, bgrid, dim3(256), (size_t)4 * n * sizeof(int), st, anchors,
+                     blk_cnt, cursor, items, part_lse, pb.Lq, pb.q_pos0, pb.G, pb.topk, n, window, b, f, root,
+                     a.E);
+  if (hipGetLastError() != hipSuccess) return SL_ERR_LAUNCH;
+  if (pb.prof_start) (void)hipEventRecord(pb.prof_start, st);
+  hipLaunchKernelGGL(span_flash_anchor_kernel, dim3(dev.grid), dim3(FlashLds<2>::kThreads),
+                     FlashLds<2>::kBytes, st, a);
+  if (pb.prof_stop) (void)hipEventRecord(pb.prof_stop, st);
+  const unsigned lgrid = local_grid(pb.Lq, a.A, pb.Hkv, pb.G);
+  hipLaunchKernelGGL(span_flash_local_kernel<false>, dim3(lgrid), dim3(FlashLds<1>::kThreads),
+                     FlashLds<1>::kBytes, st, a);
+  const int64_t rows = (int64_t)pb.Hq * pb.Lq;
+  const dim3 mgrid((unsigned)((rows + 15) / 16));
+  if (pb.topk <= 8)
+    hipLaunchKernelGGL((merge_combined_kernel<8, true>), mgrid, dim3(256), 0, st, anchors, pb.gate, part_o,
+                       part_lse, a.O, rows, pb.Lq, pb.q_pos0, 1, pb.topk);
+  else if (pb.topk <= 16)
+    hipLaunchKernelGGL((merge_combined_kernel<16, true>), mgrid, dim3(256), 0, st, anchors, pb.gate, part_o,
+                       part_lse, a.O, rows, pb.Lq, pb.q_pos0, 1, pb.topk);
+  else
+    hipLaunchKernelGGL((merge_combined_kernel<32, true>), mgrid, dim3(256), 0, st, anchors, pb.gate, part_o,
+                       part_lse, a.O, rows, pb.Lq, pb.q_pos0, 1, pb.topk);
   return hipGetLastError() == hipSuccess ? SL_OK : SL_ERR_LAUNCH;
 }
 

@@ -472,6 +472,110 @@ __global__ __launch_bounds__(256) void prefill_anchor_search_rows_kernel(
                    scores ? scores + row * topk : nullptr, i, s0, root);
 }
 
+// The same search with the key rows shared by the query heads of a kv group: a row group of LPR
+// lanes owns one query row and up to 8 query heads of its kv head; every candidate's key row is
+// loaded once and scored against all of them (the row-per-wavefront kernel above loads it once per
+// head: 8x the L2 traffic at GQA 8:1, which is what bounds it).  Lane lr of a group keeps the
+// running top-KMAX (scores and candidate numbers, in registers) of head lr % 8; candidates come in
+// ascending stride index and only a strictly larger score displaces an entry, so ties stay with the
+// nearer anchor.  Arithmetic per score as everywhere else (fp32 fma chain over the lane's
+// elements, then the lane-group sum): bit-identical to the other search kernels.
+template <typename T, int D, int KMAX>
+__global__ __launch_bounds__(256) void prefill_anchor_search_group_kernel(
+    const T* __restrict__ Qs, const T* __restrict__ K, int32_t* __restrict__ anchors,
+    float* __restrict__ scores, int64_t Lq, int64_t q_pos0, int G, int topk, int s0, int root,
+    int64_t qsh, int64_t qst, int64_t kvsh, int64_t kvst) {
+  using RL = RowLayout<T, D>;
+  constexpr int EPL = RL::EPL, LPR = RL::LPR, RPW = RL::RPW;
+  constexpr int HB = 8, U = 8;
+  static_assert(LPR >= HB, "a row group needs a lane per head of the batch");
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int g = lane / LPR, lr = lane % LPR;
+  const int nb = (G + HB - 1) / HB;
+  const int kv = blockIdx.y / nb, h0 = (blockIdx.y % nb) * HB;
+  const int64_t r = ((int64_t)blockIdx.x * 4 + wave) * RPW + g;
+  if (((int64_t)blockIdx.x * 4 + wave) * RPW >= Lq) return;  // the whole wavefront is past the last row
+  const int64_t rc = r < Lq ? r : Lq - 1;
+  const int64_t i = q_pos0 + rc;
+  const int64_t s_max = iroot_floor(i + 1, root) - 1;  // (s+1)^root <= i + 1
+  const int c = s_max >= s0 ? (int)(s_max - s0 + 1) : 0;
+  // rows ascend with the lane and so do their candidate counts: the last lane has the most
+  const int c_wave = __builtin_amdgcn_readlane(c, 63);
+
+  float qf[HB][EPL];
+#pragma unroll
+  for (int hb = 0; hb < HB; ++hb) {
+    const int h = kv * G + (h0 + hb < G ? h0 + hb : G - 1);
+    Elem<T>::unpack(load16(Qs + h * qsh + rc * qst + lr * EPL), qf[hb]);
+  }
+  const T* Kb = K + kv * kvsh;
+  float v[KMAX];
+  int id[KMAX];
+#pragma unroll
+  for (int e = 0; e < KMAX; ++e) {
+    v[e] = -INFINITY;
+    id[e] = -1;
+  }
+  const int myh = lr % HB;
+  for (int jb = 0; jb < c_wave; jb += U) {
+    uint4 kr[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int j = jb + u < c ? jb + u : c - 1;
+      const int64_t t = c > 0 ? anchor_token_of(i, (int64_t)s0 + j, root) : i;  // no candidate: any valid row
+      kr[u] = load16(Kb + t * kvst + lr * EPL);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      float kf[EPL];
+      Elem<T>::unpack(kr[u], kf);
+      float x = -INFINITY;
+#pragma unroll
+      for (int hb = 0; hb < HB; ++hb) {
+        float acc = 0.f;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) acc = fmaf(qf[hb][e], kf[e], acc);
+        acc = group_sum<LPR>(acc);
+        x = myh == hb ? acc : x;
+      }
+      const int j = jb + u;
+      x = j < c ? x : -INFINITY;
+      // insert (x, j): slot e takes the entry above it if x belongs above that one, x itself if
+      // x belongs exactly here; strict compares keep the earlier candidate on ties
+#pragma unroll
+      for (int e = KMAX - 1; e >= 0; --e) {
+        const bool up = e > 0 && x > v[e > 0 ? e - 1 : 0];
+        const bool here = !up && x > v[e];
+        id[e] = up ? id[e > 0 ? e - 1 : 0] : (here ? j : id[e]);
+        v[e] = up ? v[e > 0 ? e - 1 : 0] : (here ? x : v[e]);
+      }
+    }
+  }
+  if (r < Lq && lr < HB && h0 + lr < G) {
+    const int64_t row = (int64_t)(kv * G + h0 + lr) * Lq + r;
+    int32_t* oa = anchors + row * topk;
+    float* os = scores ? scores + row * topk : nullptr;
+    int kk = 0;
+#pragma unroll
+    for (int e = 0; e < KMAX; ++e) kk += (e < topk && id[e] >= 0) ? 1 : 0;
+    // nearest anchor first: a selected entry's slot is the number of selected entries with a lower stride index
+#pragma unroll
+    for (int e = 0; e < KMAX; ++e) {
+      if (e < topk && id[e] >= 0) {
+        int rank = 0;
+#pragma unroll
+        for (int e2 = 0; e2 < KMAX; ++e2) rank += (e2 < topk && id[e2] >= 0 && id[e2] < id[e]) ? 1 : 0;
+        oa[rank] = (int32_t)anchor_token_of(i, (int64_t)s0 + id[e], root);
+        if (os) os[rank] = v[e];
+      }
+    }
+    for (int e = kk; e < topk; ++e) {
+      oa[e] = -1;
+      if (os) os[e] = -INFINITY;
+    }
+  }
+}
+
 template <typename T, int D>
 sl_status launch_span_keys(const Problem& pb, const void* K, void* Ks, hipStream_t st) {
   using RL = RowLayout<T, D>;
@@ -601,6 +705,21 @@ template <typename T, int D>
 sl_status launch_anchor_search_rows(const Problem& pb, const void* Qs, const void* K,
                                     int32_t* anchors, float* scores, int64_t c_max, int s0,
                                     int root, hipStream_t st) {
+  if (pb.topk <= 8) {  // key rows shared by the heads of a kv group, top-k lists in registers
+    constexpr int RPW = RowLayout<T, D>::RPW;
+    const dim3 grid((unsigned)((pb.Lq + 4 * RPW - 1) / (4 * RPW)), (unsigned)(pb.Hkv * ((pb.G + 7) / 8)));
+    if (pb.prof_start) (void)hipEventRecord(pb.prof_start, st);
+#define SL_ANCHOR_GROUP(KM)                                                                               \
+  hipLaunchKernelGGL((prefill_anchor_search_group_kernel<T, D, KM>), grid, dim3(256), 0, st,              \
+                     static_cast<const T*>(Qs), static_cast<const T*>(K), anchors, scores, pb.Lq, pb.q_pos0, \
+                     pb.G, pb.topk, s0, root, pb.qsh, pb.qst, pb.kvsh, pb.kvst)
+    if (pb.topk <= 2) SL_ANCHOR_GROUP(2);
+    else if (pb.topk <= 4) SL_ANCHOR_GROUP(4);
+    else SL_ANCHOR_GROUP(8);
+#undef SL_ANCHOR_GROUP
+    if (pb.prof_stop) (void)hipEventRecord(pb.prof_stop, st);
+    return hipGetLastError() == hipSuccess ? SL_OK : SL_ERR_LAUNCH;
+  }
   const int lds_per_wave = LaneMajor::make(c_max).lds_floats();
   int W = 4;
   while (W > 1 && (size_t)W * lds_per_wave * sizeof(float) > 64 * 1024) W >>= 1;

@@ -205,32 +205,42 @@ def test_paper_geometry_decode_at_1m():
     torch.cuda.empty_cache()
 
 
-def test_paper_geometry_prefill_rows_of_the_256k_cache():
-    # the configuration bench.py times: the last rows of config 4's cache on the paper's geometry
-    # (window 1088, top-2, b = 4, f = 2), sampled rows against the oracle
+def test_paper_geometry_prefill_all_rows_of_the_256k_cache():
+    # the configuration bench.py times: every row of config 4 on the paper's geometry (window 1088,
+    # top-2, b = 4, f = 2) through the group-shared search and the bucketed matrix-core attention;
+    # sampled rows against the oracle, plus the row-stationary form on a block of rows
     cfg = W.CONFIGS["C4"]
     data = W.generate(cfg, device=DEV)
-    K, V = data["K"], data["V"]
-    w, k, b, f, rows_n = 1088, 2, 4, 2, 512
-    p0 = cfg.L - rows_n
-    Q = data["Q"][:, p0:]
+    Q, K, V = data["Q"], data["K"], data["V"]
     del data
+    w, k, b, f = 1088, 2, 4, 2
     G = cfg.Hq // cfg.Hkv
-    anchors, sc = B.sl_anchor_search_prefill(Q, K, k, w, q_pos0=p0, want_scores=True)
-    O = B.sl_anchor_attention_prefill(Q, K, V, anchors, sc, w, b, f, q_pos0=p0)
+    anchors, sc = B.sl_anchor_search_prefill(Q, K, k, w, want_scores=True)
+    O = B.sl_anchor_attention_prefill(Q, K, V, anchors, sc, w, b, f)
     torch.cuda.synchronize()
-    an, scn, Qn, On = anchors.cpu().numpy(), sc.cpu().numpy().astype(np.float64), f64(Q), f64(O)
+    assert torch.isfinite(O.float()).all()
+    rng = np.random.default_rng(3)
+    pos = sorted({0, 1, 2, 1087, 1088, 1089, 1152, 5000, cfg.L // 2, cfg.L - 2, cfg.L - 1} |
+                 {int(x) for x in rng.integers(0, cfg.L, 24)})
     Kd, Vd = DevKV(K), DevKV(V)
     for h in (0, 9, 31):
-        for r in (0, 1, 255, rows_n - 1):
-            i = p0 + r
-            _, t_o, _ = orc.anchor_search_row(Qn[h, r], DevRows(K[h // G]), i, w, k)
-            if an[h, r].tolist() != t_o + [-1] * (k - len(t_o)):
-                cand = orc.anchor_candidates(i, w)
-                allsc = [float(f64(K[h // G, t]) @ Qn[h, r]) for _, t in cand]
-                check_anchor_row(an[h, r].tolist(), t_o + [-1] * (k - len(t_o)), cand, allsc, k, (h, r))
-            o = orc.anchor_combined_row(Qn[h, r], Kd, Vd, h // G, i, w, b, f, an[h, r], scn[h, r],
-                                        1.0 / math.sqrt(cfg.D))
-            assert float(np.max(np.abs(On[h, r] - o))) <= TOL[torch.bfloat16], (h, r)
+        for r in pos:
+            qn = f64(Q[h, r])
+            an_r, sc_r = anchors[h, r].cpu().numpy(), sc[h, r].cpu().numpy().astype(np.float64)
+            _, t_o, _ = orc.anchor_search_row(qn, DevRows(K[h // G]), r, w, k)
+            want = t_o + [-1] * (k - len(t_o))
+            if an_r.tolist() != want:
+                cand = orc.anchor_candidates(r, w)
+                allsc = [float(f64(K[h // G, t]) @ qn) for _, t in cand]
+                check_anchor_row(an_r.tolist(), want, cand, allsc, k, (h, r))
+            sc_r = np.where(np.isfinite(sc_r), sc_r, 0.0)
+            o = orc.anchor_combined_row(qn, Kd, Vd, h // G, r, w, b, f, an_r, sc_r, 1.0 / math.sqrt(cfg.D))
+            assert float(np.max(np.abs(f64(O[h, r]) - o))) <= TOL[torch.bfloat16], (h, r)
+    # a block of rows through the row-stationary kernels
+    p0, nr = cfg.L - 3000, 1024
+    Or = B.sl_anchor_attention_prefill(Q[:, p0:p0 + nr], K, V, anchors[:, p0:p0 + nr].contiguous(),
+                                       sc[:, p0:p0 + nr].contiguous(), w, b, f, q_pos0=p0, row_stationary=True)
+    torch.cuda.synchronize()
+    assert float((Or.float() - O[:, p0:p0 + nr].float()).abs().max()) <= 1.5 * TOL[torch.bfloat16]
     del K, V
     torch.cuda.empty_cache()

@@ -1045,6 +1045,48 @@ def test_anchor_prefill(seed, Hq, Hkv, L, D, k, w, b, f, dtype, q_pos0, Lq):
             assert err <= TOL[dtype], (h, r, err)
 
 
+@pytest.mark.parametrize("seed,Hq,Hkv,L,k,w,b,f,root,q_pos0,Lq", [
+    (56, 8, 2, 20000, 2, 1088, 4, 2, 2, 0, None),        # the paper's kernel configuration, every row from i = 0
+    (57, 4, 1, 30000, 3, 120, 2, 1, 2, 21000, 9000),     # a chunk at the end of a longer cache, 3 slots
+    (58, 16, 2, 6000, 4, 63, 3, 0, 3, 0, None),          # exponents 1/3 and 2/3, G = 8
+    (59, 2, 2, 700, 16, 24, 1, 3, 2, 0, None),           # 16 slots, forward-heavy spans clipped at the query
+])
+def test_anchor_prefill_matrix_core_form(seed, Hq, Hkv, L, k, w, b, f, root, q_pos0, Lq):
+    """The bucketed matrix-core form of the paper's geometry against the oracle (sampled rows) and
+    against the row-stationary form (every row)."""
+    D, dtype = 128, torch.bfloat16
+    Q, K, V = make(seed, Hq, Hkv, L, D, dtype, Lq=Lq, scale=0.5)
+    Lq = Q.shape[1]
+    G = Hq // Hkv
+    anchors, sc = B.sl_anchor_search_prefill(Q, K, k, w, q_pos0=q_pos0, want_scores=True, search_root=root)
+    torch.cuda.synchronize()
+    sc_in = torch.where(torch.isfinite(sc), sc, torch.zeros_like(sc))
+    lib = B.load()
+    import ctypes
+    p = B.make_params(Q, K, 1, k, q_pos0)
+    g = B.SlAnchorGeometry(w, b, f, root, 0)
+    assert 0 < lib.sl_anchor_prefill_workspace_bytes(ctypes.byref(p), ctypes.byref(g)) < B.WORKSPACE_INVALID
+    O = B.sl_anchor_attention_prefill(Q, K, V, anchors, sc_in, w, b, f, q_pos0=q_pos0, search_root=root)
+    O_rows = B.sl_anchor_attention_prefill(Q, K, V, anchors, sc_in, w, b, f, q_pos0=q_pos0, search_root=root,
+                                           row_stationary=True)
+    torch.cuda.synchronize()
+    assert torch.isfinite(O.float()).all()
+    assert float((O.float() - O_rows.float()).abs().max()) <= 1.5 * TOL[dtype]
+    rng = np.random.default_rng(seed)
+    rows = sorted(set(rng.integers(0, Lq, 60).tolist() + [0, 1, 2, Lq - 1, Lq // 2]))
+    an, scn, Qn, On = anchors.cpu().numpy(), sc_in.cpu().numpy().astype(np.float64), f64(Q), f64(O)
+    Kd, Vd = DevKV(K), DevKV(V)
+    for h in sorted({0, Hq - 1, Hq // 2}):
+        for r in rows:
+            o = orc.anchor_combined_row(Qn[h, r], Kd, Vd, h // G, q_pos0 + r, w, b, f, an[h, r], scn[h, r],
+                                        1.0 / math.sqrt(D), root=root)
+            assert float(np.max(np.abs(On[h, r] - o))) <= TOL[dtype], (h, r)
+    # bit-reproducible
+    O2 = B.sl_anchor_attention_prefill(Q, K, V, anchors, sc_in, w, b, f, q_pos0=q_pos0, search_root=root)
+    torch.cuda.synchronize()
+    assert torch.equal(O, O2)
+
+
 def test_anchor_prefill_last_row_equals_decode():
     # the decode form is the prefill form's last row
     Hq, Hkv, L, D, k, w, b, f = 8, 2, 5000, 128, 2, 1088, 4, 2
