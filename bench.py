@@ -26,6 +26,7 @@ PEAK_HBM = 8.0e12           # B/s, MI355X HBM3E
 PEAK_BF16 = 2.5e15          # flop/s, dense bf16 MFMA
 PEAK_FP32_VALU = 157.3e12   # flop/s, fp32 vector
 N_DECODE_QUERIES = 8        # decode steps rotate over this many independent queries (different span sets)
+MAIN_ONLY = False           # --main-only: time only each configuration's own step (clean profiler traces)
 
 
 def log(*a):
@@ -48,6 +49,35 @@ class ProfEvents:
     def ms(self):
         self.b.synchronize()
         return self.a.elapsed_time(self.b)
+
+
+def device_facts(torch):
+    """Compute units and maximum clock of GPU 0 as rocminfo reports them (torch's properties as a
+    fallback), and the dense bf16 MFMA peak they imply next to the published peaks the roofline uses."""
+    import re
+    import subprocess
+    name, cus, mhz = "", 0, 0.0
+    try:
+        out = subprocess.run(["rocminfo"], capture_output=True, text=True, timeout=30).stdout
+        for agent in out.split("*******")[1:]:
+            if re.search(r"Device Type:\s+GPU", agent):
+                m = re.search(r"Marketing Name:\s+(.*)", agent)
+                name = m.group(1).strip() if m else ""
+                m = re.search(r"Compute Unit:\s+(\d+)", agent)
+                cus = int(m.group(1)) if m else 0
+                m = re.search(r"Max Clock Freq\. \(MHz\):\s+(\d+)", agent)
+                mhz = float(m.group(1)) if m else 0.0
+                break
+    except Exception:
+        pass
+    if not cus:
+        prop = torch.cuda.get_device_properties(0)
+        name, cus, mhz = prop.name, prop.multi_processor_count, getattr(prop, "clock_rate", 0) / 1e3
+    return {"name": name, "compute_units": cus, "max_clock_mhz": mhz,
+            # 4 SIMDs x 1024 flop/clk (a 32x32x16 bf16 MFMA = 32768 flop in 32 cycles) per compute unit
+            "derived_bf16_mfma_peak_tflops": cus * 4096 * mhz * 1e6 / 1e12,
+            "peaks_used": {"hbm_GBps": PEAK_HBM / 1e9, "bf16_mfma_tflops": PEAK_BF16 / 1e12,
+                           "fp32_valu_tflops": PEAK_FP32_VALU / 1e12}}
 
 
 def prefill_flops(cfg):
@@ -154,150 +184,152 @@ def bench_decode(cfg, steps, warmup, torch, B, W):
         e1.synchronize()
         rep_ms.append(e0.elapsed_time(e1) / N_DECODE_QUERIES)
     rep_ms.sort()
-    # The combination form of the same steps (search with scores, gated reduction), same replay.
-    outs_c = [torch.empty((cfg.Hq, 1, cfg.D), dtype=K.dtype, device=dev) for _ in range(N_DECODE_QUERIES)]
+    dt_combined, paper_geometry, batched = None, None, None
+    if not MAIN_ONLY:
+        # The combination form of the same steps (search with scores, gated reduction), same replay.
+        outs_c = [torch.empty((cfg.Hq, 1, cfg.D), dtype=K.dtype, device=dev) for _ in range(N_DECODE_QUERIES)]
 
-    def step_combined(i):
-        q = Qs[i % N_DECODE_QUERIES]
-        idx, sc = B.sl_span_search_decode(q, K, Ks, cfg.S, cfg.topk, want_scores=True, ws=ws)
-        B.sl_span_attention_combined_decode(q, K, V, idx, sc, cfg.S, ws=ws, out=outs_c[i % N_DECODE_QUERIES])
+        def step_combined(i):
+            q = Qs[i % N_DECODE_QUERIES]
+            idx, sc = B.sl_span_search_decode(q, K, Ks, cfg.S, cfg.topk, want_scores=True, ws=ws)
+            B.sl_span_attention_combined_decode(q, K, V, idx, sc, cfg.S, ws=ws, out=outs_c[i % N_DECODE_QUERIES])
 
-    for i in range(N_DECODE_QUERIES):
-        step_combined(i)
-    torch.cuda.synchronize()
-    cgraph = torch.cuda.CUDAGraph()
-    with torch.cuda.graph(cgraph):
         for i in range(N_DECODE_QUERIES):
             step_combined(i)
-    cgraph.replay()
-    torch.cuda.synchronize()
-    tc = time.perf_counter()
-    nrep = max(2, steps // N_DECODE_QUERIES // 2)
-    for _ in range(nrep):
-        cgraph.replay()
-    torch.cuda.synchronize()
-    dt_combined = (time.perf_counter() - tc) / (nrep * N_DECODE_QUERIES)
-    # The paper's own geometry on the same cache (anchors on the quadratic stride pattern, window
-    # 1088, top-2, b = 4, f = 2: Section 4.3's kernel configuration), same replay.
-    PW, PK, PB, PF = 1088, 2, 4, 2
-    outs_p = [torch.empty((cfg.Hq, 1, cfg.D), dtype=K.dtype, device=dev) for _ in range(N_DECODE_QUERIES)]
-
-    def step_paper(i, prof=None):
-        q = Qs[i % N_DECODE_QUERIES]
-        an, sc = B.sl_anchor_search_decode(q, K, PK, PW, want_scores=True)
-        B.sl_anchor_attention_decode(q, K, V, an, sc, PW, PB, PF, ws=ws, prof=prof, out=outs_p[i % N_DECODE_QUERIES])
-        return an
-
-    an0 = [step_paper(i).cpu().numpy() for i in range(N_DECODE_QUERIES)]
-    torch.cuda.synchronize()
-    pgraph = torch.cuda.CUDAGraph()
-    with torch.cuda.graph(pgraph):
-        for i in range(N_DECODE_QUERIES):
-            step_paper(i)
-    pgraph.replay()
-    torch.cuda.synchronize()
-    tc = time.perf_counter()
-    for _ in range(nrep):
-        pgraph.replay()
-    torch.cuda.synchronize()
-    dt_paper = (time.perf_counter() - tc) / (nrep * N_DECODE_QUERIES)
-    # its K/V streaming kernel and algorithmic bytes: per kv head the union of the heads' token
-    # ranges (span minus window, plus the window once), K and V rows
-    ell = math.isqrt(q_pos) + (0 if math.isqrt(q_pos) ** 2 == q_pos else 1)
-    G = cfg.Hq // cfg.Hkv
-    pbytes = []
-    for an in an0[:N_DECODE_QUERIES // 2]:
-        tokens = 0
-        for kv in range(cfg.Hkv):
-            cover = set()
-            for h in range(kv * G, (kv + 1) * G):
-                for t in an[h, 0].tolist():
-                    if t >= 0:
-                        cover.add((max(0, t - PB * ell), min(min(q_pos, t + PF * ell), q_pos - PW) + 1))
-            ivs = sorted(cover)
-            end = -1
-            for a0, a1 in ivs:          # union of intervals
-                a0 = max(a0, end)
-                if a1 > a0:
-                    tokens += a1 - a0
-                    end = a1
-            tokens += PW
-        pbytes.append(tokens * cfg.D * 2 * 2)
-    evp = [ProfEvents(torch) for _ in range(16)]
-    for i, ev in enumerate(evp):
-        qi = i % (N_DECODE_QUERIES // 2)
-        pgraph.replay()
-        an, sc = B.sl_anchor_search_decode(Qs[qi], K, PK, PW, want_scores=True)
-        B.sl_anchor_attention_decode(Qs[qi], K, V, an, sc, PW, PB, PF, ws=ws, prof=ev.handles(), out=outs_p[qi])
-    torch.cuda.synchronize()
-    pms = sum(ev.ms() for ev in evp) / len(evp)
-    paper_geometry = {"workload": f"anchors i-(s+1)^2+1, window {PW}, top-{PK}, b={PB}, f={PF}, combination gate",
-                      "ms_per_step": dt_paper * 1e3, "value": 1.0 / dt_paper, "unit": "steps/s",
-                      "roofline": {"bound": "hbm", "kernel": "decode_split_kernel", "kernel_ms": pms,
-                                   "algorithmic_bytes": sum(pbytes) / len(pbytes),
-                                   "achieved": sum(pbytes) / len(pbytes) / (pms * 1e-3) / 1e9,
-                                   "peak": PEAK_HBM / 1e9, "unit": "GB/s",
-                                   "frac": sum(pbytes) / len(pbytes) / (pms * 1e-3) / PEAK_HBM}}
-    # Batched decode: NB sequences with caches of their own (copies of the cache, cut to different
-    # lengths, each with a different query) advance one step in three launches.
-    esz = 2 if cfg.dtype == "bf16" else 4
-    NB = 8 if 8 * 2 * cfg.Hkv * cfg.L * cfg.D * esz <= 64e9 else 4
-    lens = [cfg.L - b * (cfg.S + 37) for b in range(NB)]
-    Kc = [K.clone()[:, :lens[b]] for b in range(NB)]
-    Vc = [V.clone()[:, :lens[b]] for b in range(NB)]
-    Ksc = [B.sl_span_keys(Kc[b], cfg.S) for b in range(NB)]
-    nrot = max(1, N_DECODE_QUERIES // NB)
-    batches = [B.DecodeBatch([Qs[(r * NB + b) % N_DECODE_QUERIES] for b in range(NB)],
-                             [Qs[(r * NB + b) % N_DECODE_QUERIES] for b in range(NB)], Kc, Vc, Ksc,
-                             cfg.S, cfg.topk) for r in range(nrot)]
-
-    def step_batched(r):
-        B.sl_span_search_decode_batched(batches[r])
-        B.sl_span_attention_decode_batched(batches[r], ws=ws)
-
-    bbytes = 0
-    for r in range(nrot):
-        step_batched(r)
         torch.cuda.synchronize()
-        ix = batches[r].idx.cpu().numpy()
-        bbytes += sum(decode_bytes(cfg, ix[b], lens[b] - 1) for b in range(NB))
-    bgraph = torch.cuda.CUDAGraph()
-    with torch.cuda.graph(bgraph):
+        cgraph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(cgraph):
+            for i in range(N_DECODE_QUERIES):
+                step_combined(i)
+        cgraph.replay()
+        torch.cuda.synchronize()
+        tc = time.perf_counter()
+        nrep = max(2, steps // N_DECODE_QUERIES // 2)
+        for _ in range(nrep):
+            cgraph.replay()
+        torch.cuda.synchronize()
+        dt_combined = (time.perf_counter() - tc) / (nrep * N_DECODE_QUERIES)
+        # The paper's own geometry on the same cache (anchors on the quadratic stride pattern, window
+        # 1088, top-2, b = 4, f = 2: Section 4.3's kernel configuration), same replay.
+        PW, PK, PB, PF = 1088, 2, 4, 2
+        outs_p = [torch.empty((cfg.Hq, 1, cfg.D), dtype=K.dtype, device=dev) for _ in range(N_DECODE_QUERIES)]
+
+        def step_paper(i, prof=None):
+            q = Qs[i % N_DECODE_QUERIES]
+            an, sc = B.sl_anchor_search_decode(q, K, PK, PW, want_scores=True)
+            B.sl_anchor_attention_decode(q, K, V, an, sc, PW, PB, PF, ws=ws, prof=prof, out=outs_p[i % N_DECODE_QUERIES])
+            return an
+
+        an0 = [step_paper(i).cpu().numpy() for i in range(N_DECODE_QUERIES)]
+        torch.cuda.synchronize()
+        pgraph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(pgraph):
+            for i in range(N_DECODE_QUERIES):
+                step_paper(i)
+        pgraph.replay()
+        torch.cuda.synchronize()
+        tc = time.perf_counter()
+        for _ in range(nrep):
+            pgraph.replay()
+        torch.cuda.synchronize()
+        dt_paper = (time.perf_counter() - tc) / (nrep * N_DECODE_QUERIES)
+        # its K/V streaming kernel and algorithmic bytes: per kv head the union of the heads' token
+        # ranges (span minus window, plus the window once), K and V rows
+        ell = math.isqrt(q_pos) + (0 if math.isqrt(q_pos) ** 2 == q_pos else 1)
+        G = cfg.Hq // cfg.Hkv
+        pbytes = []
+        for an in an0[:N_DECODE_QUERIES // 2]:
+            tokens = 0
+            for kv in range(cfg.Hkv):
+                cover = set()
+                for h in range(kv * G, (kv + 1) * G):
+                    for t in an[h, 0].tolist():
+                        if t >= 0:
+                            cover.add((max(0, t - PB * ell), min(min(q_pos, t + PF * ell), q_pos - PW) + 1))
+                ivs = sorted(cover)
+                end = -1
+                for a0, a1 in ivs:          # union of intervals
+                    a0 = max(a0, end)
+                    if a1 > a0:
+                        tokens += a1 - a0
+                        end = a1
+                tokens += PW
+            pbytes.append(tokens * cfg.D * 2 * 2)
+        evp = [ProfEvents(torch) for _ in range(16)]
+        for i, ev in enumerate(evp):
+            qi = i % (N_DECODE_QUERIES // 2)
+            pgraph.replay()
+            an, sc = B.sl_anchor_search_decode(Qs[qi], K, PK, PW, want_scores=True)
+            B.sl_anchor_attention_decode(Qs[qi], K, V, an, sc, PW, PB, PF, ws=ws, prof=ev.handles(), out=outs_p[qi])
+        torch.cuda.synchronize()
+        pms = sum(ev.ms() for ev in evp) / len(evp)
+        paper_geometry = {"workload": f"anchors i-(s+1)^2+1, window {PW}, top-{PK}, b={PB}, f={PF}, combination gate",
+                          "ms_per_step": dt_paper * 1e3, "value": 1.0 / dt_paper, "unit": "steps/s",
+                          "roofline": {"bound": "hbm", "kernel": "decode_split_kernel", "kernel_ms": pms,
+                                       "algorithmic_bytes": sum(pbytes) / len(pbytes),
+                                       "achieved": sum(pbytes) / len(pbytes) / (pms * 1e-3) / 1e9,
+                                       "peak": PEAK_HBM / 1e9, "unit": "GB/s",
+                                       "frac": sum(pbytes) / len(pbytes) / (pms * 1e-3) / PEAK_HBM}}
+        # Batched decode: NB sequences with caches of their own (copies of the cache, cut to different
+        # lengths, each with a different query) advance one step in three launches.
+        esz = 2 if cfg.dtype == "bf16" else 4
+        NB = 8 if 8 * 2 * cfg.Hkv * cfg.L * cfg.D * esz <= 64e9 else 4
+        lens = [cfg.L - b * (cfg.S + 37) for b in range(NB)]
+        Kc = [K.clone()[:, :lens[b]] for b in range(NB)]
+        Vc = [V.clone()[:, :lens[b]] for b in range(NB)]
+        Ksc = [B.sl_span_keys(Kc[b], cfg.S) for b in range(NB)]
+        nrot = max(1, N_DECODE_QUERIES // NB)
+        batches = [B.DecodeBatch([Qs[(r * NB + b) % N_DECODE_QUERIES] for b in range(NB)],
+                                 [Qs[(r * NB + b) % N_DECODE_QUERIES] for b in range(NB)], Kc, Vc, Ksc,
+                                 cfg.S, cfg.topk) for r in range(nrot)]
+
+        def step_batched(r):
+            B.sl_span_search_decode_batched(batches[r])
+            B.sl_span_attention_decode_batched(batches[r], ws=ws)
+
+        bbytes = 0
         for r in range(nrot):
             step_batched(r)
-    bgraph.replay()
-    torch.cuda.synchronize()
-    tc = time.perf_counter()
-    for _ in range(nrep):
+            torch.cuda.synchronize()
+            ix = batches[r].idx.cpu().numpy()
+            bbytes += sum(decode_bytes(cfg, ix[b], lens[b] - 1) for b in range(NB))
+        bgraph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(bgraph):
+            for r in range(nrot):
+                step_batched(r)
         bgraph.replay()
-    torch.cuda.synchronize()
-    dt_batched = (time.perf_counter() - tc) / (nrep * nrot)
-    batched = {"workload": f"{NB} sequences, caches of {lens[-1]}..{lens[0]} tokens, one query each",
-               "ms_per_step": dt_batched * 1e3, "value": NB / dt_batched, "unit": "sequence-steps/s",
-               "algorithmic_bytes": bbytes / nrot,
-               "step_hbm_frac": bbytes / nrot / dt_batched / PEAK_HBM}
-    # ... and the same batch on the paper's geometry (anchors, gated combination)
-    pbatch = B.DecodeBatch([Qs[b % N_DECODE_QUERIES] for b in range(NB)], [Qs[b % N_DECODE_QUERIES] for b in range(NB)],
-                           Kc, Vc, None, 1, PK, want_scores=True)
+        torch.cuda.synchronize()
+        tc = time.perf_counter()
+        for _ in range(nrep):
+            bgraph.replay()
+        torch.cuda.synchronize()
+        dt_batched = (time.perf_counter() - tc) / (nrep * nrot)
+        batched = {"workload": f"{NB} sequences, caches of {lens[-1]}..{lens[0]} tokens, one query each",
+                   "ms_per_step": dt_batched * 1e3, "value": NB / dt_batched, "unit": "sequence-steps/s",
+                   "algorithmic_bytes": bbytes / nrot,
+                   "step_hbm_frac": bbytes / nrot / dt_batched / PEAK_HBM}
+        # ... and the same batch on the paper's geometry (anchors, gated combination)
+        pbatch = B.DecodeBatch([Qs[b % N_DECODE_QUERIES] for b in range(NB)], [Qs[b % N_DECODE_QUERIES] for b in range(NB)],
+                               Kc, Vc, None, 1, PK, want_scores=True)
 
-    def step_batched_paper():
-        B.sl_anchor_search_decode_batched(pbatch, PW)
-        B.sl_anchor_attention_decode_batched(pbatch, PW, PB, PF, ws=ws)
+        def step_batched_paper():
+            B.sl_anchor_search_decode_batched(pbatch, PW)
+            B.sl_anchor_attention_decode_batched(pbatch, PW, PB, PF, ws=ws)
 
-    step_batched_paper()
-    torch.cuda.synchronize()
-    pbgraph = torch.cuda.CUDAGraph()
-    with torch.cuda.graph(pbgraph):
         step_batched_paper()
-    pbgraph.replay()
-    torch.cuda.synchronize()
-    tc = time.perf_counter()
-    for _ in range(nrep * 2):
+        torch.cuda.synchronize()
+        pbgraph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(pbgraph):
+            step_batched_paper()
         pbgraph.replay()
-    torch.cuda.synchronize()
-    dt_bp = (time.perf_counter() - tc) / (nrep * 2)
-    batched["paper_geometry"] = {"ms_per_step": dt_bp * 1e3, "value": NB / dt_bp, "unit": "sequence-steps/s"}
-    del Kc, Vc, Ksc, batches, bgraph, pbatch, pbgraph
+        torch.cuda.synchronize()
+        tc = time.perf_counter()
+        for _ in range(nrep * 2):
+            pbgraph.replay()
+        torch.cuda.synchronize()
+        dt_bp = (time.perf_counter() - tc) / (nrep * 2)
+        batched["paper_geometry"] = {"ms_per_step": dt_bp * 1e3, "value": NB / dt_bp, "unit": "sequence-steps/s"}
+        del Kc, Vc, Ksc, batches, bgraph, pbatch, pbgraph
     # Dominant kernel (K/V streaming + fused merge): a graph of N_DECODE_QUERIES back-to-back
     # span-attention launches, timed with HIP events on the launch stream.
     idx_dev = [torch.from_numpy(ix).to(dev) for ix in idxs]
@@ -335,7 +367,8 @@ def bench_decode(cfg, steps, warmup, torch, B, W):
         "metric": "decode steps/s (span-search + span-attention)", "value": steps / dt, "unit": "steps/s",
         "ms_per_step": dt / steps * 1e3, "ms_per_step_median": rep_ms[len(rep_ms) // 2], "steps": steps,
         "dtype": cfg.dtype, "launch": "hip-graph replay",
-        "combined_form": {"ms_per_step": dt_combined * 1e3, "value": 1.0 / dt_combined, "unit": "steps/s"},
+        "combined_form": None if dt_combined is None else
+        {"ms_per_step": dt_combined * 1e3, "value": 1.0 / dt_combined, "unit": "steps/s"},
         "paper_geometry": paper_geometry,
         "batched_decode": batched,
         "roofline": {"bound": "hbm", "kernel": "decode_split_kernel", "achieved": achieved / 1e9, "peak": PEAK_HBM / 1e9,
@@ -381,111 +414,113 @@ def bench_prefill(cfg, steps, warmup, torch, B, W):
         e1.synchronize()
         step_ms.append(e0.elapsed_time(e1))
     step_ms.sort()
-    # the combination form (per-span softmaxes gated by the search scores) of the same step
-    def step_combined():
-        B.sl_span_keys(K, cfg.S, out=Ks)
-        idx, sc = B.sl_span_search_prefill(Qs, K, Ks, cfg.S, cfg.topk, want_scores=True, ws=ws)
-        B.sl_span_attention_combined_prefill(Q, K, V, idx, sc, cfg.S, ws=ws, out=out[0])
+    dt_combined, chunked, redundant, paper = None, None, None, None
+    if not MAIN_ONLY:
+        # the combination form (per-span softmaxes gated by the search scores) of the same step
+        def step_combined():
+            B.sl_span_keys(K, cfg.S, out=Ks)
+            idx, sc = B.sl_span_search_prefill(Qs, K, Ks, cfg.S, cfg.topk, want_scores=True, ws=ws)
+            B.sl_span_attention_combined_prefill(Q, K, V, idx, sc, cfg.S, ws=ws, out=out[0])
 
-    step_combined()
-    torch.cuda.synchronize()
-    tc = time.perf_counter()
-    nc = max(1, min(steps, 3))
-    for _ in range(nc):
         step_combined()
-    torch.cuda.synchronize()
-    dt_combined = (time.perf_counter() - tc) / nc
-    # the same prefill in chunks of 32K query rows against the growing cache (Section 5's chunked
-    # prefill): chunk c sees the first (c + 1) * 32K tokens through q_pos0 / Lq
-    chunked = None
-    CH = 32768
-    if cfg.L % CH == 0 and cfg.L > CH:
-        och = (torch.empty((cfg.Hq, CH, cfg.D), dtype=Q.dtype, device=dev),
-               torch.empty((cfg.Hq, CH), dtype=torch.float32, device=dev))
-
-        def step_chunked():
-            for c in range(cfg.L // CH):
-                p0, vis = c * CH, (c + 1) * CH
-                Kc, Vc = K[:, :vis], V[:, :vis]
-                # span keys are read from the cache itself (no gathered copy per chunk)
-                idx = B.sl_span_search_prefill(Qs[:, p0:vis], Kc, None, cfg.S, cfg.topk, q_pos0=p0, ws=ws)
-                B.sl_span_attention_prefill(Q[:, p0:vis], Kc, Vc, idx, cfg.S, q_pos0=p0, ws=ws, out=och)
-
-        step_chunked()
         torch.cuda.synchronize()
-        tch = time.perf_counter()
-        nch = max(1, min(steps, 3))
-        for _ in range(nch):
+        tc = time.perf_counter()
+        nc = max(1, min(steps, 3))
+        for _ in range(nc):
+            step_combined()
+        torch.cuda.synchronize()
+        dt_combined = (time.perf_counter() - tc) / nc
+        # the same prefill in chunks of 32K query rows against the growing cache (Section 5's chunked
+        # prefill): chunk c sees the first (c + 1) * 32K tokens through q_pos0 / Lq
+        chunked = None
+        CH = 32768
+        if cfg.L % CH == 0 and cfg.L > CH:
+            och = (torch.empty((cfg.Hq, CH, cfg.D), dtype=Q.dtype, device=dev),
+                   torch.empty((cfg.Hq, CH), dtype=torch.float32, device=dev))
+
+            def step_chunked():
+                for c in range(cfg.L // CH):
+                    p0, vis = c * CH, (c + 1) * CH
+                    Kc, Vc = K[:, :vis], V[:, :vis]
+                    # span keys are read from the cache itself (no gathered copy per chunk)
+                    idx = B.sl_span_search_prefill(Qs[:, p0:vis], Kc, None, cfg.S, cfg.topk, q_pos0=p0, ws=ws)
+                    B.sl_span_attention_prefill(Q[:, p0:vis], Kc, Vc, idx, cfg.S, q_pos0=p0, ws=ws, out=och)
+
             step_chunked()
-        torch.cuda.synchronize()
-        dt_ch = (time.perf_counter() - tch) / nch
-        chunked = {"chunk_rows": CH, "ms_per_step": dt_ch * 1e3, "value": cfg.L / dt_ch, "unit": "tokens/s"}
-    # the redundant grid (anchors every S/2 tokens, spans S tokens long: twice the candidates, overlapping
-    # spans de-duplicated in the joint softmax) through the same kernels
-    redundant = None
-    if cfg.dtype == "bf16" and cfg.S % 128 == 0:
-        A = cfg.S // 2
-        Ks2 = torch.zeros((cfg.Hkv, -(-cfg.L // A), cfg.D), dtype=K.dtype, device=dev)
+            torch.cuda.synchronize()
+            tch = time.perf_counter()
+            nch = max(1, min(steps, 3))
+            for _ in range(nch):
+                step_chunked()
+            torch.cuda.synchronize()
+            dt_ch = (time.perf_counter() - tch) / nch
+            chunked = {"chunk_rows": CH, "ms_per_step": dt_ch * 1e3, "value": cfg.L / dt_ch, "unit": "tokens/s"}
+        # the redundant grid (anchors every S/2 tokens, spans S tokens long: twice the candidates, overlapping
+        # spans de-duplicated in the joint softmax) through the same kernels
+        redundant = None
+        if cfg.dtype == "bf16" and cfg.S % 128 == 0:
+            A = cfg.S // 2
+            Ks2 = torch.zeros((cfg.Hkv, -(-cfg.L // A), cfg.D), dtype=K.dtype, device=dev)
 
-        def step_redundant():
-            B.sl_span_keys(K, A, out=Ks2)
-            idx = B.sl_span_search_prefill(Qs, K, Ks2, A, cfg.topk, ws=ws)
-            B.sl_span_attention_prefill(Q, K, V, idx, cfg.S, ws=ws, out=out, span_stride=A)
+            def step_redundant():
+                B.sl_span_keys(K, A, out=Ks2)
+                idx = B.sl_span_search_prefill(Qs, K, Ks2, A, cfg.topk, ws=ws)
+                B.sl_span_attention_prefill(Q, K, V, idx, cfg.S, ws=ws, out=out, span_stride=A)
 
-        step_redundant()
-        torch.cuda.synchronize()
-        tr = time.perf_counter()
-        nr = max(1, min(steps, 3))
-        for _ in range(nr):
             step_redundant()
-        torch.cuda.synchronize()
-        dt_r = (time.perf_counter() - tr) / nr
-        redundant = {"anchor_spacing": A, "span_length": cfg.S, "topk": cfg.topk, "ms_per_step": dt_r * 1e3,
-                     "value": cfg.L / dt_r, "unit": "tokens/s"}
-        del Ks2
-    # the paper's own geometry in prefill form over ALL rows (every row has its own anchors, span
-    # length and window) at the paper's kernel configuration: group-shared anchor search, then the
-    # bucketed matrix-core span-attention + banded window + gated merge
-    paper = None
-    if cfg.dtype == "bf16" and cfg.L >= 16384:
-        PW, PK, PB, PF = 1088, 2, 4, 2
-        op = out[0]
-        ev_p = ProfEvents(torch)
+            torch.cuda.synchronize()
+            tr = time.perf_counter()
+            nr = max(1, min(steps, 3))
+            for _ in range(nr):
+                step_redundant()
+            torch.cuda.synchronize()
+            dt_r = (time.perf_counter() - tr) / nr
+            redundant = {"anchor_spacing": A, "span_length": cfg.S, "topk": cfg.topk, "ms_per_step": dt_r * 1e3,
+                         "value": cfg.L / dt_r, "unit": "tokens/s"}
+            del Ks2
+        # the paper's own geometry in prefill form over ALL rows (every row has its own anchors, span
+        # length and window) at the paper's kernel configuration: group-shared anchor search, then the
+        # bucketed matrix-core span-attention + banded window + gated merge
+        paper = None
+        if cfg.dtype == "bf16" and cfg.L >= 16384:
+            PW, PK, PB, PF = 1088, 2, 4, 2
+            op = out[0]
+            ev_p = ProfEvents(torch)
 
-        def step_paper(prof=None):
-            an, sc = B.sl_anchor_search_prefill(Qs, K, PK, PW, want_scores=True)
-            B.sl_anchor_attention_prefill(Q, K, V, an, sc, PW, PB, PF, out=op, ws=ws, prof=prof)
-            return an
+            def step_paper(prof=None):
+                an, sc = B.sl_anchor_search_prefill(Qs, K, PK, PW, want_scores=True)
+                B.sl_anchor_attention_prefill(Q, K, V, an, sc, PW, PB, PF, out=op, ws=ws, prof=prof)
+                return an
 
-        an = step_paper()
-        torch.cuda.synchronize()
-        tp = time.perf_counter()
-        npp = max(1, min(steps, 3))
-        for _ in range(npp):
-            step_paper(ev_p.handles())
-        torch.cuda.synchronize()
-        dt_p = (time.perf_counter() - tp) / npp
-        kp = ev_p.ms()
-        # algorithmic flops of the routed kernel: sum over valid (row, slot) of the span length (span minus window) x 4D
-        i_pos = torch.arange(cfg.L, device=dev, dtype=torch.int64)
-        ell = torch.sqrt(i_pos.double()).ceil().long()
-        ell = torch.where((ell - 1) * (ell - 1) >= i_pos, ell - 1, ell)        # exact ceil(sqrt(i))
-        ell = torch.where(ell * ell < i_pos, ell + 1, ell)
-        wlo = (i_pos - PW + 1).clamp(min=0)
-        keys = 0
-        for h0 in range(0, cfg.Hq, 8):
-            t = an[h0:h0 + 8].long()                                           # [8, L, k]
-            valid = (t >= 0) & (t <= i_pos[None, :, None])
-            lo = (t - PB * ell[None, :, None]).clamp(min=0)
-            hi = torch.minimum(torch.minimum(t + PF * ell[None, :, None], i_pos[None, :, None]), wlo[None, :, None] - 1) + 1
-            keys += int(((hi - lo).clamp(min=0) * valid).sum())
-        f_paper = keys * 4 * cfg.D
-        paper = {"rows": cfg.L, "window": PW, "topk": PK, "backward_factor": PB, "forward_factor": PF,
-                 "ms_per_step": dt_p * 1e3, "value": cfg.L / dt_p, "unit": "tokens/s",
-                 "roofline": {"bound": "mfma", "kernel": "span_flash_anchor_kernel", "kernel_ms": kp,
-                              "algorithmic_flops": f_paper, "achieved": f_paper / (kp * 1e-3) / 1e12,
-                              "peak": PEAK_BF16 / 1e12, "unit": "TFLOP/s", "frac": f_paper / (kp * 1e-3) / PEAK_BF16}}
-        del an
+            an = step_paper()
+            torch.cuda.synchronize()
+            tp = time.perf_counter()
+            npp = max(1, min(steps, 3))
+            for _ in range(npp):
+                step_paper(ev_p.handles())
+            torch.cuda.synchronize()
+            dt_p = (time.perf_counter() - tp) / npp
+            kp = ev_p.ms()
+            # algorithmic flops of the routed kernel: sum over valid (row, slot) of the span length (span minus window) x 4D
+            i_pos = torch.arange(cfg.L, device=dev, dtype=torch.int64)
+            ell = torch.sqrt(i_pos.double()).ceil().long()
+            ell = torch.where((ell - 1) * (ell - 1) >= i_pos, ell - 1, ell)        # exact ceil(sqrt(i))
+            ell = torch.where(ell * ell < i_pos, ell + 1, ell)
+            wlo = (i_pos - PW + 1).clamp(min=0)
+            keys = 0
+            for h0 in range(0, cfg.Hq, 8):
+                t = an[h0:h0 + 8].long()                                           # [8, L, k]
+                valid = (t >= 0) & (t <= i_pos[None, :, None])
+                lo = (t - PB * ell[None, :, None]).clamp(min=0)
+                hi = torch.minimum(torch.minimum(t + PF * ell[None, :, None], i_pos[None, :, None]), wlo[None, :, None] - 1) + 1
+                keys += int(((hi - lo).clamp(min=0) * valid).sum())
+            f_paper = keys * 4 * cfg.D
+            paper = {"rows": cfg.L, "window": PW, "topk": PK, "backward_factor": PB, "forward_factor": PF,
+                     "ms_per_step": dt_p * 1e3, "value": cfg.L / dt_p, "unit": "tokens/s",
+                     "roofline": {"bound": "mfma", "kernel": "span_flash_anchor_kernel", "kernel_ms": kp,
+                                  "algorithmic_flops": f_paper, "achieved": f_paper / (kp * 1e-3) / 1e12,
+                                  "peak": PEAK_BF16 / 1e12, "unit": "TFLOP/s", "frac": f_paper / (kp * 1e-3) / PEAK_BF16}}
+            del an
     f_search, f_routed, f_local = prefill_flops(cfg)
     f_attn = f_routed + f_local
     ka = sum(ms_a) / len(ms_a)
@@ -502,7 +537,8 @@ def bench_prefill(cfg, steps, warmup, torch, B, W):
         "ms_per_step": dt / steps * 1e3, "ms_per_step_median": step_ms[len(step_ms) // 2], "steps": steps,
         "dtype": cfg.dtype,
         "step_frac_of_peak": (f_search + f_attn) / (dt / steps) / peak,
-        "combined_form": {"ms_per_step": dt_combined * 1e3, "value": cfg.L / dt_combined, "unit": "tokens/s"},
+        "combined_form": None if dt_combined is None else
+        {"ms_per_step": dt_combined * 1e3, "value": cfg.L / dt_combined, "unit": "tokens/s"},
         "chunked_prefill": chunked,
         "redundant_spans": redundant,
         "paper_geometry_prefill": paper,
@@ -598,10 +634,15 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--configs", default="C3,C5,C4,C2,C1")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--main-only", action="store_true",
+                    help="skip the variants timed beside each configuration (gated form, chunked prefill, redundant "
+                         "grid, the paper's geometry, batched decode): a profiler trace then holds one workload")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="first run a plain elementwise copy of known size (reads 1 GiB, writes 1 GiB) three "
                          "times, so that rocprofv3 FETCH_SIZE / WRITE_SIZE readings can be scaled")
     args = ap.parse_args()
+    global MAIN_ONLY
+    MAIN_ONLY = args.main_only
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1",
               file=sys.stderr)
@@ -649,13 +690,7 @@ def main():
         torch.cuda.empty_cache()
 
     cfg, res = primary
-    prop = torch.cuda.get_device_properties(0)
-    cus, mhz = prop.multi_processor_count, getattr(prop, "clock_rate", 0) / 1e3
-    device = {"name": prop.name, "compute_units": cus, "max_clock_mhz": mhz,
-              # 4 SIMDs x 1024 flop/clk (a 32x32x16 bf16 MFMA = 32768 flop in 32 cycles) per compute unit
-              "derived_bf16_mfma_peak_tflops": cus * 4096 * mhz * 1e6 / 1e12,
-              "peaks_used": {"hbm_GBps": PEAK_HBM / 1e9, "bf16_mfma_tflops": PEAK_BF16 / 1e12,
-                             "fp32_valu_tflops": PEAK_FP32_VALU / 1e12}}
+    device = device_facts(torch)
     line = {
         "metric": "span-attn decode steps/s at L=1M" if cfg.name == "C3" else res["metric"],
         "value": res["value"], "unit": res["unit"], "n_gpus": 1, "steps": res["steps"], "warmup": args.warmup,
