@@ -61,8 +61,11 @@ def device_facts(torch):
         out = subprocess.run(["rocminfo"], capture_output=True, text=True, timeout=30).stdout
         for agent in out.split("*******")[1:]:
             if re.search(r"Device Type:\s+GPU", agent):
-                m = re.search(r"Marketing Name:\s+(.*)", agent)
+                m = re.search(r"Marketing Name:[ \t]*(.*)", agent)
                 name = m.group(1).strip() if m else ""
+                if not name:                      # some boxes leave the marketing name empty
+                    m = re.search(r"^\s*Name:[ \t]*(gfx\w+)", agent, re.M)
+                    name = m.group(1) if m else ""
                 m = re.search(r"Compute Unit:\s+(\d+)", agent)
                 cus = int(m.group(1)) if m else 0
                 m = re.search(r"Max Clock Freq\. \(MHz\):\s+(\d+)", agent)
