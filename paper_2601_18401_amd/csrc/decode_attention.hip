@@ -30,7 +30,7 @@ __device__ __forceinline__ void decode_split_body(
     const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
     const int32_t* __restrict__ idx, float* __restrict__ part, int64_t q_pos, int Hq, int Hkv,
     int S, int A, bool clip, int topk, int nchunks, int CT, float scale_log2e, int64_t qsh, int64_t kvsh,
-    int64_t kvst, int n_routed_blocks, int local_stride, const AnchorRanges ar) {
+    int64_t kvst, int n_routed_blocks, int local_stride, bool share_window, const AnchorRanges ar) {
   // Grid: anchors every A tokens, span j = the S tokens ending at (j+1)*A - 1 (A = S: disjoint spans).
   // clip (joint softmax with A < S): spans of one head overlap, and a token must count once, so an
   // entry's range starts behind the end of the nearest lower span that the same head lists.
@@ -112,18 +112,28 @@ __device__ __forceinline__ void decode_split_body(
 
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
+  // each wave takes a contiguous quarter of the chunk; one batch of loads covers it when it is
+  // at most RPW * U rows long
+  const int per_wave = CT / (kDecodeThreads / 64);
+  const bool one_batch = U <= 8 && per_wave <= RPW * U;  // (wide batches go with chunks of several batches)
 
-  // Spans (grid indices, or anchor tokens) that several heads of a kv head select are read once:
-  // the entry (head, slot) that comes first in the group's index rows owns the chunk and computes
-  // the partial of every other entry that lists the same span from the rows it has just pulled
-  // through the L2; the workgroups of those entries leave at once.  Needs the group's G * topk
-  // indices in one pass of a wavefront (larger groups: every entry reads its own span).
+  // Rows that several heads of a kv head attend are read once.  (1) A span (grid index, or anchor
+  // token) that several heads select: the entry (head, slot) that comes first in the group's index
+  // rows owns the chunk and computes the partial of every other entry that lists the same span;
+  // the workgroups of those entries leave at once.  Needs the group's G * topk indices in one pass
+  // of a wavefront (larger groups: every entry reads its own span).  (2) share_window: the local
+  // window, which all G heads attend: the first head's workgroup serves the group.  When the
+  // wave's rows fit one batch they stay in registers and every entry is computed from them;
+  // otherwise (and for clipped overlapping spans, whose range differs per entry) the owner reads
+  // the rows again per entry, through the L2.
   constexpr int kShareWords = 4;  // up to 256 (head, slot) entries per kv head
   const bool dedup = slot < topk && G * topk <= 64 * kShareWords && G > 1;
+  const bool window_group = slot == topk && share_window && one_batch && G > 1 && G <= 64;
   const int64_t jlimit = ar.on ? q_pos + 1 : c;  // valid entries: anchor tokens <= q_pos, resp. spans < c
   unsigned long long share[kShareWords] = {0ull, 0ull, 0ull, 0ull};
-  const int my_entry = (h - kv * G) * topk + slot;
-  bool shared_span = false;
+  // entry numbers: (head in group) * topk + slot for a span, head in group for the window
+  const int my_entry = window_group ? h - kv * G : (h - kv * G) * topk + slot;
+  bool multi = false;
   if (dedup) {
     // every wavefront builds the masks by itself (no LDS, no barrier): lane l looks at entries
     // l, l + 64, ... of the group's index rows, which are contiguous
@@ -140,99 +150,161 @@ __device__ __forceinline__ void decode_split_body(
     }
     if (count > 1) {
       if (first != my_entry) return;  // the owner writes this entry's record
-      shared_span = true;
+      multi = true;
     }
+  } else if (window_group) {
+    if (my_entry != 0) return;
+    share[0] = G == 64 ? ~0ull : (1ull << G) - 1ull;
+    multi = true;
   }
+  const bool per_entry_range = multi && !window_group && clip && !ar.on;
+  const bool from_regs = multi && one_batch && !per_entry_range;
 
-  // Entries served by this workgroup: its own, then (owner of a shared span) the others.
-  int entry = my_entry;
-  while (true) {
-    const int he = shared_span ? kv * G + entry / topk : h;
-    const int se = shared_span ? entry % topk : slot;
-    if (shared_span && clip && !ar.on) grid_chunk(he, idx[(int64_t)he * topk + se], t0, t1);  // the entry's own clip
-    float* prec = part + (((int64_t)he * (topk + 1) + se) * nchunks + ck) * (D + 2);
-    if (t0 >= t1) {  // empty slot or chunk past the end of the range (uniform over the workgroup)
-      if (tid < D) prec[tid] = 0.f;
+  const int g = lane / LPR, lr = lane % LPR;
+  const T* Kb = K + (int64_t)kv * kvsh;
+  const T* Vb = V + (int64_t)kv * kvsh;
+  const int gi = wave * RPW + g;
+
+  // Merges the workgroup's NG row-group states through the LDS and writes the record.
+  auto merge_and_write = [&](const AttendState<T, D>& st, float* prec) {
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) s_o[gi][lr * EPL + e] = st.o[e];
+    if (lr == 0) {
+      s_m[gi] = st.m;
+      s_l[gi] = st.l;
+    }
+    __syncthreads();
+    if (tid < D) {
+      float M = -INFINITY;
+#pragma unroll
+      for (int i = 0; i < NG; ++i) M = fmaxf(M, s_m[i]);
+      float acc = 0.f, lt = 0.f;
+#pragma unroll
+      for (int i = 0; i < NG; ++i) {
+        const float mi = s_m[i];
+        if (mi > -INFINITY) {
+          const float w = fast_exp2(mi - M);
+          acc = fmaf(w, s_o[i][tid], acc);
+          lt = fmaf(w, s_l[i], lt);
+        }
+      }
+      prec[tid] = acc;
       if (tid == 0) {
-        prec[D] = -INFINITY;
-        prec[D + 1] = 0.f;
-      }
-    } else {
-      const int g = lane / LPR, lr = lane % LPR;
-      float q2[EPL];
-      {
-        float qf[EPL];
-        Elem<T>::unpack(load16(Q + (int64_t)he * qsh + lr * EPL), qf);
-#pragma unroll
-        for (int e = 0; e < EPL; ++e) q2[e] = qf[e] * scale_log2e;
-      }
-      const T* Kb = K + (int64_t)kv * kvsh;
-      const T* Vb = V + (int64_t)kv * kvsh;
-
-      // each wave takes a contiguous quarter of the chunk
-      const int per_wave = CT / (kDecodeThreads / 64);
-      int64_t w0 = t0 + (int64_t)wave * per_wave;
-      int64_t w1 = w0 + per_wave < t1 ? w0 + per_wave : t1;
-      AttendState<T, D> st;
-      st.init();
-      // A span that one entry reads is streamed past the caches; the window (read by all G heads
-      // of its kv head) and a shared span (read again right away) stay cacheable.
-      if (slot != topk && !shared_span)
-        attend_range<T, D, U, true>(q2, Kb, Vb, kvst, w0, w1, lane, st);
-      else
-        attend_range<T, D, U, false>(q2, Kb, Vb, kvst, w0, w1, lane, st);
-
-      const int gi = wave * RPW + g;
-#pragma unroll
-      for (int e = 0; e < EPL; ++e) s_o[gi][lr * EPL + e] = st.o[e];
-      if (lr == 0) {
-        s_m[gi] = st.m;
-        s_l[gi] = st.l;
-      }
-      __syncthreads();
-      if (tid < D) {
-        float M = -INFINITY;
-#pragma unroll
-        for (int i = 0; i < NG; ++i) M = fmaxf(M, s_m[i]);
-        float acc = 0.f, lt = 0.f;
-#pragma unroll
-        for (int i = 0; i < NG; ++i) {
-          const float mi = s_m[i];
-          if (mi > -INFINITY) {
-            const float w = fast_exp2(mi - M);
-            acc = fmaf(w, s_o[i][tid], acc);
-            lt = fmaf(w, s_l[i], lt);
-          }
-        }
-        prec[tid] = acc;
-        if (tid == 0) {
-          prec[D] = M;
-          prec[D + 1] = lt;
-        }
+        prec[D] = M;
+        prec[D + 1] = lt;
       }
     }
-    if (!shared_span) break;
-    // next entry that lists the span (all threads hold the same masks)
+  };
+  auto write_empty = [&](float* prec) {
+    if (tid < D) prec[tid] = 0.f;
+    if (tid == 0) {
+      prec[D] = -INFINITY;
+      prec[D + 1] = 0.f;
+    }
+  };
+  auto scaled_query = [&](const uint4& raw, float (&q2)[EPL]) {
+    float qf[EPL];
+    Elem<T>::unpack(raw, qf);
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) q2[e] = qf[e] * scale_log2e;
+  };
+  // entry -> (head, slot) of the record
+  auto entry_head = [&](int e) { return window_group ? kv * G + e : kv * G + e / topk; };
+  auto entry_slot = [&](int e) { return window_group ? topk : e % topk; };
+  // takes `entry` out of the masks and returns the next entry that attends the same rows, or -1
+  // (all threads hold the same masks)
+  auto next_entry = [&](int entry) {
     int next = -1;
 #pragma unroll
     for (int w = kShareWords - 1; w >= 0; --w) {
       if (w == (entry >> 6)) share[w] &= ~(1ull << (entry & 63));
       if (share[w]) next = 64 * w + __builtin_ctzll(share[w]);
     }
+    return next;
+  };
+  const int64_t w0 = t0 + (int64_t)wave * per_wave;
+  const int64_t w1 = w0 + per_wave < t1 ? w0 + per_wave : t1;
+
+  if (U <= 8 && from_regs) {
+    // several entries, one range, one batch: the rows are loaded once and stay in registers
+    if (t0 >= t1) {
+      for (int entry = my_entry; entry >= 0; entry = next_entry(entry))
+        write_empty(part + (((int64_t)entry_head(entry) * (topk + 1) + entry_slot(entry)) * nchunks + ck) * (D + 2));
+      return;
+    }
+    uint4 kr[U], vr[U];
+    uint4 qraw = load16(Q + (int64_t)h * qsh + lr * EPL);
+    load_rows<T, D, U, true>(Kb, Vb, kvst, w0, w1, lane, kr, vr);
+    int entry = my_entry;
+    while (true) {
+      const int next = next_entry(entry);
+      uint4 qnext = qraw;  // the next entry's query is fetched while this one is computed
+      if (next >= 0) qnext = load16(Q + (int64_t)entry_head(next) * qsh + lr * EPL);
+      float q2[EPL];
+      scaled_query(qraw, q2);
+      AttendState<T, D> st;
+      st.init();
+      // (the rows stay packed between entries: without this the compiler unpacks all of them to
+      // fp32 ahead of the loop, which takes twice the registers)
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        asm volatile("" : "+v"(kr[u].x), "+v"(kr[u].y), "+v"(kr[u].z), "+v"(kr[u].w));
+        asm volatile("" : "+v"(vr[u].x), "+v"(vr[u].y), "+v"(vr[u].z), "+v"(vr[u].w));
+      }
+      attend_loaded<T, D, U>(q2, kr, vr, w0, w1, lane, st);
+      merge_and_write(st, part + (((int64_t)entry_head(entry) * (topk + 1) + entry_slot(entry)) * nchunks + ck) * (D + 2));
+      if (next < 0) break;
+      entry = next;
+      qraw = qnext;
+      __syncthreads();  // the merge above has read s_o / s_m / s_l
+    }
+    return;
+  }
+
+  // One entry, or several whose rows are read again per entry (through the L2).
+  int entry = my_entry;
+  while (true) {
+    const int he = multi ? entry_head(entry) : h;
+    const int se = multi ? entry_slot(entry) : slot;
+    if (per_entry_range) grid_chunk(he, idx[(int64_t)he * topk + se], t0, t1);  // the entry's own clip
+    float* prec = part + (((int64_t)he * (topk + 1) + se) * nchunks + ck) * (D + 2);
+    if (t0 >= t1) {  // empty slot or chunk past the end of the range (uniform over the workgroup)
+      write_empty(prec);
+    } else {
+      float q2[EPL];
+      scaled_query(load16(Q + (int64_t)he * qsh + lr * EPL), q2);
+      const int64_t v0 = t0 + (int64_t)wave * per_wave;
+      const int64_t v1 = v0 + per_wave < t1 ? v0 + per_wave : t1;
+      AttendState<T, D> st;
+      st.init();
+      // A span that one entry reads is streamed past the caches; the window (read by all G heads
+      // of its kv head) and a shared span (read again right away) stay cacheable.
+      if (slot != topk && !multi)
+        attend_range<T, D, U, true>(q2, Kb, Vb, kvst, v0, v1, lane, st);
+      else
+        attend_range<T, D, U, false>(q2, Kb, Vb, kvst, v0, v1, lane, st);
+      merge_and_write(st, prec);
+    }
+    if (!multi) break;
+    const int next = next_entry(entry);
     if (next < 0) break;
     entry = next;
     __syncthreads();  // the merge above has read s_o / s_m / s_l
   }
 }
 
+// Registers: the narrow-batch kernels are held to four wavefronts per SIMD (128 registers), which
+// they need without the multi-entry loop; left alone, the compiler keeps the loop's unpacked rows
+// in registers and halves the occupancy of every workgroup for the sake of a few.
 template <typename T, int D, int U>
-__global__ __launch_bounds__(kDecodeThreads) void decode_split_kernel(
+__global__ __launch_bounds__(kDecodeThreads) __attribute__((amdgpu_waves_per_eu(U <= 8 ? 4 : 2)))
+void decode_split_kernel(
     const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
     const int32_t* __restrict__ idx, float* __restrict__ part, int64_t q_pos, int Hq, int Hkv,
     int S, int A, bool clip, int topk, int nchunks, int CT, float scale_log2e, int64_t qsh, int64_t kvsh,
-    int64_t kvst, int n_routed_blocks, int local_stride, const AnchorRanges ar) {
+    int64_t kvst, int n_routed_blocks, int local_stride, bool share_window, const AnchorRanges ar) {
   decode_split_body<T, D, U>(Q, K, V, idx, part, q_pos, Hq, Hkv, S, A, clip, topk, nchunks, CT, scale_log2e,
-                          qsh, kvsh, kvst, n_routed_blocks, local_stride, ar);
+                          qsh, kvsh, kvst, n_routed_blocks, local_stride, share_window, ar);
 }
 
 // Batched decode: blockIdx.y is the sequence; its tensors and length come from the device array.
@@ -246,10 +318,12 @@ struct AnchorBatch {
 };
 
 template <typename T, int D, int U>
-__global__ __launch_bounds__(kDecodeThreads) void decode_split_batched_kernel(
+__global__ __launch_bounds__(kDecodeThreads) __attribute__((amdgpu_waves_per_eu(U <= 8 ? 4 : 2)))
+void decode_split_batched_kernel(
     const sl_decode_seq* __restrict__ seqs, float* __restrict__ part, int64_t part_stride, int Hq,
     int Hkv, int S, int A, bool clip, int topk, int nchunks, int CT, float scale_log2e, int64_t qsh,
-    int64_t kvsh, int64_t kvst, int n_routed_blocks, int local_stride, const AnchorBatch ab) {
+    int64_t kvsh, int64_t kvst, int n_routed_blocks, int local_stride, bool share_window,
+    const AnchorBatch ab) {
   const sl_decode_seq sq = seqs[blockIdx.y];
   const int64_t i = sq.L - 1;
   AnchorRanges ar{false, 0, 0, 0};
@@ -263,7 +337,7 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_split_batched_kernel(
   decode_split_body<T, D, U>(static_cast<const T*>(sq.Q), static_cast<const T*>(sq.K),
                           static_cast<const T*>(sq.V), sq.idx, part + blockIdx.y * part_stride, i, Hq,
                           Hkv, S, A, clip, topk, nchunks, CT, scale_log2e, qsh, kvsh ? kvsh : sq.L * kvst,
-                          kvst, n_routed_blocks, local_stride, ar);
+                          kvst, n_routed_blocks, local_stride, share_window, ar);
 }
 
 // Merges the (topk + 1) * nchunks partial records of a head.  grid (Hq, D / 32): each workgroup
@@ -515,12 +589,20 @@ __global__ __launch_bounds__(256) void decode_reduce_combined_batched_kernel(
 // wavefront per SIMD.
 inline bool wide_batches(int CT) { return CT >= 512; }
 
+// One workgroup serving the window of all G heads of a kv head computes them one after the other,
+// about a microsecond per head; that pays (fewer workgroups, the rows pulled once) only while the
+// rest of the grid runs much longer: from 128 MB of routed K/V rows, about 20 us of streaming.
+inline bool window_by_one_workgroup(int64_t routed_items, int CT, int D, size_t elem_bytes) {
+  return routed_items * CT * 2 * D * (int64_t)elem_bytes >= ((int64_t)128 << 20);
+}
+
 template <typename T, int D, int U>
 void launch_split_u(int grid, hipStream_t st, hipEvent_t e0, hipEvent_t e1, const void* Q, const void* K,
                     const void* V, const int32_t* idx, float* part, const Problem& pb, int S, int nchunks,
                     int CT, int n_routed, int local_stride, const AnchorRanges& ar) {
   const float scale_log2e = pb.scale * kLog2e;
   const bool clip = !ar.on && pb.A < pb.S && !pb.combined;  // overlapping spans in one joint softmax
+  const bool share_window = window_by_one_workgroup(n_routed, CT, D, sizeof(T));
   if (e0) {
     // With profiling events the launch itself carries them: they then hold the kernel's own
     // begin and end timestamps (events recorded on the stream before / after a 45 us kernel would
@@ -529,12 +611,12 @@ void launch_split_u(int grid, hipStream_t st, hipEvent_t e0, hipEvent_t e1, cons
                           0, static_cast<const T*>(Q), static_cast<const T*>(K),
                           static_cast<const T*>(V), idx, part, pb.q_pos0, pb.Hq, pb.Hkv, S, ar.on ? S : pb.A,
                           clip, pb.topk, nchunks, CT, scale_log2e, pb.qsh, pb.kvsh, pb.kvst, n_routed,
-                          local_stride, ar);
+                          local_stride, share_window, ar);
   } else {
     hipLaunchKernelGGL((decode_split_kernel<T, D, U>), dim3(grid), dim3(kDecodeThreads), 0, st,
                        static_cast<const T*>(Q), static_cast<const T*>(K), static_cast<const T*>(V), idx,
                        part, pb.q_pos0, pb.Hq, pb.Hkv, S, ar.on ? S : pb.A, clip, pb.topk, nchunks, CT,
-                       scale_log2e, pb.qsh, pb.kvsh, pb.kvst, n_routed, local_stride, ar);
+                       scale_log2e, pb.qsh, pb.kvsh, pb.kvst, n_routed, local_stride, share_window, ar);
   }
 }
 
@@ -558,14 +640,15 @@ void launch_split_batched(int grid, int B, hipStream_t st, const sl_decode_seq* 
   const int64_t kvsh = pb.kvsh_given ? pb.kvsh : (int64_t)0;
   const int A = ab.on ? S : pb.A;
   const bool clip = !ab.on && pb.A < pb.S && !pb.combined;
+  const bool share_window = window_by_one_workgroup((int64_t)n_routed * B, CT, D, sizeof(T));
   if (wide_batches(CT))
     hipLaunchKernelGGL((decode_split_batched_kernel<T, D, 16>), dim3(grid, B), dim3(kDecodeThreads), 0, st,
                        seqs, part, part_stride, pb.Hq, pb.Hkv, S, A, clip, pb.topk, nchunks, CT, scale_log2e,
-                       pb.qsh, kvsh, pb.kvst, n_routed, local_stride, ab);
+                       pb.qsh, kvsh, pb.kvst, n_routed, local_stride, share_window, ab);
   else
     hipLaunchKernelGGL((decode_split_batched_kernel<T, D, 8>), dim3(grid, B), dim3(kDecodeThreads), 0, st,
                        seqs, part, part_stride, pb.Hq, pb.Hkv, S, A, clip, pb.topk, nchunks, CT, scale_log2e,
-                       pb.qsh, kvsh, pb.kvst, n_routed, local_stride, ab);
+                       pb.qsh, kvsh, pb.kvst, n_routed, local_stride, share_window, ab);
 }
 
 // The reductions keep one weight (joint form) or two statistics (gated form) per partial record of

@@ -449,6 +449,41 @@ def test_decode_heads_of_a_group_sharing_spans(dtype, Hq, Hkv, D, S, k):
     check_attention(O, LSE, Q, K, V, idx_same, S, L - 1, 0.0)
 
 
+@pytest.mark.parametrize("dtype,Hq,Hkv", [(torch.bfloat16, 32, 4), (torch.float32, 16, 2)])
+def test_decode_rows_read_once_for_the_heads_of_a_group(dtype, Hq, Hkv):
+    """Steps whose routed rows exceed 128 MB serve the local window of all G heads from one workgroup,
+    and shared spans from registers; both the joint and the gated form, single and batched entry."""
+    D, S, k = 128, 1024, 16
+    L = S * 20 + 701                                  # ragged window: 5 full chunks and a partial one
+    G = Hq // Hkv
+    Q, K, V = make(91, Hq, Hkv, L, D, dtype, Lq=1)
+    idx, sc = B.sl_span_search_decode(Q, K, None, S, k, want_scores=True)
+    O, LSE = B.sl_span_attention_decode(Q, K, V, idx, S)
+    Oc = B.sl_span_attention_combined_decode(Q, K, V, idx, sc, S)
+    torch.cuda.synchronize()
+    check_attention(O, LSE, Q, K, V, idx, S, L - 1, 0.0)
+    check_combined(Oc, Q, K, V, idx, sc, S, L - 1, 0.0)
+    # every head of a group on its first head's spans, one slot emptied
+    same = idx[::G].repeat_interleave(G, dim=0).clone()
+    same[1::2, 0, 3] = -1
+    same = torch.sort(torch.where(same < 0, torch.full_like(same, 1 << 20), same), dim=2).values
+    same = torch.where(same == 1 << 20, torch.full_like(same, -1), same).contiguous()
+    O, LSE = B.sl_span_attention_decode(Q, K, V, same, S)
+    torch.cuda.synchronize()
+    check_attention(O, LSE, Q, K, V, same, S, L - 1, 0.0)
+    # the batched entry points with one sequence take the same path
+    batch = B.DecodeBatch([Q], [Q], [K], [V], None, S, k, want_scores=True)
+    bidx, bsc = B.sl_span_search_decode_batched(batch)
+    Ob, LSEb = B.sl_span_attention_decode_batched(batch)
+    torch.cuda.synchronize()
+    assert torch.equal(bidx[0], idx)
+    check_attention(Ob[0], LSEb[0], Q, K, V, idx, S, L - 1, 0.0)
+    bsc.copy_(torch.where(torch.isfinite(bsc), bsc, torch.zeros_like(bsc)))
+    Obc = B.sl_span_attention_combined_decode_batched(batch)
+    torch.cuda.synchronize()
+    check_combined(Obc[0], Q, K, V, idx, bsc[0], S, L - 1, 0.0)
+
+
 def test_decode_mid_cache_position_and_garbage_idx():
     Hq, Hkv, L, D, S, k = 8, 2, 16384, 128, 128, 8
     Q, K, V = make(21, Hq, Hkv, L, D, torch.bfloat16, Lq=1)
