@@ -51,12 +51,25 @@ __device__ __forceinline__ void decode_split_body(
   // reader, and at the end of the grid they would leave the HBM idle while the last of them run.
   const int n_local_blocks = (int)gridDim.x - n_routed_blocks;
   int bid = (int)blockIdx.x - n_local_blocks;
-  if (bid >= 0) {
+  if (ar.on) {
+    // the paper's geometry: the window is slot topk of every head, Hq * nchunks items, again at
+    // the front of the grid (a window item that serves its whole group runs the longest)
+    const int b = (int)blockIdx.x, nwin = Hq * nchunks;
+    if (b < nwin) {
+      h = b / nchunks;
+      ck = b % nchunks;
+      slot = topk;
+    } else {
+      ck = (b - nwin) % nchunks;
+      const int u = (b - nwin) / nchunks;
+      h = u / topk;
+      slot = u % topk;
+    }
+  } else if (bid >= 0) {
     ck = bid % nchunks;
     const int u = bid / nchunks;
-    const int ns = ar.on ? topk + 1 : topk;  // on the paper's geometry the window is slot topk of every head
-    h = u / ns;
-    slot = u % ns;
+    h = u / topk;
+    slot = u % topk;
   } else {
     // The G heads of one kv head read the same rows; their block ids differ by a multiple of 8
     // so that they run on the same XCD and share its L2.
