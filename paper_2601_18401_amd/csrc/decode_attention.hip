@@ -25,7 +25,8 @@ struct AnchorRanges {
 
 // Partial record of one (head, slot, chunk): o[D] (unnormalised, relative to m), m (log2 units), l.
 // U: 16-byte K loads (and as many V loads) in flight per lane.
-template <typename T, int D, int U>
+// AG: the paper's geometry (ar describes it) instead of the span grid.
+template <typename T, int D, int U, bool AG>
 __device__ __forceinline__ void decode_split_body(
     const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
     const int32_t* __restrict__ idx, float* __restrict__ part, int64_t q_pos, int Hq, int Hkv,
@@ -34,7 +35,7 @@ __device__ __forceinline__ void decode_split_body(
   // Grid: anchors every A tokens, span j = the S tokens ending at (j+1)*A - 1 (A = S: disjoint spans).
   // clip (joint softmax with A < S): spans of one head overlap, and a token must count once, so an
   // entry's range starts behind the end of the nearest lower span that the same head lists.
-  // ar.on: the paper's geometry (Section 3.3, Algorithm 1) instead of the grid: idx holds anchor
+  // AG: the paper's geometry (Section 3.3, Algorithm 1) instead of the grid: idx holds anchor
   // tokens, slot s of head h attends S_t minus W for t = idx[h][s] (W is a suffix of [0, q_pos], so
   // the set difference is a clip; DedupConcat(S_t, W) is then the slot's range plus the window's),
   // S_t = [max(0, t - back), min(q_pos, t + fwd)], and slot topk of every head is W = [wlo, q_pos].
@@ -51,7 +52,7 @@ __device__ __forceinline__ void decode_split_body(
   // reader, and at the end of the grid they would leave the HBM idle while the last of them run.
   const int n_local_blocks = (int)gridDim.x - n_routed_blocks;
   int bid = (int)blockIdx.x - n_local_blocks;
-  if (ar.on) {
+  if (AG) {
     // the paper's geometry: the window is slot topk of every head, Hq * nchunks items, again at
     // the front of the grid (a window item that serves its whole group runs the longest)
     const int b = (int)blockIdx.x, nwin = Hq * nchunks;
@@ -99,28 +100,42 @@ __device__ __forceinline__ void decode_split_body(
     t1 = t0 + CT < end ? t0 + CT : end;
     if (t1 < t0) t1 = t0;
   };
-  int64_t t0, t1;
-  if (ar.on) {
-    int64_t r0 = 0, r1 = 0;
+  // The paper's geometry: tokens [r0, r1) that the anchor token t contributes (S_t minus the window).
+  auto anchor_range = [&](int64_t t, int64_t& r0, int64_t& r1) {
+    r0 = r1 = 0;
+    if (t < 0 || t > q_pos) return;
+    r0 = t - ar.back > 0 ? t - ar.back : 0;
+    const int64_t e = t + ar.fwd < q_pos ? t + ar.fwd : q_pos;
+    r1 = (e < ar.wlo - 1 ? e : ar.wlo - 1) + 1;
+    if (r1 < r0) r1 = r0;
+  };
+  // [t0, t1): the tokens of this item.  cb: where the item's CT-token chunk starts (the wavefronts
+  // split the chunk from there).  On the grid a chunk starts at a multiple of CT behind the span's
+  // first token; on the paper's geometry, where spans of different heads overlap at any offset,
+  // chunks sit on the absolute CT-token lattice (chunk number a), so that overlapping spans are cut
+  // into the same pieces and a piece can be read once for all of them; a range then touches at
+  // most ceil(length / CT) + 1 chunks, which is what nchunks counts in that mode.
+  int64_t t0, t1, cb, a_chunk = 0;
+  if (AG) {
+    int64_t r0, r1;
     if (slot == topk) {
       r0 = ar.wlo;
       r1 = q_pos + 1;
     } else {
-      const int64_t t = idx[(int64_t)h * topk + slot];
-      if (t >= 0 && t <= q_pos) {
-        r0 = t - ar.back > 0 ? t - ar.back : 0;
-        const int64_t e = t + ar.fwd < q_pos ? t + ar.fwd : q_pos;
-        r1 = (e < ar.wlo - 1 ? e : ar.wlo - 1) + 1;
-        if (r1 < r0) r1 = r0;
-      }
+      anchor_range(idx[(int64_t)h * topk + slot], r0, r1);
     }
-    t0 = r0 + (int64_t)ck * CT;
-    t1 = t0 + CT < r1 ? t0 + CT : r1;
+    a_chunk = r0 / CT + ck;
+    cb = a_chunk * CT;
+    t0 = r0 > cb ? r0 : cb;
+    t1 = r1 < cb + CT ? r1 : cb + CT;
+    if (t1 < t0) t1 = t0;
   } else if (slot < topk) {
     grid_chunk(h, idx[(int64_t)h * topk + slot], t0, t1);
+    cb = t0;
   } else {
     t0 = c * A + (int64_t)ck * CT;
     t1 = t0 + CT < q_pos + 1 ? t0 + CT : q_pos + 1;
+    cb = t0;
   }
 
   const int tid = threadIdx.x;
@@ -130,24 +145,24 @@ __device__ __forceinline__ void decode_split_body(
   const int per_wave = CT / (kDecodeThreads / 64);
   const bool one_batch = U <= 8 && per_wave <= RPW * U;  // (wide batches go with chunks of several batches)
 
-  // Rows that several heads of a kv head attend are read once.  (1) A span (grid index, or anchor
-  // token) that several heads select: the entry (head, slot) that comes first in the group's index
-  // rows owns the chunk and computes the partial of every other entry that lists the same span;
-  // the workgroups of those entries leave at once.  Needs the group's G * topk indices in one pass
-  // of a wavefront (larger groups: every entry reads its own span).  (2) share_window: the local
+  // Rows that several heads of a kv head attend are read once.  (1) Grid: a span that several
+  // heads select; paper's geometry: a chunk that the spans of several (head, slot) entries cover
+  // (equal anchors, or merely overlapping spans).  The entry that comes first in the group's index
+  // rows owns the chunk and computes the partial of every other entry that attends it; the
+  // workgroups of those entries leave at once.  Needs the group's G * topk indices in one pass of
+  // a wavefront (larger groups: every entry reads its own rows).  (2) share_window: the local
   // window, which all G heads attend: the first head's workgroup serves the group.  When the
   // wave's rows fit one batch they stay in registers and every entry is computed from them;
-  // otherwise (and for clipped overlapping spans, whose range differs per entry) the owner reads
-  // the rows again per entry, through the L2.
+  // otherwise (and for clipped overlapping grid spans, whose range differs per entry) the owner
+  // reads the rows again per entry, through the L2.
   constexpr int kShareWords = 4;  // up to 256 (head, slot) entries per kv head
   const bool dedup = slot < topk && G * topk <= 64 * kShareWords && G > 1;
   const bool window_group = slot == topk && share_window && one_batch && G > 1 && G <= 64;
-  const int64_t jlimit = ar.on ? q_pos + 1 : c;  // valid entries: anchor tokens <= q_pos, resp. spans < c
   unsigned long long share[kShareWords] = {0ull, 0ull, 0ull, 0ull};
   // entry numbers: (head in group) * topk + slot for a span, head in group for the window
   const int my_entry = window_group ? h - kv * G : (h - kv * G) * topk + slot;
   bool multi = false;
-  if (dedup) {
+  if (dedup && (!AG || t0 < t1)) {
     // every wavefront builds the masks by itself (no LDS, no barrier): lane l looks at entries
     // l, l + 64, ... of the group's index rows, which are contiguous
     const int64_t jmine = idx[(int64_t)h * topk + slot];
@@ -157,7 +172,15 @@ __device__ __forceinline__ void decode_split_body(
       const int e = 64 * w + lane;
       int64_t jother = -1;
       if (e < G * topk) jother = idx[(int64_t)kv * G * topk + e];
-      share[w] = __ballot(jmine >= 0 && jmine < jlimit && jother == jmine);
+      bool same;
+      if (AG) {  // the other entry's span reaches into this chunk
+        int64_t e0, e1;
+        anchor_range(jother, e0, e1);
+        same = e1 > e0 && e0 < cb + CT && e1 > cb;
+      } else {
+        same = jmine >= 0 && jmine < c && jother == jmine;
+      }
+      share[w] = __ballot(same);
       if (share[w]) first = 64 * w + __builtin_ctzll(share[w]);
       count += __builtin_popcountll(share[w]);
     }
@@ -170,7 +193,7 @@ __device__ __forceinline__ void decode_split_body(
     share[0] = G == 64 ? ~0ull : (1ull << G) - 1ull;
     multi = true;
   }
-  const bool per_entry_range = multi && !window_group && clip && !ar.on;
+  const bool per_entry_range = multi && !window_group && clip && !AG;
   const bool from_regs = multi && one_batch && !per_entry_range;
 
   const int g = lane / LPR, lr = lane % LPR;
@@ -235,26 +258,52 @@ __device__ __forceinline__ void decode_split_body(
     }
     return next;
   };
-  const int64_t w0 = t0 + (int64_t)wave * per_wave;
-  const int64_t w1 = w0 + per_wave < t1 ? w0 + per_wave : t1;
+  // An entry's share of the chunk and its record.  Grid, window: the item's own [t0, t1) and
+  // chunk number.  Paper's geometry: the entry's span cut to the lattice chunk, and the chunk's
+  // number counted from the span's own first chunk.
+  auto entry_piece = [&](int he, int se, int64_t anchor, int64_t& lo, int64_t& hi) -> float* {
+    int cke = ck;
+    lo = t0;
+    hi = t1;
+    if (AG && se < topk) {
+      int64_t e0, e1;
+      anchor_range(anchor, e0, e1);
+      lo = e0 > cb ? e0 : cb;
+      hi = e1 < cb + CT ? e1 : cb + CT;
+      if (hi < lo) hi = lo;
+      cke = (int)(a_chunk - e0 / CT);
+    }
+    return part + (((int64_t)he * (topk + 1) + se) * nchunks + cke) * (D + 2);
+  };
+  // the wavefront's rows of the chunk
+  const int64_t w0 = cb + (int64_t)wave * per_wave;
+  const int64_t cend = AG ? (cb + CT < q_pos + 1 ? cb + CT : q_pos + 1) : t1;  // last row that may be loaded, + 1
+  const int64_t w1 = w0 + per_wave < cend ? w0 + per_wave : cend;
 
   if (U <= 8 && from_regs) {
-    // several entries, one range, one batch: the rows are loaded once and stay in registers
-    if (t0 >= t1) {
+    // several entries, one chunk, one batch: the rows are loaded once and stay in registers
+    if (t0 >= t1) {  // (the window past its end: the same for every head)
       for (int entry = my_entry; entry >= 0; entry = next_entry(entry))
         write_empty(part + (((int64_t)entry_head(entry) * (topk + 1) + entry_slot(entry)) * nchunks + ck) * (D + 2));
       return;
     }
     uint4 kr[U], vr[U];
     uint4 qraw = load16(Q + (int64_t)h * qsh + lr * EPL);
+    int64_t anchor = slot < topk ? idx[(int64_t)h * topk + slot] : -1;
     load_rows<T, D, U, true>(Kb, Vb, kvst, w0, w1, lane, kr, vr);
     int entry = my_entry;
     while (true) {
       const int next = next_entry(entry);
-      uint4 qnext = qraw;  // the next entry's query is fetched while this one is computed
-      if (next >= 0) qnext = load16(Q + (int64_t)entry_head(next) * qsh + lr * EPL);
       float q2[EPL];
       scaled_query(qraw, q2);
+      // the next entry's query (and anchor) are fetched while this one is computed
+      int64_t anchor_next = -1;
+      if (next >= 0) {
+        qraw = load16(Q + (int64_t)entry_head(next) * qsh + lr * EPL);
+        if (!window_group) anchor_next = idx[(int64_t)kv * G * topk + next];
+      }
+      int64_t lo, hi;
+      float* prec = entry_piece(entry_head(entry), entry_slot(entry), anchor, lo, hi);
       AttendState<T, D> st;
       st.init();
       // (the rows stay packed between entries: without this the compiler unpacks all of them to
@@ -264,11 +313,15 @@ __device__ __forceinline__ void decode_split_body(
         asm volatile("" : "+v"(kr[u].x), "+v"(kr[u].y), "+v"(kr[u].z), "+v"(kr[u].w));
         asm volatile("" : "+v"(vr[u].x), "+v"(vr[u].y), "+v"(vr[u].z), "+v"(vr[u].w));
       }
-      attend_loaded<T, D, U>(q2, kr, vr, w0, w1, lane, st);
-      merge_and_write(st, part + (((int64_t)entry_head(entry) * (topk + 1) + entry_slot(entry)) * nchunks + ck) * (D + 2));
+      // (positions as offsets from the chunk's first row: they fit 32 bits; the wavefront's share of
+      // the chunk may be shorter than the batch)
+      const int hi_rel = (int)(hi - cb), wave_end = (wave + 1) * per_wave;
+      attend_loaded<T, D, U>(q2, kr, vr, wave * per_wave, (int)(lo - cb), hi_rel < wave_end ? hi_rel : wave_end,
+                             lane, st);
+      merge_and_write(st, prec);
       if (next < 0) break;
       entry = next;
-      qraw = qnext;
+      anchor = anchor_next;
       __syncthreads();  // the merge above has read s_o / s_m / s_l
     }
     return;
@@ -279,19 +332,25 @@ __device__ __forceinline__ void decode_split_body(
   while (true) {
     const int he = multi ? entry_head(entry) : h;
     const int se = multi ? entry_slot(entry) : slot;
-    if (per_entry_range) grid_chunk(he, idx[(int64_t)he * topk + se], t0, t1);  // the entry's own clip
-    float* prec = part + (((int64_t)he * (topk + 1) + se) * nchunks + ck) * (D + 2);
-    if (t0 >= t1) {  // empty slot or chunk past the end of the range (uniform over the workgroup)
+    if (per_entry_range) {  // the entry's own clip
+      grid_chunk(he, idx[(int64_t)he * topk + se], t0, t1);
+      cb = t0;
+    }
+    int64_t lo, hi;
+    float* prec = entry_piece(he, se, se < topk ? (int64_t)idx[(int64_t)he * topk + se] : (int64_t)-1, lo, hi);
+    if (lo >= hi) {  // empty slot or chunk past the end of the range (uniform over the workgroup)
       write_empty(prec);
     } else {
       float q2[EPL];
       scaled_query(load16(Q + (int64_t)he * qsh + lr * EPL), q2);
-      const int64_t v0 = t0 + (int64_t)wave * per_wave;
-      const int64_t v1 = v0 + per_wave < t1 ? v0 + per_wave : t1;
+      // the wavefront's rows of the chunk, cut to the entry's piece
+      int64_t v0 = cb + (int64_t)wave * per_wave, v1 = v0 + per_wave;
+      v0 = v0 > lo ? v0 : lo;
+      v1 = v1 < hi ? v1 : hi;
       AttendState<T, D> st;
       st.init();
-      // A span that one entry reads is streamed past the caches; the window (read by all G heads
-      // of its kv head) and a shared span (read again right away) stay cacheable.
+      // Rows that one entry reads are streamed past the caches; the window (read by all G heads
+      // of its kv head) and shared rows (read again right away) stay cacheable.
       if (slot != topk && !multi)
         attend_range<T, D, U, true>(q2, Kb, Vb, kvst, v0, v1, lane, st);
       else
@@ -309,14 +368,14 @@ __device__ __forceinline__ void decode_split_body(
 // Registers: the narrow-batch kernels are held to four wavefronts per SIMD (128 registers), which
 // they need without the multi-entry loop; left alone, the compiler keeps the loop's unpacked rows
 // in registers and halves the occupancy of every workgroup for the sake of a few.
-template <typename T, int D, int U>
+template <typename T, int D, int U, bool AG>
 __global__ __launch_bounds__(kDecodeThreads) __attribute__((amdgpu_waves_per_eu(U <= 8 ? 4 : 2)))
 void decode_split_kernel(
     const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
     const int32_t* __restrict__ idx, float* __restrict__ part, int64_t q_pos, int Hq, int Hkv,
     int S, int A, bool clip, int topk, int nchunks, int CT, float scale_log2e, int64_t qsh, int64_t kvsh,
     int64_t kvst, int n_routed_blocks, int local_stride, bool share_window, const AnchorRanges ar) {
-  decode_split_body<T, D, U>(Q, K, V, idx, part, q_pos, Hq, Hkv, S, A, clip, topk, nchunks, CT, scale_log2e,
+  decode_split_body<T, D, U, AG>(Q, K, V, idx, part, q_pos, Hq, Hkv, S, A, clip, topk, nchunks, CT, scale_log2e,
                           qsh, kvsh, kvst, n_routed_blocks, local_stride, share_window, ar);
 }
 
@@ -330,8 +389,10 @@ struct AnchorBatch {
   int b, f, root;
 };
 
-template <typename T, int D, int U>
-__global__ __launch_bounds__(kDecodeThreads) __attribute__((amdgpu_waves_per_eu(U <= 8 ? 4 : 2)))
+// (the paper's geometry for a batch carries each sequence's own span extents on top: three
+// wavefronts per SIMD there, rather than spills)
+template <typename T, int D, int U, bool AG>
+__global__ __launch_bounds__(kDecodeThreads) __attribute__((amdgpu_waves_per_eu(U <= 8 ? (AG ? 3 : 4) : 2)))
 void decode_split_batched_kernel(
     const sl_decode_seq* __restrict__ seqs, float* __restrict__ part, int64_t part_stride, int Hq,
     int Hkv, int S, int A, bool clip, int topk, int nchunks, int CT, float scale_log2e, int64_t qsh,
@@ -340,14 +401,14 @@ void decode_split_batched_kernel(
   const sl_decode_seq sq = seqs[blockIdx.y];
   const int64_t i = sq.L - 1;
   AnchorRanges ar{false, 0, 0, 0};
-  if (ab.on) {
+  if (AG) {
     const int64_t ell = span_base_length(i, ab.root);
     ar.on = true;
     ar.wlo = ab.window > 0 ? (i - ab.window + 1 > 0 ? i - ab.window + 1 : 0) : i + 1;
     ar.back = (int64_t)ab.b * ell;
     ar.fwd = (int64_t)ab.f * ell;
   }
-  decode_split_body<T, D, U>(static_cast<const T*>(sq.Q), static_cast<const T*>(sq.K),
+  decode_split_body<T, D, U, AG>(static_cast<const T*>(sq.Q), static_cast<const T*>(sq.K),
                           static_cast<const T*>(sq.V), sq.idx, part + blockIdx.y * part_stride, i, Hq,
                           Hkv, S, A, clip, topk, nchunks, CT, scale_log2e, qsh, kvsh ? kvsh : sq.L * kvst,
                           kvst, n_routed_blocks, local_stride, share_window, ar);
@@ -470,19 +531,22 @@ template <typename T, int D>
 __device__ __forceinline__ void decode_reduce_combined_body(const float* __restrict__ part,
                                                             const float* __restrict__ gate,
                                                             T* __restrict__ O, int topk, int nchunks) {
-  extern __shared__ float s_dyn[];  // [nrec] m, [nrec] l
+  extern __shared__ float s_dyn[];  // [nrec] m, then each record's weight inside its slot; [nrec] l
   __shared__ float s_ms[kMaxSlots], s_ls[kMaxSlots];           // per slot: max m, l relative to it
+  __shared__ float s_gate[kMaxSlots];
   __shared__ float s_part[kMaxSlots][kReduceSub][kReduceDims];  // per slot and subset: o relative to it
   const int h = blockIdx.x, d0 = blockIdx.y * kReduceDims;
-  const int tid = threadIdx.x;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int d = tid % kReduceDims, sub = tid / kReduceDims;
   const int nslot = topk + 1, nrec = nslot * nchunks;
   float* s_m = s_dyn;
   float* s_l = s_dyn + nrec;
   const float* base = part + (int64_t)h * nrec * (D + 2);
 
-  // A thread owns dim d and the chunks sub, sub + 8, ... of every slot.  Its record loads do not
-  // depend on the statistics, so (if they fit kMaxPre registers) all of them are issued first.
+  // Every global load of the kernel is issued before the first wait: the gate, the partial outputs
+  // (a thread owns dim d and the chunks sub, sub + 8, ... of every slot; if they fit kMaxPre
+  // registers) and the statistics.  The kernel then costs one memory round trip.
+  const float gate_mine = tid < topk ? gate[(int64_t)h * topk + tid] : 0.f;
   constexpr int kMaxPre = 36;
   const int per_slot = (nchunks + kReduceSub - 1) / kReduceSub;
   const int nload = nslot * per_slot;
@@ -504,17 +568,29 @@ __device__ __forceinline__ void decode_reduce_combined_body(const float* __restr
     s_m[p] = base[(int64_t)p * (D + 2) + D];
     s_l[p] = base[(int64_t)p * (D + 2) + D + 1];
   }
+  if (tid < topk) s_gate[tid] = gate_mine;
   __syncthreads();
-  if (tid < nslot) {
+  // Per slot: the maximum of its records' m, its l relative to that, and each record's weight
+  // 2^(m_p - max) (written over m_p).  A wavefront takes slots wave, wave + 4, ...; its lanes
+  // stride over the chunks.  (LDS operations of one wavefront complete in issue order.)
+  for (int slot = wave; slot < nslot; slot += 4) {
     float m = -INFINITY;
-    for (int ck = 0; ck < nchunks; ++ck) m = fmaxf(m, s_m[tid * nchunks + ck]);
+    for (int ck = lane; ck < nchunks; ck += 64) m = fmaxf(m, s_m[slot * nchunks + ck]);
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) m = fmaxf(m, __shfl_xor(m, off, 64));
     float l = 0.f;
-    for (int ck = 0; ck < nchunks; ++ck) {
-      const float mp = s_m[tid * nchunks + ck];
-      if (mp > -INFINITY) l = fmaf(fast_exp2(mp - m), s_l[tid * nchunks + ck], l);
+    for (int ck = lane; ck < nchunks; ck += 64) {
+      const float mp = s_m[slot * nchunks + ck];
+      const float w = mp > -INFINITY ? fast_exp2(mp - m) : 0.f;
+      s_m[slot * nchunks + ck] = w;
+      l = fmaf(w, s_l[slot * nchunks + ck], l);
     }
-    s_ms[tid] = m;
-    s_ls[tid] = l;
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) l += __shfl_xor(l, off, 64);
+    if (lane == 0) {
+      s_ms[slot] = m;
+      s_ls[slot] = l;
+    }
   }
   __syncthreads();
   if (pre) {
@@ -524,10 +600,9 @@ __device__ __forceinline__ void decode_reduce_combined_body(const float* __restr
     for (int u = 0; u < kMaxPre; ++u) {
       if (u < nload) {
         const int ck = sub + it * kReduceSub;
-        const float ms = s_ms[slot];
-        if (ck < nchunks && ms > -INFINITY) {
-          const float mp = s_m[slot * nchunks + ck];
-          if (mp > -INFINITY) acc = fmaf(fast_exp2(mp - ms), ov[u], acc);
+        if (ck < nchunks) {
+          const float w = s_m[slot * nchunks + ck];
+          acc = w > 0.f ? fmaf(w, ov[u], acc) : acc;  // (a record without tokens may hold anything)
         }
         if (++it == per_slot) {
           s_part[slot][sub][d] = acc;
@@ -539,42 +614,49 @@ __device__ __forceinline__ void decode_reduce_combined_body(const float* __restr
     }
   } else {
     for (int slot = 0; slot < nslot; ++slot) {
-      const float ms = s_ms[slot];
       float acc = 0.f;
-      if (ms > -INFINITY) {
-        for (int ck = sub; ck < nchunks; ck += kReduceSub) {
-          const float mp = s_m[slot * nchunks + ck];
-          if (mp > -INFINITY)
-            acc = fmaf(fast_exp2(mp - ms), base[(int64_t)(slot * nchunks + ck) * (D + 2) + d0 + d], acc);
-        }
+      for (int ck = sub; ck < nchunks; ck += kReduceSub) {
+        const float w = s_m[slot * nchunks + ck];
+        if (w > 0.f) acc = fmaf(w, base[(int64_t)(slot * nchunks + ck) * (D + 2) + d0 + d], acc);
       }
       s_part[slot][sub][d] = acc;
     }
   }
   __syncthreads();
-  if (tid < kReduceDims) {
-    auto slot_o = [&](int slot) {
-      float o = 0.f;
+  // The gated sum over the slots, eight slots at a time (thread = dim d, slots sub, sub + 8, ...).
+  auto slot_o = [&](int slot) {
+    float o = 0.f;
 #pragma unroll
-      for (int s2 = 0; s2 < kReduceSub; ++s2) o += s_part[slot][s2][tid];
-      return o;
-    };
-    const float mw = s_ms[topk], lw = s_ls[topk];  // the window always holds the query's own token
-    const float ow = slot_o(topk);
-    float gmax = -INFINITY;
-    for (int slot = 0; slot < topk; ++slot)
-      if (s_ms[slot] > -INFINITY) gmax = fmaxf(gmax, gate[(int64_t)h * topk + slot]);
-    float acc = 0.f, asum = 0.f;
-    for (int slot = 0; slot < topk; ++slot) {
-      const float m = s_ms[slot];
-      if (m == -INFINITY) continue;
-      const float M = fmaxf(m, mw);
-      const float wa = fast_exp2(m - M), wb = fast_exp2(mw - M);
-      const float a = __expf(gate[(int64_t)h * topk + slot] - gmax);
-      asum += a;
-      acc = fmaf(a, (slot_o(slot) * wa + ow * wb) / (s_ls[slot] * wa + lw * wb), acc);
+    for (int s2 = 0; s2 < kReduceSub; ++s2) o += s_part[slot][s2][d];
+    return o;
+  };
+  float gmax = (lane < topk && s_ms[lane] > -INFINITY) ? s_gate[lane] : -INFINITY;  // topk <= 32 < 64
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) gmax = fmaxf(gmax, __shfl_xor(gmax, off, 64));
+  const float mw = s_ms[topk], lw = s_ls[topk];  // the window always holds the query's own token
+  const float ow = slot_o(topk);
+  float acc = 0.f, asum = 0.f;
+  for (int slot = sub; slot < topk; slot += kReduceSub) {
+    const float m = s_ms[slot];
+    if (m == -INFINITY) continue;
+    const float M = fmaxf(m, mw);
+    const float wa = fast_exp2(m - M), wb = fast_exp2(mw - M);
+    const float a = __expf(s_gate[slot] - gmax);
+    asum += a;
+    acc = fmaf(a, (slot_o(slot) * wa + ow * wb) / (s_ls[slot] * wa + lw * wb), acc);
+  }
+  __shared__ float s_acc[kReduceSub][kReduceDims], s_asum[kReduceSub];
+  s_acc[sub][d] = acc;
+  if (d == 0) s_asum[sub] = asum;
+  __syncthreads();
+  if (tid < kReduceDims) {
+    float at = 0.f, st = 0.f;
+#pragma unroll
+    for (int s2 = 0; s2 < kReduceSub; ++s2) {
+      at += s_acc[s2][tid];
+      st += s_asum[s2];
     }
-    Elem<T>::store1(O + (int64_t)h * D + d0 + tid, asum > 0.f ? acc / asum : (lw > 0.f ? ow / lw : 0.f));
+    Elem<T>::store1(O + (int64_t)h * D + d0 + tid, st > 0.f ? at / st : (lw > 0.f ? ow / lw : 0.f));
   }
 }
 
@@ -609,26 +691,26 @@ inline bool window_by_one_workgroup(int64_t routed_items, int CT, int D, size_t 
   return routed_items * CT * 2 * D * (int64_t)elem_bytes >= ((int64_t)128 << 20);
 }
 
-template <typename T, int D, int U>
+template <typename T, int D, int U, bool AG>
 void launch_split_u(int grid, hipStream_t st, hipEvent_t e0, hipEvent_t e1, const void* Q, const void* K,
                     const void* V, const int32_t* idx, float* part, const Problem& pb, int S, int nchunks,
                     int CT, int n_routed, int local_stride, const AnchorRanges& ar) {
   const float scale_log2e = pb.scale * kLog2e;
-  const bool clip = !ar.on && pb.A < pb.S && !pb.combined;  // overlapping spans in one joint softmax
+  const bool clip = !AG && pb.A < pb.S && !pb.combined;  // overlapping spans in one joint softmax
   const bool share_window = window_by_one_workgroup(n_routed, CT, D, sizeof(T));
   if (e0) {
     // With profiling events the launch itself carries them: they then hold the kernel's own
     // begin and end timestamps (events recorded on the stream before / after a 45 us kernel would
     // add the dispatch gaps, several microseconds).
-    hipExtLaunchKernelGGL((decode_split_kernel<T, D, U>), dim3(grid), dim3(kDecodeThreads), 0, st, e0, e1,
+    hipExtLaunchKernelGGL((decode_split_kernel<T, D, U, AG>), dim3(grid), dim3(kDecodeThreads), 0, st, e0, e1,
                           0, static_cast<const T*>(Q), static_cast<const T*>(K),
-                          static_cast<const T*>(V), idx, part, pb.q_pos0, pb.Hq, pb.Hkv, S, ar.on ? S : pb.A,
+                          static_cast<const T*>(V), idx, part, pb.q_pos0, pb.Hq, pb.Hkv, S, AG ? S : pb.A,
                           clip, pb.topk, nchunks, CT, scale_log2e, pb.qsh, pb.kvsh, pb.kvst, n_routed,
                           local_stride, share_window, ar);
   } else {
-    hipLaunchKernelGGL((decode_split_kernel<T, D, U>), dim3(grid), dim3(kDecodeThreads), 0, st,
+    hipLaunchKernelGGL((decode_split_kernel<T, D, U, AG>), dim3(grid), dim3(kDecodeThreads), 0, st,
                        static_cast<const T*>(Q), static_cast<const T*>(K), static_cast<const T*>(V), idx,
-                       part, pb.q_pos0, pb.Hq, pb.Hkv, S, ar.on ? S : pb.A, clip, pb.topk, nchunks, CT,
+                       part, pb.q_pos0, pb.Hq, pb.Hkv, S, AG ? S : pb.A, clip, pb.topk, nchunks, CT,
                        scale_log2e, pb.qsh, pb.kvsh, pb.kvst, n_routed, local_stride, share_window, ar);
   }
 }
@@ -637,31 +719,52 @@ template <typename T, int D>
 void launch_split(int grid, hipStream_t st, const void* Q, const void* K, const void* V,
                   const int32_t* idx, float* part, const Problem& pb, int S, int nchunks, int CT,
                   int n_routed, int local_stride, const AnchorRanges& ar) {
-  if (wide_batches(CT))
-    launch_split_u<T, D, 16>(grid, st, pb.prof_start, pb.prof_stop, Q, K, V, idx, part, pb, S, nchunks, CT,
-                             n_routed, local_stride, ar);
+  const bool wide = wide_batches(CT);
+  if (ar.on && wide)
+    launch_split_u<T, D, 16, true>(grid, st, pb.prof_start, pb.prof_stop, Q, K, V, idx, part, pb, S, nchunks,
+                                   CT, n_routed, local_stride, ar);
+  else if (ar.on)
+    launch_split_u<T, D, 8, true>(grid, st, pb.prof_start, pb.prof_stop, Q, K, V, idx, part, pb, S, nchunks,
+                                  CT, n_routed, local_stride, ar);
+  else if (wide)
+    launch_split_u<T, D, 16, false>(grid, st, pb.prof_start, pb.prof_stop, Q, K, V, idx, part, pb, S, nchunks,
+                                    CT, n_routed, local_stride, ar);
   else
-    launch_split_u<T, D, 8>(grid, st, pb.prof_start, pb.prof_stop, Q, K, V, idx, part, pb, S, nchunks, CT,
-                            n_routed, local_stride, ar);
+    launch_split_u<T, D, 8, false>(grid, st, pb.prof_start, pb.prof_stop, Q, K, V, idx, part, pb, S, nchunks,
+                                   CT, n_routed, local_stride, ar);
+}
+
+template <typename T, int D, int U, bool AG>
+void launch_split_batched_u(int grid, int B, hipStream_t st, const sl_decode_seq* seqs, float* part,
+                            int64_t part_stride, const Problem& pb, int S, int nchunks, int CT, int n_routed,
+                            int local_stride, const AnchorBatch& ab) {
+  const float scale_log2e = pb.scale * kLog2e;
+  const int64_t kvsh = pb.kvsh_given ? pb.kvsh : (int64_t)0;
+  const int A = AG ? S : pb.A;
+  const bool clip = !AG && pb.A < pb.S && !pb.combined;
+  const bool share_window = window_by_one_workgroup((int64_t)n_routed * B, CT, D, sizeof(T));
+  hipLaunchKernelGGL((decode_split_batched_kernel<T, D, U, AG>), dim3(grid, B), dim3(kDecodeThreads), 0, st,
+                     seqs, part, part_stride, pb.Hq, pb.Hkv, S, A, clip, pb.topk, nchunks, CT, scale_log2e,
+                     pb.qsh, kvsh, pb.kvst, n_routed, local_stride, share_window, ab);
 }
 
 template <typename T, int D>
 void launch_split_batched(int grid, int B, hipStream_t st, const sl_decode_seq* seqs, float* part,
                           int64_t part_stride, const Problem& pb, int S, int nchunks, int CT, int n_routed,
                           int local_stride, const AnchorBatch& ab) {
-  const float scale_log2e = pb.scale * kLog2e;
-  const int64_t kvsh = pb.kvsh_given ? pb.kvsh : (int64_t)0;
-  const int A = ab.on ? S : pb.A;
-  const bool clip = !ab.on && pb.A < pb.S && !pb.combined;
-  const bool share_window = window_by_one_workgroup((int64_t)n_routed * B, CT, D, sizeof(T));
-  if (wide_batches(CT))
-    hipLaunchKernelGGL((decode_split_batched_kernel<T, D, 16>), dim3(grid, B), dim3(kDecodeThreads), 0, st,
-                       seqs, part, part_stride, pb.Hq, pb.Hkv, S, A, clip, pb.topk, nchunks, CT, scale_log2e,
-                       pb.qsh, kvsh, pb.kvst, n_routed, local_stride, share_window, ab);
+  const bool wide = wide_batches(CT);
+  if (ab.on && wide)
+    launch_split_batched_u<T, D, 16, true>(grid, B, st, seqs, part, part_stride, pb, S, nchunks, CT, n_routed,
+                                           local_stride, ab);
+  else if (ab.on)
+    launch_split_batched_u<T, D, 8, true>(grid, B, st, seqs, part, part_stride, pb, S, nchunks, CT, n_routed,
+                                          local_stride, ab);
+  else if (wide)
+    launch_split_batched_u<T, D, 16, false>(grid, B, st, seqs, part, part_stride, pb, S, nchunks, CT, n_routed,
+                                            local_stride, ab);
   else
-    hipLaunchKernelGGL((decode_split_batched_kernel<T, D, 8>), dim3(grid, B), dim3(kDecodeThreads), 0, st,
-                       seqs, part, part_stride, pb.Hq, pb.Hkv, S, A, clip, pb.topk, nchunks, CT, scale_log2e,
-                       pb.qsh, kvsh, pb.kvst, n_routed, local_stride, share_window, ab);
+    launch_split_batched_u<T, D, 8, false>(grid, B, st, seqs, part, part_stride, pb, S, nchunks, CT, n_routed,
+                                           local_stride, ab);
 }
 
 // The reductions keep one weight (joint form) or two statistics (gated form) per partial record of
@@ -727,7 +830,9 @@ AnchorPlan plan_anchor(const Problem& pb, int64_t window, int b, int f, int root
   int ct = 512;
   while (ct > 64 && batch * units * ((a.maxlen + ct - 1) / ct) < 4096) ct >>= 1;
   a.CT = ct;
-  a.nchunks = (int)((a.maxlen + ct - 1) / ct);
+  // chunks sit on the absolute CT-token lattice: a range of maxlen tokens touches one more of them
+  // than its length alone fills
+  a.nchunks = (int)((a.maxlen + ct - 1) / ct) + 1;
   a.part_bytes = align_up((size_t)batch * units * a.nchunks * (pb.D + 2) * sizeof(float), 256);
   a.total_bytes = a.part_bytes;
   return a;

@@ -51,10 +51,12 @@ __device__ __forceinline__ void load_rows(const T* __restrict__ Kb, const T* __r
   }
 }
 
-// Online-softmax update of st with the batch that load_rows fetched for rows [tb, ..) of [.., t1).
-template <typename T, int D, int U>
+// Online-softmax update of st with the batch that load_rows fetched for rows tb, tb + 1, ...:
+// the rows inside [lo, hi) are attended, the others masked.
+// (I: int64_t token positions, or int offsets from a common base.)
+template <typename T, int D, int U, typename I>
 __device__ __forceinline__ void attend_loaded(const float* q2, const uint4 (&kr)[U], const uint4 (&vr)[U],
-                                              int64_t tb, int64_t t1, int lane, AttendState<T, D>& st) {
+                                              I tb, I lo, I hi, int lane, AttendState<T, D>& st) {
   using RL = RowLayout<T, D>;
   constexpr int EPL = RL::EPL, LPR = RL::LPR, RPW = RL::RPW;
   const int g = lane / LPR;
@@ -68,8 +70,8 @@ __device__ __forceinline__ void attend_loaded(const float* q2, const uint4 (&kr)
 #pragma unroll
     for (int e = 0; e < EPL; ++e) acc = fmaf(q2[e], kf[e], acc);
     acc = group_sum<LPR>(acc);
-    const bool valid = (tb + u * RPW + g) < t1;
-    s[u] = valid ? acc : -INFINITY;
+    const I tok = tb + u * RPW + g;
+    s[u] = (tok >= lo && tok < hi) ? acc : -INFINITY;
     bm = fmaxf(bm, s[u]);
   }
   const float m_new = fmaxf(st.m, bm);
@@ -99,7 +101,7 @@ __device__ __forceinline__ void attend_range(const float* q2, const T* __restric
   for (int64_t tb = t0; tb < t1; tb += RPW * U) {
     uint4 kr[U], vr[U];
     load_rows<T, D, U, STREAM>(Kb, Vb, stride_t, tb, t1, lane, kr, vr);
-    attend_loaded<T, D, U>(q2, kr, vr, tb, t1, lane, st);
+    attend_loaded<T, D, U>(q2, kr, vr, tb, t0, t1, lane, st);
   }
 }
 
