@@ -21,6 +21,7 @@ constexpr int kDecodeThreads = 256;
 struct AnchorRanges {
   bool on;
   int64_t wlo, back, fwd;
+  int wchunks;  // chunks of the window (it is shorter than the spans: fewer items, fewer records)
 };
 
 // Partial record of one (head, slot, chunk): o[D] (unnormalised, relative to m), m (log2 units), l.
@@ -53,12 +54,12 @@ __device__ __forceinline__ void decode_split_body(
   const int n_local_blocks = (int)gridDim.x - n_routed_blocks;
   int bid = (int)blockIdx.x - n_local_blocks;
   if (AG) {
-    // the paper's geometry: the window is slot topk of every head, Hq * nchunks items, again at
+    // the paper's geometry: the window is slot topk of every head, Hq * wchunks items, again at
     // the front of the grid (a window item that serves its whole group runs the longest)
-    const int b = (int)blockIdx.x, nwin = Hq * nchunks;
+    const int b = (int)blockIdx.x, nwin = Hq * ar.wchunks;
     if (b < nwin) {
-      h = b / nchunks;
-      ck = b % nchunks;
+      h = b / ar.wchunks;
+      ck = b % ar.wchunks;
       slot = topk;
     } else {
       ck = (b - nwin) % nchunks;
@@ -387,6 +388,7 @@ struct AnchorBatch {
   bool on;
   int64_t window;
   int b, f, root;
+  int wchunks;
 };
 
 // (the paper's geometry for a batch carries each sequence's own span extents on top: three
@@ -400,13 +402,14 @@ void decode_split_batched_kernel(
     const AnchorBatch ab) {
   const sl_decode_seq sq = seqs[blockIdx.y];
   const int64_t i = sq.L - 1;
-  AnchorRanges ar{false, 0, 0, 0};
+  AnchorRanges ar{false, 0, 0, 0, 0};
   if (AG) {
     const int64_t ell = span_base_length(i, ab.root);
     ar.on = true;
     ar.wlo = ab.window > 0 ? (i - ab.window + 1 > 0 ? i - ab.window + 1 : 0) : i + 1;
     ar.back = (int64_t)ab.b * ell;
     ar.fwd = (int64_t)ab.f * ell;
+    ar.wchunks = ab.wchunks;
   }
   decode_split_body<T, D, U, AG>(static_cast<const T*>(sq.Q), static_cast<const T*>(sq.K),
                           static_cast<const T*>(sq.V), sq.idx, part + blockIdx.y * part_stride, i, Hq,
@@ -530,7 +533,8 @@ constexpr int kMaxSlots = SL_MAX_TOPK + 1;
 template <typename T, int D>
 __device__ __forceinline__ void decode_reduce_combined_body(const float* __restrict__ part,
                                                             const float* __restrict__ gate,
-                                                            T* __restrict__ O, int topk, int nchunks) {
+                                                            T* __restrict__ O, int topk, int nchunks,
+                                                            int wchunks) {
   extern __shared__ float s_dyn[];  // [nrec] m, then each record's weight inside its slot; [nrec] l
   __shared__ float s_ms[kMaxSlots], s_ls[kMaxSlots];           // per slot: max m, l relative to it
   __shared__ float s_gate[kMaxSlots];
@@ -539,6 +543,8 @@ __device__ __forceinline__ void decode_reduce_combined_body(const float* __restr
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int d = tid % kReduceDims, sub = tid / kReduceDims;
   const int nslot = topk + 1, nrec = nslot * nchunks;
+  // the window (last slot) has only wchunks <= nchunks records; the rest of its row was never written
+  const int nvalid = topk * nchunks + wchunks;
   float* s_m = s_dyn;
   float* s_l = s_dyn + nrec;
   const float* base = part + (int64_t)h * nrec * (D + 2);
@@ -557,7 +563,9 @@ __device__ __forceinline__ void decode_reduce_combined_body(const float* __restr
 #pragma unroll
     for (int u = 0; u < kMaxPre; ++u) {
       const int ck = sub + it * kReduceSub;
-      ov[u] = (u < nload && ck < nchunks) ? base[(int64_t)(slot * nchunks + ck) * (D + 2) + d0 + d] : 0.f;
+      ov[u] = (u < nload && ck < nchunks && slot * nchunks + ck < nvalid)
+                  ? base[(int64_t)(slot * nchunks + ck) * (D + 2) + d0 + d]
+                  : 0.f;
       if (++it == per_slot) {
         it = 0;
         ++slot;
@@ -565,8 +573,8 @@ __device__ __forceinline__ void decode_reduce_combined_body(const float* __restr
     }
   }
   for (int p = tid; p < nrec; p += 256) {
-    s_m[p] = base[(int64_t)p * (D + 2) + D];
-    s_l[p] = base[(int64_t)p * (D + 2) + D + 1];
+    s_m[p] = p < nvalid ? base[(int64_t)p * (D + 2) + D] : -INFINITY;
+    s_l[p] = p < nvalid ? base[(int64_t)p * (D + 2) + D + 1] : 0.f;
   }
   if (tid < topk) s_gate[tid] = gate_mine;
   __syncthreads();
@@ -664,18 +672,18 @@ template <typename T, int D>
 __global__ __launch_bounds__(256) void decode_reduce_combined_kernel(const float* __restrict__ part,
                                                                     const float* __restrict__ gate,
                                                                     T* __restrict__ O, int topk,
-                                                                    int nchunks) {
-  decode_reduce_combined_body<T, D>(part, gate, O, topk, nchunks);
+                                                                    int nchunks, int wchunks) {
+  decode_reduce_combined_body<T, D>(part, gate, O, topk, nchunks, wchunks);
 }
 
 // Batched decode: blockIdx.z is the sequence; the gate is the sequence's own score array.
 template <typename T, int D>
 __global__ __launch_bounds__(256) void decode_reduce_combined_batched_kernel(
     const sl_decode_seq* __restrict__ seqs, const float* __restrict__ part, int64_t part_stride, int topk,
-    int nchunks) {
+    int nchunks, int wchunks) {
   const sl_decode_seq sq = seqs[blockIdx.z];
   decode_reduce_combined_body<T, D>(part + blockIdx.z * part_stride, sq.scores, static_cast<T*>(sq.O), topk,
-                                    nchunks);
+                                    nchunks, wchunks);
 }
 
 // Loads in flight per lane: a wavefront's quarter of a 512-token chunk is two batches of 16 K and
@@ -794,12 +802,12 @@ sl_status launch_decode(const Problem& pb, const void* Q, const void* K, const v
   const int nrec = (pb.topk + 1) * nchunks;
   if (!reduce_fits_lds(nrec, pb.combined)) return SL_ERR_UNSUPPORTED;  // before anything is enqueued
   launch_split<T, D>(grid, st, Q, K, V, idx, part, pb, pb.S, nchunks, CT, n_routed, local_stride,
-                     AnchorRanges{false, 0, 0, 0});
+                     AnchorRanges{false, 0, 0, 0, 0});
   if (hipGetLastError() != hipSuccess) return SL_ERR_LAUNCH;
   if (pb.combined) {
     hipLaunchKernelGGL((decode_reduce_combined_kernel<T, D>), dim3(pb.Hq, D / kReduceDims), dim3(256),
                        (size_t)2 * nrec * sizeof(float), st, part, pb.gate, static_cast<T*>(O),
-                       pb.topk, nchunks);
+                       pb.topk, nchunks, nchunks);
     return hipGetLastError() == hipSuccess ? SL_OK : SL_ERR_LAUNCH;
   }
   hipLaunchKernelGGL((decode_reduce_kernel<T, D>), dim3(pb.Hq, D / kReduceDims), dim3(256),
@@ -812,7 +820,7 @@ sl_status launch_decode(const Problem& pb, const void* Q, const void* K, const v
 // ------------------------------------------------------------------ the paper's own geometry
 struct AnchorPlan {
   int64_t back, fwd, wlo, maxlen;
-  int CT, nchunks;
+  int CT, nchunks, wchunks;
   size_t part_bytes, total_bytes;
 };
 
@@ -833,6 +841,8 @@ AnchorPlan plan_anchor(const Problem& pb, int64_t window, int b, int f, int root
   // chunks sit on the absolute CT-token lattice: a range of maxlen tokens touches one more of them
   // than its length alone fills
   a.nchunks = (int)((a.maxlen + ct - 1) / ct) + 1;
+  a.wchunks = (int)((wlen + ct - 1) / ct) + 1;  // of the longest sequence; wlen <= maxlen
+  if (a.wchunks > a.nchunks) a.wchunks = a.nchunks;
   a.part_bytes = align_up((size_t)batch * units * a.nchunks * (pb.D + 2) * sizeof(float), 256);
   a.total_bytes = a.part_bytes;
   return a;
@@ -843,17 +853,16 @@ sl_status launch_anchor_attention(const Problem& pb, const AnchorPlan& a, const 
                                   const void* K, const void* V, const int32_t* anchors, void* O,
                                   void* ws, hipStream_t st) {
   float* part = static_cast<float*>(ws);
-  const int units = pb.Hq * (pb.topk + 1);
-  const AnchorRanges ar{true, a.wlo, a.back, a.fwd};
-  // every (head, slot, chunk) is a routed item here: the window is slot topk of every head
-  const int grid = units * a.nchunks;
+  const AnchorRanges ar{true, a.wlo, a.back, a.fwd, a.wchunks};
+  // every (head, slot, chunk) is a routed item here: the window is slot topk of every head, wchunks items
+  const int grid = pb.Hq * (pb.topk * a.nchunks + a.wchunks);
   const int nrec = (pb.topk + 1) * a.nchunks;
   if (!reduce_fits_lds(nrec, true)) return SL_ERR_UNSUPPORTED;
   launch_split<T, D>(grid, st, Q, K, V, anchors, part, pb, 1, a.nchunks, a.CT, grid, 8, ar);
   if (hipGetLastError() != hipSuccess) return SL_ERR_LAUNCH;
   hipLaunchKernelGGL((decode_reduce_combined_kernel<T, D>), dim3(pb.Hq, D / kReduceDims), dim3(256),
                      (size_t)2 * nrec * sizeof(float), st, part, pb.gate, static_cast<T*>(O), pb.topk,
-                     a.nchunks);
+                     a.nchunks, a.wchunks);
   return hipGetLastError() == hipSuccess ? SL_OK : SL_ERR_LAUNCH;
 }
 
@@ -871,12 +880,12 @@ sl_status launch_decode_batched(const Problem& pb, const sl_decode_seq* seqs, in
   const int local_stride = (int)align_up((size_t)pb.Hkv * nchunks, 8);
   const int grid = n_routed + pb.G * local_stride;
   launch_split_batched<T, D>(grid, B, st, seqs, part, part_stride, pb, pb.S, nchunks, CT, n_routed,
-                             local_stride, AnchorBatch{false, 0, 0, 0, 2});
+                             local_stride, AnchorBatch{false, 0, 0, 0, 2, 0});
   if (hipGetLastError() != hipSuccess) return SL_ERR_LAUNCH;
   if (pb.combined)
     hipLaunchKernelGGL((decode_reduce_combined_batched_kernel<T, D>), dim3(pb.Hq, D / kReduceDims, B),
                        dim3(256), (size_t)2 * nrec * sizeof(float), st, seqs, part, part_stride, pb.topk,
-                       nchunks);
+                       nchunks, nchunks);
   else
     hipLaunchKernelGGL((decode_reduce_batched_kernel<T, D>), dim3(pb.Hq, D / kReduceDims, B), dim3(256),
                        (size_t)nrec * sizeof(float), st, seqs, part, part_stride, nrec);
@@ -886,17 +895,16 @@ sl_status launch_decode_batched(const Problem& pb, const sl_decode_seq* seqs, in
 template <typename T, int D>
 sl_status launch_anchor_batched(const Problem& pb, const AnchorPlan& a, const AnchorBatch& ab,
                                 const sl_decode_seq* seqs, int B, void* ws, hipStream_t st) {
-  const int units = pb.Hq * (pb.topk + 1);
   const int nrec = (pb.topk + 1) * a.nchunks;
   if (!reduce_fits_lds(nrec, true)) return SL_ERR_UNSUPPORTED;
   const int64_t part_stride = (int64_t)pb.Hq * nrec * (D + 2);
   float* part = static_cast<float*>(ws);
-  const int grid = units * a.nchunks;  // every (head, slot, chunk) is a routed item, as for one sequence
+  const int grid = pb.Hq * (pb.topk * a.nchunks + a.wchunks);  // as for one sequence
   launch_split_batched<T, D>(grid, B, st, seqs, part, part_stride, pb, 1, a.nchunks, a.CT, grid, 8, ab);
   if (hipGetLastError() != hipSuccess) return SL_ERR_LAUNCH;
   hipLaunchKernelGGL((decode_reduce_combined_batched_kernel<T, D>), dim3(pb.Hq, D / kReduceDims, B),
                      dim3(256), (size_t)2 * nrec * sizeof(float), st, seqs, part, part_stride, pb.topk,
-                     a.nchunks);
+                     a.nchunks, a.wchunks);
   return hipGetLastError() == hipSuccess ? SL_OK : SL_ERR_LAUNCH;
 }
 
@@ -926,7 +934,7 @@ size_t anchor_attention_batched_ws_bytes(const Problem& pb, int64_t window, int 
 sl_status anchor_attention_decode_batched(const Problem& pb, int64_t window, int b, int f, int root,
                                           const sl_decode_seq* seqs, int B, void* ws, hipStream_t st) {
   const AnchorPlan a = plan_anchor(pb, window, b, f, root, B);
-  const AnchorBatch ab{true, window, b, f, root};
+  const AnchorBatch ab{true, window, b, f, root, a.wchunks};
   if (pb.dtype == SL_BF16) {
     if (pb.D == 128) return launch_anchor_batched<bf16_t, 128>(pb, a, ab, seqs, B, ws, st);
     return launch_anchor_batched<bf16_t, 64>(pb, a, ab, seqs, B, ws, st);
