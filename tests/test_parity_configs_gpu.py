@@ -14,7 +14,7 @@ from paper_2601_18401_amd import workloads as W
 import math
 
 from tests import brute
-from tests.test_parity_gpu import (DEV, TOL, DevKV, DevRows, check_anchor_row, check_attention, check_combined,
+from tests.test_parity_gpu import (DEV, TOL, DevKV, DevRows, GatheredRows, check_anchor_row, check_attention, check_combined,
                                    check_idx, f64)
 
 pytestmark = pytest.mark.gpu
@@ -180,9 +180,11 @@ def test_batched_decode_at_the_benchmark_configuration():
     torch.cuda.empty_cache()
 
 
-def test_paper_geometry_decode_at_1m():
-    # config 3's cache with the paper's kernel configuration (window 1088, top-2, b = 4, f = 2)
-    cfg = W.CONFIGS["C3"]
+@pytest.mark.parametrize("name", ["C3", "C5"])
+def test_paper_geometry_decode_at_full_cache(name):
+    # the configuration's cache with the paper's kernel configuration (window 1088, top-2, b = 4, f = 2);
+    # 1M: 128-token chunks, shared rows computed from registers; 10M: 256-token chunks, shared rows re-read
+    cfg = W.CONFIGS[name]
     data = W.generate(cfg, device=DEV, n_queries=1)
     K, V, Q = data["K"], data["V"], data["Q"][0]
     w, k, b, f = 1088, 2, 4, 2
@@ -193,14 +195,32 @@ def test_paper_geometry_decode_at_1m():
     torch.cuda.synchronize()
     an, scn, Qn, On = anchors.cpu().numpy(), sc.cpu().numpy().astype(np.float64), f64(Q), f64(O)
     Kd, Vd = DevKV(K), DevKV(V)
+    cand = orc.anchor_candidates(i, w)
+    krows = [GatheredRows(K[kvh], [t for _, t in cand]) for kvh in range(cfg.Hkv)]   # the candidates' key rows
     for h in range(cfg.Hq):
-        _, t_o, _ = orc.anchor_search_row(Qn[h, 0], DevRows(K[h // G]), i, w, k)
+        _, t_o, _ = orc.anchor_search_row(Qn[h, 0], krows[h // G], i, w, k)
         if an[h, 0].tolist() != t_o + [-1] * (k - len(t_o)):
-            cand = orc.anchor_candidates(i, w)
-            allsc = [float(f64(K[h // G, t]) @ Qn[h, 0]) for _, t in cand]
+            allsc = [float(krows[h // G][t] @ Qn[h, 0]) for _, t in cand]
             check_anchor_row(an[h, 0].tolist(), t_o + [-1] * (k - len(t_o)), cand, allsc, k, h)
         o = orc.anchor_combined_row(Qn[h, 0], Kd, Vd, h // G, i, w, b, f, an[h, 0], scn[h, 0], 1.0 / math.sqrt(cfg.D))
         assert float(np.max(np.abs(On[h, 0] - o))) <= TOL[torch.bfloat16]
+    # the heads of every group on neighbouring anchors: their spans overlap almost entirely without
+    # being equal, so most chunks are read by one workgroup for several (head, slot) entries
+    rng = np.random.default_rng(7)
+    an2 = np.empty((cfg.Hq, 1, k), np.int32)
+    sc2 = rng.standard_normal((cfg.Hq, 1, k)).astype(np.float32)
+    for kvh in range(cfg.Hkv):
+        base = int(rng.integers(0, len(cand) - 3 * G))
+        for g in range(G):
+            picks = [base + g, base + g + 1 + (g % 3)]
+            an2[kvh * G + g, 0] = [cand[p][1] for p in picks]
+    an2_t, sc2_t = torch.from_numpy(an2).to(DEV), torch.from_numpy(sc2).to(DEV)
+    O2 = f64(B.sl_anchor_attention_decode(Q, K, V, an2_t, sc2_t, w, b, f))
+    torch.cuda.synchronize()
+    for h in list(range(G)) + list(range(cfg.Hq - G, cfg.Hq)):      # every head of the first and the last group
+        o = orc.anchor_combined_row(Qn[h, 0], Kd, Vd, h // G, i, w, b, f, an2[h, 0], sc2[h, 0].astype(np.float64),
+                                    1.0 / math.sqrt(cfg.D))
+        assert float(np.max(np.abs(O2[h, 0] - o))) <= TOL[torch.bfloat16], h
     del data, K, V
     torch.cuda.empty_cache()
 

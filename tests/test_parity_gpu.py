@@ -1202,3 +1202,15 @@ class DevRows:
 
     def __getitem__(self, t):
         return f64(self.t[t])
+
+
+class GatheredRows:
+    """The same access for a known set of tokens, fetched from the device in one gather."""
+
+    def __init__(self, t, tokens):
+        tokens = [int(x) for x in tokens]
+        rows = f64(t[torch.tensor(tokens, dtype=torch.long, device=t.device)]) if tokens else np.zeros((0, t.shape[1]))
+        self.rows = {tok: rows[n] for n, tok in enumerate(tokens)}
+
+    def __getitem__(self, t):
+        return self.rows[int(t)]
