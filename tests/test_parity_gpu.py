@@ -1025,6 +1025,52 @@ def test_anchor_decode_heads_sharing_anchors():
         assert float(np.max(np.abs(On[h, 0] - o))) <= TOL[torch.bfloat16], h
 
 
+@pytest.mark.parametrize("case_seed", list(range(301, 321)))
+def test_anchor_decode_attention_randomized_overlaps(case_seed):
+    """Random head counts, cache lengths, windows, span factors and exponents; the anchors are drawn
+    from the candidate list in clusters, so that spans of different heads and slots overlap at odd
+    offsets, are clipped by the window or by token 0, repeat, or are missing.  Every head against
+    the oracle's gated combination."""
+    rng = np.random.default_rng(case_seed)
+    Hkv = int(rng.choice([1, 2, 4]))
+    G = int(rng.choice([1, 2, 4, 8]))
+    Hq = Hkv * G
+    D = int(rng.choice([64, 128]))
+    dtype = torch.bfloat16 if rng.random() < 0.7 else torch.float32
+    root = int(rng.choice([2, 2, 3]))
+    L = int(rng.integers(2, 300)) if rng.random() < 0.25 else int(rng.integers(300, 120000))
+    k = int(rng.choice([1, 2, 3, 4, 8, 16]))
+    w = int(rng.choice([0, 1, 17, 200, 1088]))
+    b, f = int(rng.integers(0, 5)), int(rng.integers(0, 3))
+    Q, K, V = make(case_seed, Hq, Hkv, L, D, dtype, Lq=1, scale=0.5)
+    i = L - 1
+    cand = orc.anchor_candidates(i, w, root)
+    an = np.full((Hq, 1, k), -1, np.int32)
+    if cand:
+        for kv in range(Hkv):
+            centre = int(rng.integers(0, len(cand)))
+            for g in range(G):
+                for slot in range(k):
+                    r = rng.random()
+                    if r < 0.1:
+                        continue                                   # empty slot
+                    p = centre + int(rng.integers(-3, 4)) if r < 0.8 else int(rng.integers(0, len(cand)))
+                    an[kv * G + g, 0, slot] = cand[min(max(p, 0), len(cand) - 1)][1]
+    sc = rng.standard_normal((Hq, 1, k)).astype(np.float32)
+    an_t, sc_t = torch.from_numpy(an).to(DEV), torch.from_numpy(sc).to(DEV)
+    O = B.sl_anchor_attention_decode(Q, K, V, an_t, sc_t, w, b, f, search_root=root)
+    torch.cuda.synchronize()
+    On, Qn = f64(O), f64(Q)
+    Kd, Vd = f64(K), f64(V)          # on the host: the oracle reads them token by token
+    for h in range(Hq):
+        if w == 0 and not (an[h, 0] >= 0).any():
+            continue                 # no window and no span: the query attends nothing, the result is undefined
+        o = orc.anchor_combined_row(Qn[h, 0], Kd, Vd, h // G, i, w, b, f, an[h, 0], sc[h, 0].astype(np.float64),
+                                    1.0 / math.sqrt(D), root=root)
+        err = float(np.max(np.abs(On[h, 0] - o)))
+        assert err <= TOL[dtype], (case_seed, h, err, dict(Hq=Hq, Hkv=Hkv, D=D, L=L, k=k, w=w, b=b, f=f, root=root))
+
+
 # ------------------------------------------------------------------------------ the paper's own geometry (prefill form)
 
 ANCHOR_PREFILL = [
