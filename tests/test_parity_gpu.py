@@ -1025,6 +1025,24 @@ def test_anchor_decode_heads_sharing_anchors():
         assert float(np.max(np.abs(On[h, 0] - o))) <= TOL[torch.bfloat16], h
 
 
+def clustered_anchors(rng, i, w, root, Hkv, G, k):
+    """Anchors for every (head, slot) drawn from the candidates of position i in clusters (per kv head
+    around one candidate), with repeats, far outliers and empty slots."""
+    cand = orc.anchor_candidates(i, w, root)
+    an = np.full((Hkv * G, 1, k), -1, np.int32)
+    if cand:
+        for kv in range(Hkv):
+            centre = int(rng.integers(0, len(cand)))
+            for g in range(G):
+                for slot in range(k):
+                    r = rng.random()
+                    if r < 0.1:
+                        continue
+                    p = centre + int(rng.integers(-3, 4)) if r < 0.8 else int(rng.integers(0, len(cand)))
+                    an[kv * G + g, 0, slot] = cand[min(max(p, 0), len(cand) - 1)][1]
+    return an
+
+
 @pytest.mark.parametrize("case_seed", list(range(301, 321)))
 def test_anchor_decode_attention_randomized_overlaps(case_seed):
     """Random head counts, cache lengths, windows, span factors and exponents; the anchors are drawn
@@ -1044,18 +1062,7 @@ def test_anchor_decode_attention_randomized_overlaps(case_seed):
     b, f = int(rng.integers(0, 5)), int(rng.integers(0, 3))
     Q, K, V = make(case_seed, Hq, Hkv, L, D, dtype, Lq=1, scale=0.5)
     i = L - 1
-    cand = orc.anchor_candidates(i, w, root)
-    an = np.full((Hq, 1, k), -1, np.int32)
-    if cand:
-        for kv in range(Hkv):
-            centre = int(rng.integers(0, len(cand)))
-            for g in range(G):
-                for slot in range(k):
-                    r = rng.random()
-                    if r < 0.1:
-                        continue                                   # empty slot
-                    p = centre + int(rng.integers(-3, 4)) if r < 0.8 else int(rng.integers(0, len(cand)))
-                    an[kv * G + g, 0, slot] = cand[min(max(p, 0), len(cand) - 1)][1]
+    an = clustered_anchors(rng, i, w, root, Hkv, G, k)
     sc = rng.standard_normal((Hq, 1, k)).astype(np.float32)
     an_t, sc_t = torch.from_numpy(an).to(DEV), torch.from_numpy(sc).to(DEV)
     O = B.sl_anchor_attention_decode(Q, K, V, an_t, sc_t, w, b, f, search_root=root)
@@ -1069,6 +1076,43 @@ def test_anchor_decode_attention_randomized_overlaps(case_seed):
                                     1.0 / math.sqrt(D), root=root)
         err = float(np.max(np.abs(On[h, 0] - o)))
         assert err <= TOL[dtype], (case_seed, h, err, dict(Hq=Hq, Hkv=Hkv, D=D, L=L, k=k, w=w, b=b, f=f, root=root))
+
+
+@pytest.mark.parametrize("case_seed", list(range(401, 409)))
+def test_anchor_decode_batched_randomized_overlaps(case_seed):
+    """The same kind of anchors through the batched entry point: sequences of different lengths, each
+    with its own span extents and window, every head against the oracle."""
+    rng = np.random.default_rng(case_seed)
+    Hkv = int(rng.choice([1, 2, 4]))
+    G = int(rng.choice([2, 4, 8]))
+    Hq = Hkv * G
+    D = int(rng.choice([64, 128]))
+    dtype = torch.bfloat16 if rng.random() < 0.7 else torch.float32
+    root = int(rng.choice([2, 2, 3]))
+    k = int(rng.choice([1, 2, 4, 8]))
+    w = int(rng.choice([1, 17, 200, 1088]))
+    b, f = int(rng.integers(0, 5)), int(rng.integers(0, 3))
+    lengths = [int(rng.integers(2, 200)) if rng.random() < 0.25 else int(rng.integers(200, 90000))
+               for _ in range(int(rng.integers(2, 5)))]
+    Qs, Kc, Vc, ans, scs = [], [], [], [], []
+    for n, Lb in enumerate(lengths):
+        Q, K, V = make(case_seed * 10 + n, Hq, Hkv, Lb, D, dtype, Lq=1, scale=0.5)
+        Qs.append(Q), Kc.append(K), Vc.append(V)
+        ans.append(clustered_anchors(rng, Lb - 1, w, root, Hkv, G, k))
+        scs.append(rng.standard_normal((Hq, 1, k)).astype(np.float32))
+    batch = B.DecodeBatch(Qs, Qs, Kc, Vc, None, 1, k, want_scores=True)
+    batch.idx.copy_(torch.from_numpy(np.stack(ans)).to(DEV))
+    batch.scores.copy_(torch.from_numpy(np.stack(scs)).to(DEV))
+    O = B.sl_anchor_attention_decode_batched(batch, w, b, f, search_root=root)
+    torch.cuda.synchronize()
+    for n, Lb in enumerate(lengths):
+        On, Qn, Kd, Vd = f64(O[n]), f64(Qs[n]), f64(Kc[n]), f64(Vc[n])
+        for h in range(Hq):
+            o = orc.anchor_combined_row(Qn[h, 0], Kd, Vd, h // G, Lb - 1, w, b, f, ans[n][h, 0],
+                                        scs[n][h, 0].astype(np.float64), 1.0 / math.sqrt(D), root=root)
+            err = float(np.max(np.abs(On[h, 0] - o)))
+            assert err <= TOL[dtype], (case_seed, n, h, err, dict(Hq=Hq, Hkv=Hkv, D=D, lengths=lengths, k=k, w=w,
+                                                                  b=b, f=f, root=root))
 
 
 # ------------------------------------------------------------------------------ the paper's own geometry (prefill form)
