@@ -58,8 +58,7 @@ __device__ __forceinline__ void decode_search_body(
   const int g = lane / LPR, lr = lane % LPR;
   const LaneMajor lm = LaneMajor::make(c);
   if (wave == 0) select_clear(s_sc, lm, lane);
-  float qf[EPL];
-  Elem<T>::unpack(load16(Qs + (int64_t)h * qsh + lr * EPL), qf);
+  const uint4 qraw = load16(Qs + (int64_t)h * qsh + lr * EPL);
   __syncthreads();
   for (int64_t jb = (int64_t)wave * RPW * U; jb < c; jb += NW * RPW * U) {
     uint4 kr[U];
@@ -71,11 +70,7 @@ __device__ __forceinline__ void decode_search_body(
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      float kf[EPL];
-      Elem<T>::unpack(kr[u], kf);
-      float acc = 0.f;
-#pragma unroll
-      for (int e = 0; e < EPL; ++e) acc = fmaf(qf[e], kf[e], acc);
+      float acc = Piece<T>::dot(kr[u], qraw, 0.f);
       acc = group_sum<LPR>(acc);
       const int64_t j = jb + u * RPW + g;
       if (lr == 0 && j < c) s_sc[lm.slot((int)j)] = acc;
@@ -143,8 +138,7 @@ __device__ __forceinline__ void decode_search_block_body(
   const int kk = topk < c ? topk : (int)c;
 
   if (!pre_scores) {
-    float qf[EPL];
-    Elem<T>::unpack(load16(Qs + (int64_t)h * qsh + lr * EPL), qf);
+    const uint4 qraw = load16(Qs + (int64_t)h * qsh + lr * EPL);
     for (int64_t jb = (int64_t)wave * RPW * U; jb < c; jb += NW * RPW * U) {
       uint4 kr[U];
 #pragma unroll
@@ -157,11 +151,7 @@ __device__ __forceinline__ void decode_search_block_body(
       }
 #pragma unroll
       for (int u = 0; u < U; ++u) {
-        float kf[EPL];
-        Elem<T>::unpack(kr[u], kf);
-        float acc = 0.f;
-#pragma unroll
-        for (int e = 0; e < EPL; ++e) acc = fmaf(qf[e], kf[e], acc);
+        float acc = Piece<T>::dot(kr[u], qraw, 0.f);
         acc = group_sum<LPR>(acc);
         const int64_t j = jb + u * RPW + g;
         if (lr == 0 && j < c) s_sc[j] = acc;
@@ -286,7 +276,7 @@ __global__ __launch_bounds__(kDecodeSearchThreads) void decode_search_block_kern
 // all G query heads of its group, by many small workgroups (the key rows are read once instead
 // of once per head, and from every compute unit instead of from Hq of them).  grid
 // (ceil(c / kScoreCand), Hkv), 4 wavefronts; a wavefront takes kScoreCand / 4 consecutive
-// candidates, LPR lanes per key row.  Same arithmetic as the one-launch kernel (fp32 fma chain over
+// candidates, LPR lanes per key row.  Same arithmetic as the one-launch kernel (Piece<T>::dot over
 // the lane's elements, then the lane-group sum), so the scores are bit-identical to it.
 constexpr int kScoreCand = 32;
 
@@ -321,15 +311,10 @@ __global__ __launch_bounds__(256) void decode_score_group_kernel(
     }
 #pragma unroll
     for (int b = 0; b < HB; ++b) {
-      float qf[EPL];
-      Elem<T>::unpack(qr[b], qf);
+      const uint4 qraw = qr[b];
 #pragma unroll
       for (int u = 0; u < U; ++u) {
-        float kf[EPL];
-        Elem<T>::unpack(kr[u], kf);
-        float acc = 0.f;
-#pragma unroll
-        for (int e = 0; e < EPL; ++e) acc = fmaf(qf[e], kf[e], acc);
+        float acc = Piece<T>::dot(kr[u], qraw, 0.f);
         acc = group_sum<LPR>(acc);
         const int64_t j = j0 + u * RPW + g;
         if (lr == 0 && j < c && h0 + b < G) sc_out[(int64_t)(kv * G + h0 + b) * ld + j] = acc;
@@ -390,8 +375,7 @@ __global__ __launch_bounds__(256) void prefill_search_rows_kernel(
   const LaneMajor lm = LaneMajor::make(c);
   select_clear(sc, lm, lane);
   __builtin_amdgcn_wave_barrier();
-  float qf[EPL];
-  Elem<T>::unpack(load16(Qs + h * qsh + r * qst + lr * EPL), qf);
+  const uint4 qraw = load16(Qs + h * qsh + r * qst + lr * EPL);
   constexpr int U = 4;
   for (int64_t jb = 0; jb < c; jb += RPW * U) {
     uint4 kr[U];
@@ -403,11 +387,7 @@ __global__ __launch_bounds__(256) void prefill_search_rows_kernel(
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      float kf[EPL];
-      Elem<T>::unpack(kr[u], kf);
-      float acc = 0.f;
-#pragma unroll
-      for (int e = 0; e < EPL; ++e) acc = fmaf(qf[e], kf[e], acc);
+      float acc = Piece<T>::dot(kr[u], qraw, 0.f);
       acc = group_sum<LPR>(acc);
       const int64_t j = jb + u * RPW + g;
       if (lr == 0 && j < c) sc[lm.slot((int)j)] = acc;
@@ -443,8 +423,7 @@ __global__ __launch_bounds__(256) void prefill_anchor_search_rows_kernel(
   const LaneMajor lm = LaneMajor::make(c);
   select_clear(sc, lm, lane);
   __builtin_amdgcn_wave_barrier();
-  float qf[EPL];
-  Elem<T>::unpack(load16(Qs + h * qsh + r * qst + lr * EPL), qf);
+  const uint4 qraw = load16(Qs + h * qsh + r * qst + lr * EPL);
   const T* Kb = K + kv * kvsh;
   constexpr int U = 4;
   for (int64_t jb = 0; jb < c; jb += RPW * U) {
@@ -457,11 +436,7 @@ __global__ __launch_bounds__(256) void prefill_anchor_search_rows_kernel(
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      float kf[EPL];
-      Elem<T>::unpack(kr[u], kf);
-      float acc = 0.f;
-#pragma unroll
-      for (int e = 0; e < EPL; ++e) acc = fmaf(qf[e], kf[e], acc);
+      float acc = Piece<T>::dot(kr[u], qraw, 0.f);
       acc = group_sum<LPR>(acc);
       const int64_t j = jb + u * RPW + g;
       if (lr == 0 && j < c) sc[lm.slot((int)j)] = acc;
@@ -478,7 +453,7 @@ __global__ __launch_bounds__(256) void prefill_anchor_search_rows_kernel(
 // head: 8x the L2 traffic at GQA 8:1, which is what bounds it).  Lane lr of a group keeps the
 // running top-KMAX (scores and candidate numbers, in registers) of head lr % 8; candidates come in
 // ascending stride index and only a strictly larger score displaces an entry, so ties stay with the
-// nearer anchor.  Arithmetic per score as everywhere else (fp32 fma chain over the lane's
+// nearer anchor.  Arithmetic per score as everywhere else (Piece<T>::dot over the lane's
 // elements, then the lane-group sum): bit-identical to the other search kernels.
 template <typename T, int D, int KMAX>
 __global__ __launch_bounds__(256) void prefill_anchor_search_group_kernel(
@@ -502,11 +477,11 @@ __global__ __launch_bounds__(256) void prefill_anchor_search_group_kernel(
   // rows ascend with the lane and so do their candidate counts: the last lane has the most
   const int c_wave = __builtin_amdgcn_readlane(c, 63);
 
-  float qf[HB][EPL];
+  uint4 qraw[HB];
 #pragma unroll
   for (int hb = 0; hb < HB; ++hb) {
     const int h = kv * G + (h0 + hb < G ? h0 + hb : G - 1);
-    Elem<T>::unpack(load16(Qs + h * qsh + rc * qst + lr * EPL), qf[hb]);
+    qraw[hb] = load16(Qs + h * qsh + rc * qst + lr * EPL);
   }
   const T* Kb = K + kv * kvsh;
   float v[KMAX];
@@ -527,14 +502,10 @@ __global__ __launch_bounds__(256) void prefill_anchor_search_group_kernel(
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      float kf[EPL];
-      Elem<T>::unpack(kr[u], kf);
       float x = -INFINITY;
 #pragma unroll
       for (int hb = 0; hb < HB; ++hb) {
-        float acc = 0.f;
-#pragma unroll
-        for (int e = 0; e < EPL; ++e) acc = fmaf(qf[hb][e], kf[e], acc);
+        float acc = Piece<T>::dot(kr[u], qraw[hb], 0.f);
         acc = group_sum<LPR>(acc);
         x = myh == hb ? acc : x;
       }

@@ -78,6 +78,37 @@ struct Elem<bf16_t> {
   __device__ static __forceinline__ void store1(bf16_t* p, float v) { *p = f32_to_bf16(v); }
 };
 
+// Dot product of two 16-byte row pieces on top of acc, as every span-search kernel takes it
+// (eq. (2)): the same instructions in the same order everywhere, so that the kernels agree bit for
+// bit.  bf16: four two-element dot instructions on the packed pairs (exact products, fp32 sums) -
+// no unpacking; fp32: a chain of four fused multiply-adds.
+template <typename T>
+struct Piece;
+template <>
+struct Piece<float> {
+  __device__ static __forceinline__ float dot(const uint4& a, const uint4& b, float acc) {
+    acc = fmaf(__uint_as_float(a.x), __uint_as_float(b.x), acc);
+    acc = fmaf(__uint_as_float(a.y), __uint_as_float(b.y), acc);
+    acc = fmaf(__uint_as_float(a.z), __uint_as_float(b.z), acc);
+    acc = fmaf(__uint_as_float(a.w), __uint_as_float(b.w), acc);
+    return acc;
+  }
+};
+template <>
+struct Piece<bf16_t> {
+  typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+  __device__ static __forceinline__ float dot2(unsigned a, unsigned b, float acc) {
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, a), __builtin_bit_cast(bf16x2, b), acc, false);
+  }
+  __device__ static __forceinline__ float dot(const uint4& a, const uint4& b, float acc) {
+    acc = dot2(a.x, b.x, acc);
+    acc = dot2(a.y, b.y, acc);
+    acc = dot2(a.z, b.z, acc);
+    acc = dot2(a.w, b.w, acc);
+    return acc;
+  }
+};
+
 // One row of D elements is covered by LPR lanes, each holding 16 bytes; a wavefront of 64
 // lanes covers RPW rows per load instruction.
 template <typename T, int D>
