@@ -502,13 +502,11 @@ __global__ __launch_bounds__(256) void prefill_anchor_search_group_kernel(
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      float x = -INFINITY;
+      // the eight heads' partial dot products, then one reduce-scatter: this lane gets head myh's score
+      float part[HB];
 #pragma unroll
-      for (int hb = 0; hb < HB; ++hb) {
-        float acc = Piece<T>::dot(kr[u], qraw[hb], 0.f);
-        acc = group_sum<LPR>(acc);
-        x = myh == hb ? acc : x;
-      }
+      for (int hb = 0; hb < HB; ++hb) part[hb] = Piece<T>::dot(kr[u], qraw[hb], 0.f);
+      float x = group_sum_scatter8<LPR>(part, lr);
       const int j = jb + u;
       x = j < c ? x : -INFINITY;
       // insert (x, j): slot e takes the entry above it if x belongs above that one, x itself if

@@ -157,8 +157,8 @@ __host__ __device__ inline int64_t span_base_length(int64_t i, int root) {
   return ipow_root(m, root) == target ? m : m + 1;
 }
 
-// DPP lane exchange (no LDS traffic). ctrl: quad_perm 0x00-0xFF, row_mirror 0x140,
-// row_half_mirror 0x141.
+// DPP lane exchange (no LDS traffic). ctrl: quad_perm 0x00-0xFF, row_shl:n 0x100+n, row_shr:n 0x110+n,
+// row_ror:n 0x120+n, row_mirror 0x140, row_half_mirror 0x141.
 template <int CTRL>
 __device__ __forceinline__ float dpp_f32(float v) {
   return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, true));
@@ -171,6 +171,38 @@ __device__ __forceinline__ float group_sum(float v) {
   v += dpp_f32<0x4E>(v);   // lane ^ 2
   v += dpp_f32<0x141>(v);  // mirror within 8 lanes: adds the other quad
   if (LPR >= 16) v += dpp_f32<0x140>(v);  // mirror within 16 lanes: adds the other half-row
+  if (LPR >= 32) v += __shfl_xor(v, 16, 64);
+  return v;
+}
+
+// Eight values per lane (a[0..7]) summed over the LPR lanes of a row group, each lane ending up
+// with the total of ONE of them: lane lr gets the group sum of a[lr % 8].  A reduce-scatter: at
+// every level a lane passes on the half of its values that its partner keeps and adds what it
+// receives to the half it keeps (24 instructions for 16 lanes, where eight group_sum calls take 32
+// and the caller a select per value on top).  The additions pair the same partial sums as
+// group_sum does, level by level, so the totals are bit-identical to it.
+template <int LPR>
+__device__ __forceinline__ float group_sum_scatter8(const float (&a)[8], int lr) {
+  static_assert(LPR >= 8, "needs a lane per value");
+  const bool b0 = lr & 1, b1 = lr & 2, b2 = lr & 4;
+  float l1[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {  // l1[j]: the pair's sum of value 2j + b0
+    const float keep = b0 ? a[2 * j + 1] : a[2 * j], send = b0 ? a[2 * j] : a[2 * j + 1];
+    l1[j] = keep + dpp_f32<0xB1>(send);   // lane ^ 1
+  }
+  float l2[2];
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {  // l2[j]: the quad's sum of value 4j + 2*b1 + b0
+    const float keep = b1 ? l1[2 * j + 1] : l1[2 * j], send = b1 ? l1[2 * j] : l1[2 * j + 1];
+    l2[j] = keep + dpp_f32<0x4E>(send);   // lane ^ 2
+  }
+  const float keep = b2 ? l2[1] : l2[0], send = b2 ? l2[0] : l2[1];
+  // lane ^ 4: rows shifted by four lanes either way, each written to the banks it is right for
+  int other = __builtin_amdgcn_update_dpp(0, __float_as_int(send), 0x104, 0xF, 0x5, false);      // row_shl:4 -> lanes 0-3, 8-11
+  other = __builtin_amdgcn_update_dpp(other, __float_as_int(send), 0x114, 0xF, 0xA, false);      // row_shr:4 -> lanes 4-7, 12-15
+  float v = keep + __int_as_float(other);  // value 4*b2 + 2*b1 + b0 = lr % 8, summed over 8 lanes
+  if (LPR >= 16) v += dpp_f32<0x128>(v);   // row rotated by 8 = lane ^ 8: the other half-row's sum of the same value
   if (LPR >= 32) v += __shfl_xor(v, 16, 64);
   return v;
 }
